@@ -1,0 +1,322 @@
+"""CPU oracle for ADORE's per-step decode path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 implementation of what one decode step computes, written
+from the paper's definitions (arXiv 2407.02328): sparse single-query attention
+over the retained rows (Sec. 2.1, Eq. 1 and the unnumbered "target" equation),
+the controller score (Sec. 2.2, Eq. 2 and App. "Implementation Details"), the
+release of the lowest-scored rows (Sec. 2.2), the choice of the top-R released
+tokens (Sec. 2.3) and the re-projection of their K/V states (Sec. 2.3).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this module.  It shares no code with the HIP path and must never be used as a
+fallback for it.
+
+Every function below is pinned by a CPU test against something other than
+itself (a library routine, a closed form, brute force or an invariant); none
+is "parity unpinned".  What cannot be pinned at all are the paper's numeric
+results on real text (datasets, fine-tuned backbone and trained controller
+are not available).
+
+Readings of points the paper leaves open (each used exactly as stated here):
+  * K physical slots = m persistent rows + R rebuilt rows + the current token
+    (Sec. 2.3: K/V of (m+R+1) x d).
+  * Heads are independent and the softmax scale uses the head dimension.
+  * The GRU is the textbook cell with the reset gate applied to the recurrent
+    pre-activation (the variant common libraries implement), z_{-1} = 0.
+  * Position feature of token i is the scalar i * pos_scale fed to a 1 -> d'
+    fully connected layer (App. "Implementation Details", position layer).
+  * sigma_i is computed once, when token i arrives, and never changes
+    (Eq. 2 carries no dependence on the current step).
+  * The current token is not released in its own step (Sec. 2.2: an "older"
+    state is removed).
+  * Tokens released in this step may be rebuilt in this step (Sec. 2.3).
+  * Ties on sigma are broken in favour of the lower position.
+  * Rows never move: a released row frees its slot; incoming rows take the
+    lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
+    token -> lowest free slot at its insert).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def round_to_storage(a: np.ndarray, dtype: str) -> np.ndarray:
+    """One round-to-nearest-even from fp64 to the storage type, returned as fp64."""
+    a = np.asarray(a, dtype=F64)
+    if dtype == "f32":
+        return a.astype(np.float32).astype(F64)
+    if dtype == "bf16":
+        # bf16: 8 significand bits, exponent range of fp32.
+        mant, exp = np.frexp(a)                    # a = mant * 2**exp, 0.5 <= |mant| < 1
+        exp = np.maximum(exp, -125)                # below that: fixed (subnormal) spacing
+        mant = a / np.ldexp(1.0, exp)
+        return np.ldexp(np.rint(mant * 256.0), exp - 8)   # rint rounds half to even
+    raise ValueError(dtype)
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.1: attention
+# --------------------------------------------------------------------------
+def softmax_row(logits: np.ndarray) -> np.ndarray:
+    """softmax over a 1-D vector, max-subtracted."""
+    e = np.exp(logits - np.max(logits))
+    return e / np.sum(e)
+
+
+def attention_row(q: np.ndarray, Kmat: np.ndarray, Vmat: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 1 for one head and one query: softmax(q K^T / sqrt(d)) V.
+
+    q: [d]; Kmat, Vmat: [rows, d].  Returns (output [d], probabilities [rows]).
+    """
+    d = q.shape[0]
+    p = softmax_row((Kmat @ q) / np.sqrt(F64(d)))
+    return p @ Vmat, p
+
+
+def slice_rows_by_matmul(Kmat: np.ndarray, j: int) -> np.ndarray:
+    """Sec. 2.4: remove row j as S_j K with S_j = identity without its j-th row."""
+    mrows = Kmat.shape[0]
+    S_j = np.delete(np.eye(mrows), j, axis=0)
+    return S_j @ Kmat
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.2: controller
+# --------------------------------------------------------------------------
+def sigmoid(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def gru_cell(x: np.ndarray, h: np.ndarray, W_ih: np.ndarray, W_hh: np.ndarray,
+             b_ih: np.ndarray, b_hh: np.ndarray) -> np.ndarray:
+    """z_i = GRU(x_i, z_{i-1}) (Eq. 2, first line).  Gate order in the stacked weights: r, z, n."""
+    dp = h.shape[0]
+    gi = W_ih @ x + b_ih
+    gh = W_hh @ h + b_hh
+    r = sigmoid(gi[0:dp] + gh[0:dp])
+    u = sigmoid(gi[dp:2 * dp] + gh[dp:2 * dp])
+    cand = np.tanh(gi[2 * dp:] + r * gh[2 * dp:])
+    return (1.0 - u) * cand + u * h
+
+
+def keep_probability(z: np.ndarray, delta: float, wts: Dict[str, np.ndarray]) -> float:
+    """sigma_i = Sigmoid(MLP(p_i + z_i)) (Eq. 2, second line).
+
+    p_i = pos_w * delta + pos_b (position layer, 1 -> d'), interaction layer
+    with tanh, output layer followed by a sigmoid.
+    """
+    p = wts["pos_w"] * delta + wts["pos_b"]
+    u = np.tanh(wts["mlp_w1"] @ (p + z) + wts["mlp_b1"])
+    return float(sigmoid(wts["out_w"] @ u + wts["out_b"][0]))
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.2 / 2.3: the order on tokens and the two selections
+# --------------------------------------------------------------------------
+def ranked(positions: Sequence[int], score: np.ndarray) -> List[int]:
+    """Positions sorted best first: higher sigma first, equal sigma -> lower position first."""
+    return sorted((int(p) for p in positions), key=lambda p: (-float(score[p]), p))
+
+
+def release_lowest(slot_pos: np.ndarray, score: np.ndarray, current: int, m: int) -> List[int]:
+    """Slots to free so that at most m rows stay: the lowest-ranked occupied rows, never `current`.
+
+    slot_pos: [K] position per slot, -1 = free.  Returns slot indices, ascending.
+    """
+    occupied = [k for k in range(slot_pos.shape[0]) if slot_pos[k] >= 0]
+    x = max(0, len(occupied) - m)
+    if x == 0:
+        return []
+    slot_of = {int(slot_pos[k]): k for k in occupied}
+    order = ranked([p for p in slot_of if p != current], score)    # best first
+    return sorted(slot_of[p] for p in order[len(order) - x:])
+
+
+def rebuild_choice(resident: Sequence[int], n: int, score: np.ndarray, R: int) -> List[int]:
+    """Top-R of the released tokens (positions 0..n that hold no cache row), best first."""
+    res = set(int(p) for p in resident)
+    pool = [p for p in range(n + 1) if p not in res]
+    return ranked(pool, score)[:min(R, len(pool))]
+
+
+# --------------------------------------------------------------------------
+# the whole path
+# --------------------------------------------------------------------------
+@dataclass
+class OracleConfig:
+    L: int
+    B: int
+    H: int
+    d: int
+    D: int
+    K: int
+    R: int
+    N_max: int
+    dprime: int
+    dtype: str            # "f32" | "bf16"
+    pos_scale: float
+
+    @property
+    def m(self) -> int:
+        return self.K - self.R - 1
+
+
+class AdoreOracle:
+    """State of one decode job and its init / step functions.
+
+    Inputs are float arrays whose values are already exact in the storage
+    type; everything is upcast to fp64 where it is used.
+    """
+
+    def __init__(self, cfg: OracleConfig, weights: Dict[str, np.ndarray]):
+        if not (0 <= cfg.R <= cfg.K - 2):
+            raise ValueError("need 0 <= R <= K-2")
+        self.cfg = cfg
+        self.wts = weights
+        # fp64 copies of the controller parameters; W_kv is upcast per layer on first use
+        self.w64 = {k: np.asarray(v, dtype=F64) for k, v in weights.items() if k != "w_kv"}
+        self._wkv64: Dict[int, np.ndarray] = {}
+        c = cfg
+        self.Kc = np.zeros((c.L, c.B, c.H, c.K, c.d), dtype=F64)
+        self.Vc = np.zeros((c.L, c.B, c.H, c.K, c.d), dtype=F64)
+        self.slot_pos = np.full((c.B, c.H, c.K), -1, dtype=np.int32)
+        self.score = np.zeros((c.B, c.N_max), dtype=np.float32)
+        self.z = np.zeros((c.B, c.dprime), dtype=F64)
+        self.n = 0                       # position of the next token to arrive
+        self.last_probs = None           # attention probabilities of the last step (diagnostics)
+
+    # -- controller ---------------------------------------------------------
+    def _controller(self, b: int, x: np.ndarray, i: int) -> float:
+        w = self.w64
+        self.z[b] = gru_cell(x.astype(F64), self.z[b], w["gru_w_ih"], w["gru_w_hh"],
+                             w["gru_b_ih"], w["gru_b_hh"])
+        delta = F64(np.float32(i) * np.float32(self.cfg.pos_scale))
+        return keep_probability(self.z[b], delta, w)
+
+    # -- rebuild ------------------------------------------------------------
+    def _project(self, layer: int, x_rows: np.ndarray) -> np.ndarray:
+        """K/V states of tokens from their hidden states: one rounding of x W_kv^T."""
+        if layer not in self._wkv64:                     # [2*H*d, D], rows 0..H*d-1 = W_k
+            self._wkv64[layer] = np.asarray(self.wts["w_kv"][layer], dtype=F64)
+        return round_to_storage(x_rows.astype(F64) @ self._wkv64[layer].T, self.cfg.dtype)
+
+    def _place_rebuilt(self, b: int, rebuilt: List[int], hidden_store: np.ndarray) -> None:
+        c = self.cfg
+        if not rebuilt:
+            return
+        for l in range(c.L):
+            kv = self._project(l, hidden_store[l, b, rebuilt, :])           # [r, 2*H*d]
+            for h in range(c.H):
+                free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]    # ascending
+                for rho, pos in enumerate(rebuilt):
+                    s = free[rho]
+                    self.Kc[l, b, h, s] = kv[rho, h * c.d:(h + 1) * c.d]
+                    self.Vc[l, b, h, s] = kv[rho, c.H * c.d + h * c.d: c.H * c.d + (h + 1) * c.d]
+        for h in range(c.H):
+            free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]
+            for rho, pos in enumerate(rebuilt):
+                self.slot_pos[b, h, free[rho]] = pos
+
+    # -- init ---------------------------------------------------------------
+    def init_cache(self, prompt_k: np.ndarray, prompt_v: np.ndarray, hidden_store: np.ndarray,
+                   ctrl_input: np.ndarray, S: int, score_override: Optional[np.ndarray] = None):
+        """One-shot application of the step rules to a prompt of S tokens.
+
+        prompt_k/v: [L,B,H,S,d]; hidden_store: [L,B,N_max,D] (rows < S valid);
+        ctrl_input: [B,S,D]; score_override: [B,S] or None.
+        Residents = {S-1} plus the best min(S,m)-1 of the older tokens, in
+        ascending position from slot 0; then the best min(R, |rest|) of the
+        rest, by rank, re-projected from their hidden states.
+        """
+        c = self.cfg
+        self.slot_pos[:] = -1
+        self.z[:] = 0.0
+        rebuilt_all = []
+        for b in range(c.B):
+            for i in range(S):
+                s = self._controller(b, ctrl_input[b, i], i)
+                self.score[b, i] = np.float32(s) if score_override is None else score_override[b, i]
+            keep = min(S, c.m)
+            older = ranked(range(S - 1), self.score[b])[:keep - 1]
+            residents = sorted(older + [S - 1])
+            for h in range(c.H):
+                for s_idx, pos in enumerate(residents):
+                    self.Kc[:, b, h, s_idx] = prompt_k[:, b, h, pos]
+                    self.Vc[:, b, h, s_idx] = prompt_v[:, b, h, pos]
+                    self.slot_pos[b, h, s_idx] = pos
+            rebuilt = rebuild_choice(residents, S - 1, self.score[b], c.R)
+            self._place_rebuilt(b, rebuilt, hidden_store)
+            rebuilt_all.append(rebuilt)
+        self.n = S
+        return rebuilt_all
+
+    # -- one decode step ----------------------------------------------------
+    def decode_step(self, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
+                    hidden_store: np.ndarray, x_n: np.ndarray,
+                    score_override: Optional[np.ndarray] = None):
+        """q, k_new, v_new: [L,B,H,d]; hidden_store: [L,B,N_max,D]; x_n: [B,D].
+
+        Returns (out [L,B,H,d] fp64, slot_map [B,H,K] i32, released_pos [B,H,R+1] i32,
+        rebuilt_pos [B,R] i32, own_score [B] fp64) where own_score is the controller's
+        value before any override.
+        """
+        c = self.cfg
+        n = self.n
+        if n >= c.N_max:
+            raise RuntimeError("step past N_max")
+        out = np.zeros((c.L, c.B, c.H, c.d), dtype=F64)
+        released_pos = np.full((c.B, c.H, c.R + 1), -1, dtype=np.int32)
+        rebuilt_pos = np.full((c.B, c.R), -1, dtype=np.int32)
+        own_score = np.zeros(c.B, dtype=F64)
+        probs = {}
+
+        for b in range(c.B):
+            # 1. insert the current token's k, v into the lowest free slot of every head
+            for h in range(c.H):
+                free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]
+                s = free[0]
+                self.Kc[:, b, h, s] = k_new[:, b, h]
+                self.Vc[:, b, h, s] = v_new[:, b, h]
+                self.slot_pos[b, h, s] = n
+            # 2. attention over the occupied slots
+            for l in range(c.L):
+                for h in range(c.H):
+                    valid = np.nonzero(self.slot_pos[b, h] >= 0)[0]
+                    out[l, b, h], p = attention_row(q[l, b, h].astype(F64),
+                                                    self.Kc[l, b, h, valid], self.Vc[l, b, h, valid])
+                    probs[(l, b, h)] = (valid, p)
+            # 3. controller: score of the arriving token; older scores unchanged
+            own_score[b] = self._controller(b, x_n[b], n)
+            self.score[b, n] = (np.float32(own_score[b]) if score_override is None
+                                else np.float32(score_override[b]))
+            # 4. release
+            for h in range(c.H):
+                freed = release_lowest(self.slot_pos[b, h], self.score[b], n, c.m)
+                for j, s in enumerate(freed):
+                    released_pos[b, h, j] = self.slot_pos[b, h, s]
+                for s in freed:
+                    self.slot_pos[b, h, s] = -1
+            # 5. rebuild choice (uniform policy: residency is the same for every head; head 0 is read)
+            resident = [int(p) for p in self.slot_pos[b, 0] if p >= 0]
+            rebuilt = rebuild_choice(resident, n, self.score[b], c.R)
+            rebuilt_pos[b, :len(rebuilt)] = rebuilt
+            # 6. rebuild: re-project and scatter into the lowest free slots
+            self._place_rebuilt(b, rebuilt, hidden_store)
+
+        self.n = n + 1
+        self.last_probs = probs
+        return out, self.slot_pos.copy(), released_pos, rebuilt_pos, own_score
+
+
+def full_attention(q: np.ndarray, Kall: np.ndarray, Vall: np.ndarray) -> np.ndarray:
+    """Eq. 1 over all past rows, per head.  q: [H,d]; Kall, Vall: [H,n,d]."""
+    return np.stack([attention_row(q[h].astype(F64), Kall[h].astype(F64), Vall[h].astype(F64))[0]
+                     for h in range(q.shape[0])])

@@ -1,0 +1,404 @@
+"""Pins for the CPU oracle: each checks it against something other than itself.
+
+Library routines (torch CPU GRUCell / Linear / matmul, scipy softmax), closed
+forms, brute force over subsets, invariants, a hand-worked trajectory.  None of
+these touches the GPU.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from gen import SyntheticInputs, Workload
+from oracle import adore_oracle as O
+from tests.helpers import GOLDEN, make_oracle, oracle_config, parse_trajectory, small_workload
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def test_round_bf16_matches_torch_on_fp32_values():
+    rng = np.random.default_rng(0)
+    a = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_to_storage(a.astype(np.float64), "bf16")
+    assert np.array_equal(got, want)
+
+
+def test_round_bf16_ties_and_single_rounding():
+    ulp = 2.0 ** -7                      # bf16 spacing in [1, 2)
+    cases = {
+        1.0 + ulp / 2: 1.0,              # tie -> even significand
+        1.0 + 3 * ulp / 2: 1.0 + 2 * ulp,
+        1.0 + ulp / 2 + 2.0 ** -30: 1.0 + ulp,   # just above the tie: a detour through fp32 would give 1.0
+        -(1.0 + ulp / 2): -1.0,
+        0.0: 0.0,
+        3.0e-39: 3.0e-39 if False else None,     # subnormal range: checked below
+    }
+    for a, want in cases.items():
+        if want is None:
+            continue
+        assert O.round_to_storage(np.array([a]), "bf16")[0] == want
+    # subnormal spacing of bf16 is 2**-133
+    sub = O.round_to_storage(np.array([3.0e-39]), "bf16")[0]
+    assert sub == np.rint(3.0e-39 / 2.0 ** -133) * 2.0 ** -133
+
+
+def test_round_f32_is_numpy_cast():
+    a = np.random.default_rng(1).standard_normal(1000)
+    assert np.array_equal(O.round_to_storage(a, "f32"), a.astype(np.float32).astype(np.float64))
+
+
+# --------------------------------------------------------------------------
+# attention (Sec. 2.1, Eq. 1)
+# --------------------------------------------------------------------------
+def test_softmax_rows_sum_to_one_and_shift_invariance():
+    rng = np.random.default_rng(2)
+    for rows in (1, 2, 7, 64, 513):
+        q = rng.standard_normal(32)
+        Km = rng.standard_normal((rows, 32)) * 3.0
+        Vm = rng.standard_normal((rows, 32))
+        out, p = O.attention_row(q, Km, Vm)
+        assert abs(p.sum() - 1.0) < 1e-12
+        assert np.all(p >= 0)
+        # library softmax on the same logits
+        want_p = scipy.special.softmax(Km @ q / np.sqrt(32.0))
+        np.testing.assert_allclose(p, want_p, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(out, want_p @ Vm, rtol=1e-12, atol=1e-14)
+        # adding a constant to every logit (a key component along q) leaves the output unchanged
+        shift = 5.0 * q / (q @ q) * np.sqrt(32.0)
+        out2, _ = O.attention_row(q, Km + shift[None, :], Vm)
+        np.testing.assert_allclose(out2, out, rtol=1e-9, atol=1e-12)
+
+
+def test_single_row_attention_returns_that_value_row():
+    rng = np.random.default_rng(3)
+    q, k, v = rng.standard_normal(16), rng.standard_normal((1, 16)), rng.standard_normal((1, 16))
+    out, p = O.attention_row(q, k, v)
+    assert p[0] == 1.0 and np.array_equal(out, v[0])
+
+
+def test_scale_uses_head_dim():
+    # with q = k = ones(d) the logit is d / sqrt(d) = sqrt(d); two rows, second key zero
+    d = 64
+    q = np.ones(d)
+    Km = np.stack([np.ones(d), np.zeros(d)])
+    Vm = np.stack([np.ones(d), -np.ones(d)])
+    out, p = O.attention_row(q, Km, Vm)
+    want_p0 = 1.0 / (1.0 + np.exp(-np.sqrt(d)))
+    assert abs(p[0] - want_p0) < 1e-15
+
+
+def test_slicing_matrix_identity():
+    """Sec. 2.4: S_j K equals K with row j removed, so a release is just a dropped row."""
+    rng = np.random.default_rng(4)
+    Km = rng.standard_normal((9, 5))
+    for j in range(9):
+        assert np.array_equal(O.slice_rows_by_matmul(Km, j), np.delete(Km, j, axis=0))
+
+
+# --------------------------------------------------------------------------
+# controller (Sec. 2.2, Eq. 2)
+# --------------------------------------------------------------------------
+def test_gru_cell_matches_torch_grucell():
+    torch.manual_seed(0)
+    D, dp = 48, 12
+    cell = torch.nn.GRUCell(D, dp).double()
+    x = torch.randn(5, D, dtype=torch.float64)
+    h = torch.randn(5, dp, dtype=torch.float64)
+    want = cell(x, h).detach().numpy()
+    W_ih, W_hh = cell.weight_ih.detach().numpy(), cell.weight_hh.detach().numpy()
+    b_ih, b_hh = cell.bias_ih.detach().numpy(), cell.bias_hh.detach().numpy()
+    for i in range(5):
+        got = O.gru_cell(x[i].numpy(), h[i].numpy(), W_ih, W_hh, b_ih, b_hh)
+        np.testing.assert_allclose(got, want[i], rtol=1e-12, atol=1e-13)
+
+
+def test_gru_sequence_matches_torch_gru_from_zero_state():
+    torch.manual_seed(1)
+    D, dp, S = 20, 6, 9
+    gru = torch.nn.GRU(D, dp, num_layers=1, batch_first=True, bidirectional=False).double()
+    xs = torch.randn(1, S, D, dtype=torch.float64)
+    want, _ = gru(xs)
+    h = np.zeros(dp)
+    for i in range(S):
+        h = O.gru_cell(xs[0, i].numpy(), h, gru.weight_ih_l0.detach().numpy(),
+                       gru.weight_hh_l0.detach().numpy(), gru.bias_ih_l0.detach().numpy(),
+                       gru.bias_hh_l0.detach().numpy())
+        np.testing.assert_allclose(h, want[0, i].detach().numpy(), rtol=1e-11, atol=1e-12)
+
+
+def test_keep_probability_matches_torch_layers():
+    torch.manual_seed(2)
+    dp = 10
+    pos = torch.nn.Linear(1, dp).double()
+    inter = torch.nn.Linear(dp, dp).double()
+    outl = torch.nn.Linear(dp, 1).double()
+    z = torch.randn(dp, dtype=torch.float64)
+    for delta in (0.0, 0.25, 3.0):
+        want = torch.sigmoid(outl(torch.tanh(inter(pos(torch.tensor([delta], dtype=torch.float64)) + z))))
+        wts = dict(pos_w=pos.weight.detach().numpy()[:, 0], pos_b=pos.bias.detach().numpy(),
+                   mlp_w1=inter.weight.detach().numpy(), mlp_b1=inter.bias.detach().numpy(),
+                   out_w=outl.weight.detach().numpy()[0], out_b=outl.bias.detach().numpy())
+        got = O.keep_probability(z.numpy(), delta, wts)
+        assert abs(got - want.item()) < 1e-14
+
+
+def test_oracle_scores_follow_gru_then_mlp_over_a_prompt():
+    """The stateful path feeds positions i * pos_scale and carries z across tokens."""
+    w = small_workload(B=1, S=7, T=2)
+    orc, inp, wts = make_oracle(w)
+    hs = inp.hidden_store()
+    pk, pv = inp.prompt_kv()
+    orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S)
+    cell = torch.nn.GRUCell(w.D, w.dprime).double()
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(wts["gru_w_ih"].astype(np.float64)))
+        cell.weight_hh.copy_(torch.from_numpy(wts["gru_w_hh"].astype(np.float64)))
+        cell.bias_ih.copy_(torch.from_numpy(wts["gru_b_ih"].astype(np.float64)))
+        cell.bias_hh.copy_(torch.from_numpy(wts["gru_b_hh"].astype(np.float64)))
+        h = torch.zeros(1, w.dprime, dtype=torch.float64)
+        for i in range(w.S):
+            h = cell(torch.from_numpy(hs[0][0, i].astype(np.float64))[None], h)
+            p = torch.from_numpy(wts["pos_w"].astype(np.float64)) * (i * w.pos_scale) + \
+                torch.from_numpy(wts["pos_b"].astype(np.float64))
+            u = torch.tanh(torch.from_numpy(wts["mlp_w1"].astype(np.float64)) @ (p + h[0]) +
+                           torch.from_numpy(wts["mlp_b1"].astype(np.float64)))
+            s = torch.sigmoid(torch.from_numpy(wts["out_w"].astype(np.float64)) @ u + float(wts["out_b"][0]))
+            assert abs(float(orc.score[0, i]) - s.item()) < 1e-6     # score is stored as fp32
+    np.testing.assert_allclose(orc.z[0], h[0].numpy(), rtol=1e-11, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# selections (Sec. 2.2 release, Sec. 2.3 rebuild choice): brute force
+# --------------------------------------------------------------------------
+def _better(i, j, score):
+    """i ranks above j."""
+    return score[i] > score[j] or (score[i] == score[j] and i < j)
+
+
+def test_release_is_the_unique_lowest_set_by_brute_force():
+    rng = np.random.default_rng(5)
+    K = 8
+    for trial in range(150):
+        npos = 14
+        score = rng.choice(np.array([0.1, 0.3, 0.3, 0.5, 0.7, 0.7, 0.9], dtype=np.float32), npos)
+        occ = rng.integers(3, K + 1)
+        slots = rng.permutation(K)[:occ]
+        positions = rng.permutation(npos)[:occ]
+        slot_pos = np.full(K, -1, dtype=np.int32)
+        slot_pos[slots] = positions
+        current = int(positions[rng.integers(occ)])
+        m = int(rng.integers(1, occ + 1))
+        got = O.release_lowest(slot_pos, score, current, m)
+        x = max(0, occ - m)
+        assert len(got) == x and got == sorted(got)
+        cands = [int(s) for s in slots if slot_pos[s] != current]
+        # exactly one subset of size x has every member ranked below every non-member
+        hits = []
+        for sub in itertools.combinations(sorted(cands), x):
+            rest = [s for s in cands if s not in sub]
+            if all(_better(slot_pos[r], slot_pos[s], score) for s in sub for r in rest):
+                hits.append(list(sub))
+        assert hits == [got]
+
+
+def test_rebuild_choice_by_brute_force():
+    rng = np.random.default_rng(6)
+    for trial in range(150):
+        n = int(rng.integers(3, 11))
+        score = rng.choice(np.array([0.2, 0.4, 0.4, 0.6, 0.8], dtype=np.float32), n + 1)
+        resident = list(rng.permutation(n + 1)[:rng.integers(1, n + 1)])
+        R = int(rng.integers(0, 5))
+        got = O.rebuild_choice(resident, n, score, R)
+        pool = [p for p in range(n + 1) if p not in resident]
+        r = min(R, len(pool))
+        assert len(got) == r and set(got) <= set(pool)
+        # best first, and nothing left in the pool beats a chosen token
+        for a, b in zip(got, got[1:]):
+            assert _better(a, b, score)
+        for p in pool:
+            if p not in got:
+                assert all(_better(g, p, score) for g in got)
+
+
+# --------------------------------------------------------------------------
+# whole path
+# --------------------------------------------------------------------------
+def _run(orc, inp, w, steps, override=None, collect=None):
+    hs = inp.hidden_store()
+    pk, pv = inp.prompt_kv()
+    orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S,
+                   score_override=None if override is None else override[:, :w.S])
+    outs = []
+    for t in range(steps):
+        n = w.S + t
+        q, k, v = inp.step_qkv(n)
+        res = orc.decode_step(q, k, v, hs, hs[0][:, n], None if override is None else override[:, n])
+        outs.append(res)
+        if collect is not None:
+            collect(n, res)
+    return outs, hs, pk, pv
+
+
+def test_hand_worked_trajectory():
+    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, "slot_trajectory_K4_R1.txt"))
+    S = len(init_scores)
+    w = Workload("golden", L=1, B=1, H=2, d=4, D=8, K=4, R=1, S=S, T=len(steps), dtype="f32", dprime=4)
+    orc, inp, _ = make_oracle(w)
+    hs = inp.hidden_store()
+    pk, pv = inp.prompt_kv()
+    rb = orc.init_cache(pk, pv, hs, hs[0][:, :S], S, score_override=init_scores[None, :])
+    for h in range(w.H):
+        assert orc.slot_pos[0, h].tolist() == after_init["slot_map"]
+    assert rb[0] == after_init["rebuilt"]
+    for st in steps:
+        q, k, v = inp.step_qkv(st["n"])
+        out, slot_map, released, rebuilt, _ = orc.decode_step(
+            q, k, v, hs, hs[0][:, st["n"]], np.array([st["score"]], dtype=np.float32))
+        for h in range(w.H):
+            assert slot_map[0, h].tolist() == st["slot_map"], st
+            assert released[0, h].tolist() == st["released"], st
+        assert rebuilt[0].tolist() == st["rebuilt"], st
+
+
+def test_no_release_when_cache_holds_everything_equals_full_attention():
+    """K - R - 1 >= N_max: nothing is ever released, slot k holds position k, output = Eq. 1 over all rows."""
+    for R in (0, 3):
+        w = small_workload(S=6, T=10, K=6 + 10 + R + 1, R=R, H=3)
+        orc, inp, _ = make_oracle(w)
+        outs, hs, pk, pv = _run(orc, inp, w, w.T)
+        Kall = [pk[0][:, :, i] for i in range(w.S)]
+        Vall = [pv[0][:, :, i] for i in range(w.S)]
+        for t, (out, slot_map, released, rebuilt, _) in enumerate(outs):
+            n = w.S + t
+            q, k, v = inp.step_qkv(n)
+            Kall.append(k[0]); Vall.append(v[0])
+            Km = np.stack(Kall, axis=2).astype(np.float64)      # [B,H,n+1,d]
+            Vm = np.stack(Vall, axis=2).astype(np.float64)
+            logits = np.einsum("bhd,bhnd->bhn", q[0].astype(np.float64), Km) / np.sqrt(w.d)
+            want = np.einsum("bhn,bhnd->bhd", scipy.special.softmax(logits, axis=-1), Vm)
+            np.testing.assert_allclose(out[0], want, rtol=1e-11, atol=1e-13)
+            expect_map = np.full(w.K, -1); expect_map[:n + 1] = np.arange(n + 1)
+            assert np.all(slot_map == expect_map[None, None, :])
+            assert np.all(released == -1) and np.all(rebuilt == -1)
+
+
+def test_static_scores_closed_form():
+    """With fixed scores, after step n: persistent rows = {n} + best (m-1) of the older tokens,
+    rebuilt rows = the next R in rank."""
+    w = small_workload(B=2, H=2, K=12, R=3, S=20, T=24)
+    rng = np.random.default_rng(7)
+    override = rng.choice(np.linspace(0.05, 0.95, 13).astype(np.float32), (w.B, w.N_max))   # many ties
+    orc, inp, _ = make_oracle(w)
+
+    def check(n, res):
+        out, slot_map, released, rebuilt, _ = res
+        for b in range(w.B):
+            older = np.arange(n)
+            order = older[np.lexsort((older, -override[b, :n].astype(np.float64)))]    # best first
+            persistent = set(order[:w.m - 1].tolist()) | {n}
+            want_rebuilt = order[w.m - 1:w.m - 1 + w.R].tolist()
+            assert rebuilt[b].tolist() == want_rebuilt
+            for h in range(w.H):
+                held = [int(p) for p in slot_map[b, h] if p >= 0]
+                assert len(held) == len(set(held)) == w.K - 1
+                assert set(held) == persistent | set(want_rebuilt)
+
+    _run(orc, inp, w, w.T, override=override, collect=check)
+
+
+def test_invariants_with_controller_scores():
+    w = small_workload(B=2, H=3, K=10, R=2, S=5, T=30)
+    orc, inp, _ = make_oracle(w)
+    state = {"prev_occ": min(w.S, w.m) + min(w.R, w.S - min(w.S, w.m))}
+
+    def check(n, res):
+        out, slot_map, released, rebuilt, own = res
+        for b in range(w.B):
+            # uniform policy: every head of a sequence holds the same map
+            for h in range(1, w.H):
+                assert np.array_equal(slot_map[b, h], slot_map[b, 0])
+                assert np.array_equal(released[b, h], released[b, 0])
+            held = [int(p) for p in slot_map[b, 0] if p >= 0]
+            assert len(held) == len(set(held)) <= w.K - 1          # one slot stays free
+            assert n in held                                        # current token survives its step
+            rb = [int(p) for p in rebuilt[b] if p >= 0]
+            rel = [int(p) for p in released[b, 0] if p >= 0]
+            assert set(rb) <= set(held)
+            occ_before_release = state["prev_occ"] + 1
+            assert occ_before_release == min(n + 1, w.K) or n < w.K
+            assert len(rel) == max(0, occ_before_release - w.m)
+            pool = set(range(n + 1)) - (set(held) - set(rb))
+            assert len(rb) == min(w.R, len(pool))
+            assert 0.0 < own[b] < 1.0 and orc.score[b, n] == np.float32(own[b])
+        state["prev_occ"] = len(held)
+        # attention probabilities of every row sum to one
+        for (valid, p) in orc.last_probs.values():
+            assert abs(p.sum() - 1.0) < 1e-12
+
+    _run(orc, inp, w, w.T, collect=check)
+
+
+def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fits():
+    """If the supplied K/V are the projections of the hidden states, a rebuilt row is identical to
+    the row that was released; while |pool| <= R every token is present, so the output is Eq. 1
+    over all tokens."""
+    w = small_workload(B=1, H=2, K=12, R=5, S=4, T=7, dtype="f32")     # m = 6; pool <= 5 up to n = 10
+    orc, inp, wts = make_oracle(w)
+    hs = inp.hidden_store()
+    W = wts["w_kv"][0].astype(np.float64)
+    kv_all = (hs[0].astype(np.float64) @ W.T).astype(np.float32).astype(np.float64)    # [B,N,2Hd]
+    Hd = w.H * w.d
+    k_all = kv_all[:, :, :Hd].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)    # [B,H,N,d]
+    v_all = kv_all[:, :, Hd:].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)
+    orc.init_cache(k_all[None, :, :, :w.S], v_all[None, :, :, :w.S], hs, hs[0][:, :w.S], w.S)
+    for n in range(w.S, w.S + w.T):
+        q, _, _ = inp.step_qkv(n)
+        out, slot_map, released, rebuilt, _ = orc.decode_step(
+            q, k_all[None, :, :, n], v_all[None, :, :, n], hs, hs[0][:, n])
+        logits = np.einsum("bhd,bhnd->bhn", q[0].astype(np.float64), k_all[:, :, :n + 1]) / np.sqrt(w.d)
+        want = np.einsum("bhn,bhnd->bhd", scipy.special.softmax(logits, axis=-1), v_all[:, :, :n + 1])
+        np.testing.assert_allclose(out[0], want, rtol=1e-10, atol=1e-12)
+        for h in range(w.H):
+            for s in range(w.K):
+                p = slot_map[0, h, s]
+                if p >= 0:
+                    assert np.array_equal(orc.Kc[0, 0, h, s], k_all[0, h, p])
+                    assert np.array_equal(orc.Vc[0, 0, h, s], v_all[0, h, p])
+    assert (rebuilt >= 0).sum() == 5        # the last step did rebuild R tokens
+
+
+def test_projection_matches_triple_loop_and_torch_matmul():
+    w = small_workload(B=1, H=2, d=4, D=6, dtype="bf16")
+    orc, inp, wts = make_oracle(w)
+    x = inp.hidden_store()[0, 0, :3]
+    got = orc._project(0, x)
+    W = wts["w_kv"][0]
+    naive = np.zeros((3, 2 * w.H * w.d))
+    for i in range(3):
+        for j in range(2 * w.H * w.d):
+            acc = 0.0
+            for t in range(w.D):
+                acc += float(x[i, t]) * float(W[j, t])
+            naive[i, j] = acc
+    lib = (torch.from_numpy(x.astype(np.float64)) @ torch.from_numpy(W.astype(np.float64)).T).numpy()
+    np.testing.assert_allclose(naive, lib, rtol=1e-13, atol=1e-15)
+    assert np.array_equal(got, O.round_to_storage(lib, "bf16"))
+    # every result is a bf16 value
+    assert np.array_equal(got, torch.from_numpy(got).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+def test_oracle_rejects_bad_budget_and_overrun():
+    w = small_workload(K=4, R=3)
+    with pytest.raises(ValueError):
+        make_oracle(w)
+    w = small_workload(S=3, T=1)
+    orc, inp, _ = make_oracle(w)
+    _run(orc, inp, w, 1)
+    q, k, v = inp.step_qkv(w.S)
+    with pytest.raises(RuntimeError):
+        orc.decode_step(q, k, v, inp.hidden_store(), inp.hidden_store()[0][:, 0])
