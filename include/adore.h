@@ -1,0 +1,205 @@
+/*
+ * adore.h - C ABI of the ADORE decode-step library for MI355X (gfx950).
+ *
+ * One context holds the state of one decode job of B sequences: per layer a
+ * fixed-size, slot-addressed K/V cache of K rows per (sequence, head), the
+ * per-token keep probabilities sigma_i, and the controller's GRU state.
+ * One decode step = the four stages of the paper's method (arXiv 2407.02328):
+ *
+ *   attend    single-query attention over the occupied slots, the current
+ *             token's k, v included                       (Sec. 2.1, Eq. 1 and
+ *                                                          the "target" equation)
+ *   schedule  controller score of the arriving token       (Sec. 2.2, Eq. 2;
+ *             App. "Implementation Details", controller module),
+ *             release of the lowest-scored rows            (Sec. 2.2, third
+ *                                                          design strategy),
+ *             choice of the top-R released tokens          (Sec. 2.3)
+ *   rebuild   K/V of the chosen tokens re-projected from their hidden states
+ *             with W_k / W_v and written into the freed slots (Sec. 2.3)
+ *
+ * Symbols: L layers, B sequences, H heads, d head_dim, D hidden size, K cache
+ * slots per (sequence, head), R rebuild budget per step and sequence,
+ * m = K - R - 1 persistent rows, d' controller hidden size, n = 0-based
+ * position of the current token, S prompt length.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The two
+ *     structs below are read on the host.
+ *   - All arrays are contiguous, row-major, last index fastest, bases 16-byte
+ *     aligned.  "storage type" is adore_config.dtype (bf16 or fp32).
+ *   - The caller owns all memory.  The library allocates no device memory; the
+ *     workspace passed to adore_create holds all of its state.
+ *   - attend / schedule / rebuild / decode_step only enqueue work on the
+ *     context's stream and never synchronise it: outputs are valid once the
+ *     caller has synchronised that stream.  Input buffers must stay unchanged
+ *     until then.
+ *   - The return value is the only error channel.  Arguments are validated on
+ *     the host before anything is enqueued: a call that fails has no effect.
+ *   - A context is bound to one stream and is not thread-safe.  Contexts are
+ *     independent of each other.
+ *   - Ties between equal sigma are broken in favour of the lower position, so
+ *     every selection has exactly one result.  A NaN sigma is treated as 0.
+ */
+#ifndef ADORE_H
+#define ADORE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADORE_ABI_VERSION 1
+
+typedef struct adore_ctx adore_ctx; /* opaque */
+
+enum { ADORE_F32 = 0, ADORE_BF16 = 1 };
+
+enum {
+  ADORE_OK = 0,
+  ADORE_E_INVALID = -1,     /* null pointer, bad shape or value */
+  ADORE_E_STATE = -2,       /* call out of order, or step past max_positions */
+  ADORE_E_UNSUPPORTED = -3, /* valid in principle, no kernel for it */
+  ADORE_E_WORKSPACE = -4,   /* workspace too small or misaligned */
+  ADORE_E_HIP = -5          /* a HIP runtime call failed */
+};
+
+typedef struct {
+  int32_t layers, batch, heads, head_dim, hidden;     /* L, B, H, d, D */
+  int32_t cache_slots, rebuild_budget, max_positions; /* K, R (0 <= R <= K-2), N_max */
+  int32_t ctrl_hidden;                                /* d' */
+  int32_t dtype;                                      /* ADORE_F32 | ADORE_BF16 */
+  float pos_scale;                                    /* position feature of token i = (float)i * pos_scale */
+} adore_config;
+
+/* Device pointers, caller-owned, read-only, must outlive the context. */
+typedef struct {
+  const void *w_kv;      /* [L][2*H*d][D] storage type; rows 0..H*d-1 = W_k, the rest = W_v;
+                            within each half, rows h*d..h*d+d-1 belong to head h */
+  const void *gru_w_ih;  /* [3*d'][D]  storage type, gate order r, z, n */
+  const void *gru_w_hh;  /* [3*d'][d'] storage type, gate order r, z, n */
+  const float *gru_b_ih; /* [3*d'] */
+  const float *gru_b_hh; /* [3*d'] */
+  const float *pos_w;    /* [d']      position layer, 1 -> d' */
+  const float *pos_b;    /* [d'] */
+  const float *mlp_w1;   /* [d'][d']  interaction layer (tanh) */
+  const float *mlp_b1;   /* [d'] */
+  const float *out_w;    /* [d']      output layer (sigmoid) */
+  const float *out_b;    /* [1] */
+} adore_weights;
+
+/* Bytes of device workspace adore_create needs for this configuration (0 if the
+ * configuration is invalid).  HOST call, no GPU work. */
+size_t adore_workspace_bytes(const adore_config *cfg);
+
+/* Creates a context over `workspace` (device memory, 256-byte aligned, at least
+ * adore_workspace_bytes(cfg) bytes, owned by the caller and kept alive until
+ * adore_destroy).  `hip_stream` is a hipStream_t (NULL = the default stream).
+ * cfg and weights are HOST structs and are copied.  The cache starts empty;
+ * call adore_init_cache before the first step.
+ * Errors: E_INVALID (null, R > K-2, sizes <= 0), E_UNSUPPORTED (head_dim not in
+ * {64,128}, K > 1024 ... see adore_strerror), E_WORKSPACE. */
+int adore_create(const adore_config *cfg, const adore_weights *weights, void *workspace,
+                 size_t workspace_bytes, void *hip_stream, adore_ctx **out);
+
+/* Frees the host-side context.  Does not touch device memory. */
+int adore_destroy(adore_ctx *ctx);
+
+/* Loads a prompt of S >= 1 tokens (the paper's user input t_1..t_s, Sec. 2.1) by
+ * applying the step rules once: the controller scores tokens 0..S-1 in order
+ * (Eq. 2); the residents are token S-1 plus the best min(S,m)-1 older tokens,
+ * placed from slot 0 in ascending position with the given K/V; the best
+ * min(R, rest) of the remaining tokens are rebuilt from hidden_store into the
+ * next slots by rank.
+ *   prompt_k, prompt_v  [L][B][H][S][d]  storage type
+ *   hidden_store        [L][B][N_max][D] storage type, rows < S valid
+ *   ctrl_input          [B][S][D]        storage type (token embeddings x_i)
+ *   score_override      [B][S] fp32 or NULL: if given, replaces the controller's sigma
+ * Enqueues work; does not synchronise.  May be called again to restart.
+ * Errors: E_INVALID (null, S < 1, S >= N_max). */
+int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
+                     const void *hidden_store, const void *ctrl_input,
+                     const float *score_override, int32_t S);
+
+/* Stage 1 for one layer (Sec. 2.1): writes k_new, v_new into the slot reserved
+ * for the current token and computes
+ *   out[b][h][:] = sum_k softmax_k(q . Kc[k] / sqrt(d)) Vc[k]  over occupied slots.
+ *   q, k_new, v_new  [B][H][d] storage type;  out [B][H][d] fp32.
+ * Each layer must be attended exactly once per step, before adore_schedule.
+ * Errors: E_INVALID, E_STATE (no init, layer already attended, step past N_max). */
+int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new,
+                 const void *v_new, float *out);
+
+/* Stages 2 and 3, once per step for all layers (uniform policy, Sec. 2.2):
+ * sigma_n from the controller (Eq. 2) or from score_override; release of the
+ * x = max(0, occupied - m) lowest-ranked rows of every (b,h), never the current
+ * token; choice of the best min(R, pool) released tokens per sequence
+ * (Sec. 2.3); assignment of rebuilt rank rho to the rho-th lowest free slot.
+ *   x_n             [B][D] storage type (embedding of the current token)
+ *   score_override  [B] fp32 or NULL
+ *   slot_map        [B][H][K] i32 or NULL: position held by each slot after the
+ *                   step, -1 = free
+ *   released_pos    [B][H][R+1] i32 or NULL: released positions in ascending slot
+ *                   order, -1 padded
+ *   rebuilt_pos     [B][max(R,1)] i32 or NULL: chosen positions best first, -1 padded
+ * Errors: E_INVALID, E_STATE (a layer not yet attended, schedule already done). */
+int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override,
+                   int32_t *slot_map, int32_t *released_pos, int32_t *rebuilt_pos);
+
+/* Stage 4 for one layer (Sec. 2.3): for each chosen token, one rounding to the
+ * storage type of W_kv[layer] . hidden_store_layer[b][pos] (fp32 accumulation),
+ * head slices scattered into the slots assigned by adore_schedule.
+ *   hidden_store_layer  [B][N_max][D] storage type; rows of all positions <= n valid
+ * Each layer must be rebuilt exactly once per step, after adore_schedule; the
+ * step completes (n advances) when the last layer is rebuilt.
+ * Errors: E_INVALID, E_STATE. */
+int adore_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer);
+
+/* The whole step for L == 1: attend(0); schedule; rebuild(0).
+ *   q, k_new, v_new [B][H][d]; hidden_store [B][N_max][D]; x_n [B][D];
+ *   score_override [B] or NULL; out [B][H][d] fp32; slot_map [B][H][K] or NULL.
+ * Errors: as the three calls; E_INVALID if L != 1. */
+int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                      const void *hidden_store, const void *x_n, const float *score_override,
+                      float *out, int32_t *slot_map);
+
+/* Snapshot / restore between steps.  Any pointer may be NULL (skipped).
+ *   slot_pos [B][H][K] i32; scores [B][N_max] fp32; z [B][d'] fp32;
+ *   cache_k, cache_v [L][B][H][K][d] storage type; step: HOST pointer, the
+ *   position n of the next token.
+ * get enqueues device-to-device copies (no synchronisation; *step is written at
+ * once).  set copies, then SYNCHRONISES the stream to recount the occupied
+ * slots; slot_pos must be given and must leave at least one free slot per (b,h).
+ * Errors: E_INVALID, E_STATE (in the middle of a step). */
+int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z,
+                    void *cache_k, void *cache_v, int32_t *step);
+int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores,
+                    const float *z, const void *cache_k, const void *cache_v, int32_t step);
+
+/* Per-kernel timing with HIP events on the context's stream (for benchmarks).
+ * While enabled, every kernel launch is bracketed by two events.
+ * adore_read_timing SYNCHRONISES the stream, adds up the elapsed milliseconds
+ * per kernel since the last read into ms[ADORE_N_KERNELS] and the launch counts
+ * into launches[ADORE_N_KERNELS] (both HOST arrays), and clears the record. */
+enum {
+  ADORE_KERNEL_ATTEND = 0,      /* insert + attention partials */
+  ADORE_KERNEL_ATTEND_COMBINE,  /* merge of the split partials */
+  ADORE_KERNEL_CTRL_INPUT,      /* GRU input projection */
+  ADORE_KERNEL_CTRL_CELL,       /* GRU cell + MLP + sigmoid */
+  ADORE_KERNEL_RELEASE,         /* per-(b,h) release select */
+  ADORE_KERNEL_REBUILD_SELECT,  /* per-sequence top-R select + slot assignment */
+  ADORE_KERNEL_REBUILD_GEMM,    /* re-projection + scatter */
+  ADORE_N_KERNELS
+};
+int adore_set_timing(adore_ctx *ctx, int32_t enable);
+int adore_read_timing(adore_ctx *ctx, float *ms, int32_t *launches);
+const char *adore_kernel_name(int32_t kernel);
+
+const char *adore_strerror(int code);
+int adore_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADORE_H */

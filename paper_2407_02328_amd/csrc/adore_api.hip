@@ -1,0 +1,399 @@
+// Host side of the C ABI declared in include/adore.h: argument checks, the
+// per-step state machine, the workspace layout and the launch order.
+//
+// Nothing here waits for the GPU inside a step.  The numbers of occupied slots
+// (o), released slots (x) and rebuilt tokens (r) of a step depend only on
+// (n, S, K, R), so the host knows every launch shape without reading results
+// back:  o = occupied_before + 1,  x = max(0, o - m),  r = min(R, n + 1 - min(o, m)).
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "adore_internal.h"
+
+using namespace adore;
+
+namespace adore {
+
+ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel) : ctx_(ctx), stop_(nullptr) {
+  if (!ctx->timing) return;
+  hipEvent_t ev[2];
+  for (int i = 0; i < 2; ++i) {
+    if (!ctx->event_pool.empty()) {
+      ev[i] = ctx->event_pool.back();
+      ctx->event_pool.pop_back();
+    } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+      ctx_ = nullptr;
+      return;
+    }
+  }
+  hipEventRecord(ev[0], ctx->stream);
+  stop_ = ev[1];
+  ctx->timed.push_back(TimedLaunch{kernel, ev[0], ev[1]});
+}
+
+ScopedTimer::~ScopedTimer() {
+  if (ctx_ && stop_) hipEventRecord(stop_, ctx_->stream);
+}
+
+}  // namespace adore
+
+namespace {
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Layout {
+  size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
+      att_part, gi, total;
+};
+
+bool config_ok(const adore_config *c) {
+  return c && c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
+         c->cache_slots >= 2 && c->rebuild_budget >= 0 && c->rebuild_budget <= c->cache_slots - 2 &&
+         c->max_positions >= 2 && c->ctrl_hidden > 0 && (c->dtype == ADORE_F32 || c->dtype == ADORE_BF16) &&
+         std::isfinite(c->pos_scale);
+}
+
+bool config_supported(const adore_config *c) {
+  return (c->head_dim == 64 || c->head_dim == 128) && c->cache_slots <= kMaxSlots && c->hidden % 8 == 0 &&
+         c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024;
+}
+
+Layout make_layout(const adore_config &c) {
+  const size_t es = elem_size(c);
+  const size_t BH = size_t(c.batch) * c.heads;
+  const size_t R1 = size_t(c.rebuild_budget) + 1;
+  Layout l;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes);
+    return at;
+  };
+  l.cache_k = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
+  l.cache_v = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
+  l.slot_pos = take(BH * c.cache_slots * 4);
+  l.score = take(size_t(c.batch) * c.max_positions * 4);
+  l.z = take(size_t(c.batch) * c.ctrl_hidden * 4);
+  l.insert_slot = take(BH * 4);
+  l.free_list = take(BH * R1 * 4);
+  l.released_pos = take(BH * R1 * 4);
+  l.rebuilt_pos = take(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4);
+  l.init_res = take(size_t(c.batch) * c.cache_slots * 4);
+  l.att_part = take(BH * kMaxSplits * (size_t(c.head_dim) + 2) * 4);
+  l.gi = take(size_t(c.batch) * kPromptChunk * 3 * c.ctrl_hidden * 4);
+  l.total = off;
+  return l;
+}
+
+// Splits per (b,h) row so that the attention launch has enough workgroups to fill
+// 256 compute units a few times over, without cutting a row below 64 slots.
+void choose_split(adore_ctx *ctx) {
+  const adore_config &c = ctx->cfg;
+  const int rows = c.batch * c.heads;
+  int nsplit = 1;
+  while (nsplit < kMaxSplits && rows * nsplit < 2048 && c.cache_slots / (nsplit * 2) >= 64) nsplit *= 2;
+  ctx->nsplit = nsplit;
+  ctx->chunk = (c.cache_slots + nsplit - 1) / nsplit;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? ADORE_OK : ADORE_E_HIP; }
+
+#define ADORE_TRY(expr)              \
+  do {                               \
+    const hipError_t e_ = (expr);    \
+    if (e_ != hipSuccess) return ADORE_E_HIP; \
+  } while (0)
+
+void reset_step(adore_ctx *ctx) {
+  std::fill(ctx->attended.begin(), ctx->attended.end(), 0);
+  std::fill(ctx->rebuilt.begin(), ctx->rebuilt.end(), 0);
+  ctx->n_attended = ctx->n_rebuilt = 0;
+  ctx->scheduled = false;
+  ctx->r_step = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t adore_workspace_bytes(const adore_config *cfg) {
+  if (!config_ok(cfg)) return 0;
+  return make_layout(*cfg).total;
+}
+
+int adore_create(const adore_config *cfg, const adore_weights *weights, void *workspace,
+                 size_t workspace_bytes, void *hip_stream, adore_ctx **out) {
+  if (!cfg || !weights || !workspace || !out) return ADORE_E_INVALID;
+  if (!config_ok(cfg)) return ADORE_E_INVALID;
+  if (!weights->w_kv || !weights->gru_w_ih || !weights->gru_w_hh || !weights->gru_b_ih || !weights->gru_b_hh ||
+      !weights->pos_w || !weights->pos_b || !weights->mlp_w1 || !weights->mlp_b1 || !weights->out_w ||
+      !weights->out_b)
+    return ADORE_E_INVALID;
+  if (!config_supported(cfg)) return ADORE_E_UNSUPPORTED;
+  const Layout l = make_layout(*cfg);
+  if (workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return ADORE_E_WORKSPACE;
+  adore_ctx *ctx = new (std::nothrow) adore_ctx();
+  if (!ctx) return ADORE_E_INVALID;
+  ctx->cfg = *cfg;
+  ctx->w = *weights;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  char *base = static_cast<char *>(workspace);
+  ctx->cache_k = base + l.cache_k;
+  ctx->cache_v = base + l.cache_v;
+  ctx->slot_pos = reinterpret_cast<int32_t *>(base + l.slot_pos);
+  ctx->score = reinterpret_cast<float *>(base + l.score);
+  ctx->z = reinterpret_cast<float *>(base + l.z);
+  ctx->insert_slot = reinterpret_cast<int32_t *>(base + l.insert_slot);
+  ctx->free_list = reinterpret_cast<int32_t *>(base + l.free_list);
+  ctx->released_pos = reinterpret_cast<int32_t *>(base + l.released_pos);
+  ctx->rebuilt_pos = reinterpret_cast<int32_t *>(base + l.rebuilt_pos);
+  ctx->init_res = reinterpret_cast<int32_t *>(base + l.init_res);
+  ctx->att_part = reinterpret_cast<float *>(base + l.att_part);
+  ctx->gi = reinterpret_cast<float *>(base + l.gi);
+  ctx->inited = false;
+  ctx->n = 0;
+  ctx->occ = 0;
+  ctx->attended.assign(cfg->layers, 0);
+  ctx->rebuilt.assign(cfg->layers, 0);
+  ctx->timing = false;
+  reset_step(ctx);
+  choose_split(ctx);
+  *out = ctx;
+  return ADORE_OK;
+}
+
+int adore_destroy(adore_ctx *ctx) {
+  if (!ctx) return ADORE_E_INVALID;
+  for (auto &t : ctx->timed) {
+    hipEventDestroy(t.start);
+    hipEventDestroy(t.stop);
+  }
+  for (auto &e : ctx->event_pool) hipEventDestroy(e);
+  delete ctx;
+  return ADORE_OK;
+}
+
+int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, const void *hidden_store,
+                     const void *ctrl_input, const float *score_override, int32_t S) {
+  if (!ctx || !prompt_k || !prompt_v || !hidden_store || !ctrl_input) return ADORE_E_INVALID;
+  const adore_config &c = ctx->cfg;
+  if (S < 1 || S >= c.max_positions) return ADORE_E_INVALID;
+  const size_t es = elem_size(c);
+  const int m = c.cache_slots - c.rebuild_budget - 1;
+  const int keep = S < m ? S : m;
+  const int pool = S - keep;
+  const int r0 = pool < c.rebuild_budget ? pool : c.rebuild_budget;
+
+  // controller over the prompt: z_{-1} = 0, tokens in order, in chunks
+  ADORE_TRY(launch_fill_i32(ctx, reinterpret_cast<int32_t *>(ctx->z), 0, size_t(c.batch) * c.ctrl_hidden));
+  for (int i0 = 0; i0 < S; i0 += kPromptChunk) {
+    const int len = (S - i0 < kPromptChunk) ? S - i0 : kPromptChunk;
+    const char *x = static_cast<const char *>(ctrl_input) + size_t(i0) * c.hidden * es;
+    ADORE_TRY(launch_ctrl_input(ctx, x, c.batch * len, len, S));
+    ADORE_TRY(launch_ctrl_cell(ctx, len, i0, score_override ? score_override + i0 : nullptr, S));
+  }
+  ADORE_TRY(launch_init_select(ctx, S, keep, r0));
+  ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
+  const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
+  for (int l = 0; l < c.layers; ++l) {
+    ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, r0));
+  }
+  ctx->n = S;
+  ctx->occ = keep + r0;
+  ctx->inited = true;
+  reset_step(ctx);
+  return ADORE_OK;
+}
+
+int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                 float *out) {
+  if (!ctx || !q || !k_new || !v_new || !out) return ADORE_E_INVALID;
+  if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
+  if (!ctx->inited || ctx->scheduled || ctx->attended[layer] || ctx->n >= ctx->cfg.max_positions)
+    return ADORE_E_STATE;
+  ADORE_TRY(launch_attend(ctx, layer, q, k_new, v_new, out));
+  ctx->attended[layer] = 1;
+  ctx->n_attended++;
+  return ADORE_OK;
+}
+
+int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
+                   int32_t *released_pos, int32_t *rebuilt_pos) {
+  if (!ctx || !x_n) return ADORE_E_INVALID;
+  const adore_config &c = ctx->cfg;
+  if (!ctx->inited || ctx->scheduled || ctx->n_attended != c.layers) return ADORE_E_STATE;
+  const int m = c.cache_slots - c.rebuild_budget - 1;
+  const int o = ctx->occ + 1;
+  const int x = o > m ? o - m : 0;
+  const int kept = o - x;
+  const int pool = ctx->n + 1 - kept;
+  const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
+
+  ADORE_TRY(launch_ctrl_input(ctx, x_n, c.batch, 1, 1));
+  ADORE_TRY(launch_ctrl_cell(ctx, 1, ctx->n, score_override, 1));
+  ADORE_TRY(launch_release(ctx, x));
+  ADORE_TRY(launch_rebuild_select(ctx, r));
+  const size_t BH = size_t(c.batch) * c.heads;
+  if (slot_map)
+    ADORE_TRY(hipMemcpyAsync(slot_map, ctx->slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  if (released_pos)
+    ADORE_TRY(hipMemcpyAsync(released_pos, ctx->released_pos, BH * (c.rebuild_budget + 1) * 4,
+                             hipMemcpyDeviceToDevice, ctx->stream));
+  if (rebuilt_pos)
+    ADORE_TRY(hipMemcpyAsync(rebuilt_pos, ctx->rebuilt_pos,
+                             size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4,
+                             hipMemcpyDeviceToDevice, ctx->stream));
+  ctx->scheduled = true;
+  ctx->r_step = r;
+  ctx->occ = kept + r;
+  return ADORE_OK;
+}
+
+int adore_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
+  if (!ctx || !hidden_store_layer) return ADORE_E_INVALID;
+  if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
+  if (!ctx->inited || !ctx->scheduled || ctx->rebuilt[layer]) return ADORE_E_STATE;
+  ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, ctx->r_step));
+  ctx->rebuilt[layer] = 1;
+  if (++ctx->n_rebuilt == ctx->cfg.layers) {
+    ctx->n++;
+    reset_step(ctx);
+  }
+  return ADORE_OK;
+}
+
+int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                      const void *hidden_store, const void *x_n, const float *score_override, float *out,
+                      int32_t *slot_map) {
+  if (!ctx || !q || !k_new || !v_new || !hidden_store || !x_n || !out) return ADORE_E_INVALID;
+  if (ctx->cfg.layers != 1) return ADORE_E_INVALID;
+  if (!ctx->inited || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
+    return ADORE_E_STATE;
+  int rc = adore_attend(ctx, 0, q, k_new, v_new, out);
+  if (rc != ADORE_OK) return rc;
+  rc = adore_schedule(ctx, x_n, score_override, slot_map, nullptr, nullptr);
+  if (rc != ADORE_OK) return rc;
+  return adore_rebuild(ctx, 0, hidden_store);
+}
+
+int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, void *cache_k, void *cache_v,
+                    int32_t *step) {
+  if (!ctx) return ADORE_E_INVALID;
+  if (!ctx->inited || ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
+  const adore_config &c = ctx->cfg;
+  const size_t BH = size_t(c.batch) * c.heads;
+  const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
+  if (step) *step = ctx->n;
+  if (slot_pos)
+    ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  if (scores)
+    ADORE_TRY(hipMemcpyAsync(scores, ctx->score, size_t(c.batch) * c.max_positions * 4, hipMemcpyDeviceToDevice,
+                             ctx->stream));
+  if (z)
+    ADORE_TRY(hipMemcpyAsync(z, ctx->z, size_t(c.batch) * c.ctrl_hidden * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  if (cache_k) ADORE_TRY(hipMemcpyAsync(cache_k, ctx->cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+  if (cache_v) ADORE_TRY(hipMemcpyAsync(cache_v, ctx->cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+  return ADORE_OK;
+}
+
+int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores, const float *z,
+                    const void *cache_k, const void *cache_v, int32_t step) {
+  if (!ctx || !slot_pos) return ADORE_E_INVALID;
+  const adore_config &c = ctx->cfg;
+  if (step < 1 || step >= c.max_positions) return ADORE_E_INVALID;
+  if (ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
+  const size_t BH = size_t(c.batch) * c.heads;
+  const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
+  // count the occupied slots and find the reserved slot of every row on the host
+  std::vector<int32_t> host(BH * c.cache_slots);
+  ADORE_TRY(hipMemcpyAsync(host.data(), slot_pos, host.size() * 4, hipMemcpyDeviceToHost, ctx->stream));
+  ADORE_TRY(hipStreamSynchronize(ctx->stream));
+  std::vector<int32_t> ins(BH);
+  int occ = -1;
+  for (size_t row = 0; row < BH; ++row) {
+    int cnt = 0, first_free = -1;
+    for (int k = 0; k < c.cache_slots; ++k) {
+      const int32_t p = host[row * c.cache_slots + k];
+      if (p >= step) return ADORE_E_INVALID;
+      if (p >= 0) cnt++;
+      else if (first_free < 0) first_free = k;
+    }
+    if (first_free < 0) return ADORE_E_INVALID;
+    if (occ < 0) occ = cnt;
+    if (cnt != occ) return ADORE_E_INVALID;   // uniform policy: same occupancy everywhere
+    ins[row] = first_free;
+  }
+  ADORE_TRY(hipMemcpyAsync(ctx->slot_pos, slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  ADORE_TRY(hipMemcpyAsync(ctx->insert_slot, ins.data(), BH * 4, hipMemcpyHostToDevice, ctx->stream));
+  if (scores)
+    ADORE_TRY(hipMemcpyAsync(ctx->score, scores, size_t(c.batch) * c.max_positions * 4, hipMemcpyDeviceToDevice,
+                             ctx->stream));
+  if (z)
+    ADORE_TRY(hipMemcpyAsync(ctx->z, z, size_t(c.batch) * c.ctrl_hidden * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  if (cache_k) ADORE_TRY(hipMemcpyAsync(ctx->cache_k, cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+  if (cache_v) ADORE_TRY(hipMemcpyAsync(ctx->cache_v, cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+  ADORE_TRY(hipStreamSynchronize(ctx->stream));   // `ins` lives on this stack frame
+  ctx->n = step;
+  ctx->occ = occ;
+  ctx->inited = true;
+  reset_step(ctx);
+  return ADORE_OK;
+}
+
+int adore_set_timing(adore_ctx *ctx, int32_t enable) {
+  if (!ctx) return ADORE_E_INVALID;
+  ctx->timing = enable != 0;
+  return ADORE_OK;
+}
+
+int adore_read_timing(adore_ctx *ctx, float *ms, int32_t *launches) {
+  if (!ctx || !ms || !launches) return ADORE_E_INVALID;
+  ADORE_TRY(hipStreamSynchronize(ctx->stream));
+  for (int i = 0; i < ADORE_N_KERNELS; ++i) {
+    ms[i] = 0.f;
+    launches[i] = 0;
+  }
+  for (auto &t : ctx->timed) {
+    float e = 0.f;
+    if (hipEventElapsedTime(&e, t.start, t.stop) == hipSuccess) {
+      ms[t.kernel] += e;
+      launches[t.kernel]++;
+    }
+    ctx->event_pool.push_back(t.start);
+    ctx->event_pool.push_back(t.stop);
+  }
+  ctx->timed.clear();
+  return ADORE_OK;
+}
+
+const char *adore_kernel_name(int32_t kernel) {
+  switch (kernel) {
+    case ADORE_KERNEL_ATTEND: return "attend";
+    case ADORE_KERNEL_ATTEND_COMBINE: return "attend_combine";
+    case ADORE_KERNEL_CTRL_INPUT: return "ctrl_input";
+    case ADORE_KERNEL_CTRL_CELL: return "ctrl_cell";
+    case ADORE_KERNEL_RELEASE: return "release";
+    case ADORE_KERNEL_REBUILD_SELECT: return "rebuild_select";
+    case ADORE_KERNEL_REBUILD_GEMM: return "rebuild_gemm";
+    default: return "?";
+  }
+}
+
+const char *adore_strerror(int code) {
+  switch (code) {
+    case ADORE_OK: return "ok";
+    case ADORE_E_INVALID: return "invalid argument (null pointer, bad shape or value)";
+    case ADORE_E_STATE: return "call out of order for this step, or step past max_positions";
+    case ADORE_E_UNSUPPORTED:
+      return "unsupported configuration (need head_dim in {64,128}, cache_slots <= 1024, hidden % 8 == 0, "
+             "max_positions <= 262144, ctrl_hidden <= 1024)";
+    case ADORE_E_WORKSPACE: return "workspace too small or not 256-byte aligned";
+    case ADORE_E_HIP: return "HIP runtime call failed";
+    default: return "unknown error";
+  }
+}
+
+int adore_abi_version(void) { return ADORE_ABI_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+// Internal declarations shared by the host API and the kernel launchers.
+// Not part of the public ABI (that is include/adore.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "adore.h"
+
+namespace adore {
+
+// Storage element tags.  bf16 values travel as raw 16-bit patterns.
+struct bf16_t {
+  uint16_t bits;
+};
+
+constexpr int kMaxSplits = 16;        // attention partials per (b,h) row
+constexpr int kMaxSlots = 1024;       // K handled by the one-slot-per-thread release kernel
+constexpr int kMaxPositions = 1 << 18; // residency bitmap of a sequence lives in LDS
+constexpr int kPromptChunk = 512;     // tokens per GRU input-projection launch at init
+
+struct TimedLaunch {
+  int kernel;
+  hipEvent_t start, stop;
+};
+
+}  // namespace adore
+
+struct adore_ctx {
+  adore_config cfg;
+  adore_weights w;
+  hipStream_t stream;
+
+  // --- workspace sections (device) ---
+  char *cache_k, *cache_v;   // [L][B][H][K][d] storage type
+  int32_t *slot_pos;         // [B][H][K]   position per slot, -1 = free
+  float *score;              // [B][N_max]  sigma_i
+  float *z;                  // [B][d']     GRU state
+  int32_t *insert_slot;      // [B][H]      slot reserved for the next token
+  int32_t *free_list;        // [B][H][R+1] ascending free slots after the release
+  int32_t *released_pos;     // [B][H][R+1]
+  int32_t *rebuilt_pos;      // [B][max(R,1)]
+  int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
+  float *att_part;           // [B*H][kMaxSplits][d+2]
+  float *gi;                 // [max(B, B*kPromptChunk)][3d'] GRU input pre-activations
+
+  // --- host-side step state ---
+  bool inited;
+  int32_t n;                 // position of the current / next token
+  int32_t occ;               // occupied slots per (b,h) between steps
+  int32_t r_step;            // rebuilt tokens chosen by this step's schedule
+  bool scheduled;
+  std::vector<uint8_t> attended, rebuilt;
+  int32_t n_attended, n_rebuilt;
+
+  // --- launch shape ---
+  int32_t nsplit, chunk;     // attention: splits per row and slots per split
+
+  // --- timing ---
+  bool timing;
+  std::vector<adore::TimedLaunch> timed;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace adore {
+
+inline size_t elem_size(const adore_config &c) { return c.dtype == ADORE_BF16 ? 2 : 4; }
+
+// Brackets one kernel launch with events when timing is on.
+class ScopedTimer {
+ public:
+  ScopedTimer(adore_ctx *ctx, int kernel);
+  ~ScopedTimer();
+
+ private:
+  adore_ctx *ctx_;
+  hipEvent_t stop_;
+};
+
+// Launchers.  Each validates nothing (the API did) and returns the launch status.
+hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
+                         const void *v_new, float *out);
+hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows);
+hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *score_override,
+                            int override_stride);
+hipError_t launch_release(adore_ctx *ctx, int x);
+hipError_t launch_rebuild_select(adore_ctx *ctx, int r);
+hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int r);
+hipError_t launch_init_select(adore_ctx *ctx, int S, int keep, int r0);
+hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
+                            int keep);
+hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t count);
+
+}  // namespace adore

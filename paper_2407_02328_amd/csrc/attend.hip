@@ -1,0 +1,205 @@
+// Stage 1: insert the current token's k, v and single-query attention over the
+// occupied slots of every (sequence, head)  (paper Sec. 2.1: Eq. 1 restricted to
+// the retained rows plus the current token).
+//
+// Memory-bound: every step streams K*d*2 elements of K and V per row once.  A
+// row of d elements is 16-byte vectors spread over LPR consecutive lanes, so a
+// wave reads 64/LPR whole cache rows (1 KB, contiguous) per load instruction.
+// The slots of one (b,h) are cut into `nsplit` chunks, one workgroup each, so
+// that small batches still fill the chip; partial (max, sum, acc) triples are
+// merged by a second small kernel.  Softmax runs online in fp32, base 2.
+#include "device_utils.h"
+
+namespace adore {
+
+namespace {
+
+struct AttendArgs {
+  const void *q, *k_new, *v_new;   // [B*H][d]
+  void *Kc, *Vc;                   // [B*H][K][d] of this layer
+  int32_t *slot_pos;               // [B*H][K]
+  const int32_t *insert_slot;      // [B*H]
+  float *part;                     // [B*H][nsplit][d+2]
+  float *out;                      // [B*H][d]
+  int K, chunk, nsplit, n;
+  float scale_log2;                // log2(e) / sqrt(d)
+};
+
+template <typename T, int DH, int U>
+__global__ __launch_bounds__(256) void attend_kernel(const AttendArgs a) {
+  constexpr int EPL = Vec16<T>::EPL;    // elements per lane
+  constexpr int LPR = DH / EPL;         // lanes per cache row
+  constexpr int RPW = 64 / LPR;         // rows per wave and load
+  constexpr int G = 4 * RPW;            // lane groups (rows in flight) per workgroup
+  static_assert(LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must be a power-of-two lane group");
+
+  const int bh = blockIdx.x / a.nsplit;
+  const int sp = blockIdx.x - bh * a.nsplit;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int grp = (tid >> 6) * RPW + lane / LPR;
+  const int lig = lane % LPR;
+
+  const T *Kb = static_cast<const T *>(a.Kc) + size_t(bh) * a.K * DH;
+  const T *Vb = static_cast<const T *>(a.Vc) + size_t(bh) * a.K * DH;
+  const int32_t *sp_row = a.slot_pos + size_t(bh) * a.K;
+  const int s_ins = a.insert_slot[bh];
+
+  float qf[EPL];
+  Vec16<T>::load(static_cast<const T *>(a.q) + size_t(bh) * DH + lig * EPL, qf);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qf[e] *= a.scale_log2;
+
+  const int begin = sp * a.chunk;
+  const int end = min(a.K, begin + a.chunk);
+
+  float m = -INFINITY, l = 0.f, acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+  for (int base = begin; base < end; base += G * U) {
+    float kf[U][EPL], vf[U][EPL], logit[U];
+    bool valid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int slot = base + u * G + grp;
+      const bool inr = slot < end;
+      const bool ins = inr && slot == s_ins;
+      valid[u] = false;
+      if (ins) {
+        // the current token: take k, v from the step inputs and store them in the cache
+        const T *kn = static_cast<const T *>(a.k_new) + size_t(bh) * DH + lig * EPL;
+        const T *vn = static_cast<const T *>(a.v_new) + size_t(bh) * DH + lig * EPL;
+        Vec16<T>::load(kn, kf[u]);
+        Vec16<T>::load(vn, vf[u]);
+        Vec16<T>::copy(const_cast<T *>(Kb) + size_t(slot) * DH + lig * EPL, kn);
+        Vec16<T>::copy(const_cast<T *>(Vb) + size_t(slot) * DH + lig * EPL, vn);
+        if (lig == 0) a.slot_pos[size_t(bh) * a.K + slot] = a.n;
+        valid[u] = true;
+      } else if (inr) {
+        Vec16<T>::load(Kb + size_t(slot) * DH + lig * EPL, kf[u]);
+        Vec16<T>::load(Vb + size_t(slot) * DH + lig * EPL, vf[u]);
+        valid[u] = sp_row[slot] >= 0;
+      }
+    }
+    float mb = m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float dot = 0.f;
+      if (valid[u]) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], kf[u][e], dot);
+      }
+#pragma unroll
+      for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
+      logit[u] = valid[u] ? dot : -INFINITY;
+      mb = fmaxf(mb, logit[u]);
+    }
+    if (mb == -INFINITY) continue;  // nothing occupied so far in this lane group
+    const float corr = exp2f(m - mb);
+    l *= corr;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] *= corr;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (valid[u]) {
+        const float p = exp2f(logit[u] - mb);
+        l += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[u][e], acc[e]);
+      }
+    }
+    m = mb;
+  }
+
+  // ---- merge the G lane groups of this workgroup ----
+  __shared__ float s_m[G], s_l[G];
+  __shared__ float s_acc[G][DH];
+  if (lig == 0) s_m[grp] = m;
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int g = 0; g < G; ++g) M = fmaxf(M, s_m[g]);
+  const float f = (m == -INFINITY) ? 0.f : exp2f(m - M);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) s_acc[grp][lig * EPL + e] = acc[e] * f;
+  if (lig == 0) s_l[grp] = l * f;
+  __syncthreads();
+  if (tid < DH) {
+    float sum = 0.f, L = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      sum += s_acc[g][tid];
+      L += s_l[g];
+    }
+    if (a.nsplit == 1) {
+      a.out[size_t(bh) * DH + tid] = sum / L;   // the current token is always present: L > 0
+    } else {
+      float *p = a.part + (size_t(bh) * a.nsplit + sp) * (DH + 2);
+      p[tid] = sum;
+      if (tid == 0) {
+        p[DH] = M;
+        p[DH + 1] = L;
+      }
+    }
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, float *out, int nsplit) {
+  const int bh = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float *p = part + size_t(bh) * nsplit * (DH + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[s * (DH + 2) + DH]);
+  float sum = 0.f, L = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float ms = p[s * (DH + 2) + DH];
+    const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
+    sum = fmaf(p[s * (DH + 2) + tid], f, sum);
+    L = fmaf(p[s * (DH + 2) + DH + 1], f, L);
+  }
+  out[size_t(bh) * DH + tid] = sum / L;
+}
+
+template <typename T, int DH>
+hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
+  {
+    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND);
+    hipLaunchKernelGGL((attend_kernel<T, DH, 4>), dim3(rows * a.nsplit), dim3(256), 0, ctx->stream, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.nsplit > 1) {
+    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND_COMBINE);
+    hipLaunchKernelGGL((attend_combine_kernel<DH>), dim3(rows), dim3(DH), 0, ctx->stream, a.part, a.out,
+                       a.nsplit);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace
+
+hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new,
+                         float *out) {
+  const adore_config &c = ctx->cfg;
+  const size_t layer_bytes = size_t(c.batch) * c.heads * c.cache_slots * c.head_dim * elem_size(c);
+  AttendArgs a;
+  a.q = q; a.k_new = k_new; a.v_new = v_new;
+  a.Kc = ctx->cache_k + layer * layer_bytes;
+  a.Vc = ctx->cache_v + layer * layer_bytes;
+  a.slot_pos = ctx->slot_pos;
+  a.insert_slot = ctx->insert_slot;
+  a.part = ctx->att_part;
+  a.out = out;
+  a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit; a.n = ctx->n;
+  a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
+  const int rows = c.batch * c.heads;
+  if (c.dtype == ADORE_BF16) {
+    return c.head_dim == 128 ? launch_typed<bf16_t, 128>(ctx, a, rows) : launch_typed<bf16_t, 64>(ctx, a, rows);
+  }
+  return c.head_dim == 128 ? launch_typed<float, 128>(ctx, a, rows) : launch_typed<float, 64>(ctx, a, rows);
+}
+
+}  // namespace adore

@@ -1,0 +1,77 @@
+// Device helpers: 16-byte storage loads, bf16 conversion, the ranking key.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "adore_internal.h"
+
+namespace adore {
+
+// ---- storage access: one 16-byte vector -> EPL floats ----------------------
+template <typename T>
+struct Vec16;
+
+template <>
+struct Vec16<float> {
+  static constexpr int EPL = 4;  // elements per 16-byte load
+  __device__ static inline void load(const float *p, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+  __device__ static inline void copy(float *dst, const float *src) {
+    *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+  }
+};
+
+template <>
+struct Vec16<bf16_t> {
+  static constexpr int EPL = 8;
+  __device__ static inline void load(const bf16_t *p, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+  __device__ static inline void copy(bf16_t *dst, const bf16_t *src) {
+    *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+  }
+};
+
+__device__ inline float to_float(float v) { return v; }
+__device__ inline float to_float(bf16_t v) { return __uint_as_float(uint32_t(v.bits) << 16); }
+
+// fp32 -> bf16, round to nearest, ties to even.  NaN stays NaN.
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+__device__ inline void store_elem(float *p, float v) { *p = v; }
+__device__ inline void store_elem(bf16_t *p, float v) { p->bits = f32_to_bf16_rne(v); }
+
+// ---- ranking key ------------------------------------------------------------
+// Tokens of one sequence are ranked by sigma (higher is better) and, between
+// equal sigma, by position (lower is better).  The 64-bit key is monotone in
+// that order: larger key = better token.  Keys of distinct positions differ.
+// -0 is folded into +0, NaN is treated as 0.  A valid key is never 0.
+__device__ inline uint64_t rank_key(float sigma, int pos) {
+  sigma = (sigma != sigma) ? 0.0f : sigma + 0.0f;
+  uint32_t u = __float_as_uint(sigma);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return (uint64_t(u) << 32) | uint64_t(0xffffffffu - uint32_t(pos));
+}
+__device__ inline int key_pos(uint64_t key) { return int(0xffffffffu - uint32_t(key & 0xffffffffu)); }
+
+// ---- wave helpers (64 lanes) ------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+}  // namespace adore

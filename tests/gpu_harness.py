@@ -1,0 +1,151 @@
+"""Runs the HIP path (through the C-ABI binding) next to the oracle on the same seeded inputs."""
+import numpy as np
+import torch
+
+from gen import SyntheticInputs, Workload
+from paper_2407_02328_amd import Adore, make_config
+from tests.helpers import make_oracle
+
+DEV = "cuda:0"
+
+
+def storage_dtype(w: Workload):
+    return torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+
+def to_dev(a: np.ndarray, dtype) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
+
+
+def adore_config(w: Workload):
+    return make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
+                       rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
+                       pos_scale=w.pos_scale)
+
+
+def device_weights(w: Workload, wts):
+    st = storage_dtype(w)
+    return {k: to_dev(v, st if k in ("w_kv", "gru_w_ih", "gru_w_hh") else torch.float32) for k, v in wts.items()}
+
+
+class GpuJob:
+    """Device-side twin of an oracle run: same workload, same inputs, uploaded byte for byte."""
+
+    def __init__(self, w: Workload, inp: SyntheticInputs = None, wts=None, hidden=None, prompt=None):
+        self.w = w
+        self.inp = inp or SyntheticInputs(w)
+        self.wts = wts if wts is not None else self.inp.weights()
+        st = storage_dtype(w)
+        self.st = st
+        self.adore = Adore(adore_config(w), device_weights(w, self.wts), DEV)
+        self.hidden_np = self.inp.hidden_store() if hidden is None else hidden
+        self.hidden = to_dev(self.hidden_np, st)
+        self.prompt_np = self.inp.prompt_kv() if prompt is None else prompt
+        self.out = torch.empty((w.L, w.B, w.H, w.d), dtype=torch.float32, device=DEV)
+        self.slot_map = torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=DEV)
+        self.released = torch.empty((w.B, w.H, w.R + 1), dtype=torch.int32, device=DEV)
+        self.rebuilt = torch.empty((w.B, max(w.R, 1)), dtype=torch.int32, device=DEV)
+        self.state = self.adore.empty_state()
+
+    def init(self, score_override=None):
+        w = self.w
+        pk, pv = self.prompt_np
+        ov = None if score_override is None else to_dev(score_override, torch.float32)
+        self.adore.init_cache(to_dev(pk, self.st), to_dev(pv, self.st), self.hidden,
+                              self.hidden[0][:, :w.S].contiguous(), ov, w.S)
+        torch.cuda.synchronize()
+
+    def step(self, n, qkv=None, override=None):
+        """One step through the fine-grained calls.  Returns numpy (out, slot_map, released, rebuilt, score_n)."""
+        w = self.w
+        q, k, v = self.inp.step_qkv(n) if qkv is None else qkv
+        qd, kd, vd = (to_dev(a, self.st) for a in (q, k, v))
+        for l in range(w.L):
+            self.adore.attend(l, qd[l], kd[l], vd[l], self.out[l])
+        ov = None if override is None else to_dev(np.asarray(override, dtype=np.float32), torch.float32)
+        self.adore.schedule(self.hidden[0][:, n].contiguous(), ov, self.slot_map, self.released, self.rebuilt)
+        for l in range(w.L):
+            self.adore.rebuild(l, self.hidden[l])
+        self.adore.get_state(scores=self.state["scores"])
+        torch.cuda.synchronize()
+        score_n = self.state["scores"][:, n].cpu().numpy()
+        return (self.out.cpu().numpy().astype(np.float64), self.slot_map.cpu().numpy(),
+                self.released.cpu().numpy(), self.rebuilt.cpu().numpy()[:, :w.R], score_n)
+
+    def snapshot(self):
+        self.adore.get_state(**self.state)
+        torch.cuda.synchronize()
+        return {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+                for k, v in self.state.items()}
+
+
+def row_rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """max over rows of  max|got - want| / max|want|  (rows = last axis)."""
+    num = np.abs(got - want).max(axis=-1)
+    den = np.abs(want).max(axis=-1)
+    return float((num / np.maximum(den, 1e-30)).max())
+
+
+def out_tol(w: Workload) -> float:
+    return 2e-3 if w.dtype == "bf16" else 1e-5
+
+
+def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=None):
+    """Free-running GPU trajectory with the oracle in lockstep.
+
+    Each step the oracle computes its own sigma_n, which must agree with the GPU's to 1e-5; it then
+    adopts the GPU's bits so that both sides select from identical keys.  Slot maps, released and
+    rebuilt positions must be identical; outputs within the storage type's tolerance.
+    """
+    orc, inp, wts = make_oracle(w, wts)
+    job = GpuJob(w, inp, wts)
+    hs = job.hidden_np
+    pk, pv = job.prompt_np
+    job.init(None if override is None else override[:, :w.S])
+    snap = job.snapshot()
+    # init: the oracle adopts the GPU's prompt scores after checking them
+    orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S,
+                   score_override=None if override is None else override[:, :w.S])
+    gpu_scores = snap["scores"][:, :w.S]
+    assert np.abs(gpu_scores.astype(np.float64) - orc.score[:, :w.S].astype(np.float64)).max() < 1e-5
+    if override is None and not np.array_equal(gpu_scores, orc.score[:, :w.S]):
+        orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S, score_override=gpu_scores)
+    assert np.array_equal(snap["slot_pos"], orc.slot_pos), "slot map after init"
+    compare_cache(w, snap, orc)
+    worst = 0.0
+    for t in range(steps):
+        n = w.S + t
+        qkv = inp.step_qkv(n)
+        ov = None if override is None else override[:, n]
+        out_g, map_g, rel_g, rb_g, score_g = job.step(n, qkv, ov)
+        out_o, map_o, rel_o, rb_o, own = orc.decode_step(*qkv, hs, hs[0][:, n],
+                                                         score_override=score_g)
+        if override is None:
+            assert np.abs(own - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        else:
+            assert np.array_equal(score_g, ov.astype(np.float32))
+        assert np.array_equal(map_g, map_o), f"slot map at n={n}"
+        assert np.array_equal(rel_g, rel_o), f"released at n={n}"
+        assert np.array_equal(rb_g, rb_o), f"rebuilt at n={n}"
+        err = row_rel_err(out_g, out_o)
+        worst = max(worst, err)
+        assert err < out_tol(w), f"attention output at n={n}: {err}"
+        if check_cache_every and (t + 1) % check_cache_every == 0:
+            compare_cache(w, job.snapshot(), orc)
+    return worst, job, orc
+
+
+def compare_cache(w: Workload, snap, orc):
+    """Occupied rows of the GPU cache against the oracle's: inserted rows are copies (exact);
+    rebuilt rows are fp32-accumulated and rounded once, so they may differ by one unit in the
+    last place of the storage type."""
+    occ = orc.slot_pos >= 0                                  # [B,H,K]
+    for name, ref in (("cache_k", orc.Kc), ("cache_v", orc.Vc)):
+        got = snap[name].astype(np.float64)                  # [L,B,H,K,d]
+        for l in range(w.L):
+            g, r = got[l][occ], ref[l][occ]
+            if w.dtype == "bf16":
+                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r), 1e-30))) - 7)
+                assert np.all(np.abs(g - r) <= ulp * 1.0001 + 1e-30), name
+            else:
+                assert np.all(np.abs(g - r) <= 2e-6 * np.maximum(np.abs(r).max(), 1e-30)), name

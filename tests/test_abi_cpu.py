@@ -1,0 +1,121 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, sizes its workspace, and rejects bad arguments and out-of-order calls before touching
+any device memory (the pointers used here are never dereferenced on the host)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from gen import workload
+from paper_2407_02328_amd import EXPORTS, LIB_PATH, load_library
+from paper_2407_02328_amd.binding import AdoreConfig, AdoreWeights, make_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000       # 256-byte aligned, never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB_PATH):
+        from paper_2407_02328_amd.build import build_library
+        build_library()
+    return load_library()
+
+
+def cfg_for(w, **kw):
+    base = dict(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
+                rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
+                pos_scale=w.pos_scale)
+    base.update(kw)
+    return make_config(**base)
+
+
+def fake_weights():
+    w = AdoreWeights()
+    for name, _ in AdoreWeights._fields_:
+        setattr(w, name, FAKE)
+    return w
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "adore.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(adore_[a-z_]+)\s*\(", text))
+    assert declared == set(EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.adore_abi_version() == 1
+
+
+def test_workspace_bytes(lib):
+    w = workload("llama7b_layer")
+    c = cfg_for(w)
+    n = lib.adore_workspace_bytes(ctypes.byref(c))
+    cache = 2 * w.L * w.B * w.H * w.K * w.d * 2
+    assert cache <= n < cache + (32 << 20)
+    assert n % 256 == 0
+    bad = cfg_for(w, rebuild_budget=w.K - 1)
+    assert lib.adore_workspace_bytes(ctypes.byref(bad)) == 0
+    assert lib.adore_workspace_bytes(None) == 0
+
+
+def test_create_rejects_bad_arguments(lib):
+    w = workload("tiny")
+    c, wt = cfg_for(w), fake_weights()
+    h = ctypes.c_void_p()
+    n = lib.adore_workspace_bytes(ctypes.byref(c))
+    assert lib.adore_create(None, ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1
+    assert lib.adore_create(ctypes.byref(c), None, FAKE, n, None, ctypes.byref(h)) == -1
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), None, n, None, ctypes.byref(h)) == -1
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), FAKE, n - 1, None, ctypes.byref(h)) == -4
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), FAKE + 16, n, None, ctypes.byref(h)) == -4
+    for kw in (dict(rebuild_budget=w.K - 1), dict(batch=0), dict(dtype=7), dict(rebuild_budget=-1),
+               dict(cache_slots=1, rebuild_budget=0)):
+        bad = cfg_for(w, **kw)
+        assert lib.adore_create(ctypes.byref(bad), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1, kw
+    for kw in (dict(head_dim=96), dict(cache_slots=2048), dict(hidden=260)):
+        uns = cfg_for(w, **kw)
+        big = lib.adore_workspace_bytes(ctypes.byref(uns))
+        assert lib.adore_create(ctypes.byref(uns), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3, kw
+    wt2 = fake_weights()
+    wt2.out_b = None
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt2), FAKE, n, None, ctypes.byref(h)) == -1
+
+
+def test_calls_out_of_order_are_state_errors(lib):
+    w = workload("tiny")
+    c, wt = cfg_for(w), fake_weights()
+    h = ctypes.c_void_p()
+    n = lib.adore_workspace_bytes(ctypes.byref(c))
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == 0
+    try:
+        # nothing may run before init_cache; none of these reaches a kernel launch
+        assert lib.adore_attend(h, 0, FAKE, FAKE, FAKE, FAKE) == -2
+        assert lib.adore_schedule(h, FAKE, None, None, None, None) == -2
+        assert lib.adore_rebuild(h, 0, FAKE) == -2
+        assert lib.adore_decode_step(h, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == -2
+        step = ctypes.c_int32()
+        assert lib.adore_get_state(h, None, None, None, None, None, ctypes.byref(step)) == -2
+        # argument errors come first
+        assert lib.adore_attend(h, 1, FAKE, FAKE, FAKE, FAKE) == -1
+        assert lib.adore_attend(h, 0, None, FAKE, FAKE, FAKE) == -1
+        assert lib.adore_init_cache(h, FAKE, FAKE, FAKE, FAKE, None, 0) == -1
+        assert lib.adore_init_cache(h, FAKE, FAKE, FAKE, FAKE, None, w.N_max) == -1
+        assert lib.adore_init_cache(h, None, FAKE, FAKE, FAKE, None, 4) == -1
+        assert lib.adore_set_state(h, None, None, None, None, None, 5) == -1
+        assert lib.adore_set_state(h, FAKE, None, None, None, None, 0) == -1
+    finally:
+        assert lib.adore_destroy(h) == 0
+    assert lib.adore_destroy(None) == -1
+
+
+def test_strerror_and_kernel_names(lib):
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        s = lib.adore_strerror(code).decode()
+        assert s
+        seen.add(s)
+    assert len(seen) == 7
+    from paper_2407_02328_amd import KERNELS
+    assert [lib.adore_kernel_name(i).decode() for i in range(len(KERNELS))] == KERNELS

@@ -1,0 +1,218 @@
+"""Parity of the HIP path (called through the C-ABI) with the CPU oracle on the same seeded inputs.
+
+Slot maps, released and rebuilt positions must be identical; attention outputs within 1e-5 (fp32)
+or 2e-3 (bf16) of the oracle, measured per row as max|diff| / max|ref|; the controller's sigma
+within 1e-5.  Both sides rank tokens from the same fp32 sigma bits (the oracle checks its own
+value against the GPU's, then adopts the GPU's bits).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from gen import SyntheticInputs, Workload, workload
+from oracle import adore_oracle as O
+from tests.helpers import GOLDEN, parse_trajectory, small_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _harness():
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def test_tiny_full_trajectory():
+    """The tiny workload end to end: prompt 128, all 256 decode steps, fp32."""
+    h = _harness()
+    w = workload("tiny")
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=64)
+    print(f"tiny: worst output error {worst:.3e}")
+    job.adore.close()
+
+
+def test_bf16_trajectory_spanning_tiles_with_ragged_sizes():
+    """bf16, d=128: K=200 is not a multiple of the 64-slot tile, B*R=15 rows leave the GEMM tile ragged,
+    the attention splits each row over several workgroups."""
+    h = _harness()
+    w = Workload("bf16_small", L=1, B=3, H=4, d=128, D=512, K=200, R=5, S=260, T=40, dtype="bf16")
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=10)
+    assert job.adore.cfg.cache_slots == 200
+    print(f"bf16_small: worst output error {worst:.3e}")
+    job.adore.close()
+
+
+def test_bf16_head_dim_64_and_two_layers():
+    h = _harness()
+    w = Workload("bf16_d64", L=2, B=2, H=4, d=64, D=256, K=96, R=8, S=120, T=24, dtype="bf16")
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=8)
+    job.adore.close()
+
+
+def test_fp32_head_dim_128():
+    h = _harness()
+    w = Workload("f32_d128", L=1, B=2, H=2, d=128, D=128, K=80, R=4, S=100, T=16, dtype="f32",
+                 act_std=0.3, w_std=0.1)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=8)
+    job.adore.close()
+
+
+def test_warm_up_from_a_short_prompt():
+    """S < m: the cache fills up first (nothing released, nothing rebuilt), then reaches steady state."""
+    h = _harness()
+    w = small_workload(B=2, H=2, d=64, D=64, K=20, R=4, S=3, T=40, dtype="f32", dprime=16)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5)
+    job.adore.close()
+
+
+def test_no_rebuild_budget():
+    h = _harness()
+    w = small_workload(B=1, H=2, d=64, D=64, K=16, R=0, S=30, T=20, dtype="f32", dprime=16)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5)
+    job.adore.close()
+
+
+def test_maximum_slots_and_single_token_prompt():
+    h = _harness()
+    w = Workload("k1024", L=1, B=1, H=2, d=64, D=64, K=1024, R=30, S=1, T=12, dtype="bf16", dprime=16)
+    worst, job, _ = h.lockstep(w, steps=w.T)
+    job.adore.close()
+    w = Workload("k1024_full", L=1, B=1, H=2, d=64, D=64, K=1024, R=1022, S=1500, T=6, dtype="bf16", dprime=16)
+    worst, job, _ = h.lockstep(w, steps=w.T)
+    job.adore.close()
+
+
+def test_injected_ties_are_broken_by_position():
+    """Scores drawn from 7 values: most comparisons are ties."""
+    h = _harness()
+    w = small_workload(B=2, H=2, d=64, D=64, K=24, R=5, S=70, T=30, dtype="f32", dprime=16)
+    rng = np.random.default_rng(11)
+    override = rng.choice(np.array([0.0, -0.0, 0.25, 0.5, 0.5, 0.75, 1.0], dtype=np.float32), (w.B, w.N_max))
+    worst, job, _ = h.lockstep(w, steps=w.T, override=override, check_cache_every=10)
+    job.adore.close()
+
+
+def test_hand_worked_trajectory_on_gpu():
+    h = _harness()
+    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, "slot_trajectory_K4_R1.txt"))
+    S = len(init_scores)
+    w = Workload("golden", L=1, B=1, H=2, d=64, D=64, K=4, R=1, S=S, T=len(steps), dtype="f32", dprime=16)
+    job = h.GpuJob(w)
+    job.init(init_scores[None, :])
+    snap = job.snapshot()
+    for hh in range(w.H):
+        assert snap["slot_pos"][0, hh].tolist() == after_init["slot_map"]
+    for st in steps:
+        out, slot_map, released, rebuilt, score = job.step(st["n"], override=np.array([st["score"]], np.float32))
+        for hh in range(w.H):
+            assert slot_map[0, hh].tolist() == st["slot_map"], st
+            assert released[0, hh].tolist() == st["released"], st
+        assert rebuilt[0].tolist() == st["rebuilt"], st
+    job.adore.close()
+
+
+def test_decode_step_entry_point_and_determinism():
+    """adore_decode_step (L = 1) gives the same result as attend + schedule + rebuild, and a second run
+    from the same inputs reproduces slot maps and outputs bit for bit."""
+    h = _harness()
+    w = Workload("ds", L=1, B=2, H=4, d=128, D=256, K=72, R=6, S=90, T=10, dtype="bf16")
+    inp = SyntheticInputs(w)
+    results = []
+    for rep in range(2):
+        job = h.GpuJob(w, inp)
+        job.init()
+        maps, outs = [], []
+        for n in range(w.S, w.S + w.T):
+            q, k, v = (h.to_dev(a[0], job.st) for a in inp.step_qkv(n))
+            if rep == 0:
+                job.adore.decode_step(q, k, v, job.hidden[0], job.hidden[0][:, n].contiguous(), None,
+                                      job.out[0], job.slot_map)
+            else:
+                job.adore.attend(0, q, k, v, job.out[0])
+                job.adore.schedule(job.hidden[0][:, n].contiguous(), None, job.slot_map, None, None)
+                job.adore.rebuild(0, job.hidden[0])
+            torch.cuda.synchronize()
+            maps.append(job.slot_map.cpu().numpy().copy())
+            outs.append(job.out.cpu().numpy().copy())
+        results.append((maps, outs, job.snapshot()))
+        job.adore.close()
+    for a, b in zip(results[0][0], results[1][0]):
+        assert np.array_equal(a, b)
+    for a, b in zip(results[0][1], results[1][1]):
+        assert np.array_equal(a, b)
+    for key in ("cache_k", "cache_v", "scores", "z", "slot_pos"):
+        s0, s1 = results[0][2][key], results[1][2][key]
+        if key == "scores":
+            s0, s1 = s0[:, :w.S + w.T], s1[:, :w.S + w.T]
+        if key in ("cache_k", "cache_v"):
+            occ = results[0][2]["slot_pos"] >= 0
+            s0, s1 = s0[0][occ], s1[0][occ]
+        assert np.array_equal(s0, s1), key
+
+
+def test_state_snapshot_and_restore():
+    h = _harness()
+    w = Workload("snap", L=1, B=2, H=2, d=64, D=128, K=40, R=4, S=60, T=12, dtype="bf16", dprime=32)
+    inp = SyntheticInputs(w)
+    job = h.GpuJob(w, inp)
+    job.init()
+    for n in range(w.S, w.S + 4):
+        job.step(n)
+    saved = {k: v.clone() for k, v in job.state.items()}
+    step = job.adore.get_state(**saved)
+    torch.cuda.synchronize()
+    assert step == w.S + 4
+    ref = [job.step(n) for n in range(w.S + 4, w.S + 8)]
+    job.adore.set_state(saved["slot_pos"], saved["scores"], saved["z"], saved["cache_k"], saved["cache_v"], step)
+    again = [job.step(n) for n in range(w.S + 4, w.S + 8)]
+    for a, b in zip(ref, again):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    job.adore.close()
+
+
+def test_state_machine_on_device():
+    h = _harness()
+    from paper_2407_02328_amd import AdoreError
+    w = Workload("sm", L=2, B=1, H=2, d=64, D=64, K=16, R=2, S=20, T=2, dtype="f32", dprime=16)
+    inp = SyntheticInputs(w)
+    job = h.GpuJob(w, inp)
+    job.init()
+    q, k, v = (h.to_dev(a, job.st) for a in inp.step_qkv(w.S))
+    x = job.hidden[0][:, w.S].contiguous()
+    with pytest.raises(AdoreError) as e:
+        job.adore.schedule(x)                       # no layer attended yet
+    assert e.value.code == -2
+    job.adore.attend(0, q[0], k[0], v[0], job.out[0])
+    with pytest.raises(AdoreError):
+        job.adore.attend(0, q[0], k[0], v[0], job.out[0])      # twice
+    with pytest.raises(AdoreError):
+        job.adore.schedule(x)                       # layer 1 missing
+    with pytest.raises(AdoreError):
+        job.adore.rebuild(0, job.hidden[0])         # before schedule
+    job.adore.attend(1, q[1], k[1], v[1], job.out[1])
+    job.adore.schedule(x)
+    with pytest.raises(AdoreError):
+        job.adore.schedule(x)
+    job.adore.rebuild(1, job.hidden[1])
+    with pytest.raises(AdoreError):
+        job.adore.rebuild(1, job.hidden[1])
+    with pytest.raises(AdoreError):
+        job.adore.get_state()                       # mid-step
+    job.adore.rebuild(0, job.hidden[0])
+    assert job.adore.get_state() == w.S + 1
+    # one more step reaches N_max; the next attend is refused
+    q, k, v = (h.to_dev(a, job.st) for a in inp.step_qkv(w.S + 1))
+    for l in range(2):
+        job.adore.attend(l, q[l], k[l], v[l], job.out[l])
+    job.adore.schedule(job.hidden[0][:, w.S + 1].contiguous())
+    for l in range(2):
+        job.adore.rebuild(l, job.hidden[l])
+    with pytest.raises(AdoreError) as e:
+        job.adore.attend(0, q[0], k[0], v[0], job.out[0])
+    assert e.value.code == -2
+    with pytest.raises(ValueError):
+        job.adore.attend(0, q[0].float().double(), k[0], v[0], job.out[0])   # wrong dtype caught by the binding
+    torch.cuda.synchronize()
+    job.adore.close()
