@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADORE decode step on one MI355X.
+
+A "step" is one pass of the whole hot path (insert + sparse attention, controller, release select,
+rebuild select, re-projection GEMM + scatter) for one batch of B sequences of one decoder layer, in
+steady state (cache full, R tokens rebuilt per sequence and step).  All inputs are generated from a
+seed, uploaded, and resident in HBM before the timed region.
+
+Prints ONE JSON line: tokens/s per layer for the whole job, per-kernel times measured live with HIP
+events on the library's stream, the roofline fraction of the dominant kernel, and the CPU oracle
+timed on this host on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_work(w):
+    """Bytes / flops one step must move / compute, per kernel (not the dense work the method avoids)."""
+    es = 2 if w.dtype == "bf16" else 4
+    BH = w.B * w.H
+    att_bytes = 2 * BH * w.K * w.d * es + BH * (w.K * 4 + 3 * w.d * es + w.d * 4)
+    gemm_flops = 2.0 * (w.B * w.R) * w.D * (2 * w.H * w.d)
+    ctrl_flops = 2.0 * w.B * w.D * 3 * w.dprime + 2.0 * w.B * w.dprime * 4 * w.dprime
+    sel_bytes = BH * w.K * 8 + w.B * w.N_max * 4
+    return dict(attend_bytes=att_bytes, gemm_flops=gemm_flops, ctrl_flops=ctrl_flops, select_bytes=sel_bytes)
+
+
+def run_gpu(w, steps, warmup, prof_steps):
+    import torch
+    from gen import SyntheticInputs
+    from tests.gpu_harness import GpuJob, to_dev
+    t0 = time.time()
+    inp = SyntheticInputs(w)
+    job = GpuJob(w, inp)
+    log(f"inputs generated and uploaded in {time.time() - t0:.1f}s")
+    job.init()
+    total = warmup + steps + prof_steps
+    assert w.S + total <= w.N_max, "not enough positions for this many steps"
+    qkv = []
+    for t in range(total):
+        q, k, v = inp.step_qkv(w.S + t)
+        qkv.append(tuple(to_dev(a[0], job.st) for a in (q, k, v)))
+    xs = [job.hidden[0][:, w.S + t].contiguous() for t in range(total)]
+    hidden0 = job.hidden[0]
+    out = job.out[0]
+    torch.cuda.synchronize()
+
+    def step(t):
+        q, k, v = qkv[t]
+        job.adore.decode_step(q, k, v, hidden0, xs[t], None, out, job.slot_map)
+
+    for t in range(warmup):
+        step(t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+
+    # per-kernel durations, HIP events on the library's stream around every launch
+    job.adore.set_timing(True)
+    for t in range(warmup + steps, total):
+        step(t)
+    timing = job.adore.read_timing()
+    job.adore.set_timing(False)
+    per_kernel_us = {k: (1e3 * ms / cnt if cnt else 0.0) for k, (ms, cnt) in timing.items()}
+    assert bool(torch.isfinite(out).all())
+    job.adore.close()
+    return elapsed, per_kernel_us
+
+
+def run_cpu_baseline(w, seqs=16, steps=40):
+    """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
+    from threadpoolctl import threadpool_info
+    from gen import SyntheticInputs
+    from tests.helpers import make_oracle
+    seqs = min(seqs, w.B)
+    ws = w.scaled(B=seqs, T=steps + 1)
+    orc, inp, _ = make_oracle(ws)
+    hs = inp.hidden_store()
+    pk, pv = inp.prompt_kv()
+    rng = np.random.default_rng(ws.seed)
+    prompt_scores = rng.random((ws.B, ws.S), dtype=np.float32)     # skip nothing: init still runs the GRU
+    orc.init_cache(pk, pv, hs, hs[0][:, :ws.S], ws.S, score_override=prompt_scores)
+    qkvs = [inp.step_qkv(ws.S + t) for t in range(steps)]
+    t0 = time.perf_counter()
+    for t in range(steps):
+        orc.decode_step(*qkvs[t], hs, hs[0][:, ws.S + t])
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return dict(value=seqs * steps / dt, unit="tokens/s/layer", cores=int(threads), kind="oracle",
+                sample=f"{seqs} of {w.B} sequences, {steps} steady-state steps after a {ws.S}-token prompt "
+                       f"(numpy fp64; BLAS threads for the re-projection, Python loops elsewhere)",
+                seconds=round(dt, 2))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--profile-steps", type=int, default=50, help="extra steps with per-kernel events")
+    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (the decode step shards by "
+                 "sequence or by head with no exchange; see DESIGN.md). Run with --gpus 1.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (the HIP path has no CPU fallback)")
+    from gen import workload
+    w = workload(args.workload)
+    if w.L != 1:
+        sys.exit("bench.py times single-layer workloads")
+    work = algorithmic_work(w)
+    elapsed, per_kernel_us = run_gpu(w, args.steps, args.warmup, args.profile_steps)
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = w.B * args.steps / elapsed
+
+    att_us = per_kernel_us["attend"]
+    gemm_us = per_kernel_us["rebuild_gemm"]
+    att_gbs = work["attend_bytes"] / (att_us * 1e-6) / 1e9 if att_us else 0.0
+    gemm_tflops = work["gemm_flops"] / (gemm_us * 1e-6) / 1e12 if gemm_us else 0.0
+    roof_att = dict(kernel="attend", bound="hbm", achieved=round(att_gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(att_gbs / HBM_PEAK_GBS, 4), traffic=None, us_per_launch=round(att_us, 2),
+                    algorithmic_bytes=work["attend_bytes"])
+    peak = MFMA_PEAK_TFLOPS[w.dtype]
+    roof_gemm = dict(kernel="rebuild_gemm", bound="mfma" if w.dtype == "bf16" else "alu",
+                     achieved=round(gemm_tflops, 1), peak=peak, unit="TFLOP/s", frac=round(gemm_tflops / peak, 4),
+                     traffic=None, us_per_launch=round(gemm_us, 2), algorithmic_flops=work["gemm_flops"])
+    dominant = roof_gemm if gemm_us >= att_us else roof_att
+
+    line = {
+        "metric": "decoded tokens/sec per decode layer at cache K",
+        "value": round(value, 1), "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
+                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": 1},
+        "roofline": dominant,
+        "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
+        "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
+        "kernel_us_sum": round(sum(per_kernel_us.values()), 2),
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.time()
+        line["cpu_baseline"] = run_cpu_baseline(w)
+        log(f"cpu baseline took {time.time() - t0:.1f}s in total")
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -24,6 +24,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // plain vector: stays in registers
 
 struct GemmArgs {
   const void *X;               // [B][N_max][D] hidden states entering this layer
@@ -40,9 +41,10 @@ constexpr int CH = BK / 8;   // 16-byte chunks per tile row
 
 __device__ inline int swz(int row, int chunk) { return row * CH + (chunk ^ ((row >> 1) & 7)); }
 
+template <int NS>   // register stages: tiles of k-steps ks+1 .. ks+NS are in flight while ks is multiplied
 __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
-  __shared__ uint4 sA[2][BM * CH];
-  __shared__ uint4 sB[2][BN * CH];
+  __shared__ u32x4 sA[2][BM * CH];
+  __shared__ u32x4 sB[2][BN * CH];
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // tiles in which the M-tiles of one W panel are neighbours, so a panel is fetched
@@ -57,9 +59,9 @@ __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // ---- global -> register staging: 4 chunks of A and 4 of B per thread ----
+  // ---- global -> register staging: 4 chunks of A and 4 of B per thread and k-step ----
   const int lchunk = tid & 7, lrow = tid >> 3;   // rows lrow + 32*i
-  const uint4 *gA[4], *gB[4];
+  const u32x4 *gA[4], *gB[4];
   const bf16_t *X = static_cast<const bf16_t *>(a.X);
   const bf16_t *W = static_cast<const bf16_t *>(a.W);
 #pragma unroll
@@ -70,20 +72,26 @@ __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
       const int b = mi / a.r, rho = mi - b * a.r;
       src_row = size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + rho];
     }
-    gA[i] = reinterpret_cast<const uint4 *>(X + src_row * a.D) + lchunk;
-    gB[i] = reinterpret_cast<const uint4 *>(W + size_t(n0 + lrow + 32 * i) * a.D) + lchunk;
+    gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
+    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + lrow + 32 * i) * a.D) + lchunk;
   }
-  uint4 ra[4], rb[4];
+  const int nk = a.D / BK;
+  u32x4 ra[NS][4], rb[NS][4];
+#define ADORE_GLOAD(SET, KS)                    \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) { \
+    ra[SET][i] = gA[i][(KS) * CH];              \
+    rb[SET][i] = gB[i][(KS) * CH];              \
+  }
+#define ADORE_LSTORE(SET, ST)                                 \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {             \
+    sA[ST][swz(lrow + 32 * i, lchunk)] = ra[SET][i];          \
+    sB[ST][swz(lrow + 32 * i, lchunk)] = rb[SET][i];          \
+  }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = gA[i][0];
-    rb[i] = gB[i][0];
+  for (int s = 0; s < NS; ++s) {
+    if (s < nk) { ADORE_GLOAD(s, s) }
   }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    sA[0][swz(lrow + 32 * i, lchunk)] = ra[i];
-    sB[0][swz(lrow + 32 * i, lchunk)] = rb[i];
-  }
+  ADORE_LSTORE(0, 0)
   __syncthreads();
 
   f32x16 acc[2][2];
@@ -94,43 +102,39 @@ __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = a.D / BK;
-  for (int ks = 0; ks < nk; ++ks) {
-    const int st = ks & 1;
-    if (ks + 1 < nk) {
+  for (int ks0 = 0; ks0 < nk; ks0 += NS) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = gA[i][(ks + 1) * CH];
-        rb[i] = gB[i][(ks + 1) * CH];
+    for (int u = 0; u < NS; ++u) {
+      const int ks = ks0 + u;   // nk is a multiple of NS (checked at launch)
+      {
+        const int st = ks & 1;
+        // register set u went to LDS one step ago: refill it with the tile NS steps ahead
+        if (ks + NS < nk) { ADORE_GLOAD(u, ks + NS) }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          const int ch = kk * 2 + (lane >> 5);
+          bf16x8 fa[2], fb[2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const u32x4 va = sA[st][swz(wm * 64 + i * 32 + (lane & 31), ch)];
+            const u32x4 vb = sB[st][swz(wn * 64 + i * 32 + (lane & 31), ch)];
+            fa[i] = *reinterpret_cast<const bf16x8 *>(&va);
+            fb[i] = *reinterpret_cast<const bf16x8 *>(&vb);
+          }
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (ks + 1 < nk) { ADORE_LSTORE((u + 1) % NS, st ^ 1) }
+        __syncthreads();
       }
     }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int ch = kk * 2 + (lane >> 5);
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint4 va = sA[st][swz(wm * 64 + i * 32 + (lane & 31), ch)];
-        const uint4 vb = sB[st][swz(wn * 64 + i * 32 + (lane & 31), ch)];
-        fa[i] = *reinterpret_cast<const bf16x8 *>(&va);
-        fb[i] = *reinterpret_cast<const bf16x8 *>(&vb);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (ks + 1 < nk) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sA[st ^ 1][swz(lrow + 32 * i, lchunk)] = ra[i];
-        sB[st ^ 1][swz(lrow + 32 * i, lchunk)] = rb[i];
-      }
-    }
-    __syncthreads();
   }
 
+#undef ADORE_GLOAD
+#undef ADORE_LSTORE
   // ---- epilogue: round once to bf16 and scatter into the assigned slots ----
   // accumulator element v of lane L: row 8*(v/4) + 4*(L/32) + v%4, column L%32 of its 32x32 block
   const int Hd = a.H * a.d;
@@ -211,7 +215,10 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   if (mfma_ok) {
     const int total = a.tiles_m * a.tiles_n;
     const int grid = (total + 7) / 8 * 8;
-    hipLaunchKernelGGL(rebuild_mfma_kernel, dim3(grid), dim3(256), 0, ctx->stream, a);
+    const int nk = c.hidden / BK;   // the k-loop is unrolled by the number of register stages
+    if (nk % 4 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<4>), dim3(grid), dim3(256), 0, ctx->stream, a);
+    else if (nk % 2 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<2>), dim3(grid), dim3(256), 0, ctx->stream, a);
+    else hipLaunchKernelGGL((rebuild_mfma_kernel<1>), dim3(grid), dim3(256), 0, ctx->stream, a);
   } else {
     const size_t waves = size_t(a.M) * a.N;
     const unsigned blocks = unsigned((waves + 3) / 4);
