@@ -183,8 +183,8 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
  * per kernel since the last read into ms[ADORE_N_KERNELS] and the launch counts
  * into launches[ADORE_N_KERNELS] (both HOST arrays), and clears the record. */
 enum {
-  ADORE_KERNEL_ATTEND = 0,      /* insert + attention partials */
-  ADORE_KERNEL_ATTEND_COMBINE,  /* merge of the split partials */
+  ADORE_KERNEL_ATTEND = 0,      /* insert + attention (partials when a row is split) */
+  ADORE_KERNEL_ATTEND_COMBINE,  /* merge of the split partials; not launched for one split */
   ADORE_KERNEL_CTRL_INPUT,      /* GRU input projection */
   ADORE_KERNEL_CTRL_CELL,       /* GRU cell + MLP + sigmoid */
   ADORE_KERNEL_RELEASE,         /* per-(b,h) release select */

@@ -6,6 +6,7 @@
 // (n, S, K, R), so the host knows every launch shape without reading results
 // back:  o = occupied_before + 1,  x = max(0, o - m),  r = min(R, n + 1 - min(o, m)).
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -27,13 +28,13 @@ ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel) : ctx_(ctx), stop_(nullptr)
       return;
     }
   }
-  hipEventRecord(ev[0], ctx->stream);
+  (void)hipEventRecord(ev[0], ctx->stream);
   stop_ = ev[1];
   ctx->timed.push_back(TimedLaunch{kernel, ev[0], ev[1]});
 }
 
 ScopedTimer::~ScopedTimer() {
-  if (ctx_ && stop_) hipEventRecord(stop_, ctx_->stream);
+  if (ctx_ && stop_) (void)hipEventRecord(stop_, ctx_->stream);
 }
 
 }  // namespace adore
@@ -81,23 +82,34 @@ Layout make_layout(const adore_config &c) {
   l.rebuilt_pos = take(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4);
   l.init_res = take(size_t(c.batch) * c.cache_slots * 4);
   l.att_part = take(BH * kMaxSplits * (size_t(c.head_dim) + 2) * 4);
-  l.gi = take(size_t(c.batch) * kPromptChunk * 3 * c.ctrl_hidden * 4);
+  size_t gi_rows = size_t(c.batch) * kPromptChunk;
+  if (gi_rows < size_t(kMaxCtrlSplit) * kCtrlSplitTokens) gi_rows = size_t(kMaxCtrlSplit) * kCtrlSplitTokens;
+  l.gi = take(gi_rows * 3 * c.ctrl_hidden * 4);
   l.total = off;
   return l;
 }
 
-// Splits per (b,h) row so that the attention launch has enough workgroups to fill
-// 256 compute units a few times over, without cutting a row below 64 slots.
+// Launch shape of the attention kernel.  As few splits per (b,h) row as still give every
+// compute unit a workgroup (each split costs a partial and, above one, the merge kernel);
+// then as many waves per workgroup as leave each wave at least 32 slots.
+// ADORE_ATTEND_SPLIT / ADORE_ATTEND_WAVES override the choice (for tuning runs).
 void choose_split(adore_ctx *ctx) {
   const adore_config &c = ctx->cfg;
   const int rows = c.batch * c.heads;
   int nsplit = 1;
-  while (nsplit < kMaxSplits && rows * nsplit < 2048 && c.cache_slots / (nsplit * 2) >= 64) nsplit *= 2;
+  while (nsplit < kMaxSplits && rows * nsplit < 256 && c.cache_slots / (nsplit * 2) >= 64) nsplit *= 2;
+  if (const char *e = getenv("ADORE_ATTEND_SPLIT")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= kMaxSplits) nsplit = v;
+  }
   ctx->nsplit = nsplit;
   ctx->chunk = (c.cache_slots + nsplit - 1) / nsplit;
+  ctx->attend_waves = ctx->chunk >= 512 ? 16 : ctx->chunk >= 256 ? 8 : 4;
+  if (const char *e = getenv("ADORE_ATTEND_WAVES")) {
+    const int v = atoi(e);
+    if (v == 4 || v == 8 || v == 16) ctx->attend_waves = v;
+  }
 }
-
-int hip_rc(hipError_t e) { return e == hipSuccess ? ADORE_OK : ADORE_E_HIP; }
 
 #define ADORE_TRY(expr)              \
   do {                               \
@@ -166,10 +178,10 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
 int adore_destroy(adore_ctx *ctx) {
   if (!ctx) return ADORE_E_INVALID;
   for (auto &t : ctx->timed) {
-    hipEventDestroy(t.start);
-    hipEventDestroy(t.stop);
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
   }
-  for (auto &e : ctx->event_pool) hipEventDestroy(e);
+  for (auto &e : ctx->event_pool) (void)hipEventDestroy(e);
   delete ctx;
   return ADORE_OK;
 }
@@ -190,8 +202,9 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   for (int i0 = 0; i0 < S; i0 += kPromptChunk) {
     const int len = (S - i0 < kPromptChunk) ? S - i0 : kPromptChunk;
     const char *x = static_cast<const char *>(ctrl_input) + size_t(i0) * c.hidden * es;
-    ADORE_TRY(launch_ctrl_input(ctx, x, c.batch * len, len, S));
-    ADORE_TRY(launch_ctrl_cell(ctx, len, i0, score_override ? score_override + i0 : nullptr, S));
+    int ksplit = 1;
+    ADORE_TRY(launch_ctrl_input(ctx, x, c.batch * len, len, S, &ksplit));
+    ADORE_TRY(launch_ctrl_cell(ctx, len, i0, score_override ? score_override + i0 : nullptr, S, ksplit));
   }
   ADORE_TRY(launch_init_select(ctx, S, keep, r0));
   ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
@@ -230,8 +243,9 @@ int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override,
   const int pool = ctx->n + 1 - kept;
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
 
-  ADORE_TRY(launch_ctrl_input(ctx, x_n, c.batch, 1, 1));
-  ADORE_TRY(launch_ctrl_cell(ctx, 1, ctx->n, score_override, 1));
+  int ksplit = 1;
+  ADORE_TRY(launch_ctrl_input(ctx, x_n, c.batch, 1, 1, &ksplit));
+  ADORE_TRY(launch_ctrl_cell(ctx, 1, ctx->n, score_override, 1, ksplit));
   ADORE_TRY(launch_release(ctx, x));
   ADORE_TRY(launch_rebuild_select(ctx, r));
   const size_t BH = size_t(c.batch) * c.heads;

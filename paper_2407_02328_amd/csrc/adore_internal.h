@@ -20,6 +20,8 @@ constexpr int kMaxSplits = 16;        // attention partials per (b,h) row
 constexpr int kMaxSlots = 1024;       // K handled by the one-slot-per-thread release kernel
 constexpr int kMaxPositions = 1 << 18; // residency bitmap of a sequence lives in LDS
 constexpr int kPromptChunk = 512;     // tokens per GRU input-projection launch at init
+constexpr int kMaxCtrlSplit = 16;     // D-slices of the GRU input projection
+constexpr int kCtrlSplitTokens = 256; // the projection is only sliced for launches of at most this many tokens
 
 struct TimedLaunch {
   int kernel;
@@ -44,7 +46,7 @@ struct adore_ctx {
   int32_t *rebuilt_pos;      // [B][max(R,1)]
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
-  float *gi;                 // [max(B, B*kPromptChunk)][3d'] GRU input pre-activations
+  float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
 
   // --- host-side step state ---
   bool inited;
@@ -57,6 +59,7 @@ struct adore_ctx {
 
   // --- launch shape ---
   int32_t nsplit, chunk;     // attention: splits per row and slots per split
+  int32_t attend_waves;      // attention: waves per workgroup (4, 8 or 16)
 
   // --- timing ---
   bool timing;
@@ -82,9 +85,10 @@ class ScopedTimer {
 // Launchers.  Each validates nothing (the API did) and returns the launch status.
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
                          const void *v_new, float *out);
-hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows);
+hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows,
+                             int *ksplit_out);
 hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *score_override,
-                            int override_stride);
+                            int override_stride, int ksplit);
 hipError_t launch_release(adore_ctx *ctx, int x);
 hipError_t launch_rebuild_select(adore_ctx *ctx, int r);
 hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int r);

@@ -7,7 +7,11 @@
 // wave reads 64/LPR whole cache rows (1 KB, contiguous) per load instruction.
 // The slots of one (b,h) are cut into `nsplit` chunks, one workgroup each, so
 // that small batches still fill the chip; partial (max, sum, acc) triples are
-// merged by a second small kernel.  Softmax runs online in fp32, base 2.
+// merged by a second small kernel (a merge inside the first kernel would need a
+// device-scope release per workgroup, which on a multi-XCD part writes back the
+// whole L2 and costs far more than the extra launch).  When there are enough
+// rows, one workgroup of up to 16 waves takes a whole row and no merge kernel
+// runs.  Softmax runs online in fp32, base 2.
 #include "device_utils.h"
 
 namespace adore {
@@ -25,12 +29,12 @@ struct AttendArgs {
   float scale_log2;                // log2(e) / sqrt(d)
 };
 
-template <typename T, int DH, int U>
-__global__ __launch_bounds__(256) void attend_kernel(const AttendArgs a) {
+template <typename T, int DH, int U, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) {
   constexpr int EPL = Vec16<T>::EPL;    // elements per lane
   constexpr int LPR = DH / EPL;         // lanes per cache row
   constexpr int RPW = 64 / LPR;         // rows per wave and load
-  constexpr int G = 4 * RPW;            // lane groups (rows in flight) per workgroup
+  constexpr int G = WAVES * RPW;        // lane groups (rows in flight) per workgroup
   static_assert(LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must be a power-of-two lane group");
 
   const int bh = blockIdx.x / a.nsplit;
@@ -127,7 +131,7 @@ __global__ __launch_bounds__(256) void attend_kernel(const AttendArgs a) {
   __syncthreads();
   if (tid < DH) {
     float sum = 0.f, L = 0.f;
-#pragma unroll
+#pragma unroll 8
     for (int g = 0; g < G; ++g) {
       sum += s_acc[g][tid];
       L += s_l[g];
@@ -166,7 +170,13 @@ template <typename T, int DH>
 hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
   {
     ScopedTimer t(ctx, ADORE_KERNEL_ATTEND);
-    hipLaunchKernelGGL((attend_kernel<T, DH, 4>), dim3(rows * a.nsplit), dim3(256), 0, ctx->stream, a);
+    const dim3 grid(rows * a.nsplit);
+    if (ctx->attend_waves == 16)
+      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 16>), grid, dim3(1024), 0, ctx->stream, a);
+    else if (ctx->attend_waves == 8)
+      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 8>), grid, dim3(512), 0, ctx->stream, a);
+    else
+      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 4>), grid, dim3(256), 0, ctx->stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

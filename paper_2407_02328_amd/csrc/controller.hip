@@ -6,9 +6,13 @@
 //   sigma_i = sigmoid(out_w . tanh(W_1 (p_i + z_i) + b_1) + out_b),  p_i = pos_w * (i * pos_scale) + pos_b
 //
 // Two kernels.  ctrl_input computes the input pre-activations W_ih x for a
-// batch of tokens (the only part that reads D-wide data; it has no dependence
-// between tokens, so a whole prompt chunk goes in one launch).  ctrl_cell does
-// the recurrent part token by token: W_hh z, the gates, the MLP and the score.
+// batch of tokens: the only part that reads D-wide data, and free of any
+// dependence between tokens, so a whole prompt chunk goes in one launch.  In
+// bf16 it is a [tokens x D] x [D x 3d'] contraction on the matrix cores
+// (16x16x32 tiles: 16 tokens x 16 gate rows), cut along D into `ksplit` slices
+// so that a decode step (16 tokens) still spreads over many compute units; the
+// slices are added up in a fixed order by the cell kernel.  ctrl_cell does the
+// recurrent part token by token: W_hh z, the gates, the MLP and the score.
 // All sums are fp32 in a fixed order, so results are reproducible run to run.
 #include "device_utils.h"
 
@@ -16,6 +20,53 @@ namespace adore {
 
 namespace {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- input projection, bf16, matrix cores -----------------------------------------
+// grid (3d'/16, ceil(ntok/16), ksplit), 256 threads.  The workgroup owns a 16-token x 16-row
+// tile and the D-slice z; its 4 waves cut the slice again and are summed through LDS.
+// Inside a wave, lane group g = lane/16 walks the g-th quarter of the wave's k-range in
+// 16-byte steps (both operands use the same assignment, so the order of k does not matter).
+// part[z][tok][j] = sum over the slice of W_ih[j][k] * x_tok[k].
+__global__ __launch_bounds__(256) void ctrl_input_mfma_kernel(const bf16_t *__restrict__ W_ih,
+                                                              const bf16_t *__restrict__ x,
+                                                              float *__restrict__ part, int D, int G3, int ntok,
+                                                              int per_seq, int seq_rows, int kslice) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j0 = blockIdx.x * 16, t0 = blockIdx.y * 16;
+  const int kw = kslice / 4;                       // k-range of one wave, a multiple of 32
+  const int kbeg = blockIdx.z * kslice + wave * kw + (lane >> 4) * (kw / 4);
+  int tok = t0 + (lane & 15);
+  if (tok >= ntok) tok = ntok - 1;                 // padded rows read a valid token; dropped at the store
+  const size_t xrow = size_t(tok / per_seq) * seq_rows + tok % per_seq;
+  int j = j0 + (lane & 15);
+  if (j >= G3) j = G3 - 1;
+  const u32x4 *pa = reinterpret_cast<const u32x4 *>(x + xrow * D + kbeg);
+  const u32x4 *pb = reinterpret_cast<const u32x4 *>(W_ih + size_t(j) * D + kbeg);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const int steps = kw / 32;                       // each MFMA consumes 32 k: 8 per lane group
+  for (int s = 0; s < steps; ++s) {
+    const u32x4 va = pa[s], vb = pb[s];
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&va),
+                                                  *reinterpret_cast<const bf16x8 *>(&vb), acc, 0, 0, 0);
+  }
+  // accumulator element v of lane L: token 4*(L/16) + v, gate row L%16
+  __shared__ float red[4][16][17];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) red[wave][4 * (lane >> 4) + v][lane & 15] = acc[v];
+  __syncthreads();
+  {
+    const int m = tid >> 4, nn = tid & 15;
+    if (t0 + m < ntok && j0 + nn < G3) {
+      const float s = (red[0][m][nn] + red[1][m][nn]) + (red[2][m][nn] + red[3][m][nn]);
+      part[(size_t(blockIdx.z) * ntok + t0 + m) * G3 + j0 + nn] = s;
+    }
+  }
+}
+
+// ---- input projection, any storage type, plain ALUs ---------------------------------
 constexpr int JT = 4;  // gate rows per workgroup
 constexpr int NB = 8;  // tokens per workgroup
 
@@ -84,15 +135,116 @@ struct CellArgs {
   const void *W_hh;            // [3d'][d'] storage type
   const float *b_ih, *b_hh;    // [3d']
   const float *pos_w, *pos_b, *W1, *b1, *out_w, *out_b;
-  const float *gi;             // [B*nsteps][3d'], token (b, i) at row b*nsteps + i
+  const float *gi;             // [ksplit][B*nsteps][3d'], token (b, i) at row b*nsteps + i
   float *z;                    // [B][d']
   float *score;                // [B][N_max]
   const float *override_;      // [B][override_stride] or null
   int override_stride;
-  int dp, nsteps, pos0, N_max;
+  int dp, nsteps, pos0, N_max, ksplit, ntok;
   float pos_scale;
 };
 
+// sum of the D-slices of one input pre-activation, in slice order
+__device__ inline float gi_sum(const CellArgs &a, size_t tok, int j) {
+  float s = 0.f;
+  for (int k = 0; k < a.ksplit; ++k) s += a.gi[(size_t(k) * a.ntok + tok) * 3 * a.dp + j];
+  return s;
+}
+
+// ---- cell, d' fixed at compile time: every weight row lives in the registers of one thread ----
+// One workgroup of 4*DP threads per sequence.  Thread t < 3*DP owns row t of W_hh, thread
+// 3*DP + j owns row j of W_1; rows are loaded once and reused for every token of the launch.
+template <typename T, int DP>
+__global__ __launch_bounds__(4 * DP) void ctrl_cell_rows_kernel(const CellArgs a) {
+  constexpr int EPL = Vec16<T>::EPL;
+  __shared__ __attribute__((aligned(16))) float h[DP];
+  __shared__ __attribute__((aligned(16))) float t_in[DP];
+  __shared__ float gh[3 * DP];
+  __shared__ float red[DP / 64];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  float wrow[DP];
+  if (tid < 3 * DP) {
+    const T *src = static_cast<const T *>(a.W_hh) + size_t(tid) * DP;
+#pragma unroll
+    for (int c = 0; c < DP; c += EPL) {
+      float f[EPL];
+      Vec16<T>::load(src + c, f);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) wrow[c + e] = f[e];
+    }
+  } else {
+    const float *src = a.W1 + size_t(tid - 3 * DP) * DP;
+#pragma unroll
+    for (int c = 0; c < DP; c += 4) {
+      float f[4];
+      Vec16<float>::load(src + c, f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) wrow[c + e] = f[e];
+    }
+  }
+  const float bias = tid < 3 * DP ? a.b_hh[tid] : a.b1[tid - 3 * DP];
+  const float ow = tid < 3 * DP ? 0.f : a.out_w[tid - 3 * DP];
+  if (tid < DP) h[tid] = a.z[size_t(b) * DP + tid];
+  __syncthreads();
+
+  for (int i = 0; i < a.nsteps; ++i) {
+    const size_t tok = size_t(b) * a.nsteps + i;
+    float g_r = 0.f, g_u = 0.f, g_n = 0.f;
+    if (tid < DP) {   // issue the loads of the input pre-activations before the row product
+      g_r = gi_sum(a, tok, tid) + a.b_ih[tid];
+      g_u = gi_sum(a, tok, DP + tid) + a.b_ih[DP + tid];
+      g_n = gi_sum(a, tok, 2 * DP + tid) + a.b_ih[2 * DP + tid];
+    }
+    if (tid < 3 * DP) {
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+      for (int c = 0; c < DP; c += 4) {
+        const float4 hv = *reinterpret_cast<const float4 *>(&h[c]);
+        s0 = fmaf(wrow[c], hv.x, s0);
+        s1 = fmaf(wrow[c + 1], hv.y, s1);
+        s2 = fmaf(wrow[c + 2], hv.z, s2);
+        s3 = fmaf(wrow[c + 3], hv.w, s3);
+      }
+      gh[tid] = ((s0 + s1) + (s2 + s3)) + bias;
+    }
+    __syncthreads();
+    if (tid < DP) {
+      const float r = sigmoidf_(g_r + gh[tid]);
+      const float u = sigmoidf_(g_u + gh[DP + tid]);
+      const float cand = tanhf(g_n + r * gh[2 * DP + tid]);
+      const float hnew = (1.0f - u) * cand + u * h[tid];
+      const float delta = float(a.pos0 + i) * a.pos_scale;
+      h[tid] = hnew;
+      t_in[tid] = fmaf(a.pos_w[tid], delta, a.pos_b[tid]) + hnew;
+    }
+    __syncthreads();
+    if (tid >= 3 * DP) {
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+      for (int c = 0; c < DP; c += 4) {
+        const float4 tv = *reinterpret_cast<const float4 *>(&t_in[c]);
+        s0 = fmaf(wrow[c], tv.x, s0);
+        s1 = fmaf(wrow[c + 1], tv.y, s1);
+        s2 = fmaf(wrow[c + 2], tv.z, s2);
+        s3 = fmaf(wrow[c + 3], tv.w, s3);
+      }
+      const float part = wave_sum(ow * tanhf(((s0 + s1) + (s2 + s3)) + bias));
+      if (lane == 0) red[(tid - 3 * DP) >> 6] = part;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      float s = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < DP / 64; ++wv) s += red[wv];
+      float sig = sigmoidf_(s + a.out_b[0]);
+      if (a.override_) sig = a.override_[size_t(b) * a.override_stride + i];
+      a.score[size_t(b) * a.N_max + a.pos0 + i] = sig;
+    }
+  }
+  if (tid < DP) a.z[size_t(b) * DP + tid] = h[tid];
+}
+
+// ---- cell, any d' -------------------------------------------------------------------
 // One workgroup per sequence; loops over `nsteps` consecutive tokens starting at position pos0.
 template <typename T>
 __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
@@ -112,7 +264,7 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
   __syncthreads();
 
   for (int i = 0; i < a.nsteps; ++i) {
-    const float *gi = a.gi + (size_t(b) * a.nsteps + i) * 3 * dp;
+    const size_t tok = size_t(b) * a.nsteps + i;
     // recurrent pre-activations: one wave per row, lanes along the row
     for (int row = wave; row < 3 * dp; row += nwaves) {
       float s = 0.f;
@@ -123,9 +275,9 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
     __syncthreads();
     const float delta = float(a.pos0 + i) * a.pos_scale;
     for (int j = tid; j < dp; j += blockDim.x) {
-      const float r = sigmoidf_(gi[j] + a.b_ih[j] + gh[j]);
-      const float u = sigmoidf_(gi[dp + j] + a.b_ih[dp + j] + gh[dp + j]);
-      const float cand = tanhf(gi[2 * dp + j] + a.b_ih[2 * dp + j] + r * gh[2 * dp + j]);
+      const float r = sigmoidf_(gi_sum(a, tok, j) + a.b_ih[j] + gh[j]);
+      const float u = sigmoidf_(gi_sum(a, tok, dp + j) + a.b_ih[dp + j] + gh[dp + j]);
+      const float cand = tanhf(gi_sum(a, tok, 2 * dp + j) + a.b_ih[2 * dp + j] + r * gh[2 * dp + j]);
       const float hnew = (1.0f - u) * cand + u * h[j];
       hn[j] = hnew;
       t_in[j] = fmaf(a.pos_w[j], delta, a.pos_b[j]) + hnew;
@@ -154,18 +306,38 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
   for (int j = tid; j < dp; j += blockDim.x) a.z[size_t(b) * dp + j] = h[j];
 }
 
+// Number of D-slices of the bf16 input projection: enough workgroups to cover the chip when
+// there are few tokens, one slice when there are many.  A slice is a multiple of 128 (4 waves x 32).
+int ctrl_input_ksplit(const adore_config &c, int ntok) {
+  const int tiles = ((3 * c.ctrl_hidden + 15) / 16) * ((ntok + 15) / 16);
+  int ks = 1;
+  if (ntok > kCtrlSplitTokens) return 1;
+  while (ks < kMaxCtrlSplit && tiles * ks < 256 && c.hidden % (ks * 2 * 128) == 0) ks *= 2;
+  return ks;
+}
+
 }  // namespace
 
-hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows) {
+hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows,
+                             int *ksplit_out) {
   const adore_config &c = ctx->cfg;
   const int G3 = 3 * c.ctrl_hidden;
-  dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_INPUT);
-  if (c.dtype == ADORE_BF16) {
+  *ksplit_out = 1;
+  if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0) {
+    const int ks = ctrl_input_ksplit(c, ntok);
+    *ksplit_out = ks;
+    dim3 grid((G3 + 15) / 16, (ntok + 15) / 16, ks);
+    hipLaunchKernelGGL(ctrl_input_mfma_kernel, grid, dim3(256), 0, ctx->stream,
+                       static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
+                       c.hidden, G3, ntok, per_seq, seq_rows, c.hidden / ks);
+  } else if (c.dtype == ADORE_BF16) {
+    dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
     hipLaunchKernelGGL((ctrl_input_kernel<bf16_t>), grid, dim3(256), 0, ctx->stream,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
   } else {
+    dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
     hipLaunchKernelGGL((ctrl_input_kernel<float>), grid, dim3(256), 0, ctx->stream,
                        static_cast<const float *>(ctx->w.gru_w_ih), static_cast<const float *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
@@ -174,7 +346,7 @@ hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_se
 }
 
 hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *score_override,
-                            int override_stride) {
+                            int override_stride, int ksplit) {
   const adore_config &c = ctx->cfg;
   CellArgs a;
   a.W_hh = ctx->w.gru_w_hh;
@@ -185,13 +357,22 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *s
   a.gi = ctx->gi; a.z = ctx->z; a.score = ctx->score;
   a.override_ = score_override; a.override_stride = override_stride;
   a.dp = c.ctrl_hidden; a.nsteps = nsteps; a.pos0 = pos0; a.N_max = c.max_positions;
+  a.ksplit = ksplit; a.ntok = c.batch * nsteps;
   a.pos_scale = c.pos_scale;
-  const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL);
-  if (c.dtype == ADORE_BF16) {
-    hipLaunchKernelGGL((ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+  if (c.ctrl_hidden == 128) {
+    if (c.dtype == ADORE_BF16) {
+      hipLaunchKernelGGL((ctrl_cell_rows_kernel<bf16_t, 128>), dim3(c.batch), dim3(512), 0, ctx->stream, a);
+    } else {
+      hipLaunchKernelGGL((ctrl_cell_rows_kernel<float, 128>), dim3(c.batch), dim3(512), 0, ctx->stream, a);
+    }
   } else {
-    hipLaunchKernelGGL((ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+    const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);
+    if (c.dtype == ADORE_BF16) {
+      hipLaunchKernelGGL((ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+    } else {
+      hipLaunchKernelGGL((ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+    }
   }
   return hipGetLastError();
 }

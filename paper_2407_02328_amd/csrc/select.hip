@@ -8,8 +8,8 @@
 //                   rank rho -> rho-th lowest free slot of every head
 //
 // Ranking uses the 64-bit integer key of device_utils.h, so every selection has
-// exactly one answer and is reproducible bit for bit.  Release ranks the K keys
-// of a row against each other in LDS (one slot per thread, K <= 1024).  The
+// exactly one answer and is reproducible bit for bit.  Release is a wave-level
+// binary radix select over the K keys of a row held in registers (K <= 1024).  The
 // per-sequence choice is a most-significant-digit radix select over up to N_max
 // keys with 8-bit digits and an LDS histogram; it stops as soon as the digit
 // bucket holding the r-th key is taken whole.
@@ -18,29 +18,6 @@
 namespace adore {
 
 namespace {
-
-constexpr uint64_t kNoKey = ~uint64_t(0);
-
-// ---- block-wide helpers ------------------------------------------------------
-
-// Exclusive prefix of `flag` over the workgroup in thread order; *total gets the count.
-// s_cnt needs blockDim/64 ints.  Ends with a barrier.
-__device__ inline int block_rank_of_flag(bool flag, int *s_cnt, int *total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-  const uint64_t bal = __ballot(flag);
-  const int within = __popcll(bal & ((uint64_t(1) << lane) - 1));
-  if (lane == 0) s_cnt[wave] = __popcll(bal);
-  __syncthreads();
-  int before = 0, all = 0;
-  for (int wv = 0; wv < nwaves; ++wv) {
-    const int cw = s_cnt[wv];
-    if (wv < wave) before += cw;
-    all += cw;
-  }
-  __syncthreads();
-  *total = all;
-  return before + within;
-}
 
 // Radix select.  key_of(i) for i in [0, ncand) returns the key of candidate i or 0
 // if i is not a candidate.  Finds (*thr, *shift) such that exactly c candidates
@@ -125,40 +102,103 @@ __device__ inline void collect_sorted(KeyFn key_of, int ncand, int c, uint64_t t
 }
 
 // ---- release -------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void release_kernel(int32_t *__restrict__ slot_pos,
-                                                       const float *__restrict__ score,
-                                                       int32_t *__restrict__ free_list,
-                                                       int32_t *__restrict__ released_pos, int K, int H,
-                                                       int N_max, int n, int x, int R1) {
-  extern __shared__ uint64_t s_keys[];  // [K]
-  __shared__ int s_cnt[16];
-  const int bh = blockIdx.x, b = bh / H;
-  const int k = threadIdx.x;
-  int pos = -1;
-  uint64_t key = kNoKey;
-  if (k < K) {
-    pos = slot_pos[size_t(bh) * K + k];
-    if (pos >= 0 && pos != n) key = rank_key(score[size_t(b) * N_max + pos], pos);
-    s_keys[k] = key;
+// One wave per (b,h) row, no LDS, no barriers.  Lane L holds the keys of slots L, L+64, ...
+// (KPL per lane).  The x lowest keys are found by a binary radix select from the top bit
+// down: a ballot counts the candidates whose bit is 0; if there are at least `need` of them
+// the ones drop out, otherwise all zeros are taken and the search goes on among the ones.
+// Bits on which all candidates agree are skipped.  Keys are distinct, so exactly x are taken.
+template <int KPL>
+__global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot_pos,
+                                                      const float *__restrict__ score,
+                                                      int32_t *__restrict__ free_list,
+                                                      int32_t *__restrict__ released_pos, int rows, int K,
+                                                      int H, int N_max, int n, int x, int R1) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;                      // whole wave leaves together
+  const int lane = threadIdx.x & 63;
+  const int b = row / H;
+  int32_t *sp = slot_pos + size_t(row) * K;
+  const float *sc = score + size_t(b) * N_max;
+
+  int pos[KPL];
+  uint32_t khi[KPL], klo[KPL];
+  uint32_t cand = 0;                            // bit j: slot j*64+lane holds a releasable token
+  uint32_t or_hi = 0, or_lo = 0, and_hi = ~0u, and_lo = ~0u;
+#pragma unroll
+  for (int j = 0; j < KPL; ++j) {
+    const int k = j * 64 + lane;
+    pos[j] = k < K ? sp[k] : -1;
   }
-  __syncthreads();
-  bool rel = false;
-  if (k < K && key != kNoKey && x > 0) {
-    int rank = 0;  // number of candidates ranked below this one
-#pragma unroll 8
-    for (int j = 0; j < K; ++j) rank += s_keys[j] < key;
-    rel = rank < x;
+#pragma unroll
+  for (int j = 0; j < KPL; ++j) {
+    khi[j] = klo[j] = 0;
+    if (pos[j] >= 0 && pos[j] != n) {
+      const uint64_t key = rank_key(sc[pos[j]], pos[j]);
+      khi[j] = uint32_t(key >> 32);
+      klo[j] = uint32_t(key);
+      cand |= 1u << j;
+      or_hi |= khi[j]; or_lo |= klo[j];
+      and_hi &= khi[j]; and_lo &= klo[j];
+    }
   }
-  const bool free_after = k < K && (pos < 0 || rel);
-  int total;
-  const int fidx = block_rank_of_flag(free_after, s_cnt, &total);
-  if (free_after && fidx < R1) free_list[size_t(bh) * R1 + fidx] = k;
-  const int ridx = block_rank_of_flag(rel, s_cnt, &total);
-  if (rel) {
-    released_pos[size_t(bh) * R1 + ridx] = pos;
-    slot_pos[size_t(bh) * K + k] = -1;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    or_hi |= __shfl_xor(or_hi, off, 64); or_lo |= __shfl_xor(or_lo, off, 64);
+    and_hi &= __shfl_xor(and_hi, off, 64); and_lo &= __shfl_xor(and_lo, off, 64);
   }
-  if (k >= total && k < R1) released_pos[size_t(bh) * R1 + k] = -1;
+  const uint32_t diff_hi = or_hi & ~and_hi, diff_lo = or_lo & ~and_lo;   // bits that tell candidates apart
+
+  uint32_t active = cand, sel = 0;
+  int need = x;
+  if (need > 0) {
+#pragma unroll 1
+    for (int word = 1; word >= 0 && need > 0; --word) {
+      uint32_t diff = word ? diff_hi : diff_lo;
+      while (diff != 0 && need > 0) {
+        const int bit = 31 - __clz(diff);
+        diff &= ~(1u << bit);
+        uint32_t zero = 0;                      // active candidates of this lane whose bit is 0
+        int cnt0 = 0;
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+          const uint32_t kw = word ? khi[j] : klo[j];
+          const bool z = ((active >> j) & 1u) && !((kw >> bit) & 1u);
+          zero |= uint32_t(z) << j;
+          cnt0 += __popcll(__ballot(z));
+        }
+        if (cnt0 >= need) {
+          active = zero;                        // the answer lies among the zeros
+        } else {
+          sel |= zero;                          // all zeros are taken, go on among the ones
+          active &= ~zero;
+          need -= cnt0;
+        }
+      }
+    }
+    if (need > 0) sel |= active;                // what is left is exactly `need` keys
+  }
+
+  // ascending slot order = j major, lane minor
+  int nfree = 0, nrel = 0;
+#pragma unroll
+  for (int j = 0; j < KPL; ++j) {
+    const int k = j * 64 + lane;
+    const bool rel = (sel >> j) & 1u;
+    const bool free_after = k < K && (pos[j] < 0 || rel);
+    const uint64_t bf = __ballot(free_after), br = __ballot(rel);
+    const uint64_t below = (uint64_t(1) << lane) - 1;
+    if (free_after) {
+      const int idx = nfree + __popcll(bf & below);
+      if (idx < R1) free_list[size_t(row) * R1 + idx] = k;
+    }
+    if (rel) {
+      released_pos[size_t(row) * R1 + nrel + __popcll(br & below)] = pos[j];
+      sp[k] = -1;
+    }
+    nfree += __popcll(bf);
+    nrel += __popcll(br);
+  }
+  for (int t = nrel + lane; t < R1; t += 64) released_pos[size_t(row) * R1 + t] = -1;
 }
 
 // ---- per-sequence choice of the tokens to rebuild -------------------------------
@@ -348,11 +388,18 @@ int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 hipError_t launch_release(adore_ctx *ctx, int x) {
   const adore_config &c = ctx->cfg;
-  const int threads = round_up64(max(c.cache_slots, c.rebuild_budget + 1));
+  const int rows = c.batch * c.heads;
+  const dim3 grid((rows + 3) / 4), block(256);
   ScopedTimer t(ctx, ADORE_KERNEL_RELEASE);
-  hipLaunchKernelGGL(release_kernel, dim3(c.batch * c.heads), dim3(threads), size_t(c.cache_slots) * 8,
-                     ctx->stream, ctx->slot_pos, ctx->score, ctx->free_list, ctx->released_pos, c.cache_slots,
-                     c.heads, c.max_positions, ctx->n, x, c.rebuild_budget + 1);
+#define ADORE_RELEASE(KPL)                                                                                  \
+  hipLaunchKernelGGL((release_kernel<KPL>), grid, block, 0, ctx->stream, ctx->slot_pos, ctx->score,          \
+                     ctx->free_list, ctx->released_pos, rows, c.cache_slots, c.heads, c.max_positions, ctx->n, \
+                     x, c.rebuild_budget + 1)
+  if (c.cache_slots <= 128) ADORE_RELEASE(2);
+  else if (c.cache_slots <= 256) ADORE_RELEASE(4);
+  else if (c.cache_slots <= 512) ADORE_RELEASE(8);
+  else ADORE_RELEASE(16);
+#undef ADORE_RELEASE
   return hipGetLastError();
 }
 

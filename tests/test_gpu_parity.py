@@ -216,3 +216,15 @@ def test_state_machine_on_device():
         job.adore.attend(0, q[0].float().double(), k[0], v[0], job.out[0])   # wrong dtype caught by the binding
     torch.cuda.synchronize()
     job.adore.close()
+
+
+@pytest.mark.parametrize("split,waves", [(1, 4), (1, 16), (2, 8), (4, 4), (3, 16)])
+def test_attention_launch_shapes(split, waves, monkeypatch):
+    """Every split count / workgroup width of the attention kernel gives the oracle's result."""
+    h = _harness()
+    monkeypatch.setenv("ADORE_ATTEND_SPLIT", str(split))
+    monkeypatch.setenv("ADORE_ATTEND_WAVES", str(waves))
+    w = Workload("shapes", L=1, B=2, H=3, d=128, D=256, K=300, R=7, S=400, T=6, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T)
+    assert job.adore.cfg.cache_slots == 300
+    job.adore.close()
