@@ -13,8 +13,11 @@
 // (v_mfma_f32_32x32x16_bf16).  Both operands are contiguous along the reduction
 // dimension, which is exactly the per-lane operand layout of that instruction
 // (8 consecutive k for one row), so tiles go global -> LDS -> registers as
-// 16-byte vectors with no transposes.  128x128 output tile per workgroup, four
-// waves of 64x64, BK = 64, LDS double-buffered and XOR-swizzled.
+// 16-byte vectors with no transposes.  128x128 output tile per workgroup (one
+// per compute unit at the 7B shape: M = 512, N = 8192), BK = 64, LDS
+// triple-buffered and XOR-swizzled (conflict-free for 16-byte reads and writes).
+// The output tile is rounded to bf16 into LDS and leaves as 16-byte vectors: a
+// row of the tile is a contiguous head slice of one cache row.
 // fp32 path (and shapes the tile kernel does not take): one wave per output.
 #include "device_utils.h"
 
@@ -38,17 +41,29 @@ struct GemmArgs {
 
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int CH = BK / 8;   // 16-byte chunks per tile row
+constexpr int LS = 3;        // LDS stages
 
 __device__ inline int swz(int row, int chunk) { return row * CH + (chunk ^ ((row >> 1) & 7)); }
 
-template <int NS>   // register stages: tiles of k-steps ks+1 .. ks+NS are in flight while ks is multiplied
-__global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
-  __shared__ u32x4 sA[2][BM * CH];
-  __shared__ u32x4 sB[2][BN * CH];
+// Workgroup = 8 waves on a 128x128 output tile.  Waves 0-3 and 4-7 form two k-groups: each group
+// holds the whole tile as four 64x64 wave tiles and multiplies one half of every 64-wide k-step, so
+// the LDS read traffic is that of four waves while every SIMD has two waves to switch between.  The
+// two halves are added through LDS at the end.
+//   global -> registers: NS k-steps ahead (NS register sets, refilled right after they are spilled to LDS)
+//   registers -> LDS:    three stages, so the tile of step ks+2 is written while ks is read and ks+1 is
+//                        already complete; one barrier per k-step, and the first fragments of the next
+//                        step are fetched before it
+//   LDS -> fragments:    one 16-wide k-slice ahead of the MFMAs that use them
+// sched_barrier keeps the compiler from sinking the fragment loads below the MFMAs they overlap with.
+template <int NS>
+__global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
+  // one LDS block: LS stages of (A tile, B tile); after the k-loop the first 64 KB carry the upper
+  // k-group's accumulators and the last 32 KB the bf16 output tile
+  __shared__ u32x4 smem[LS * (BM + BN) * CH];
+  __shared__ long long s_dst[BM * (BN / 64)];   // element offset of each output row slice in the cache, -1 = none
+  u32x4 (*sA)[BM * CH] = reinterpret_cast<u32x4 (*)[BM * CH]>(smem);
+  u32x4 (*sB)[BN * CH] = reinterpret_cast<u32x4 (*)[BN * CH]>(smem + LS * BM * CH);
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-  // tiles in which the M-tiles of one W panel are neighbours, so a panel is fetched
-  // into one L2 only.
   const int total = a.tiles_m * a.tiles_n;
   const int per_xcd = (total + 7) / 8;
   const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -57,41 +72,78 @@ __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int kgrp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
 
-  // ---- global -> register staging: 4 chunks of A and 4 of B per thread and k-step ----
-  const int lchunk = tid & 7, lrow = tid >> 3;   // rows lrow + 32*i
-  const u32x4 *gA[4], *gB[4];
+  // where every row of the output tile goes: looked up now, used after the k-loop
+  const int Hd = a.H * a.d;
+  const int nh = BN / a.d > 0 ? BN / a.d : 1;     // heads covered by the tile's 128 columns (d = 64: 2, d >= 128: 1)
+  if (tid < BM * nh) {
+    const int row = tid / nh, hh = tid - row * nh;
+    const int mi = m0 + row;
+    long long off = -1;
+    if (mi < a.M) {
+      const int b = mi / a.r, rho = mi - b * a.r;
+      const int nf = n0 + hh * a.d;
+      const int rem = nf % Hd;
+      const int h = rem / a.d;
+      const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
+      off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+    }
+    s_dst[tid] = off;
+  }
+  const int lchunk = tid & 7, lrow = tid >> 3;   // rows lrow + 64*i
+  const u32x4 *gA[2], *gB[2];
   const bf16_t *X = static_cast<const bf16_t *>(a.X);
   const bf16_t *W = static_cast<const bf16_t *>(a.W);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int mi = m0 + lrow + 32 * i;
-    size_t src_row = 0;   // rows past M read a valid row and are dropped in the epilogue
+  for (int i = 0; i < 2; ++i) {
+    const int mi = m0 + lrow + 64 * i;
+    size_t src_row = 0;
     if (mi < a.M) {
       const int b = mi / a.r, rho = mi - b * a.r;
       src_row = size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + rho];
     }
     gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
-    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + lrow + 32 * i) * a.D) + lchunk;
+    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + lrow + 64 * i) * a.D) + lchunk;
   }
   const int nk = a.D / BK;
-  u32x4 ra[NS][4], rb[NS][4];
-#define ADORE_GLOAD(SET, KS)                    \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) { \
-    ra[SET][i] = gA[i][(KS) * CH];              \
-    rb[SET][i] = gB[i][(KS) * CH];              \
+  u32x4 ra[NS][2], rb[NS][2];
+#define GLOAD(SET, KS)                                              \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                   \
+    ra[SET][i] = gA[i][(KS) * CH];                                  \
+    rb[SET][i] = gB[i][(KS) * CH];                                  \
   }
-#define ADORE_LSTORE(SET, ST)                                 \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {             \
-    sA[ST][swz(lrow + 32 * i, lchunk)] = ra[SET][i];          \
-    sB[ST][swz(lrow + 32 * i, lchunk)] = rb[SET][i];          \
+#define LSTORE(SET, ST)                                             \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                   \
+    sA[ST][swz(lrow + 64 * i, lchunk)] = ra[SET][i];                \
+    sB[ST][swz(lrow + 64 * i, lchunk)] = rb[SET][i];                \
+  }
+#define FRAGS(FA, FB, ST, KK)                                                         \
+  {                                                                                   \
+    const int ch_ = (KK) * 2 + (lane >> 5);                                           \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                   \
+      const u32x4 va_ = sA[ST][swz(wm * 64 + i * 32 + (lane & 31), ch_)];             \
+      const u32x4 vb_ = sB[ST][swz(wn * 64 + i * 32 + (lane & 31), ch_)];             \
+      FA[i] = *reinterpret_cast<const bf16x8 *>(&va_);                                \
+      FB[i] = *reinterpret_cast<const bf16x8 *>(&vb_);                                \
+    }                                                                                 \
+  }
+#define MFMA4(FA, FB)                                                                 \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i)                                       \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                     \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);
+
+  // prologue: tiles 0 and 1 to LDS, tiles 2 .. NS+1 into the register sets (set of tile t = t % NS)
+  GLOAD(0, 0)
+  LSTORE(0, 0)
+  if (nk > 1) {
+    GLOAD(1 % NS, 1)
+    LSTORE(1 % NS, 1)
   }
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    if (s < nk) { ADORE_GLOAD(s, s) }
+    if (s + 2 < nk) { GLOAD((s + 2) % NS, s + 2) }
   }
-  ADORE_LSTORE(0, 0)
   __syncthreads();
 
   f32x16 acc[2][2];
@@ -102,61 +154,89 @@ __global__ __launch_bounds__(256) void rebuild_mfma_kernel(const GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  for (int ks0 = 0; ks0 < nk; ks0 += NS) {
+  const int kk0 = 2 * kgrp, kk1 = 2 * kgrp + 1;
+  bf16x8 fa0[2], fb0[2], fa1[2], fb1[2];
+  FRAGS(fa0, fb0, 0, kk0)
+  int st = 0;   // LDS stage of tile ks
+  // One k-step.  IF(c) guards the parts that run out near the end; it is empty in the steady loop so
+  // that the loop body is a single basic block (the wait counters are then tracked exactly).
+#define KSTEP(U, KS, IF)                                                         \
+  {                                                                              \
+    const int st1 = st == LS - 1 ? 0 : st + 1;                                   \
+    const int st2 = st1 == LS - 1 ? 0 : st1 + 1;                                 \
+    FRAGS(fa1, fb1, st, kk1)                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                           \
+    MFMA4(fa0, fb0)                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                           \
+    IF((KS) + 2 < nk) { LSTORE(((U) + 2) % NS, st2) }                            \
+    IF((KS) + 2 + NS < nk) { GLOAD(((U) + 2) % NS, (KS) + 2 + NS) }              \
+    IF((KS) + 1 < nk) { FRAGS(fa0, fb0, st1, kk0) }                              \
+    __builtin_amdgcn_sched_barrier(0);                                           \
+    MFMA4(fa1, fb1)                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                           \
+    __syncthreads();                                                             \
+    st = st1;                                                                    \
+  }
+#define ALWAYS(c)
+#define GUARDED(c) if (c)
+  const int nk_main = nk >= NS + 2 ? (nk - NS - 2) / NS * NS : 0;   // k-steps that need no guard
+  int ks0 = 0;
+  for (; ks0 < nk_main; ks0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) KSTEP(u, ks0 + u, ALWAYS)
+  }
+  for (; ks0 < nk; ks0 += NS) {
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
-      const int ks = ks0 + u;   // nk is a multiple of NS (checked at launch)
-      {
-        const int st = ks & 1;
-        // register set u went to LDS one step ago: refill it with the tile NS steps ahead
-        if (ks + NS < nk) { ADORE_GLOAD(u, ks + NS) }
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-          const int ch = kk * 2 + (lane >> 5);
-          bf16x8 fa[2], fb[2];
-#pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            const u32x4 va = sA[st][swz(wm * 64 + i * 32 + (lane & 31), ch)];
-            const u32x4 vb = sB[st][swz(wn * 64 + i * 32 + (lane & 31), ch)];
-            fa[i] = *reinterpret_cast<const bf16x8 *>(&va);
-            fb[i] = *reinterpret_cast<const bf16x8 *>(&vb);
-          }
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-        if (ks + 1 < nk) { ADORE_LSTORE((u + 1) % NS, st ^ 1) }
-        __syncthreads();
-      }
+      if (ks0 + u < nk) KSTEP(u, ks0 + u, GUARDED)   // uniform over the workgroup: the barrier inside is safe
     }
   }
+#undef KSTEP
+#undef ALWAYS
+#undef GUARDED
+#undef GLOAD
+#undef LSTORE
+#undef FRAGS
+#undef MFMA4
 
-#undef ADORE_GLOAD
-#undef ADORE_LSTORE
-  // ---- epilogue: round once to bf16 and scatter into the assigned slots ----
+  // ---- add the two k-groups: the upper four waves hand their accumulators over through LDS ----
+  float *red = reinterpret_cast<float *>(smem) + (wave & 3) * 64 * 64 + lane;   // 4 x 16 KB
+  if (kgrp == 1) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[((i * 2 + j) * 16 + v) * 64] = acc[i][j][v];
+  }
+  __syncthreads();
+  // ---- round once to bf16 into a row-major LDS tile ----
   // accumulator element v of lane L: row 8*(v/4) + 4*(L/32) + v%4, column L%32 of its 32x32 block
-  const int Hd = a.H * a.d;
-  bf16_t *Kc = static_cast<bf16_t *>(a.Kc);
-  bf16_t *Vc = static_cast<bf16_t *>(a.Vc);
+  uint16_t *sOut = reinterpret_cast<uint16_t *>(smem) + 64 * 1024 / 2;            // [BM][BN] bf16 = 32 KB
+  if (kgrp == 0) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int nf = n0 + wn * 64 + j * 32 + (lane & 31);
-    const int half = nf / Hd, rem = nf - half * Hd;
-    const int h = rem / a.d, cc = rem - h * a.d;
-    bf16_t *dst_base = half ? Vc : Kc;
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int mi = m0 + wm * 64 + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-        if (mi < a.M) {
-          const int b = mi / a.r, rho = mi - b * a.r;
-          const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
-          dst_base[((size_t(b) * a.H + h) * a.K + slot) * a.d + cc].bits = f32_to_bf16_rne(acc[i][j][v]);
+        for (int v = 0; v < 16; ++v) {
+          const float s = acc[i][j][v] + red[((i * 2 + j) * 16 + v) * 64];
+          const int row = wm * 64 + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+          const int col = wn * 64 + j * 32 + (lane & 31);
+          sOut[row * BN + col] = f32_to_bf16_rne(s);
         }
-      }
+  }
+  __syncthreads();
+  // ---- scatter: every output row slice is contiguous in the cache; 16 bytes per lane ----
+  bf16_t *dst_half = static_cast<bf16_t *>(n0 >= Hd ? a.Vc : a.Kc);
+#pragma unroll
+  for (int i = 0; i < (BM * BN / 8) / 512; ++i) {
+    const int idx = i * 512 + tid;
+    const int row = idx >> 4, vec = idx & 15;            // 16 vectors of 8 columns per row
+    const long long off = s_dst[row * nh + (vec * 8) / a.d];
+    if (off >= 0) {
+      const u32x4 val = *reinterpret_cast<const u32x4 *>(sOut + row * BN + vec * 8);
+      *reinterpret_cast<u32x4 *>(dst_half + off + (vec * 8) % a.d) = val;
     }
   }
 }
@@ -211,14 +291,15 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   a.M = c.batch * r; a.N = 2 * c.heads * c.head_dim;
   a.tiles_m = (a.M + BM - 1) / BM; a.tiles_n = a.N / BN;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM);
-  const bool mfma_ok = c.dtype == ADORE_BF16 && c.hidden % BK == 0 && a.N % BN == 0 && c.head_dim % 32 == 0;
+  const bool mfma_ok = c.dtype == ADORE_BF16 && c.hidden % BK == 0 && (c.heads * c.head_dim) % BN == 0 &&
+                       (BN % c.head_dim == 0 || c.head_dim % BN == 0);
   if (mfma_ok) {
     const int total = a.tiles_m * a.tiles_n;
     const int grid = (total + 7) / 8 * 8;
     const int nk = c.hidden / BK;   // the k-loop is unrolled by the number of register stages
-    if (nk % 4 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<4>), dim3(grid), dim3(256), 0, ctx->stream, a);
-    else if (nk % 2 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<2>), dim3(grid), dim3(256), 0, ctx->stream, a);
-    else hipLaunchKernelGGL((rebuild_mfma_kernel<1>), dim3(grid), dim3(256), 0, ctx->stream, a);
+    if (nk % 4 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<4>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    else if (nk % 2 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<2>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    else hipLaunchKernelGGL((rebuild_mfma_kernel<1>), dim3(grid), dim3(512), 0, ctx->stream, a);
   } else {
     const size_t waves = size_t(a.M) * a.N;
     const unsigned blocks = unsigned((waves + 3) / 4);
