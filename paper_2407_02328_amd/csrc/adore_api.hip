@@ -5,6 +5,15 @@
 // (o), released slots (x) and rebuilt tokens (r) of a step depend only on
 // (n, S, K, R), so the host knows every launch shape without reading results
 // back:  o = occupied_before + 1,  x = max(0, o - m),  r = min(R, n + 1 - min(o, m)).
+//
+// Two streams.  Attention and the rebuild GEMM run on the caller's stream.  The controller and the
+// two selections run on a side stream owned by the context: they depend on neither the attention
+// output nor the cache contents, only on the previous step's selections, so the chain of step n+1
+// runs under the GEMM of step n (and the attention of step n+1).  What makes this safe is the
+// double buffering of slot_pos / insert_slot / free_list / rebuilt_pos by step parity and three
+// events: the chain of a step waits for the previous step's attention (which reads the buffer the
+// chain is about to overwrite), and the GEMM waits for its own step's chain.
+// ADORE_NO_OVERLAP=1 puts everything on the caller's stream.
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -16,7 +25,8 @@ using namespace adore;
 
 namespace adore {
 
-ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel) : ctx_(ctx), stop_(nullptr) {
+ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel, hipStream_t stream)
+    : ctx_(ctx), stream_(stream), stop_(nullptr) {
   if (!ctx->timing) return;
   hipEvent_t ev[2];
   for (int i = 0; i < 2; ++i) {
@@ -28,13 +38,13 @@ ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel) : ctx_(ctx), stop_(nullptr)
       return;
     }
   }
-  (void)hipEventRecord(ev[0], ctx->stream);
+  (void)hipEventRecord(ev[0], stream);
   stop_ = ev[1];
   ctx->timed.push_back(TimedLaunch{kernel, ev[0], ev[1]});
 }
 
 ScopedTimer::~ScopedTimer() {
-  if (ctx_ && stop_) (void)hipEventRecord(stop_, ctx_->stream);
+  if (ctx_ && stop_) (void)hipEventRecord(stop_, stream_);
 }
 
 }  // namespace adore
@@ -73,13 +83,13 @@ Layout make_layout(const adore_config &c) {
   };
   l.cache_k = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
   l.cache_v = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
-  l.slot_pos = take(BH * c.cache_slots * 4);
+  l.slot_pos = take(2 * BH * c.cache_slots * 4);
   l.score = take(size_t(c.batch) * c.max_positions * 4);
   l.z = take(size_t(c.batch) * c.ctrl_hidden * 4);
-  l.insert_slot = take(BH * 4);
-  l.free_list = take(BH * R1 * 4);
+  l.insert_slot = take(2 * align_up(BH * 4));
+  l.free_list = take(2 * align_up(BH * R1 * 4));
   l.released_pos = take(BH * R1 * 4);
-  l.rebuilt_pos = take(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4);
+  l.rebuilt_pos = take(2 * align_up(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4));
   l.init_res = take(size_t(c.batch) * c.cache_slots * 4);
   l.att_part = take(BH * kMaxSplits * (size_t(c.head_dim) + 2) * 4);
   size_t gi_rows = size_t(c.batch) * kPromptChunk;
@@ -104,7 +114,7 @@ void choose_split(adore_ctx *ctx) {
   }
   ctx->nsplit = nsplit;
   ctx->chunk = (c.cache_slots + nsplit - 1) / nsplit;
-  ctx->attend_waves = ctx->chunk >= 512 ? 16 : ctx->chunk >= 256 ? 8 : 4;
+  ctx->attend_waves = ctx->chunk >= 256 ? 8 : 4;   // measured: 16 waves lose to 8 at 512 slots per row
   if (const char *e = getenv("ADORE_ATTEND_WAVES")) {
     const int v = atoi(e);
     if (v == 4 || v == 8 || v == 16) ctx->attend_waves = v;
@@ -116,6 +126,19 @@ void choose_split(adore_ctx *ctx) {
     const hipError_t e_ = (expr);    \
     if (e_ != hipSuccess) return ADORE_E_HIP; \
   } while (0)
+
+// The side stream and its events are made on the first call that touches the GPU, so that a
+// context can be created (and its host-side checks exercised) on a machine without one.
+int ensure_side_stream(adore_ctx *ctx) {
+  if (!ctx->overlap || ctx->side_ready) return ADORE_OK;
+  bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_att[0], hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_att[1], hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
+  if (!ok) return ADORE_E_HIP;
+  ctx->side_ready = true;
+  return ADORE_OK;
+}
 
 void reset_step(adore_ctx *ctx) {
   std::fill(ctx->attended.begin(), ctx->attended.end(), 0);
@@ -153,19 +176,30 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   char *base = static_cast<char *>(workspace);
   ctx->cache_k = base + l.cache_k;
   ctx->cache_v = base + l.cache_v;
-  ctx->slot_pos = reinterpret_cast<int32_t *>(base + l.slot_pos);
+  const size_t BH = size_t(cfg->batch) * cfg->heads;
+  const size_t R1 = size_t(cfg->rebuild_budget) + 1;
+  const size_t Rdim = cfg->rebuild_budget > 0 ? cfg->rebuild_budget : 1;
+  for (int i = 0; i < 2; ++i) {
+    ctx->slot_pos[i] = reinterpret_cast<int32_t *>(base + l.slot_pos + i * BH * cfg->cache_slots * 4);
+    ctx->insert_slot[i] = reinterpret_cast<int32_t *>(base + l.insert_slot + i * align_up(BH * 4));
+    ctx->free_list[i] = reinterpret_cast<int32_t *>(base + l.free_list + i * align_up(BH * R1 * 4));
+    ctx->rebuilt_pos[i] = reinterpret_cast<int32_t *>(base + l.rebuilt_pos + i * align_up(size_t(cfg->batch) * Rdim * 4));
+  }
   ctx->score = reinterpret_cast<float *>(base + l.score);
   ctx->z = reinterpret_cast<float *>(base + l.z);
-  ctx->insert_slot = reinterpret_cast<int32_t *>(base + l.insert_slot);
-  ctx->free_list = reinterpret_cast<int32_t *>(base + l.free_list);
   ctx->released_pos = reinterpret_cast<int32_t *>(base + l.released_pos);
-  ctx->rebuilt_pos = reinterpret_cast<int32_t *>(base + l.rebuilt_pos);
   ctx->init_res = reinterpret_cast<int32_t *>(base + l.init_res);
   ctx->att_part = reinterpret_cast<float *>(base + l.att_part);
   ctx->gi = reinterpret_cast<float *>(base + l.gi);
   ctx->inited = false;
   ctx->n = 0;
   ctx->occ = 0;
+  ctx->cur = 0;
+  const char *no = getenv("ADORE_NO_OVERLAP");
+  ctx->overlap = !(no && atoi(no) != 0);
+  ctx->side = ctx->stream;
+  ctx->ev_att[0] = ctx->ev_att[1] = ctx->ev_join = nullptr;
+  ctx->side_ready = false;
   ctx->attended.assign(cfg->layers, 0);
   ctx->rebuilt.assign(cfg->layers, 0);
   ctx->timing = false;
@@ -182,6 +216,12 @@ int adore_destroy(adore_ctx *ctx) {
     (void)hipEventDestroy(t.stop);
   }
   for (auto &e : ctx->event_pool) (void)hipEventDestroy(e);
+  if (ctx->overlap && ctx->side_ready) {
+    (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamDestroy(ctx->side);
+    for (hipEvent_t e : {ctx->ev_att[0], ctx->ev_att[1], ctx->ev_join})
+      if (e) (void)hipEventDestroy(e);
+  }
   delete ctx;
   return ADORE_OK;
 }
@@ -197,20 +237,30 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   const int pool = S - keep;
   const int r0 = pool < c.rebuild_budget ? pool : c.rebuild_budget;
 
+  // init runs on the caller's stream only; anything a previous job left on the side stream ends first
+  if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
+  if (ctx->overlap) ADORE_TRY(hipStreamSynchronize(ctx->side));
+  hipStream_t st = ctx->stream;
+  ctx->cur = 0;
   // controller over the prompt: z_{-1} = 0, tokens in order, in chunks
   ADORE_TRY(launch_fill_i32(ctx, reinterpret_cast<int32_t *>(ctx->z), 0, size_t(c.batch) * c.ctrl_hidden));
   for (int i0 = 0; i0 < S; i0 += kPromptChunk) {
     const int len = (S - i0 < kPromptChunk) ? S - i0 : kPromptChunk;
     const char *x = static_cast<const char *>(ctrl_input) + size_t(i0) * c.hidden * es;
     int ksplit = 1;
-    ADORE_TRY(launch_ctrl_input(ctx, x, c.batch * len, len, S, &ksplit));
-    ADORE_TRY(launch_ctrl_cell(ctx, len, i0, score_override ? score_override + i0 : nullptr, S, ksplit));
+    ADORE_TRY(launch_ctrl_input(ctx, st, x, c.batch * len, len, S, &ksplit));
+    ADORE_TRY(launch_ctrl_cell(ctx, st, len, i0, score_override ? score_override + i0 : nullptr, S, ksplit));
   }
-  ADORE_TRY(launch_init_select(ctx, S, keep, r0));
+  // slot map and reserved slot go to buffer `cur`, the rebuild lists to `cur ^ 1` (where a step's GEMM reads them)
+  ADORE_TRY(launch_init_select(ctx, ctx->cur, ctx->cur ^ 1, S, keep, r0));
   ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
   const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
   for (int l = 0; l < c.layers; ++l) {
-    ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, r0));
+    ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur ^ 1, r0));
+  }
+  if (ctx->overlap) {   // the first step's selections overwrite the lists the GEMMs above read
+    ADORE_TRY(hipEventRecord(ctx->ev_att[0], st));
+    ADORE_TRY(hipEventRecord(ctx->ev_att[1], st));
   }
   ctx->n = S;
   ctx->occ = keep + r0;
@@ -219,62 +269,93 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   return ADORE_OK;
 }
 
-int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
-                 float *out) {
-  if (!ctx || !q || !k_new || !v_new || !out) return ADORE_E_INVALID;
-  if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
-  if (!ctx->inited || ctx->scheduled || ctx->attended[layer] || ctx->n >= ctx->cfg.max_positions)
-    return ADORE_E_STATE;
+namespace {
+
+// The three stages without the order checks (the public calls do those).
+
+int do_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out) {
   ADORE_TRY(launch_attend(ctx, layer, q, k_new, v_new, out));
   ctx->attended[layer] = 1;
-  ctx->n_attended++;
+  if (++ctx->n_attended == ctx->cfg.layers && ctx->overlap) {
+    ADORE_TRY(hipEventRecord(ctx->ev_att[ctx->cur], ctx->stream));   // buffer `cur` has been read for the last time
+  }
   return ADORE_OK;
 }
 
-int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
-                   int32_t *released_pos, int32_t *rebuilt_pos) {
-  if (!ctx || !x_n) return ADORE_E_INVALID;
+int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
+                int32_t *released_pos, int32_t *rebuilt_pos) {
   const adore_config &c = ctx->cfg;
-  if (!ctx->inited || ctx->scheduled || ctx->n_attended != c.layers) return ADORE_E_STATE;
   const int m = c.cache_slots - c.rebuild_budget - 1;
   const int o = ctx->occ + 1;
   const int x = o > m ? o - m : 0;
   const int kept = o - x;
   const int pool = ctx->n + 1 - kept;
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
+  const int src = ctx->cur, dst = ctx->cur ^ 1;
+  hipStream_t st = ctx->side;
 
+  // buffer `dst` was `cur` one step ago: wait until that step's attention has read it
+  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
   int ksplit = 1;
-  ADORE_TRY(launch_ctrl_input(ctx, x_n, c.batch, 1, 1, &ksplit));
-  ADORE_TRY(launch_ctrl_cell(ctx, 1, ctx->n, score_override, 1, ksplit));
-  ADORE_TRY(launch_release(ctx, x));
-  ADORE_TRY(launch_rebuild_select(ctx, r));
+  ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, 1, &ksplit));
+  ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
+  ADORE_TRY(launch_release(ctx, st, src, dst, x));
+  ADORE_TRY(launch_rebuild_select(ctx, st, dst, r));
   const size_t BH = size_t(c.batch) * c.heads;
   if (slot_map)
-    ADORE_TRY(hipMemcpyAsync(slot_map, ctx->slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    ADORE_TRY(hipMemcpyAsync(slot_map, ctx->slot_pos[dst], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, st));
   if (released_pos)
     ADORE_TRY(hipMemcpyAsync(released_pos, ctx->released_pos, BH * (c.rebuild_budget + 1) * 4,
-                             hipMemcpyDeviceToDevice, ctx->stream));
+                             hipMemcpyDeviceToDevice, st));
   if (rebuilt_pos)
-    ADORE_TRY(hipMemcpyAsync(rebuilt_pos, ctx->rebuilt_pos,
+    ADORE_TRY(hipMemcpyAsync(rebuilt_pos, ctx->rebuilt_pos[dst],
                              size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4,
-                             hipMemcpyDeviceToDevice, ctx->stream));
+                             hipMemcpyDeviceToDevice, st));
+  if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
   ctx->scheduled = true;
   ctx->r_step = r;
   ctx->occ = kept + r;
   return ADORE_OK;
 }
 
+int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
+  if (ctx->n_rebuilt == 0 && ctx->overlap) {
+    // from here on the caller's stream sees everything the selections wrote, outputs included
+    ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+  }
+  ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, ctx->cur ^ 1, ctx->r_step));
+  ctx->rebuilt[layer] = 1;
+  if (++ctx->n_rebuilt == ctx->cfg.layers) {
+    ctx->n++;
+    ctx->cur ^= 1;
+    reset_step(ctx);
+  }
+  return ADORE_OK;
+}
+
+}  // namespace
+
+int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                 float *out) {
+  if (!ctx || !q || !k_new || !v_new || !out) return ADORE_E_INVALID;
+  if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
+  if (!ctx->inited || ctx->scheduled || ctx->attended[layer] || ctx->n >= ctx->cfg.max_positions)
+    return ADORE_E_STATE;
+  return do_attend(ctx, layer, q, k_new, v_new, out);
+}
+
+int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
+                   int32_t *released_pos, int32_t *rebuilt_pos) {
+  if (!ctx || !x_n) return ADORE_E_INVALID;
+  if (!ctx->inited || ctx->scheduled || ctx->n_attended != ctx->cfg.layers) return ADORE_E_STATE;
+  return do_schedule(ctx, x_n, score_override, slot_map, released_pos, rebuilt_pos);
+}
+
 int adore_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
   if (!ctx || !hidden_store_layer) return ADORE_E_INVALID;
   if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
   if (!ctx->inited || !ctx->scheduled || ctx->rebuilt[layer]) return ADORE_E_STATE;
-  ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, ctx->r_step));
-  ctx->rebuilt[layer] = 1;
-  if (++ctx->n_rebuilt == ctx->cfg.layers) {
-    ctx->n++;
-    reset_step(ctx);
-  }
-  return ADORE_OK;
+  return do_rebuild(ctx, layer, hidden_store_layer);
 }
 
 int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new,
@@ -284,11 +365,13 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
   if (ctx->cfg.layers != 1) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
-  int rc = adore_attend(ctx, 0, q, k_new, v_new, out);
+  // The selections do not depend on this step's attention: enqueue them first so that they start
+  // while the previous step's GEMM is still running.
+  int rc = do_schedule(ctx, x_n, score_override, slot_map, nullptr, nullptr);
   if (rc != ADORE_OK) return rc;
-  rc = adore_schedule(ctx, x_n, score_override, slot_map, nullptr, nullptr);
+  rc = do_attend(ctx, 0, q, k_new, v_new, out);
   if (rc != ADORE_OK) return rc;
-  return adore_rebuild(ctx, 0, hidden_store);
+  return do_rebuild(ctx, 0, hidden_store);
 }
 
 int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, void *cache_k, void *cache_v,
@@ -300,7 +383,8 @@ int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, 
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
   if (step) *step = ctx->n;
   if (slot_pos)
-    ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos[ctx->cur], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
+                             ctx->stream));
   if (scores)
     ADORE_TRY(hipMemcpyAsync(scores, ctx->score, size_t(c.batch) * c.max_positions * 4, hipMemcpyDeviceToDevice,
                              ctx->stream));
@@ -319,6 +403,8 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   if (ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
   const size_t BH = size_t(c.batch) * c.heads;
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
+  if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
+  if (ctx->overlap) ADORE_TRY(hipStreamSynchronize(ctx->side));
   // count the occupied slots and find the reserved slot of every row on the host
   std::vector<int32_t> host(BH * c.cache_slots);
   ADORE_TRY(hipMemcpyAsync(host.data(), slot_pos, host.size() * 4, hipMemcpyDeviceToHost, ctx->stream));
@@ -338,8 +424,9 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
     if (cnt != occ) return ADORE_E_INVALID;   // uniform policy: same occupancy everywhere
     ins[row] = first_free;
   }
-  ADORE_TRY(hipMemcpyAsync(ctx->slot_pos, slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, ctx->stream));
-  ADORE_TRY(hipMemcpyAsync(ctx->insert_slot, ins.data(), BH * 4, hipMemcpyHostToDevice, ctx->stream));
+  ADORE_TRY(hipMemcpyAsync(ctx->slot_pos[ctx->cur], slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
+                           ctx->stream));
+  ADORE_TRY(hipMemcpyAsync(ctx->insert_slot[ctx->cur], ins.data(), BH * 4, hipMemcpyHostToDevice, ctx->stream));
   if (scores)
     ADORE_TRY(hipMemcpyAsync(ctx->score, scores, size_t(c.batch) * c.max_positions * 4, hipMemcpyDeviceToDevice,
                              ctx->stream));
@@ -348,6 +435,10 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   if (cache_k) ADORE_TRY(hipMemcpyAsync(ctx->cache_k, cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_v) ADORE_TRY(hipMemcpyAsync(ctx->cache_v, cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   ADORE_TRY(hipStreamSynchronize(ctx->stream));   // `ins` lives on this stack frame
+  if (ctx->overlap) {   // the next selections may start at once
+    ADORE_TRY(hipEventRecord(ctx->ev_att[0], ctx->stream));
+    ADORE_TRY(hipEventRecord(ctx->ev_att[1], ctx->stream));
+  }
   ctx->n = step;
   ctx->occ = occ;
   ctx->inited = true;
@@ -364,6 +455,7 @@ int adore_set_timing(adore_ctx *ctx, int32_t enable) {
 int adore_read_timing(adore_ctx *ctx, float *ms, int32_t *launches) {
   if (!ctx || !ms || !launches) return ADORE_E_INVALID;
   ADORE_TRY(hipStreamSynchronize(ctx->stream));
+  if (ctx->overlap && ctx->side_ready) ADORE_TRY(hipStreamSynchronize(ctx->side));
   for (int i = 0; i < ADORE_N_KERNELS; ++i) {
     ms[i] = 0.f;
     launches[i] = 0;

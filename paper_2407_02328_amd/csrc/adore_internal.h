@@ -33,23 +33,32 @@ struct TimedLaunch {
 struct adore_ctx {
   adore_config cfg;
   adore_weights w;
-  hipStream_t stream;
+  hipStream_t stream;        // the caller's stream: attention and the rebuild GEMM
+  hipStream_t side;          // controller and selections; equals `stream` when overlap is off
+  hipEvent_t ev_att[2];      // recorded on `stream` after the last attention of a step (by step parity)
+  hipEvent_t ev_join;        // recorded on `side` after the selections of a step
+  bool overlap;              // two-stream mode requested
+  bool side_ready;           // side stream and events exist (made on first GPU use)
 
   // --- workspace sections (device) ---
+  // Arrays marked x2 are double-buffered by step parity `cur`: a step's attention reads [cur] while
+  // its selections write [cur ^ 1], so the selections of step n+1 may run while the GEMM of step n
+  // still reads the lists of step n.
   char *cache_k, *cache_v;   // [L][B][H][K][d] storage type
-  int32_t *slot_pos;         // [B][H][K]   position per slot, -1 = free
+  int32_t *slot_pos[2];      // x2 [B][H][K]   position per slot, -1 = free
   float *score;              // [B][N_max]  sigma_i
   float *z;                  // [B][d']     GRU state
-  int32_t *insert_slot;      // [B][H]      slot reserved for the next token
-  int32_t *free_list;        // [B][H][R+1] ascending free slots after the release
+  int32_t *insert_slot[2];   // x2 [B][H]      slot reserved for the next token
+  int32_t *free_list[2];     // x2 [B][H][R+1] ascending free slots after the release
   int32_t *released_pos;     // [B][H][R+1]
-  int32_t *rebuilt_pos;      // [B][max(R,1)]
+  int32_t *rebuilt_pos[2];   // x2 [B][max(R,1)]
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
 
   // --- host-side step state ---
   bool inited;
+  int32_t cur;               // buffer index valid for the next attention
   int32_t n;                 // position of the current / next token
   int32_t occ;               // occupied slots per (b,h) between steps
   int32_t r_step;            // rebuilt tokens chosen by this step's schedule
@@ -74,25 +83,27 @@ inline size_t elem_size(const adore_config &c) { return c.dtype == ADORE_BF16 ? 
 // Brackets one kernel launch with events when timing is on.
 class ScopedTimer {
  public:
-  ScopedTimer(adore_ctx *ctx, int kernel);
+  ScopedTimer(adore_ctx *ctx, int kernel, hipStream_t stream);
   ~ScopedTimer();
 
  private:
   adore_ctx *ctx_;
+  hipStream_t stream_;
   hipEvent_t stop_;
 };
 
-// Launchers.  Each validates nothing (the API did) and returns the launch status.
+// Launchers.  Each validates nothing (the API did) and returns the launch status.  `st` is the
+// stream to launch on; `src` / `dst` are buffer indices of the double-buffered arrays.
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
                          const void *v_new, float *out);
-hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows,
-                             int *ksplit_out);
-hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *score_override,
-                            int override_stride, int ksplit);
-hipError_t launch_release(adore_ctx *ctx, int x);
-hipError_t launch_rebuild_select(adore_ctx *ctx, int r);
-hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int r);
-hipError_t launch_init_select(adore_ctx *ctx, int S, int keep, int r0);
+hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int ntok, int per_seq,
+                             int seq_rows, int *ksplit_out);
+hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0,
+                            const float *score_override, int override_stride, int ksplit);
+hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x);
+hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r);
+hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r);
+hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep, int r0);
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);
 hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t count);

@@ -21,11 +21,11 @@ namespace {
 struct AttendArgs {
   const void *q, *k_new, *v_new;   // [B*H][d]
   void *Kc, *Vc;                   // [B*H][K][d] of this layer
-  int32_t *slot_pos;               // [B*H][K]
+  const int32_t *slot_pos;         // [B*H][K]
   const int32_t *insert_slot;      // [B*H]
   float *part;                     // [B*H][nsplit][d+2]
   float *out;                      // [B*H][d]
-  int K, chunk, nsplit, n;
+  int K, chunk, nsplit;
   float scale_log2;                // log2(e) / sqrt(d)
 };
 
@@ -71,14 +71,14 @@ __global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) 
       const bool ins = inr && slot == s_ins;
       valid[u] = false;
       if (ins) {
-        // the current token: take k, v from the step inputs and store them in the cache
+        // the current token: take k, v from the step inputs and store them in the cache (its slot is
+        // marked occupied by the release kernel, which also knows the reserved slot)
         const T *kn = static_cast<const T *>(a.k_new) + size_t(bh) * DH + lig * EPL;
         const T *vn = static_cast<const T *>(a.v_new) + size_t(bh) * DH + lig * EPL;
         Vec16<T>::load(kn, kf[u]);
         Vec16<T>::load(vn, vf[u]);
         Vec16<T>::copy(const_cast<T *>(Kb) + size_t(slot) * DH + lig * EPL, kn);
         Vec16<T>::copy(const_cast<T *>(Vb) + size_t(slot) * DH + lig * EPL, vn);
-        if (lig == 0) a.slot_pos[size_t(bh) * a.K + slot] = a.n;
         valid[u] = true;
       } else if (inr) {
         Vec16<T>::load(Kb + size_t(slot) * DH + lig * EPL, kf[u]);
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, f
 template <typename T, int DH>
 hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
   {
-    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND);
+    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND, ctx->stream);
     const dim3 grid(rows * a.nsplit);
     if (ctx->attend_waves == 16)
       hipLaunchKernelGGL((attend_kernel<T, DH, 4, 16>), grid, dim3(1024), 0, ctx->stream, a);
@@ -181,7 +181,7 @@ hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.nsplit > 1) {
-    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND_COMBINE);
+    ScopedTimer t(ctx, ADORE_KERNEL_ATTEND_COMBINE, ctx->stream);
     hipLaunchKernelGGL((attend_combine_kernel<DH>), dim3(rows), dim3(DH), 0, ctx->stream, a.part, a.out,
                        a.nsplit);
     e = hipGetLastError();
@@ -199,11 +199,11 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
   a.q = q; a.k_new = k_new; a.v_new = v_new;
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
-  a.slot_pos = ctx->slot_pos;
-  a.insert_slot = ctx->insert_slot;
+  a.slot_pos = ctx->slot_pos[ctx->cur];
+  a.insert_slot = ctx->insert_slot[ctx->cur];
   a.part = ctx->att_part;
   a.out = out;
-  a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit; a.n = ctx->n;
+  a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
   const int rows = c.batch * c.heads;
   if (c.dtype == ADORE_BF16) {

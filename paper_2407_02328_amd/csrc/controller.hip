@@ -318,35 +318,35 @@ int ctrl_input_ksplit(const adore_config &c, int ntok) {
 
 }  // namespace
 
-hipError_t launch_ctrl_input(adore_ctx *ctx, const void *x, int ntok, int per_seq, int seq_rows,
-                             int *ksplit_out) {
+hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int ntok, int per_seq,
+                             int seq_rows, int *ksplit_out) {
   const adore_config &c = ctx->cfg;
   const int G3 = 3 * c.ctrl_hidden;
-  ScopedTimer t(ctx, ADORE_KERNEL_CTRL_INPUT);
+  ScopedTimer t(ctx, ADORE_KERNEL_CTRL_INPUT, st);
   *ksplit_out = 1;
   if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0) {
     const int ks = ctrl_input_ksplit(c, ntok);
     *ksplit_out = ks;
     dim3 grid((G3 + 15) / 16, (ntok + 15) / 16, ks);
-    hipLaunchKernelGGL(ctrl_input_mfma_kernel, grid, dim3(256), 0, ctx->stream,
+    hipLaunchKernelGGL(ctrl_input_mfma_kernel, grid, dim3(256), 0, st,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows, c.hidden / ks);
   } else if (c.dtype == ADORE_BF16) {
     dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
-    hipLaunchKernelGGL((ctrl_input_kernel<bf16_t>), grid, dim3(256), 0, ctx->stream,
+    hipLaunchKernelGGL((ctrl_input_kernel<bf16_t>), grid, dim3(256), 0, st,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
   } else {
     dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
-    hipLaunchKernelGGL((ctrl_input_kernel<float>), grid, dim3(256), 0, ctx->stream,
+    hipLaunchKernelGGL((ctrl_input_kernel<float>), grid, dim3(256), 0, st,
                        static_cast<const float *>(ctx->w.gru_w_ih), static_cast<const float *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *score_override,
-                            int override_stride, int ksplit) {
+hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0,
+                            const float *score_override, int override_stride, int ksplit) {
   const adore_config &c = ctx->cfg;
   CellArgs a;
   a.W_hh = ctx->w.gru_w_hh;
@@ -359,19 +359,19 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, int nsteps, int pos0, const float *s
   a.dp = c.ctrl_hidden; a.nsteps = nsteps; a.pos0 = pos0; a.N_max = c.max_positions;
   a.ksplit = ksplit; a.ntok = c.batch * nsteps;
   a.pos_scale = c.pos_scale;
-  ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL);
+  ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
   if (c.ctrl_hidden == 128) {
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((ctrl_cell_rows_kernel<bf16_t, 128>), dim3(c.batch), dim3(512), 0, ctx->stream, a);
+      hipLaunchKernelGGL((ctrl_cell_rows_kernel<bf16_t, 128>), dim3(c.batch), dim3(512), 0, st, a);
     } else {
-      hipLaunchKernelGGL((ctrl_cell_rows_kernel<float, 128>), dim3(c.batch), dim3(512), 0, ctx->stream, a);
+      hipLaunchKernelGGL((ctrl_cell_rows_kernel<float, 128>), dim3(c.batch), dim3(512), 0, st, a);
     }
   } else {
     const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+      hipLaunchKernelGGL((ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, st, a);
     } else {
-      hipLaunchKernelGGL((ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, ctx->stream, a);
+      hipLaunchKernelGGL((ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, st, a);
     }
   }
   return hipGetLastError();

@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
 
 }  // namespace
 
-hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int r) {
+hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r) {
   const adore_config &c = ctx->cfg;
   if (r <= 0) return hipSuccess;
   const size_t es = elem_size(c);
@@ -284,13 +284,13 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   a.W = static_cast<const char *>(ctx->w.w_kv) + size_t(layer) * 2 * c.heads * c.head_dim * c.hidden * es;
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
-  a.rebuilt_pos = ctx->rebuilt_pos;
-  a.free_list = ctx->free_list;
+  a.rebuilt_pos = ctx->rebuilt_pos[lists];
+  a.free_list = ctx->free_list[lists];
   a.B = c.batch; a.H = c.heads; a.d = c.head_dim; a.D = c.hidden; a.K = c.cache_slots;
   a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.M = c.batch * r; a.N = 2 * c.heads * c.head_dim;
   a.tiles_m = (a.M + BM - 1) / BM; a.tiles_n = a.N / BN;
-  ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM);
+  ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM, ctx->stream);
   const bool mfma_ok = c.dtype == ADORE_BF16 && c.hidden % BK == 0 && (c.heads * c.head_dim) % BN == 0 &&
                        (BN % c.head_dim == 0 || c.head_dim % BN == 0);
   if (mfma_ok) {

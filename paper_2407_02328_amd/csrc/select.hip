@@ -108,7 +108,9 @@ __device__ inline void collect_sorted(KeyFn key_of, int ncand, int c, uint64_t t
 // the ones drop out, otherwise all zeros are taken and the search goes on among the ones.
 // Bits on which all candidates agree are skipped.  Keys are distinct, so exactly x are taken.
 template <int KPL>
-__global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot_pos,
+__global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict__ slot_src,
+                                                      int32_t *__restrict__ slot_dst,
+                                                      const int32_t *__restrict__ insert_slot,
                                                       const float *__restrict__ score,
                                                       int32_t *__restrict__ free_list,
                                                       int32_t *__restrict__ released_pos, int rows, int K,
@@ -117,8 +119,9 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
   if (row >= rows) return;                      // whole wave leaves together
   const int lane = threadIdx.x & 63;
   const int b = row / H;
-  int32_t *sp = slot_pos + size_t(row) * K;
+  const int32_t *sp = slot_src + size_t(row) * K;
   const float *sc = score + size_t(b) * N_max;
+  const int s_ins = insert_slot[row];           // the slot the attention of this step filled with token n
 
   int pos[KPL];
   uint32_t khi[KPL], klo[KPL];
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
 #pragma unroll
   for (int j = 0; j < KPL; ++j) {
     const int k = j * 64 + lane;
-    pos[j] = k < K ? sp[k] : -1;
+    pos[j] = k < K ? (k == s_ins ? n : sp[k]) : -1;
   }
 #pragma unroll
   for (int j = 0; j < KPL; ++j) {
@@ -150,11 +153,14 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
 
   uint32_t active = cand, sel = 0;
   int need = x;
+  int nactive = 0;                              // candidates still in play, whole row
+#pragma unroll
+  for (int j = 0; j < KPL; ++j) nactive += __popcll(__ballot((cand >> j) & 1u));
   if (need > 0) {
 #pragma unroll 1
-    for (int word = 1; word >= 0 && need > 0; --word) {
+    for (int word = 1; word >= 0 && need > 0 && nactive > need; --word) {
       uint32_t diff = word ? diff_hi : diff_lo;
-      while (diff != 0 && need > 0) {
+      while (diff != 0 && need > 0 && nactive > need) {
         const int bit = 31 - __clz(diff);
         diff &= ~(1u << bit);
         uint32_t zero = 0;                      // active candidates of this lane whose bit is 0
@@ -168,10 +174,12 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
         }
         if (cnt0 >= need) {
           active = zero;                        // the answer lies among the zeros
+          nactive = cnt0;
         } else {
           sel |= zero;                          // all zeros are taken, go on among the ones
           active &= ~zero;
           need -= cnt0;
+          nactive -= cnt0;
         }
       }
     }
@@ -180,6 +188,7 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
 
   // ascending slot order = j major, lane minor
   int nfree = 0, nrel = 0;
+  int32_t *dp = slot_dst + size_t(row) * K;
 #pragma unroll
   for (int j = 0; j < KPL; ++j) {
     const int k = j * 64 + lane;
@@ -191,10 +200,8 @@ __global__ __launch_bounds__(256) void release_kernel(int32_t *__restrict__ slot
       const int idx = nfree + __popcll(bf & below);
       if (idx < R1) free_list[size_t(row) * R1 + idx] = k;
     }
-    if (rel) {
-      released_pos[size_t(row) * R1 + nrel + __popcll(br & below)] = pos[j];
-      sp[k] = -1;
-    }
+    if (rel) released_pos[size_t(row) * R1 + nrel + __popcll(br & below)] = pos[j];
+    if (k < K) dp[k] = rel ? -1 : pos[j];
     nfree += __popcll(bf);
     nrel += __popcll(br);
   }
@@ -386,15 +393,15 @@ int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 }  // namespace
 
-hipError_t launch_release(adore_ctx *ctx, int x) {
+hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x) {
   const adore_config &c = ctx->cfg;
   const int rows = c.batch * c.heads;
   const dim3 grid((rows + 3) / 4), block(256);
-  ScopedTimer t(ctx, ADORE_KERNEL_RELEASE);
-#define ADORE_RELEASE(KPL)                                                                                  \
-  hipLaunchKernelGGL((release_kernel<KPL>), grid, block, 0, ctx->stream, ctx->slot_pos, ctx->score,          \
-                     ctx->free_list, ctx->released_pos, rows, c.cache_slots, c.heads, c.max_positions, ctx->n, \
-                     x, c.rebuild_budget + 1)
+  ScopedTimer t(ctx, ADORE_KERNEL_RELEASE, st);
+#define ADORE_RELEASE(KPL)                                                                                   \
+  hipLaunchKernelGGL((release_kernel<KPL>), grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],       \
+                     ctx->insert_slot[src], ctx->score, ctx->free_list[dst], ctx->released_pos, rows,         \
+                     c.cache_slots, c.heads, c.max_positions, ctx->n, x, c.rebuild_budget + 1)
   if (c.cache_slots <= 128) ADORE_RELEASE(2);
   else if (c.cache_slots <= 256) ADORE_RELEASE(4);
   else if (c.cache_slots <= 512) ADORE_RELEASE(8);
@@ -403,25 +410,25 @@ hipError_t launch_release(adore_ctx *ctx, int x) {
   return hipGetLastError();
 }
 
-hipError_t launch_rebuild_select(adore_ctx *ctx, int r) {
+hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r) {
   const adore_config &c = ctx->cfg;
   RebuildSelectArgs a;
-  a.slot_pos = ctx->slot_pos; a.score = ctx->score; a.free_list = ctx->free_list;
-  a.rebuilt_pos = ctx->rebuilt_pos; a.insert_slot = ctx->insert_slot;
+  a.slot_pos = ctx->slot_pos[dst]; a.score = ctx->score; a.free_list = ctx->free_list[dst];
+  a.rebuilt_pos = ctx->rebuilt_pos[dst]; a.insert_slot = ctx->insert_slot[dst];
   a.K = c.cache_slots; a.H = c.heads; a.N_max = c.max_positions; a.n = ctx->n; a.r = r;
   a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.words = (c.max_positions + 31) / 32;
   const size_t smem = size_t(max(r, 1)) * 8 + 4 * 8 + 256 * 4 + size_t(a.words) * 4 + size_t(max(r, 1)) * 4;
-  ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_SELECT);
-  hipLaunchKernelGGL(rebuild_select_kernel, dim3(c.batch), dim3(1024), smem, ctx->stream, a);
+  ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_SELECT, st);
+  hipLaunchKernelGGL(rebuild_select_kernel, dim3(c.batch), dim3(1024), smem, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_init_select(adore_ctx *ctx, int S, int keep, int r0) {
+hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep, int r0) {
   const adore_config &c = ctx->cfg;
   InitSelectArgs a;
-  a.slot_pos = ctx->slot_pos; a.score = ctx->score; a.free_list = ctx->free_list;
-  a.rebuilt_pos = ctx->rebuilt_pos; a.insert_slot = ctx->insert_slot; a.init_res = ctx->init_res;
+  a.slot_pos = ctx->slot_pos[dst]; a.score = ctx->score; a.free_list = ctx->free_list[lists];
+  a.rebuilt_pos = ctx->rebuilt_pos[lists]; a.insert_slot = ctx->insert_slot[dst]; a.init_res = ctx->init_res;
   a.K = c.cache_slots; a.H = c.heads; a.N_max = c.max_positions; a.S = S; a.keep = keep; a.r0 = r0;
   a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.words = (c.max_positions + 31) / 32;
