@@ -144,68 +144,115 @@ struct CellArgs {
   float pos_scale;
 };
 
-// sum of the D-slices of one input pre-activation, in slice order
+// sum of the D-slices of one input pre-activation, in slice order; loads go out eight at a time
 __device__ inline float gi_sum(const CellArgs &a, size_t tok, int j) {
+  const size_t stride = size_t(a.ntok) * 3 * a.dp;
+  const float *p = a.gi + tok * 3 * a.dp + j;
   float s = 0.f;
-  for (int k = 0; k < a.ksplit; ++k) s += a.gi[(size_t(k) * a.ntok + tok) * 3 * a.dp + j];
+  int k = 0;
+  for (; k + 8 <= a.ksplit; k += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[size_t(k + u) * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; k < a.ksplit; ++k) s += p[size_t(k) * stride];
   return s;
 }
 
-// ---- cell, d' fixed at compile time: every weight row lives in the registers of one thread ----
-// One workgroup of 4*DP threads per sequence.  Thread t < 3*DP owns row t of W_hh, thread
-// 3*DP + j owns row j of W_1; rows are loaded once and reused for every token of the launch.
-template <typename T, int DP>
-__global__ __launch_bounds__(4 * DP) void ctrl_cell_rows_kernel(const CellArgs a) {
-  constexpr int EPL = Vec16<T>::EPL;
-  __shared__ __attribute__((aligned(16))) float h[DP];
-  __shared__ __attribute__((aligned(16))) float t_in[DP];
-  __shared__ float gh[3 * DP];
-  __shared__ float red[DP / 64];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  float wrow[DP];
-  if (tid < 3 * DP) {
-    const T *src = static_cast<const T *>(a.W_hh) + size_t(tid) * DP;
+// ---- cell, d' = 128 --------------------------------------------------------------------
+// One workgroup of 4 waves per sequence, small enough in registers to share a compute unit with
+// the rebuild GEMM of the previous step.  A weight row of 128 elements is one coalesced wave load
+// (two elements per lane); a wave multiplies a batch of rows by the state it holds in registers and
+// reduces the whole batch at once: at every halving step a lane keeps one half of its partial sums
+// and hands the other half to its partner, so N rows cost N-1 shuffles instead of 6N.
+
+// v[i] is this lane's partial sum of row i.  Returns, in every lane, the complete sum of row
+// lane / (64 / N).
+template <int N, int OFF>
+struct ReduceRows {
+  __device__ static inline float run(float (&v)[N], int lane) {
+    const bool upper = (lane & OFF) != 0;
+    float w[N / 2];
 #pragma unroll
-    for (int c = 0; c < DP; c += EPL) {
-      float f[EPL];
-      Vec16<T>::load(src + c, f);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) wrow[c + e] = f[e];
+    for (int i = 0; i < N / 2; ++i) {
+      const float keep = upper ? v[i + N / 2] : v[i];
+      const float send = upper ? v[i] : v[i + N / 2];
+      w[i] = keep + __shfl_xor(send, OFF, 64);
     }
-  } else {
-    const float *src = a.W1 + size_t(tid - 3 * DP) * DP;
-#pragma unroll
-    for (int c = 0; c < DP; c += 4) {
-      float f[4];
-      Vec16<float>::load(src + c, f);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) wrow[c + e] = f[e];
-    }
+    return ReduceRows<N / 2, OFF / 2>::run(w, lane);
   }
-  const float bias = tid < 3 * DP ? a.b_hh[tid] : a.b1[tid - 3 * DP];
-  const float ow = tid < 3 * DP ? 0.f : a.out_w[tid - 3 * DP];
+};
+template <int OFF>
+struct ReduceRows<1, OFF> {
+  __device__ static inline float run(float (&v)[1], int) {
+    float s = v[0];
+#pragma unroll
+    for (int off = OFF; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+  }
+};
+template <int N>
+__device__ inline float reduce_rows(float (&v)[N], int lane) {
+  return ReduceRows<N, 32>::run(v, lane);
+}
+
+// two consecutive elements of a weight row, raw, and their conversion
+__device__ inline uint32_t load_raw2(const bf16_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+__device__ inline float2 load_raw2(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+__device__ inline float dot2(uint32_t u, float x0, float x1) {
+  return fmaf(__uint_as_float(u << 16), x0, __uint_as_float(u & 0xffff0000u) * x1);
+}
+__device__ inline float dot2(float2 u, float x0, float x1) { return fmaf(u.x, x0, u.y * x1); }
+
+// out[row0 + r] = bias[row0 + r] + W[row0 + r][:] . x   for r < N, x held as (x0, x1) = x[2*lane], x[2*lane+1]
+template <typename T, int N>
+__device__ inline void rows_times_vec(const T *W, int row0, float x0, float x1, const float *bias, float *out,
+                                      int lane) {
+  decltype(load_raw2(W)) raw[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) raw[i] = load_raw2(W + size_t(row0 + i) * 128 + 2 * lane);
+  __builtin_amdgcn_sched_barrier(0);   // all N loads go out before the first is waited for
+  float v[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dot2(raw[i], x0, x1);
+  const float s = reduce_rows<N>(v, lane);
+  constexpr int LPRW = 64 / N;   // lanes holding the same row
+  if ((lane & (LPRW - 1)) == 0) {
+    const int r = row0 + lane / LPRW;
+    out[r] = s + bias[r];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void ctrl_cell128_kernel(const CellArgs a) {
+  constexpr int DP = 128;
+  __shared__ float h[DP];        // z_{i-1}, then z_i
+  __shared__ float t_in[DP];     // p_i + z_i
+  __shared__ float gh[3 * DP];   // W_hh h + b_hh
+  __shared__ float u1[DP];       // W_1 (p + z) + b_1
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T *W_hh = static_cast<const T *>(a.W_hh);
   if (tid < DP) h[tid] = a.z[size_t(b) * DP + tid];
   __syncthreads();
 
   for (int i = 0; i < a.nsteps; ++i) {
+    // weights are streamed from L2 for every token rather than parked in registers: the kernel must
+    // stay small enough to run beside the GEMM
+    asm volatile("" ::: "memory");
     const size_t tok = size_t(b) * a.nsteps + i;
     float g_r = 0.f, g_u = 0.f, g_n = 0.f;
-    if (tid < DP) {   // issue the loads of the input pre-activations before the row product
+    if (tid < DP) {   // the loads of the input pre-activations go out before the row products
       g_r = gi_sum(a, tok, tid) + a.b_ih[tid];
       g_u = gi_sum(a, tok, DP + tid) + a.b_ih[DP + tid];
       g_n = gi_sum(a, tok, 2 * DP + tid) + a.b_ih[2 * DP + tid];
     }
-    if (tid < 3 * DP) {
-      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-      for (int c = 0; c < DP; c += 4) {
-        const float4 hv = *reinterpret_cast<const float4 *>(&h[c]);
-        s0 = fmaf(wrow[c], hv.x, s0);
-        s1 = fmaf(wrow[c + 1], hv.y, s1);
-        s2 = fmaf(wrow[c + 2], hv.z, s2);
-        s3 = fmaf(wrow[c + 3], hv.w, s3);
-      }
-      gh[tid] = ((s0 + s1) + (s2 + s3)) + bias;
+    {   // recurrent pre-activations: 96 rows per wave
+      const float x0 = h[2 * lane], x1 = h[2 * lane + 1];
+#pragma unroll 1   // one batch of 32 row loads in flight at a time: keeps the register count low
+      for (int part = 0; part < 3; ++part)
+        rows_times_vec<T, 32>(W_hh, wave * 96 + part * 32, x0, x1, a.b_hh, gh, lane);
     }
     __syncthreads();
     if (tid < DP) {
@@ -218,27 +265,19 @@ __global__ __launch_bounds__(4 * DP) void ctrl_cell_rows_kernel(const CellArgs a
       t_in[tid] = fmaf(a.pos_w[tid], delta, a.pos_b[tid]) + hnew;
     }
     __syncthreads();
-    if (tid >= 3 * DP) {
-      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-      for (int c = 0; c < DP; c += 4) {
-        const float4 tv = *reinterpret_cast<const float4 *>(&t_in[c]);
-        s0 = fmaf(wrow[c], tv.x, s0);
-        s1 = fmaf(wrow[c + 1], tv.y, s1);
-        s2 = fmaf(wrow[c + 2], tv.z, s2);
-        s3 = fmaf(wrow[c + 3], tv.w, s3);
-      }
-      const float part = wave_sum(ow * tanhf(((s0 + s1) + (s2 + s3)) + bias));
-      if (lane == 0) red[(tid - 3 * DP) >> 6] = part;
+    {   // interaction layer: 32 rows per wave
+      const float x0 = t_in[2 * lane], x1 = t_in[2 * lane + 1];
+      rows_times_vec<float, 32>(a.W1, wave * 32, x0, x1, a.b1, u1, lane);
     }
     __syncthreads();
-    if (tid == 0) {
-      float s = 0.f;
-#pragma unroll
-      for (int wv = 0; wv < DP / 64; ++wv) s += red[wv];
-      float sig = sigmoidf_(s + a.out_b[0]);
-      if (a.override_) sig = a.override_[size_t(b) * a.override_stride + i];
-      a.score[size_t(b) * a.N_max + a.pos0 + i] = sig;
+    if (wave == 0) {   // output layer and sigmoid
+      float s = fmaf(a.out_w[lane], tanhf(u1[lane]), a.out_w[lane + 64] * tanhf(u1[lane + 64]));
+      s = wave_sum(s);
+      if (lane == 0) {
+        float sig = sigmoidf_(s + a.out_b[0]);
+        if (a.override_) sig = a.override_[size_t(b) * a.override_stride + i];
+        a.score[size_t(b) * a.N_max + a.pos0 + i] = sig;
+      }
     }
   }
   if (tid < DP) a.z[size_t(b) * DP + tid] = h[tid];
@@ -362,9 +401,9 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
   if (c.ctrl_hidden == 128) {
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((ctrl_cell_rows_kernel<bf16_t, 128>), dim3(c.batch), dim3(512), 0, st, a);
+      hipLaunchKernelGGL((ctrl_cell128_kernel<bf16_t>), dim3(c.batch), dim3(256), 0, st, a);
     } else {
-      hipLaunchKernelGGL((ctrl_cell_rows_kernel<float, 128>), dim3(c.batch), dim3(512), 0, st, a);
+      hipLaunchKernelGGL((ctrl_cell128_kernel<float>), dim3(c.batch), dim3(256), 0, st, a);
     }
   } else {
     const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);
