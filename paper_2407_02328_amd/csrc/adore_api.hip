@@ -25,26 +25,19 @@ using namespace adore;
 
 namespace adore {
 
-ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel, hipStream_t stream)
-    : ctx_(ctx), stream_(stream), stop_(nullptr) {
+ScopedTimer::ScopedTimer(adore_ctx *ctx, int kernel, hipStream_t) : on_(false) {
+  ev_[0] = ev_[1] = nullptr;
   if (!ctx->timing) return;
-  hipEvent_t ev[2];
   for (int i = 0; i < 2; ++i) {
     if (!ctx->event_pool.empty()) {
-      ev[i] = ctx->event_pool.back();
+      ev_[i] = ctx->event_pool.back();
       ctx->event_pool.pop_back();
-    } else if (hipEventCreate(&ev[i]) != hipSuccess) {
-      ctx_ = nullptr;
-      return;
+    } else if (hipEventCreate(&ev_[i]) != hipSuccess) {
+      return;   // falls back to an untimed launch
     }
   }
-  (void)hipEventRecord(ev[0], stream);
-  stop_ = ev[1];
-  ctx->timed.push_back(TimedLaunch{kernel, ev[0], ev[1]});
-}
-
-ScopedTimer::~ScopedTimer() {
-  if (ctx_ && stop_) (void)hipEventRecord(stop_, stream_);
+  on_ = true;
+  ctx->timed.push_back(TimedLaunch{kernel, ev_[0], ev_[1]});
 }
 
 }  // namespace adore

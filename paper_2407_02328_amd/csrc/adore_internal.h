@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 #include <vector>
@@ -80,17 +81,29 @@ namespace adore {
 
 inline size_t elem_size(const adore_config &c) { return c.dtype == ADORE_BF16 ? 2 : 4; }
 
-// Brackets one kernel launch with events when timing is on.
+// Per-kernel timing.  When timing is on, the kernel is launched with hipExtLaunchKernelGGL, which ties
+// the two events to the dispatch itself (its begin and end time stamps), so the elapsed time is the
+// kernel's own duration without the queueing of an event bracket.
 class ScopedTimer {
  public:
   ScopedTimer(adore_ctx *ctx, int kernel, hipStream_t stream);
-  ~ScopedTimer();
+  bool on() const { return on_; }
+  hipEvent_t start() const { return ev_[0]; }
+  hipEvent_t stop() const { return ev_[1]; }
 
  private:
-  adore_ctx *ctx_;
-  hipStream_t stream_;
-  hipEvent_t stop_;
+  bool on_;
+  hipEvent_t ev_[2];
 };
+
+#define ADORE_LAUNCH(TIMER, KERNEL, GRID, BLOCK, SMEM, STREAM, ...)                                   \
+  do {                                                                                                \
+    if ((TIMER).on())                                                                                 \
+      hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, SMEM, STREAM, (TIMER).start(), (TIMER).stop(), 0,    \
+                            __VA_ARGS__);                                                             \
+    else                                                                                              \
+      hipLaunchKernelGGL(KERNEL, GRID, BLOCK, SMEM, STREAM, __VA_ARGS__);                             \
+  } while (0)
 
 // Launchers.  Each validates nothing (the API did) and returns the launch status.  `st` is the
 // stream to launch on; `src` / `dst` are buffer indices of the double-buffered arrays.

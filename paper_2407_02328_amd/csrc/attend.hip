@@ -172,17 +172,17 @@ hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
     ScopedTimer t(ctx, ADORE_KERNEL_ATTEND, ctx->stream);
     const dim3 grid(rows * a.nsplit);
     if (ctx->attend_waves == 16)
-      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 16>), grid, dim3(1024), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 16>), grid, dim3(1024), 0, ctx->stream, a);
     else if (ctx->attend_waves == 8)
-      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 8>), grid, dim3(512), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 8>), grid, dim3(512), 0, ctx->stream, a);
     else
-      hipLaunchKernelGGL((attend_kernel<T, DH, 4, 4>), grid, dim3(256), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 4>), grid, dim3(256), 0, ctx->stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.nsplit > 1) {
     ScopedTimer t(ctx, ADORE_KERNEL_ATTEND_COMBINE, ctx->stream);
-    hipLaunchKernelGGL((attend_combine_kernel<DH>), dim3(rows), dim3(DH), 0, ctx->stream, a.part, a.out,
+    ADORE_LAUNCH(t, (attend_combine_kernel<DH>), dim3(rows), dim3(DH), 0, ctx->stream, a.part, a.out,
                        a.nsplit);
     e = hipGetLastError();
   }

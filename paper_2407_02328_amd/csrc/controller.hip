@@ -367,17 +367,17 @@ hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int 
     const int ks = ctrl_input_ksplit(c, ntok);
     *ksplit_out = ks;
     dim3 grid((G3 + 15) / 16, (ntok + 15) / 16, ks);
-    hipLaunchKernelGGL(ctrl_input_mfma_kernel, grid, dim3(256), 0, st,
+    ADORE_LAUNCH(t, ctrl_input_mfma_kernel, grid, dim3(256), 0, st,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows, c.hidden / ks);
   } else if (c.dtype == ADORE_BF16) {
     dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
-    hipLaunchKernelGGL((ctrl_input_kernel<bf16_t>), grid, dim3(256), 0, st,
+    ADORE_LAUNCH(t, (ctrl_input_kernel<bf16_t>), grid, dim3(256), 0, st,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
   } else {
     dim3 grid((G3 + JT - 1) / JT, (ntok + NB - 1) / NB);
-    hipLaunchKernelGGL((ctrl_input_kernel<float>), grid, dim3(256), 0, st,
+    ADORE_LAUNCH(t, (ctrl_input_kernel<float>), grid, dim3(256), 0, st,
                        static_cast<const float *>(ctx->w.gru_w_ih), static_cast<const float *>(x), ctx->gi,
                        c.hidden, G3, ntok, per_seq, seq_rows);
   }
@@ -401,16 +401,16 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
   if (c.ctrl_hidden == 128) {
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((ctrl_cell128_kernel<bf16_t>), dim3(c.batch), dim3(256), 0, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell128_kernel<bf16_t>), dim3(c.batch), dim3(256), 0, st, a);
     } else {
-      hipLaunchKernelGGL((ctrl_cell128_kernel<float>), dim3(c.batch), dim3(256), 0, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell128_kernel<float>), dim3(c.batch), dim3(256), 0, st, a);
     }
   } else {
     const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell_kernel<bf16_t>), dim3(c.batch), dim3(512), smem, st, a);
     } else {
-      hipLaunchKernelGGL((ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, st, a);
     }
   }
   return hipGetLastError();

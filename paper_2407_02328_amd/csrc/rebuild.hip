@@ -297,16 +297,16 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
     const int total = a.tiles_m * a.tiles_n;
     const int grid = (total + 7) / 8 * 8;
     const int nk = c.hidden / BK;   // the k-loop is unrolled by the number of register stages
-    if (nk % 4 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<4>), dim3(grid), dim3(512), 0, ctx->stream, a);
-    else if (nk % 2 == 0) hipLaunchKernelGGL((rebuild_mfma_kernel<2>), dim3(grid), dim3(512), 0, ctx->stream, a);
-    else hipLaunchKernelGGL((rebuild_mfma_kernel<1>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    if (nk % 4 == 0) ADORE_LAUNCH(t, (rebuild_mfma_kernel<4>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    else if (nk % 2 == 0) ADORE_LAUNCH(t, (rebuild_mfma_kernel<2>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    else ADORE_LAUNCH(t, (rebuild_mfma_kernel<1>), dim3(grid), dim3(512), 0, ctx->stream, a);
   } else {
     const size_t waves = size_t(a.M) * a.N;
     const unsigned blocks = unsigned((waves + 3) / 4);
     if (c.dtype == ADORE_BF16) {
-      hipLaunchKernelGGL((rebuild_dot_kernel<bf16_t>), dim3(blocks), dim3(256), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (rebuild_dot_kernel<bf16_t>), dim3(blocks), dim3(256), 0, ctx->stream, a);
     } else {
-      hipLaunchKernelGGL((rebuild_dot_kernel<float>), dim3(blocks), dim3(256), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (rebuild_dot_kernel<float>), dim3(blocks), dim3(256), 0, ctx->stream, a);
     }
   }
   return hipGetLastError();

@@ -399,7 +399,7 @@ hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int 
   const dim3 grid((rows + 3) / 4), block(256);
   ScopedTimer t(ctx, ADORE_KERNEL_RELEASE, st);
 #define ADORE_RELEASE(KPL)                                                                                   \
-  hipLaunchKernelGGL((release_kernel<KPL>), grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],       \
+  ADORE_LAUNCH(t, (release_kernel<KPL>), grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],       \
                      ctx->insert_slot[src], ctx->score, ctx->free_list[dst], ctx->released_pos, rows,         \
                      c.cache_slots, c.heads, c.max_positions, ctx->n, x, c.rebuild_budget + 1)
   if (c.cache_slots <= 128) ADORE_RELEASE(2);
@@ -420,7 +420,7 @@ hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r)
   a.words = (c.max_positions + 31) / 32;
   const size_t smem = size_t(max(r, 1)) * 8 + 4 * 8 + 256 * 4 + size_t(a.words) * 4 + size_t(max(r, 1)) * 4;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_SELECT, st);
-  hipLaunchKernelGGL(rebuild_select_kernel, dim3(c.batch), dim3(1024), smem, st, a);
+  ADORE_LAUNCH(t, rebuild_select_kernel, dim3(c.batch), dim3(1024), smem, st, a);
   return hipGetLastError();
 }
 
