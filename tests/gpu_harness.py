@@ -137,8 +137,9 @@ def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=No
 
 def compare_cache(w: Workload, snap, orc):
     """Occupied rows of the GPU cache against the oracle's: inserted rows are copies (exact);
-    rebuilt rows are fp32-accumulated and rounded once, so they may differ by one unit in the
-    last place of the storage type."""
+    rebuilt rows are fp32-accumulated and rounded once, so a value may land on the neighbouring
+    storage value (one unit in the last place); entries that cancel to almost zero additionally
+    carry the fp32 accumulation error itself, bounded here by 2e-5 of the largest entry."""
     occ = orc.slot_pos >= 0                                  # [B,H,K]
     for name, ref in (("cache_k", orc.Kc), ("cache_v", orc.Vc)):
         got = snap[name].astype(np.float64)                  # [L,B,H,K,d]
@@ -146,6 +147,6 @@ def compare_cache(w: Workload, snap, orc):
             g, r = got[l][occ], ref[l][occ]
             if w.dtype == "bf16":
                 ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r), 1e-30))) - 7)
-                assert np.all(np.abs(g - r) <= ulp * 1.0001 + 1e-30), name
+                assert np.all(np.abs(g - r) <= ulp * 1.0001 + 2e-5 * np.abs(r).max()), name
             else:
                 assert np.all(np.abs(g - r) <= 2e-6 * np.maximum(np.abs(r).max(), 1e-30)), name

@@ -228,3 +228,33 @@ def test_attention_launch_shapes(split, waves, monkeypatch):
     worst, job, _ = h.lockstep(w, steps=w.T)
     assert job.adore.cfg.cache_slots == 300
     job.adore.close()
+
+
+def test_llama7b_layer_full_size_steps():
+    """The benchmark workload at its full size and in the launch configuration bench.py times
+    (B16 H32 d128 D4096 K512 R32, prompt 1024): init plus six free-running steps, every slot map,
+    every output row and every occupied cache row against the oracle."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(T=8)
+    worst, job, _ = h.lockstep(w, steps=6, check_cache_every=3)
+    print(f"llama7b_layer: worst output error {worst:.3e}")
+    job.adore.close()
+
+
+def test_long_context_reduced_with_salience():
+    """The long-context recipe (Zipf salience in key dimension 0 and in the controller input, K = 1024,
+    rows split over several workgroups) at a prompt the oracle finishes in seconds."""
+    h = _harness()
+    w = workload("long_context").scaled(B=1, H=4, S=2048, T=12)
+    worst, job, _ = h.lockstep(w, steps=10, check_cache_every=5)
+    assert job.adore.cfg.cache_slots == 1024
+    print(f"long_context (reduced): worst output error {worst:.3e}")
+    job.adore.close()
+
+
+def test_high_batch_reduced():
+    """The high-batch recipe (K = 256, R = 16) with 8 of its 128 sequences."""
+    h = _harness()
+    w = workload("high_batch").scaled(B=8, T=10)
+    worst, job, _ = h.lockstep(w, steps=8, check_cache_every=4)
+    job.adore.close()
