@@ -41,6 +41,19 @@ def algorithmic_work(w):
     return dict(attend_bytes=att_bytes, gemm_flops=gemm_flops, ctrl_flops=ctrl_flops, select_bytes=sel_bytes)
 
 
+def recorded_traffic(w):
+    """HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE / WRITE_SIZE scaled by a copy
+    kernel of known size); recorded in profiles/ because bench.py cannot run the profiler on itself."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_{w.name}_hbm_traffic.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes":
+                out[parts[1]] = int(parts[2])
+    return out
+
+
 def run_gpu(w, steps, warmup, prof_steps):
     import torch
     from gen import SyntheticInputs
@@ -139,13 +152,14 @@ def main():
     gemm_us = per_kernel_us["rebuild_gemm"]
     att_gbs = work["attend_bytes"] / (att_us * 1e-6) / 1e9 if att_us else 0.0
     gemm_tflops = work["gemm_flops"] / (gemm_us * 1e-6) / 1e12 if gemm_us else 0.0
+    traffic = recorded_traffic(w)
     roof_att = dict(kernel="attend", bound="hbm", achieved=round(att_gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(att_gbs / HBM_PEAK_GBS, 4), traffic=None, us_per_launch=round(att_us, 2),
+                    frac=round(att_gbs / HBM_PEAK_GBS, 4), traffic=traffic.get("attend"), us_per_launch=round(att_us, 2),
                     algorithmic_bytes=work["attend_bytes"])
     peak = MFMA_PEAK_TFLOPS[w.dtype]
     roof_gemm = dict(kernel="rebuild_gemm", bound="mfma" if w.dtype == "bf16" else "alu",
                      achieved=round(gemm_tflops, 1), peak=peak, unit="TFLOP/s", frac=round(gemm_tflops / peak, 4),
-                     traffic=None, us_per_launch=round(gemm_us, 2), algorithmic_flops=work["gemm_flops"])
+                     traffic=traffic.get("rebuild_gemm"), us_per_launch=round(gemm_us, 2), algorithmic_flops=work["gemm_flops"])
     dominant = roof_gemm if gemm_us >= att_us else roof_att
 
     line = {
