@@ -287,11 +287,13 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   const int src = ctx->cur, dst = ctx->cur ^ 1;
   hipStream_t st = ctx->side;
 
-  // buffer `dst` was `cur` one step ago: wait until that step's attention has read it
-  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
+  // the controller touches only its own state and the score array: it may run as early as the
+  // previous step's selections are done
   int ksplit = 1;
   ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, 1, &ksplit));
   ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
+  // buffer `dst` was `cur` one step ago: the selections wait until that step's attention has read it
+  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x));
   ADORE_TRY(launch_rebuild_select(ctx, st, dst, r));
   const size_t BH = size_t(c.batch) * c.heads;
