@@ -294,18 +294,8 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
   // buffer `dst` was `cur` one step ago: the selections wait until that step's attention has read it
   if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
-  ADORE_TRY(launch_release(ctx, st, src, dst, x));
-  ADORE_TRY(launch_rebuild_select(ctx, st, dst, r));
-  const size_t BH = size_t(c.batch) * c.heads;
-  if (slot_map)
-    ADORE_TRY(hipMemcpyAsync(slot_map, ctx->slot_pos[dst], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice, st));
-  if (released_pos)
-    ADORE_TRY(hipMemcpyAsync(released_pos, ctx->released_pos, BH * (c.rebuild_budget + 1) * 4,
-                             hipMemcpyDeviceToDevice, st));
-  if (rebuilt_pos)
-    ADORE_TRY(hipMemcpyAsync(rebuilt_pos, ctx->rebuilt_pos[dst],
-                             size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4,
-                             hipMemcpyDeviceToDevice, st));
+  ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
+  ADORE_TRY(launch_rebuild_select(ctx, st, dst, r, slot_map, rebuilt_pos));
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
   ctx->scheduled = true;
   ctx->r_step = r;

@@ -113,8 +113,12 @@ hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int 
                              int seq_rows, int *ksplit_out);
 hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0,
                             const float *score_override, int override_stride, int ksplit);
-hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x);
-hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r);
+// The two selections also write the caller's copies of their results (slot map, released and rebuilt
+// positions) when given a pointer, so a step needs no device-to-device copies.
+hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x, int32_t *map_out,
+                          int32_t *rel_out);
+hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r, int32_t *map_out,
+                                 int32_t *rb_out);
 hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r);
 hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep, int r0);
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,

@@ -113,7 +113,9 @@ __global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict_
                                                       const int32_t *__restrict__ insert_slot,
                                                       const float *__restrict__ score,
                                                       int32_t *__restrict__ free_list,
-                                                      int32_t *__restrict__ released_pos, int rows, int K,
+                                                      int32_t *__restrict__ released_pos,
+                                                      int32_t *__restrict__ map_out,
+                                                      int32_t *__restrict__ rel_out, int rows, int K,
                                                       int H, int N_max, int n, int x, int R1) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;                      // whole wave leaves together
@@ -200,12 +202,22 @@ __global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict_
       const int idx = nfree + __popcll(bf & below);
       if (idx < R1) free_list[size_t(row) * R1 + idx] = k;
     }
-    if (rel) released_pos[size_t(row) * R1 + nrel + __popcll(br & below)] = pos[j];
-    if (k < K) dp[k] = rel ? -1 : pos[j];
+    if (rel) {
+      const size_t at = size_t(row) * R1 + nrel + __popcll(br & below);
+      released_pos[at] = pos[j];
+      if (rel_out) rel_out[at] = pos[j];
+    }
+    if (k < K) {
+      dp[k] = rel ? -1 : pos[j];
+      if (map_out) map_out[size_t(row) * K + k] = rel ? -1 : pos[j];   // the caller's copy; rebuilt slots follow
+    }
     nfree += __popcll(bf);
     nrel += __popcll(br);
   }
-  for (int t = nrel + lane; t < R1; t += 64) released_pos[size_t(row) * R1 + t] = -1;
+  for (int t = nrel + lane; t < R1; t += 64) {
+    released_pos[size_t(row) * R1 + t] = -1;
+    if (rel_out) rel_out[size_t(row) * R1 + t] = -1;
+  }
 }
 
 // ---- per-sequence choice of the tokens to rebuild -------------------------------
@@ -215,6 +227,8 @@ struct RebuildSelectArgs {
   const int32_t *free_list;    // [B][H][R1]
   int32_t *rebuilt_pos;        // [B][Rdim]
   int32_t *insert_slot;        // [B][H]
+  int32_t *map_out;            // [B][H][K] caller's slot map (already holds the map after the release), or null
+  int32_t *rb_out;             // [B][Rdim] caller's copy of rebuilt_pos, or null
   int K, H, N_max, n, r, R1, Rdim, words;
 };
 
@@ -248,15 +262,22 @@ __global__ __launch_bounds__(1024) void rebuild_select_kernel(const RebuildSelec
     int shift;
     radix_select(key_of, a.n + 1, r, s_hist, s_ctl, &thr, &shift);
     collect_sorted(key_of, a.n + 1, r, thr, shift, s_keys, &s_count, s_sel);
-    for (int t = tid; t < r; t += blockDim.x) a.rebuilt_pos[size_t(b) * a.Rdim + t] = s_sel[t];
+    for (int t = tid; t < r; t += blockDim.x) {
+      a.rebuilt_pos[size_t(b) * a.Rdim + t] = s_sel[t];
+      if (a.rb_out) a.rb_out[size_t(b) * a.Rdim + t] = s_sel[t];
+    }
     // rebuilt rank rho takes the rho-th lowest free slot of every head
     for (int idx = tid; idx < a.H * r; idx += blockDim.x) {
       const int h = idx / r, rho = idx - h * r;
       const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
       a.slot_pos[(size_t(b) * a.H + h) * a.K + slot] = s_sel[rho];
+      if (a.map_out) a.map_out[(size_t(b) * a.H + h) * a.K + slot] = s_sel[rho];
     }
   }
-  for (int t = r + tid; t < a.Rdim; t += blockDim.x) a.rebuilt_pos[size_t(b) * a.Rdim + t] = -1;
+  for (int t = r + tid; t < a.Rdim; t += blockDim.x) {
+    a.rebuilt_pos[size_t(b) * a.Rdim + t] = -1;
+    if (a.rb_out) a.rb_out[size_t(b) * a.Rdim + t] = -1;
+  }
   // the next free slot is reserved for the next token
   for (int h = tid; h < a.H; h += blockDim.x) {
     a.insert_slot[size_t(b) * a.H + h] = a.free_list[(size_t(b) * a.H + h) * a.R1 + r];
@@ -393,14 +414,15 @@ int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 }  // namespace
 
-hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x) {
+hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int x, int32_t *map_out,
+                          int32_t *rel_out) {
   const adore_config &c = ctx->cfg;
   const int rows = c.batch * c.heads;
   const dim3 grid((rows + 3) / 4), block(256);
   ScopedTimer t(ctx, ADORE_KERNEL_RELEASE, st);
 #define ADORE_RELEASE(KPL)                                                                                   \
   ADORE_LAUNCH(t, (release_kernel<KPL>), grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],       \
-                     ctx->insert_slot[src], ctx->score, ctx->free_list[dst], ctx->released_pos, rows,         \
+                     ctx->insert_slot[src], ctx->score, ctx->free_list[dst], ctx->released_pos, map_out, rel_out, rows, \
                      c.cache_slots, c.heads, c.max_positions, ctx->n, x, c.rebuild_budget + 1)
   if (c.cache_slots <= 128) ADORE_RELEASE(2);
   else if (c.cache_slots <= 256) ADORE_RELEASE(4);
@@ -410,11 +432,13 @@ hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int 
   return hipGetLastError();
 }
 
-hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r) {
+hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r, int32_t *map_out,
+                                 int32_t *rb_out) {
   const adore_config &c = ctx->cfg;
   RebuildSelectArgs a;
   a.slot_pos = ctx->slot_pos[dst]; a.score = ctx->score; a.free_list = ctx->free_list[dst];
   a.rebuilt_pos = ctx->rebuilt_pos[dst]; a.insert_slot = ctx->insert_slot[dst];
+  a.map_out = map_out; a.rb_out = rb_out;
   a.K = c.cache_slots; a.H = c.heads; a.N_max = c.max_positions; a.n = ctx->n; a.r = r;
   a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.words = (c.max_positions + 31) / 32;
