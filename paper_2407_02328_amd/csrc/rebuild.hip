@@ -13,11 +13,14 @@
 // (v_mfma_f32_32x32x16_bf16).  Both operands are contiguous along the reduction
 // dimension, which is exactly the per-lane operand layout of that instruction
 // (8 consecutive k for one row), so tiles go global -> LDS -> registers as
-// 16-byte vectors with no transposes.  128x128 output tile per workgroup (one
-// per compute unit at the 7B shape: M = 512, N = 8192), BK = 64, LDS
-// triple-buffered and XOR-swizzled (conflict-free for 16-byte reads and writes).
-// The output tile is rounded to bf16 into LDS and leaves as 16-byte vectors: a
-// row of the tile is a contiguous head slice of one cache row.
+// 16-byte vectors with no transposes.  One kernel template covers a family of
+// output tiles; the launcher takes the largest tile that still gives every compute
+// unit a workgroup (M = 512 at the 7B shape: 128x128, one tile per unit;
+// M >= 2048: 256x256; M <= 128: 128x32).  Larger tiles move fewer LDS bytes per
+// flop, and LDS bandwidth is what the 128x128 tile runs into first.  LDS stages
+// are XOR-swizzled (conflict-free for 16-byte reads and writes).  The output tile
+// is rounded to bf16 into LDS and leaves as 16-byte vectors: a row of the tile is
+// a run of contiguous head slices of cache rows.
 // fp32 path (and shapes the tile kernel does not take): one wave per output.
 #include "device_utils.h"
 
@@ -39,30 +42,41 @@ struct GemmArgs {
   int tiles_m, tiles_n;
 };
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int CH = BK / 8;   // 16-byte chunks per tile row
-constexpr int LS = 3;        // LDS stages
-
-__device__ inline int swz(int row, int chunk) { return row * CH + (chunk ^ ((row >> 1) & 7)); }
-
-// Workgroup = 8 waves on a 128x128 output tile.  Waves 0-3 and 4-7 form two k-groups: each group
-// holds the whole tile as four 64x64 wave tiles and multiplies one half of every 64-wide k-step, so
-// the LDS read traffic is that of four waves while every SIMD has two waves to switch between.  The
-// two halves are added through LDS at the end.
+// Workgroup = 8 waves on a BM x BN output tile, k-steps of BK.
+//   KG = 1: the waves form a WM x WN grid, each holding (BM/WM) x (BN/WN) of the tile.
+//   KG = 2: two such grids of four waves (k-groups); each multiplies one half of every k-step, so the
+//           LDS read traffic is that of four waves while every SIMD still has two waves to switch
+//           between.  The halves are added through LDS at the end.
 //   global -> registers: NS k-steps ahead (NS register sets, refilled right after they are spilled to LDS)
-//   registers -> LDS:    three stages, so the tile of step ks+2 is written while ks is read and ks+1 is
-//                        already complete; one barrier per k-step, and the first fragments of the next
-//                        step are fetched before it
+//   registers -> LDS:    LS stages; the tile of step ks+LS-1 is written while ks is read, one barrier per
+//                        k-step.  With LS >= 3 the tile of ks+1 is complete during ks, so the first
+//                        fragments of the next step are fetched before the barrier.
 //   LDS -> fragments:    one 16-wide k-slice ahead of the MFMAs that use them
 // sched_barrier keeps the compiler from sinking the fragment loads below the MFMAs they overlap with.
-template <int NS>
+template <int BM, int BN, int BK, int KG, int WM, int WN, int LS, int NS>
 __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
-  // one LDS block: LS stages of (A tile, B tile); after the k-loop the first 64 KB carry the upper
-  // k-group's accumulators and the last 32 KB the bf16 output tile
-  __shared__ u32x4 smem[LS * (BM + BN) * CH];
-  __shared__ long long s_dst[BM * (BN / 64)];   // element offset of each output row slice in the cache, -1 = none
-  u32x4 (*sA)[BM * CH] = reinterpret_cast<u32x4 (*)[BM * CH]>(smem);
-  u32x4 (*sB)[BN * CH] = reinterpret_cast<u32x4 (*)[BN * CH]>(smem + LS * BM * CH);
+  constexpr int CH = BK / 8;             // 16-byte chunks per tile row
+  constexpr int RPP = 512 / CH;          // tile rows the workgroup loads per pass
+  constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);   // 32x32 blocks per wave
+  static_assert(KG * WM * WN == 8 && (KG == 1 || KG == 2), "eight waves");
+  static_assert(TM * WM * 32 == BM && TN * WN * 32 == BN, "tile shape");
+  constexpr int NA = BM / RPP, NB = (BN + RPP - 1) / RPP;   // 16-byte loads per thread and k-step
+  static_assert(NA * RPP == BM && (NB * RPP == BN || BN < RPP), "tile rows");
+  constexpr int KSUB = BK / 16 / KG;     // 16-wide k-slices per wave and k-step
+  static_assert(KSUB == 2 || KSUB == 4, "fragment double buffering needs an even number of k-slices");
+  constexpr int LEAD = LS - 1;
+  constexpr int STAGE = (BM + BN) * CH;  // 16-byte units per LDS stage
+  constexpr int LOOP_BYTES = LS * STAGE * 16;
+  constexpr int RED_BYTES = KG == 2 ? 4 * TM * TN * 16 * 64 * 4 : 0;
+  constexpr int OUT_BYTES = BM * BN * 2;
+  constexpr int SMEM_BYTES = LOOP_BYTES > RED_BYTES ? (LOOP_BYTES > OUT_BYTES ? LOOP_BYTES : OUT_BYTES)
+                                                    : (RED_BYTES > OUT_BYTES ? RED_BYTES : OUT_BYTES);
+  constexpr int NH_MAX = BN / 64 > 0 ? BN / 64 : 1;
+  // one LDS block: the stages during the k-loop, then the upper k-group's accumulators, then the bf16 output tile
+  __shared__ u32x4 smem[SMEM_BYTES / 16];
+  __shared__ long long s_dst[BM * NH_MAX];   // element offset of each output row slice in the cache, -1 = none
+  // rows are 128 B (BK = 64) or 64 B (BK = 32): 16 consecutive rows at one chunk index hit 16 different bank groups
+  auto swz = [](int row, int chunk) { return row * CH + (chunk ^ (CH == 8 ? (row >> 1) & 7 : (row >> 2) & 3)); };
 
   const int total = a.tiles_m * a.tiles_n;
   const int per_xcd = (total + 7) / 8;
@@ -72,13 +86,13 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kgrp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
+  const int kgrp = wave / (WM * WN), wm = (wave / WN) % WM, wn = wave % WN;
 
   // where every row of the output tile goes: looked up now, used after the k-loop
   const int Hd = a.H * a.d;
-  const int nh = BN / a.d > 0 ? BN / a.d : 1;     // heads covered by the tile's 128 columns (d = 64: 2, d >= 128: 1)
-  if (tid < BM * nh) {
-    const int row = tid / nh, hh = tid - row * nh;
+  const int nh = BN / a.d > 0 ? BN / a.d : 1;     // head slices in one tile row
+  for (int t = tid; t < BM * nh; t += 512) {
+    const int row = t / nh, hh = t - row * nh;
     const int mi = m0 + row;
     long long off = -1;
     if (mi < a.M) {
@@ -89,97 +103,116 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
       const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
       off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
     }
-    s_dst[tid] = off;
+    s_dst[t] = off;
   }
-  const int lchunk = tid & 7, lrow = tid >> 3;   // rows lrow + 64*i
-  const u32x4 *gA[2], *gB[2];
+  const int lchunk = tid % CH, lrow = tid / CH;   // rows lrow + RPP*i
+  const bool b_on = BN >= RPP || lrow < BN;       // narrow tiles: only some threads load W rows
+  const u32x4 *gA[NA], *gB[NB];
   const bf16_t *X = static_cast<const bf16_t *>(a.X);
   const bf16_t *W = static_cast<const bf16_t *>(a.W);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int mi = m0 + lrow + 64 * i;
+  for (int i = 0; i < NA; ++i) {
+    const int mi = m0 + lrow + RPP * i;
     size_t src_row = 0;
     if (mi < a.M) {
       const int b = mi / a.r, rho = mi - b * a.r;
       src_row = size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + rho];
     }
     gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
-    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + lrow + 64 * i) * a.D) + lchunk;
+  }
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int nrow = b_on ? lrow + RPP * i : 0;
+    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + nrow) * a.D) + lchunk;
   }
   const int nk = a.D / BK;
-  u32x4 ra[NS][2], rb[NS][2];
-#define GLOAD(SET, KS)                                              \
-  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                   \
-    ra[SET][i] = gA[i][(KS) * CH];                                  \
-    rb[SET][i] = gB[i][(KS) * CH];                                  \
+  u32x4 ra[NS][NA], rb[NS][NB];
+#define SA(ST) (smem + (ST) * STAGE)
+#define SB(ST) (smem + (ST) * STAGE + BM * CH)
+#define GLOAD(SET, KS)                                                                   \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) ra[SET][i] = gA[i][(KS) * CH];        \
+    _Pragma("unroll") for (int i = 0; i < NB; ++i) rb[SET][i] = gB[i][(KS) * CH];        \
   }
-#define LSTORE(SET, ST)                                             \
-  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                   \
-    sA[ST][swz(lrow + 64 * i, lchunk)] = ra[SET][i];                \
-    sB[ST][swz(lrow + 64 * i, lchunk)] = rb[SET][i];                \
+#define LSTORE(SET, ST)                                                                  \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                       \
+      SA(ST)[swz(lrow + RPP * i, lchunk)] = ra[SET][i];                                  \
+    if (b_on) {                                                                          \
+      _Pragma("unroll") for (int i = 0; i < NB; ++i)                                     \
+        SB(ST)[swz(lrow + RPP * i, lchunk)] = rb[SET][i];                                \
+    }                                                                                    \
   }
-#define FRAGS(FA, FB, ST, KK)                                                         \
-  {                                                                                   \
-    const int ch_ = (KK) * 2 + (lane >> 5);                                           \
-    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                   \
-      const u32x4 va_ = sA[ST][swz(wm * 64 + i * 32 + (lane & 31), ch_)];             \
-      const u32x4 vb_ = sB[ST][swz(wn * 64 + i * 32 + (lane & 31), ch_)];             \
-      FA[i] = *reinterpret_cast<const bf16x8 *>(&va_);                                \
-      FB[i] = *reinterpret_cast<const bf16x8 *>(&vb_);                                \
-    }                                                                                 \
+#define FRAGS(BUF, ST, KK)                                                               \
+  {                                                                                      \
+    const int ch_ = (KK) * 2 + (lane >> 5);                                              \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
+      const u32x4 va_ = SA(ST)[swz((wm * TM + i) * 32 + (lane & 31), ch_)];              \
+      fa[BUF][i] = *reinterpret_cast<const bf16x8 *>(&va_);                              \
+    }                                                                                    \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
+      const u32x4 vb_ = SB(ST)[swz((wn * TN + j) * 32 + (lane & 31), ch_)];              \
+      fb[BUF][j] = *reinterpret_cast<const bf16x8 *>(&vb_);                              \
+    }                                                                                    \
   }
-#define MFMA4(FA, FB)                                                                 \
-  _Pragma("unroll") for (int i = 0; i < 2; ++i)                                       \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                     \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);
+#define MFMAS(BUF)                                                                       \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                       \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[BUF][i], fb[BUF][j], acc[i][j], 0, 0, 0);
 
-  // prologue: tiles 0 and 1 to LDS, tiles 2 .. NS+1 into the register sets (set of tile t = t % NS)
-  GLOAD(0, 0)
-  LSTORE(0, 0)
-  if (nk > 1) {
-    GLOAD(1 % NS, 1)
-    LSTORE(1 % NS, 1)
+  // prologue: tiles 0 .. LEAD-1 to LDS, tiles LEAD .. LEAD+NS-1 into the register sets (set of tile t = t % NS)
+#pragma unroll
+  for (int t = 0; t < LEAD; ++t) {
+    if (t < nk) {
+      GLOAD(t % NS, t)
+      LSTORE(t % NS, t)
+    }
   }
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    if (s + 2 < nk) { GLOAD((s + 2) % NS, s + 2) }
+    if (s + LEAD < nk) { GLOAD((s + LEAD) % NS, s + LEAD) }
   }
   __syncthreads();
 
-  f32x16 acc[2][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int kk0 = 2 * kgrp, kk1 = 2 * kgrp + 1;
-  bf16x8 fa0[2], fb0[2], fa1[2], fb1[2];
-  FRAGS(fa0, fb0, 0, kk0)
-  int st = 0;   // LDS stage of tile ks
+  const int kbase = KSUB * kgrp;   // first k-slice of this wave's k-group
+  bf16x8 fa[2][TM], fb[2][TN];     // double-buffered fragments
+  FRAGS(0, 0, kbase)
+  int st = 0;                      // LDS stage of tile ks
   // One k-step.  IF(c) guards the parts that run out near the end; it is empty in the steady loop so
   // that the loop body is a single basic block (the wait counters are then tracked exactly).
-#define KSTEP(U, KS, IF)                                                         \
-  {                                                                              \
-    const int st1 = st == LS - 1 ? 0 : st + 1;                                   \
-    const int st2 = st1 == LS - 1 ? 0 : st1 + 1;                                 \
-    FRAGS(fa1, fb1, st, kk1)                                                     \
-    __builtin_amdgcn_sched_barrier(0);                                           \
-    MFMA4(fa0, fb0)                                                              \
-    __builtin_amdgcn_sched_barrier(0);                                           \
-    IF((KS) + 2 < nk) { LSTORE(((U) + 2) % NS, st2) }                            \
-    IF((KS) + 2 + NS < nk) { GLOAD(((U) + 2) % NS, (KS) + 2 + NS) }              \
-    IF((KS) + 1 < nk) { FRAGS(fa0, fb0, st1, kk0) }                              \
-    __builtin_amdgcn_sched_barrier(0);                                           \
-    MFMA4(fa1, fb1)                                                              \
-    __builtin_amdgcn_sched_barrier(0);                                           \
-    __syncthreads();                                                             \
-    st = st1;                                                                    \
+#define KSTEP(U, KS, IF)                                                                 \
+  {                                                                                      \
+    const int st1 = st == LS - 1 ? 0 : st + 1;                                           \
+    const int stw = st + LEAD >= LS ? st + LEAD - LS : st + LEAD;                        \
+    _Pragma("unroll") for (int kk = 0; kk < KSUB; ++kk) {                                \
+      if (kk + 1 < KSUB) {                                                               \
+        FRAGS((kk + 1) & 1, st, kbase + kk + 1)                                          \
+      } else if (LS > 2) {                                                               \
+        IF((KS) + 1 < nk) { FRAGS(0, st1, kbase) }                                       \
+      }                                                                                  \
+      __builtin_amdgcn_sched_barrier(0);                                                 \
+      MFMAS(kk & 1)                                                                      \
+      __builtin_amdgcn_sched_barrier(0);                                                 \
+      if (kk == 0) {                                                                     \
+        IF((KS) + LEAD < nk) { LSTORE(((U) + LEAD) % NS, stw) }                          \
+        IF((KS) + LEAD + NS < nk) { GLOAD(((U) + LEAD) % NS, (KS) + LEAD + NS) }         \
+      }                                                                                  \
+    }                                                                                    \
+    __syncthreads();                                                                     \
+    if (LS == 2) { IF((KS) + 1 < nk) { FRAGS(0, st1, kbase) } }                          \
+    st = st1;                                                                            \
   }
 #define ALWAYS(c)
 #define GUARDED(c) if (c)
-  const int nk_main = nk >= NS + 2 ? (nk - NS - 2) / NS * NS : 0;   // k-steps that need no guard
+  const int nk_main = nk >= NS + LEAD ? (nk - NS - LEAD) / NS * NS : 0;   // k-steps that need no guard
   int ks0 = 0;
   for (; ks0 < nk_main; ks0 += NS) {
 #pragma unroll
@@ -197,42 +230,53 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
 #undef GLOAD
 #undef LSTORE
 #undef FRAGS
-#undef MFMA4
+#undef MFMAS
+#undef SA
+#undef SB
 
   // ---- add the two k-groups: the upper four waves hand their accumulators over through LDS ----
-  float *red = reinterpret_cast<float *>(smem) + (wave & 3) * 64 * 64 + lane;   // 4 x 16 KB
-  if (kgrp == 1) {
+  if (KG == 2) {
+    float *red = reinterpret_cast<float *>(smem) + (wave % (WM * WN)) * (TM * TN * 16 * 64) + lane;
+    if (kgrp == 1) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) red[((i * 2 + j) * 16 + v) * 64] = acc[i][j][v];
+          for (int v = 0; v < 16; ++v) red[((i * TN + j) * 16 + v) * 64] = acc[i][j][v];
+    }
+    __syncthreads();
+    if (kgrp == 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] += red[((i * TN + j) * 16 + v) * 64];
+    }
+    __syncthreads();   // the output tile below overwrites what was just read
   }
-  __syncthreads();
   // ---- round once to bf16 into a row-major LDS tile ----
   // accumulator element v of lane L: row 8*(v/4) + 4*(L/32) + v%4, column L%32 of its 32x32 block
-  uint16_t *sOut = reinterpret_cast<uint16_t *>(smem) + 64 * 1024 / 2;            // [BM][BN] bf16 = 32 KB
+  uint16_t *sOut = reinterpret_cast<uint16_t *>(smem);   // [BM][BN] bf16
   if (kgrp == 0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float s = acc[i][j][v] + red[((i * 2 + j) * 16 + v) * 64];
-          const int row = wm * 64 + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-          const int col = wn * 64 + j * 32 + (lane & 31);
-          sOut[row * BN + col] = f32_to_bf16_rne(s);
+          const int row = (wm * TM + i) * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+          const int col = (wn * TN + j) * 32 + (lane & 31);
+          sOut[row * BN + col] = f32_to_bf16_rne(acc[i][j][v]);
         }
   }
   __syncthreads();
   // ---- scatter: every output row slice is contiguous in the cache; 16 bytes per lane ----
   bf16_t *dst_half = static_cast<bf16_t *>(n0 >= Hd ? a.Vc : a.Kc);
-#pragma unroll
-  for (int i = 0; i < (BM * BN / 8) / 512; ++i) {
-    const int idx = i * 512 + tid;
-    const int row = idx >> 4, vec = idx & 15;            // 16 vectors of 8 columns per row
+  constexpr int VPR = BN / 8;   // 16-byte vectors per tile row
+  for (int idx = tid; idx < BM * VPR; idx += 512) {
+    const int row = idx / VPR, vec = idx - row * VPR;
     const long long off = s_dst[row * nh + (vec * 8) / a.d];
     if (off >= 0) {
       const u32x4 val = *reinterpret_cast<const u32x4 *>(sOut + row * BN + vec * 8);
@@ -272,6 +316,18 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
   }
 }
 
+// The tile shapes the launcher chooses from, largest first.
+struct TileShape {
+  int bm, bn, bk;
+};
+constexpr TileShape kTiles[] = {{256, 256, 32}, {256, 128, 64}, {128, 128, 64}, {128, 64, 64}, {128, 32, 64}};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+bool tile_fits(const adore_config &c, const TileShape &t) {
+  const int Hd = c.heads * c.head_dim;
+  return c.hidden % t.bk == 0 && Hd % t.bn == 0 && (t.bn % c.head_dim == 0 || c.head_dim % t.bn == 0);
+}
+
 }  // namespace
 
 hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r) {
@@ -289,18 +345,36 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   a.B = c.batch; a.H = c.heads; a.d = c.head_dim; a.D = c.hidden; a.K = c.cache_slots;
   a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.M = c.batch * r; a.N = 2 * c.heads * c.head_dim;
-  a.tiles_m = (a.M + BM - 1) / BM; a.tiles_n = a.N / BN;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM, ctx->stream);
-  const bool mfma_ok = c.dtype == ADORE_BF16 && c.hidden % BK == 0 && (c.heads * c.head_dim) % BN == 0 &&
-                       (BN % c.head_dim == 0 || c.head_dim % BN == 0);
-  if (mfma_ok) {
+  // the largest tile that still gives each of the 256 compute units a workgroup; the smallest that fits otherwise
+  int pick = -1;
+  if (c.dtype == ADORE_BF16) {
+    for (int i = 0; i < kNumTiles; ++i) {
+      if (!tile_fits(c, kTiles[i])) continue;
+      pick = i;
+      const long long tiles = (long long)((a.M + kTiles[i].bm - 1) / kTiles[i].bm) * (a.N / kTiles[i].bn);
+      if (tiles >= 256) break;
+    }
+    if (const char *e = getenv("ADORE_GEMM_TILE")) {   // tuning runs: force a tile shape by index
+      const int v = atoi(e);
+      if (v >= 0 && v < kNumTiles && tile_fits(c, kTiles[v])) pick = v;
+    }
+  }
+  if (pick >= 0) {
+    a.tiles_m = (a.M + kTiles[pick].bm - 1) / kTiles[pick].bm;
+    a.tiles_n = a.N / kTiles[pick].bn;
     const int total = a.tiles_m * a.tiles_n;
-    const int grid = (total + 7) / 8 * 8;
-    const int nk = c.hidden / BK;   // the k-loop is unrolled by the number of register stages
-    if (nk % 4 == 0) ADORE_LAUNCH(t, (rebuild_mfma_kernel<4>), dim3(grid), dim3(512), 0, ctx->stream, a);
-    else if (nk % 2 == 0) ADORE_LAUNCH(t, (rebuild_mfma_kernel<2>), dim3(grid), dim3(512), 0, ctx->stream, a);
-    else ADORE_LAUNCH(t, (rebuild_mfma_kernel<1>), dim3(grid), dim3(512), 0, ctx->stream, a);
+    const dim3 grid((total + 7) / 8 * 8), block(512);
+    //                                        BM   BN  BK KG WM WN LS NS
+    switch (pick) {
+      case 0: ADORE_LAUNCH(t, (rebuild_mfma_kernel<256, 256, 32, 1, 2, 4, 4, 2>), grid, block, 0, ctx->stream, a); break;
+      case 1: ADORE_LAUNCH(t, (rebuild_mfma_kernel<256, 128, 64, 1, 4, 2, 3, 2>), grid, block, 0, ctx->stream, a); break;
+      case 2: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 128, 64, 2, 2, 2, 3, 4>), grid, block, 0, ctx->stream, a); break;
+      case 3: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 64, 64, 2, 2, 2, 3, 4>), grid, block, 0, ctx->stream, a); break;
+      default: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 32, 64, 2, 4, 1, 3, 4>), grid, block, 0, ctx->stream, a); break;
+    }
   } else {
+    a.tiles_m = a.tiles_n = 0;
     const size_t waves = size_t(a.M) * a.N;
     const unsigned blocks = unsigned((waves + 3) / 4);
     if (c.dtype == ADORE_BF16) {

@@ -230,6 +230,18 @@ def test_attention_launch_shapes(split, waves, monkeypatch):
     job.adore.close()
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+def test_rebuild_gemm_tile_shapes(tile, monkeypatch):
+    """Every output-tile shape of the re-projection kernel (256x256 ... 128x32) gives the oracle's cache rows
+    and outputs: M = B*R = 3*45 = 135 rows is a ragged tile in each of them, d = 64 puts up to four head
+    slices into one tile row, and D = 448 leaves a guarded tail in every pipeline depth."""
+    h = _harness()
+    monkeypatch.setenv("ADORE_GEMM_TILE", str(tile))
+    w = Workload("tiles", L=1, B=3, H=8, d=64, D=448, K=128, R=45, S=200, T=5, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=1)
+    job.adore.close()
+
+
 def test_llama7b_layer_full_size_steps():
     """The benchmark workload at its full size and in the launch configuration bench.py times
     (B16 H32 d128 D4096 K512 R32, prompt 1024): init plus six free-running steps, every slot map,
