@@ -99,6 +99,92 @@ def run_gpu(w, steps, warmup, prof_steps):
     return elapsed, per_kernel_us
 
 
+def run_stack(w, steps, warmup, prof_steps):
+    """Layer-stack workload: every step runs attend x L, one schedule, rebuild x L through the fine-grained
+    calls, layers launched one after the other.  Next to it the full-attention comparator of Eq. 1: the
+    same attention kernel over a cache with room for every token (K_full - 1 >= N_max, nothing released,
+    nothing rebuilt), which reads n+1 rows per (sequence, head) instead of K.
+
+    The large tensors (W_kv, hidden states, prompt K/V) are drawn on the device from a seeded torch
+    generator: tens of GB, which the host generator of the parity tests would take minutes to produce;
+    the small controller weights come from that generator as everywhere else."""
+    import torch
+    from gen import SyntheticInputs
+    from paper_2407_02328_amd import Adore, make_config
+    from tests.gpu_harness import DEV, storage_dtype, to_dev
+    st = storage_dtype(w)
+    total = warmup + steps + prof_steps
+    assert w.S + total <= w.N_max, "not enough positions for this many steps"
+    g = torch.Generator(device=DEV)
+    g.manual_seed(w.seed)
+
+    def randn(shape, std=1.0):
+        out = torch.empty(shape, dtype=st, device=DEV)
+        flat = out.view(-1)
+        piece = 1 << 28
+        for i in range(0, flat.numel(), piece):         # bounded temporaries
+            n = min(piece, flat.numel() - i)
+            flat[i:i + n] = (torch.randn(n, generator=g, device=DEV, dtype=torch.float32) * std).to(st)
+        return out
+
+    t0 = time.time()
+    dp = w.dprime
+    small = SyntheticInputs(w.scaled(L=1, H=1, d=64, B=1)).weights()    # controller tensors do not depend on L, H, d, B
+    wts = {k: to_dev(v, st if k in ("gru_w_ih", "gru_w_hh") else torch.float32) for k, v in small.items() if k != "w_kv"}
+    wts["w_kv"] = randn((w.L, 2 * w.H * w.d, w.D), w.w_std)
+    hidden = randn((w.L, w.B, w.N_max, w.D))
+    q = randn((w.L, w.B, w.H, w.d)); k = randn((w.L, w.B, w.H, w.d)); v = randn((w.L, w.B, w.H, w.d))
+    out = torch.empty((w.L, w.B, w.H, w.d), dtype=torch.float32, device=DEV)
+    prompt_k = randn((w.L, w.B, w.H, w.S, w.d)); prompt_v = randn((w.L, w.B, w.H, w.S, w.d))
+    ctrl_in = hidden[0][:, :w.S].contiguous()
+    xs = [hidden[0][:, w.S + t].contiguous() for t in range(total)]
+    torch.cuda.synchronize()
+    log(f"stack inputs drawn on the device in {time.time() - t0:.1f}s")
+
+    def make(K, R):
+        cfg = make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=K,
+                          rebuild_budget=R, max_positions=w.N_max, ctrl_hidden=dp, dtype=w.dtype,
+                          pos_scale=w.pos_scale)
+        a = Adore(cfg, wts, DEV)
+        a.init_cache(prompt_k, prompt_v, hidden, ctrl_in, None, w.S)
+        torch.cuda.synchronize()
+        return a
+
+    def timed(a, with_rebuild):
+        def step(t):
+            for l in range(w.L):
+                a.attend(l, q[l], k[l], v[l], out[l])
+            a.schedule(xs[t], None, None, None, None)
+            for l in range(w.L):
+                a.rebuild(l, hidden[l])
+        for t in range(warmup):
+            step(t)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for t in range(warmup, warmup + steps):
+            step(t)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t1
+        a.set_timing(True)
+        for t in range(warmup + steps, total):
+            step(t)
+        timing = a.read_timing()
+        a.set_timing(False)
+        assert bool(torch.isfinite(out).all())
+        # per launch: a step launches attend and the GEMM once per layer
+        return elapsed, {kk: (1e3 * ms / cnt if cnt else 0.0) for kk, (ms, cnt) in timing.items()}
+
+    sparse = make(w.K, w.R)
+    el_s, us_s = timed(sparse, True)
+    sparse.close()
+    del sparse
+    torch.cuda.empty_cache()
+    full = make(w.N_max + 1, 0)            # m = K - 0 - 1 = N_max: every token stays
+    el_f, us_f = timed(full, False)
+    full.close()
+    return el_s, us_s, el_f, us_f
+
+
 def run_cpu_baseline(w, seqs=16, steps=40):
     """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
     from threadpoolctl import threadpool_info
@@ -141,10 +227,22 @@ def main():
         sys.exit("bench.py needs a GPU (the HIP path has no CPU fallback)")
     from gen import workload
     w = workload(args.workload)
-    if w.L != 1:
-        sys.exit("bench.py times single-layer workloads")
     work = algorithmic_work(w)
-    elapsed, per_kernel_us = run_gpu(w, args.steps, args.warmup, args.profile_steps)
+    stack = None
+    if w.L != 1:
+        elapsed, per_kernel_us, el_full, us_full = run_stack(w, args.steps, args.warmup, args.profile_steps)
+        n_mid = w.S + args.warmup + args.steps // 2
+        full_bytes = 4 * w.B * w.H * (n_mid + 1) * w.d * (2 if w.dtype == "bf16" else 4) // 2
+        stack = {"layers": w.L, "ms_per_step_all_layers": round(1e3 * elapsed / args.steps, 4),
+                 "full_attention_ms_per_step_all_layers": round(1e3 * el_full / args.steps, 4),
+                 "sparse_vs_full_throughput": round(el_full / elapsed, 3),
+                 "full_attention_attend_us": round(us_full["attend"] + us_full["attend_combine"], 2),
+                 "full_attention_attend_GBs": round(full_bytes / ((us_full["attend"] + us_full["attend_combine"]) * 1e-6) / 1e9, 1),
+                 "full_attention_rows_per_head": n_mid + 1}
+        elapsed /= w.L                       # the metric is per decode layer
+        args.no_cpu_baseline = True          # the oracle sample is defined on the single-layer workloads
+    else:
+        elapsed, per_kernel_us = run_gpu(w, args.steps, args.warmup, args.profile_steps)
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.B * args.steps / elapsed
 
@@ -168,12 +266,14 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
-                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": 1},
+                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L},
         "roofline": dominant,
         "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
         "kernel_us_sum": round(sum(per_kernel_us.values()), 2),
     }
+    if stack:
+        line["stack"] = stack
     if not args.no_cpu_baseline:
         t0 = time.time()
         line["cpu_baseline"] = run_cpu_baseline(w)

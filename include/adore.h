@@ -99,7 +99,8 @@ size_t adore_workspace_bytes(const adore_config *cfg);
  * cfg and weights are HOST structs and are copied.  The cache starts empty;
  * call adore_init_cache before the first step.
  * Errors: E_INVALID (null, R > K-2, sizes <= 0), E_UNSUPPORTED (head_dim not in
- * {64,128}, K > 1024 ... see adore_strerror), E_WORKSPACE. */
+ * {64,128}, K > 1024 unless K - R - 1 >= N_max, i.e. a cache that holds every
+ * token and is the full attention of Eq. 1 ... see adore_strerror), E_WORKSPACE. */
 int adore_create(const adore_config *cfg, const adore_weights *weights, void *workspace,
                  size_t workspace_bytes, void *hip_stream, adore_ctx **out);
 

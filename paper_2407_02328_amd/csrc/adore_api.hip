@@ -59,8 +59,11 @@ bool config_ok(const adore_config *c) {
 }
 
 bool config_supported(const adore_config *c) {
-  return (c->head_dim == 64 || c->head_dim == 128) && c->cache_slots <= kMaxSlots && c->hidden % 8 == 0 &&
-         c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024;
+  // the selecting release kernel keeps a row's keys in the registers of one wave; a cache that never has to
+  // release (K - R - 1 >= N_max: full attention) may have any number of slots
+  const bool never_releases = c->cache_slots - c->rebuild_budget - 1 >= c->max_positions;
+  return (c->head_dim == 64 || c->head_dim == 128) && (c->cache_slots <= kMaxSlots || never_releases) &&
+         c->hidden % 8 == 0 && c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024;
 }
 
 Layout make_layout(const adore_config &c) {
@@ -477,8 +480,9 @@ const char *adore_strerror(int code) {
     case ADORE_E_INVALID: return "invalid argument (null pointer, bad shape or value)";
     case ADORE_E_STATE: return "call out of order for this step, or step past max_positions";
     case ADORE_E_UNSUPPORTED:
-      return "unsupported configuration (need head_dim in {64,128}, cache_slots <= 1024, hidden % 8 == 0, "
-             "max_positions <= 262144, ctrl_hidden <= 1024)";
+      return "unsupported configuration (need head_dim in {64,128}, cache_slots <= 1024 or "
+             "cache_slots - rebuild_budget - 1 >= max_positions, hidden % 8 == 0, max_positions <= 262144, "
+             "ctrl_hidden <= 1024)";
     case ADORE_E_WORKSPACE: return "workspace too small or not 256-byte aligned";
     case ADORE_E_HIP: return "HIP runtime call failed";
     default: return "unknown error";

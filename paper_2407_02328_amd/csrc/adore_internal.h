@@ -18,7 +18,7 @@ struct bf16_t {
 };
 
 constexpr int kMaxSplits = 16;        // attention partials per (b,h) row
-constexpr int kMaxSlots = 1024;       // K handled by the one-slot-per-thread release kernel
+constexpr int kMaxSlots = 1024;       // largest K of a cache that releases (a row's keys live in one wave's registers)
 constexpr int kMaxPositions = 1 << 18; // residency bitmap of a sequence lives in LDS
 constexpr int kPromptChunk = 512;     // tokens per GRU input-projection launch at init
 constexpr int kMaxCtrlSplit = 16;     // D-slices of the GRU input projection

@@ -220,6 +220,45 @@ __global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict_
   }
 }
 
+// Release step of a row that gives nothing up (x = 0: the cache still has room for every token, which
+// is always so when K - R - 1 >= N_max, the full-attention setting of Eq. 1).  Any K: the wave walks
+// the row in chunks of 64 slots, enters the current token and lists the first R1 free slots.
+__global__ __launch_bounds__(256) void release_none_kernel(const int32_t *__restrict__ slot_src,
+                                                           int32_t *__restrict__ slot_dst,
+                                                           const int32_t *__restrict__ insert_slot,
+                                                           int32_t *__restrict__ free_list,
+                                                           int32_t *__restrict__ released_pos,
+                                                           int32_t *__restrict__ map_out,
+                                                           int32_t *__restrict__ rel_out, int rows, int K, int n,
+                                                           int R1) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;                      // whole wave leaves together
+  const int lane = threadIdx.x & 63;
+  const int32_t *sp = slot_src + size_t(row) * K;
+  int32_t *dp = slot_dst + size_t(row) * K;
+  const int s_ins = insert_slot[row];
+  int nfree = 0;
+  for (int k0 = 0; k0 < K; k0 += 64) {          // uniform trip count: the ballots see all 64 lanes
+    const int k = k0 + lane;
+    const int pos = k < K ? (k == s_ins ? n : sp[k]) : 0;
+    const bool is_free = k < K && pos < 0;
+    const uint64_t bf = __ballot(is_free);
+    if (is_free) {
+      const int idx = nfree + __popcll(bf & ((uint64_t(1) << lane) - 1));
+      if (idx < R1) free_list[size_t(row) * R1 + idx] = k;
+    }
+    if (k < K) {
+      dp[k] = pos;
+      if (map_out) map_out[size_t(row) * K + k] = pos;
+    }
+    nfree += __popcll(bf);
+  }
+  for (int t = lane; t < R1; t += 64) {
+    released_pos[size_t(row) * R1 + t] = -1;
+    if (rel_out) rel_out[size_t(row) * R1 + t] = -1;
+  }
+}
+
 // ---- per-sequence choice of the tokens to rebuild -------------------------------
 struct RebuildSelectArgs {
   int32_t *slot_pos;           // [B][H][K]
@@ -420,6 +459,13 @@ hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int 
   const int rows = c.batch * c.heads;
   const dim3 grid((rows + 3) / 4), block(256);
   ScopedTimer t(ctx, ADORE_KERNEL_RELEASE, st);
+  if (c.cache_slots > kMaxSlots) {
+    if (x != 0) return hipErrorInvalidValue;   // the API only admits such K when nothing is ever released
+    ADORE_LAUNCH(t, release_none_kernel, grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],
+                 ctx->insert_slot[src], ctx->free_list[dst], ctx->released_pos, map_out, rel_out, rows,
+                 c.cache_slots, ctx->n, c.rebuild_budget + 1);
+    return hipGetLastError();
+  }
 #define ADORE_RELEASE(KPL)                                                                                   \
   ADORE_LAUNCH(t, (release_kernel<KPL>), grid, block, 0, st, ctx->slot_pos[src], ctx->slot_pos[dst],       \
                      ctx->insert_slot[src], ctx->score, ctx->free_list[dst], ctx->released_pos, map_out, rel_out, rows, \

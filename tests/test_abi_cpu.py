@@ -74,10 +74,18 @@ def test_create_rejects_bad_arguments(lib):
                dict(cache_slots=1, rebuild_budget=0)):
         bad = cfg_for(w, **kw)
         assert lib.adore_create(ctypes.byref(bad), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1, kw
-    for kw in (dict(head_dim=96), dict(cache_slots=2048), dict(hidden=260)):
+    for kw in (dict(head_dim=96), dict(cache_slots=2048, max_positions=4096), dict(hidden=260)):
         uns = cfg_for(w, **kw)
         big = lib.adore_workspace_bytes(ctypes.byref(uns))
         assert lib.adore_create(ctypes.byref(uns), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3, kw
+    # more than 1024 slots are fine when the cache never has to release: K - R - 1 >= N_max (full attention)
+    full = cfg_for(w, cache_slots=2048, max_positions=2048 - w.R - 1)
+    big = lib.adore_workspace_bytes(ctypes.byref(full))
+    assert lib.adore_create(ctypes.byref(full), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
+    assert lib.adore_destroy(h) == 0
+    over = cfg_for(w, cache_slots=2048, max_positions=2048 - w.R)
+    big = lib.adore_workspace_bytes(ctypes.byref(over))
+    assert lib.adore_create(ctypes.byref(over), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3
     wt2 = fake_weights()
     wt2.out_b = None
     assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt2), FAKE, n, None, ctypes.byref(h)) == -1

@@ -230,6 +230,18 @@ def test_attention_launch_shapes(split, waves, monkeypatch):
     job.adore.close()
 
 
+def test_full_attention_cache_holds_every_token():
+    """K - R - 1 >= N_max: nothing is ever released, the step is the full attention of Eq. 1 over a cache of
+    more than 1024 slots (the no-release kernel walks the row in chunks), and the slot map stays the identity."""
+    h = _harness()
+    w = Workload("full", L=1, B=2, H=2, d=128, D=256, K=1500, R=4, S=1100, T=5, dtype="bf16", dprime=32)
+    worst, job, orc = h.lockstep(w, steps=w.T)
+    sm = job.slot_map.cpu().numpy()
+    n_last = w.S + w.T - 1
+    assert (sm[..., :n_last + 1] == np.arange(n_last + 1)).all() and (sm[..., n_last + 1:] == -1).all()
+    job.adore.close()
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_rebuild_gemm_tile_shapes(tile, monkeypatch):
     """Every output-tile shape of the re-projection kernel (256x256 ... 128x32) gives the oracle's cache rows
