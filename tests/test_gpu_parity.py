@@ -282,3 +282,14 @@ def test_high_batch_reduced():
     w = workload("high_batch").scaled(B=8, T=10)
     worst, job, _ = h.lockstep(w, steps=8, check_cache_every=4)
     job.adore.close()
+
+
+def test_stack32_reduced_all_layers():
+    """The 32-layer stack (attend x 32, one schedule, rebuild x 32 through the fine-grained calls) with small
+    heads and hidden size: every layer's outputs, slot maps and cache rows over eight steps, so that a wrong
+    per-layer offset into the cache, W_kv or the hidden store shows on the layer it belongs to."""
+    h = _harness()
+    w = workload("stack32").scaled(B=2, H=2, D=256, K=64, R=8, S=100, T=10, dprime=32)
+    assert w.L == 32
+    worst, job, _ = h.lockstep(w, steps=8, check_cache_every=4)
+    job.adore.close()
