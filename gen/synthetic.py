@@ -53,6 +53,7 @@ class Workload:
     act_std: float = 1.0     # q, k, v, hidden
     w_std: float = 0.02      # W_kv
     salience: bool = False   # heavy-tailed per-token offset (long-context workload)
+    rescore: bool = False    # controller scores every token again at every step (relative position)
     seed: int = BASE_SEED
 
     @property

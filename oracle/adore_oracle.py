@@ -26,7 +26,12 @@ Readings of points the paper leaves open (each used exactly as stated here):
   * Position feature of token i is the scalar i * pos_scale fed to a 1 -> d'
     fully connected layer (App. "Implementation Details", position layer).
   * sigma_i is computed once, when token i arrives, and never changes
-    (Eq. 2 carries no dependence on the current step).
+    (Eq. 2 carries no dependence on the current step).  The other reading of
+    Sec. 2.2 and the caption of Fig. 2 (the controller rates every cached
+    token "for the current token") is the `rescore` mode: at step n every
+    token i <= n is scored again from its stored GRU state z_i with the
+    RELATIVE position (n - i) * pos_scale in place of i * pos_scale, and
+    both selections of that step use the new values.
   * The current token is not released in its own step (Sec. 2.2: an "older"
     state is removed).
   * Tokens released in this step may be rebuilt in this step (Sec. 2.3).
@@ -163,6 +168,7 @@ class OracleConfig:
     dprime: int
     dtype: str            # "f32" | "bf16"
     pos_scale: float
+    rescore: bool = False # score every token again at every step, with its distance to the current token
 
     @property
     def m(self) -> int:
@@ -190,6 +196,8 @@ class AdoreOracle:
         self.slot_pos = np.full((c.B, c.H, c.K), -1, dtype=np.int32)
         self.score = np.zeros((c.B, c.N_max), dtype=np.float32)
         self.z = np.zeros((c.B, c.dprime), dtype=F64)
+        self.z_all = np.zeros((c.B, c.N_max, c.dprime), dtype=F64) if c.rescore else None   # z_i of every token
+        self.own_scores = None           # rescore mode: the scores of the last step before any override
         self.n = 0                       # position of the next token to arrive
         self.last_probs = None           # attention probabilities of the last step (diagnostics)
 
@@ -198,8 +206,21 @@ class AdoreOracle:
         w = self.w64
         self.z[b] = gru_cell(x.astype(F64), self.z[b], w["gru_w_ih"], w["gru_w_hh"],
                              w["gru_b_ih"], w["gru_b_hh"])
-        delta = F64(np.float32(i) * np.float32(self.cfg.pos_scale))
+        if self.cfg.rescore:
+            self.z_all[b, i] = self.z[b]
+            delta = F64(0.0)             # the arriving token is at distance 0 from itself
+        else:
+            delta = F64(np.float32(i) * np.float32(self.cfg.pos_scale))
         return keep_probability(self.z[b], delta, w)
+
+    def _rescore(self, b: int, n: int) -> np.ndarray:
+        """Rescore mode: sigma_i for every token i <= n as seen from the current token n (Eq. 2 with the
+        position feature of the distance n - i and the stored state z_i)."""
+        out = np.zeros(n + 1, dtype=F64)
+        for i in range(n + 1):
+            delta = F64(np.float32(n - i) * np.float32(self.cfg.pos_scale))
+            out[i] = keep_probability(self.z_all[b, i], delta, self.w64)
+        return out
 
     # -- rebuild ------------------------------------------------------------
     def _project(self, layer: int, x_rows: np.ndarray) -> np.ndarray:
@@ -244,6 +265,12 @@ class AdoreOracle:
             for i in range(S):
                 s = self._controller(b, ctrl_input[b, i], i)
                 self.score[b, i] = np.float32(s) if score_override is None else score_override[b, i]
+            if c.rescore:                # all prompt tokens as seen from the last one
+                own = self._rescore(b, S - 1)
+                if self.own_scores is None or self.own_scores.shape[1] != S:
+                    self.own_scores = np.zeros((c.B, S), dtype=F64)
+                self.own_scores[b] = own
+                self.score[b, :S] = own.astype(np.float32) if score_override is None else score_override[b, :S]
             keep = min(S, c.m)
             older = ranked(range(S - 1), self.score[b])[:keep - 1]
             residents = sorted(older + [S - 1])
@@ -266,7 +293,8 @@ class AdoreOracle:
 
         Returns (out [L,B,H,d] fp64, slot_map [B,H,K] i32, released_pos [B,H,R+1] i32,
         rebuilt_pos [B,R] i32, own_score [B] fp64) where own_score is the controller's
-        value before any override.
+        value before any override.  In rescore mode score_override, if given, is [B, n+1]
+        (every token's score of this step) and `own_scores` [B, n+1] keeps the oracle's own.
         """
         c = self.cfg
         n = self.n
@@ -295,8 +323,15 @@ class AdoreOracle:
                     probs[(l, b, h)] = (valid, p)
             # 3. controller: score of the arriving token; older scores unchanged
             own_score[b] = self._controller(b, x_n[b], n)
-            self.score[b, n] = (np.float32(own_score[b]) if score_override is None
-                                else np.float32(score_override[b]))
+            if c.rescore:
+                if b == 0:
+                    self.own_scores = np.zeros((c.B, n + 1), dtype=F64)
+                self.own_scores[b] = self._rescore(b, n)
+                self.score[b, :n + 1] = (self.own_scores[b].astype(np.float32) if score_override is None
+                                         else np.asarray(score_override[b], dtype=np.float32))
+            else:
+                self.score[b, n] = (np.float32(own_score[b]) if score_override is None
+                                    else np.float32(score_override[b]))
             # 4. release
             for h in range(c.H):
                 freed = release_lowest(self.slot_pos[b, h], self.score[b], n, c.m)

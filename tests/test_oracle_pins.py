@@ -343,6 +343,108 @@ def test_invariants_with_controller_scores():
     _run(orc, inp, w, w.T, collect=check)
 
 
+# --------------------------------------------------------------------------
+# rescore mode (every token scored again at every step, with its distance to the current token)
+# --------------------------------------------------------------------------
+def test_rescore_without_position_dependence_is_the_static_policy():
+    """With a zero position layer weight the score cannot depend on the distance, so scoring every token
+    again gives back the values of the static mode: both modes must walk the same trajectory.  Fails if the
+    stored state z_i is off by one token, if scores land on the wrong positions, or if the selections read
+    stale values."""
+    w_static = small_workload(B=2, H=2, K=12, R=3, S=20, T=24)
+    w_re = w_static.scaled(rescore=True)
+    wts = SyntheticInputs(w_static).weights()
+    wts = dict(wts, pos_w=np.zeros_like(wts["pos_w"]))
+    a, inp, _ = make_oracle(w_static, wts)
+    b, _, _ = make_oracle(w_re, wts)
+    ra = _run(a, inp, w_static, w_static.T)[0]
+    rb = _run(b, inp, w_re, w_re.T)[0]
+    for (oa, ma, rla, rba, sa), (ob, mb, rlb, rbb, sb) in zip(ra, rb):
+        assert np.array_equal(ma, mb) and np.array_equal(rla, rlb) and np.array_equal(rba, rbb)
+        assert np.array_equal(oa, ob)
+        assert np.allclose(sa, sb, rtol=0, atol=1e-15)
+    assert np.array_equal(a.score, b.score)
+
+
+def test_rescore_with_pure_recency_scores_is_a_sliding_window():
+    """GRU weights zero (z_i = 0 for every token), identity interaction layer, positive output weights and
+    a negative position weight: the score is a strictly decreasing function of the distance n - i alone,
+    so the policy must keep exactly the m most recent tokens and rebuild the R before them, most recent
+    first -- window attention.  Absolute positions, a flipped sign of the distance or an off-by-one in
+    it all break this."""
+    w = small_workload(B=2, H=2, K=12, R=3, S=20, T=24, rescore=True, pos_scale=2.0 ** -6)
+    wts = SyntheticInputs(w).weights()
+    dp = w.dprime
+    wts = dict(wts, gru_w_ih=np.zeros_like(wts["gru_w_ih"]), gru_w_hh=np.zeros_like(wts["gru_w_hh"]),
+               gru_b_ih=np.zeros_like(wts["gru_b_ih"]), gru_b_hh=np.zeros_like(wts["gru_b_hh"]),
+               pos_w=np.full(dp, -1.0, dtype=np.float32), pos_b=np.zeros(dp, dtype=np.float32),
+               mlp_w1=np.eye(dp, dtype=np.float32), mlp_b1=np.zeros(dp, dtype=np.float32),
+               out_w=np.ones(dp, dtype=np.float32), out_b=np.zeros(1, dtype=np.float32))
+    orc, inp, _ = make_oracle(w, wts)
+
+    def check(n, res):
+        out, slot_map, released, rebuilt, _ = res
+        want_rebuilt = [n - w.m - j for j in range(w.R)]
+        window = set(range(n - w.m + 1, n + 1))
+        for b in range(w.B):
+            assert rebuilt[b].tolist() == want_rebuilt
+            for h in range(w.H):
+                held = {int(p) for p in slot_map[b, h] if p >= 0}
+                assert held == window | set(want_rebuilt)
+            assert np.all(np.diff(orc.score[b, :n + 1].astype(np.float64)) > 0)     # newer = higher
+
+    _run(orc, inp, w, w.T, collect=check)
+
+
+def test_rescore_invariants_and_promotion_of_rebuilt_tokens():
+    """Random controller weights in rescore mode: the counting invariants of the static mode still hold
+    (one free slot, current token kept, released count, rebuilt = top of the pool by this step's scores),
+    and scores do change between steps, so that a rebuilt token can stay as a resident (a promotion)."""
+    w = small_workload(B=2, H=3, K=10, R=2, S=12, T=40, rescore=True, pos_scale=2.0 ** -3)
+    orc, inp, _ = make_oracle(w)
+    seen = {"changed": False, "promoted": False, "prev_rb": [set() for _ in range(w.B)], "prev": None}
+
+    def check(n, res):
+        out, slot_map, released, rebuilt, own = res
+        for b in range(w.B):
+            for h in range(1, w.H):
+                assert np.array_equal(slot_map[b, h], slot_map[b, 0])
+            held = [int(p) for p in slot_map[b, 0] if p >= 0]
+            assert len(held) == len(set(held)) == min(n + 1, w.K - 1) and n in held
+            rb = [int(p) for p in rebuilt[b] if p >= 0]
+            rel = [int(p) for p in released[b, 0] if p >= 0]
+            assert len(rel) == max(0, min(n + 1, w.K) - w.m)
+            sc = orc.score[b, :n + 1]
+            assert np.allclose(sc, orc.own_scores[b], rtol=0, atol=1e-7)
+            pool = sorted(set(range(n + 1)) - (set(held) - set(rb)), key=lambda p: (-float(sc[p]), p))
+            assert rb == pool[:min(w.R, len(pool))]
+            persistent = set(held) - set(rb)
+            if seen["prev_rb"][b] & persistent:
+                seen["promoted"] = True          # rebuilt last step, resident now
+            seen["prev_rb"][b] = set(rb)
+        if seen["prev"] is not None and not np.array_equal(seen["prev"], orc.score[:, :n]):
+            seen["changed"] = True
+        seen["prev"] = orc.score[:, :n + 1].copy()
+
+    _run(orc, inp, w, w.T, collect=check)
+    assert seen["changed"] and seen["promoted"]
+    # the value itself: torch layers applied to the stored GRU states (a torch GRU over the same inputs)
+    # with the distance to the last token as position feature.  Catches an offset in the distance.
+    wt = {k: torch.tensor(np.asarray(v, dtype=np.float64)) for k, v in orc.w64.items()}
+    gru = torch.nn.GRU(w.D, w.dprime, batch_first=True).double()
+    with torch.no_grad():
+        gru.weight_ih_l0.copy_(wt["gru_w_ih"]); gru.weight_hh_l0.copy_(wt["gru_w_hh"])
+        gru.bias_ih_l0.copy_(wt["gru_b_ih"]); gru.bias_hh_l0.copy_(wt["gru_b_hh"])
+        x = torch.tensor(inp.hidden_store()[0].astype(np.float64))             # [B, N_max, D]
+        z_all, _ = gru(x)
+        n = w.N_max - 1
+        dist = torch.tensor((n - np.arange(n + 1)).astype(np.float32) * np.float32(w.pos_scale), dtype=torch.float64)
+        p = dist[:, None] * wt["pos_w"][None, :] + wt["pos_b"][None, :]       # [n+1, d']
+        u = torch.tanh((p[None] + z_all[:, :n + 1]) @ wt["mlp_w1"].T + wt["mlp_b1"])
+        want = torch.sigmoid(u @ wt["out_w"] + wt["out_b"][0]).numpy()
+    assert np.abs(want - orc.own_scores).max() < 1e-12
+
+
 def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fits():
     """If the supplied K/V are the projections of the hidden states, a rebuilt row is identical to
     the row that was released; while |pool| <= R every token is present, so the output is Eq. 1
