@@ -218,6 +218,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=50, help="extra steps with per-kernel events")
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rescore", action="store_true",
+                    help="controller scores every token again at every step (relative position)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (the decode step shards by "
@@ -227,6 +229,8 @@ def main():
         sys.exit("bench.py needs a GPU (the HIP path has no CPU fallback)")
     from gen import workload
     w = workload(args.workload)
+    if args.rescore:
+        w = w.scaled(rescore=True)
     work = algorithmic_work(w)
     stack = None
     if w.L != 1:
@@ -266,7 +270,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
-                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L},
+                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
+                   "score_mode": "rescore" if w.rescore else "static"},
         "roofline": dominant,
         "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},

@@ -50,11 +50,20 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 1
+#define ADORE_ABI_VERSION 2
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
 enum { ADORE_F32 = 0, ADORE_BF16 = 1 };
+
+/* When the controller's score of a token is taken (the two readings of Sec. 2.2):
+ * STATIC:  sigma_i once, when token i arrives, with the position feature i * pos_scale (Eq. 2 as printed).
+ * RESCORE: at every step n, sigma_i for every token i <= n from its stored GRU state z_i with the
+ *          position feature (n - i) * pos_scale (the controller rates the cached tokens "for the current
+ *          token", Sec. 2.2 and the caption of Fig. 2); both selections of the step use the new values,
+ *          so a rebuilt token can be kept.  score_override must be NULL in every call, set_state is
+ *          not available, and d' must be a multiple of 4. */
+enum { ADORE_SCORE_STATIC = 0, ADORE_SCORE_RESCORE = 1 };
 
 enum {
   ADORE_OK = 0,
@@ -71,6 +80,7 @@ typedef struct {
   int32_t ctrl_hidden;                                /* d' */
   int32_t dtype;                                      /* ADORE_F32 | ADORE_BF16 */
   float pos_scale;                                    /* position feature of token i = (float)i * pos_scale */
+  int32_t score_mode;                                 /* ADORE_SCORE_STATIC | ADORE_SCORE_RESCORE */
 } adore_config;
 
 /* Device pointers, caller-owned, read-only, must outlive the context. */
@@ -191,6 +201,7 @@ enum {
   ADORE_KERNEL_RELEASE,         /* per-(b,h) release select */
   ADORE_KERNEL_REBUILD_SELECT,  /* per-sequence top-R select + slot assignment */
   ADORE_KERNEL_REBUILD_GEMM,    /* re-projection + scatter */
+  ADORE_KERNEL_RESCORE,         /* RESCORE mode: sigma of every token for the current step */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

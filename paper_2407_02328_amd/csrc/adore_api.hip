@@ -48,13 +48,14 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
-      att_part, gi, total;
+      att_part, gi, cvec, avec, total;
 };
 
 bool config_ok(const adore_config *c) {
   return c && c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
          c->cache_slots >= 2 && c->rebuild_budget >= 0 && c->rebuild_budget <= c->cache_slots - 2 &&
          c->max_positions >= 2 && c->ctrl_hidden > 0 && (c->dtype == ADORE_F32 || c->dtype == ADORE_BF16) &&
+         (c->score_mode == ADORE_SCORE_STATIC || c->score_mode == ADORE_SCORE_RESCORE) &&
          std::isfinite(c->pos_scale);
 }
 
@@ -63,7 +64,8 @@ bool config_supported(const adore_config *c) {
   // release (K - R - 1 >= N_max: full attention) may have any number of slots
   const bool never_releases = c->cache_slots - c->rebuild_budget - 1 >= c->max_positions;
   return (c->head_dim == 64 || c->head_dim == 128) && (c->cache_slots <= kMaxSlots || never_releases) &&
-         c->hidden % 8 == 0 && c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024;
+         c->hidden % 8 == 0 && c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024 &&
+         (c->score_mode == ADORE_SCORE_STATIC || c->ctrl_hidden % 4 == 0);
 }
 
 Layout make_layout(const adore_config &c) {
@@ -91,6 +93,9 @@ Layout make_layout(const adore_config &c) {
   size_t gi_rows = size_t(c.batch) * kPromptChunk;
   if (gi_rows < size_t(kMaxCtrlSplit) * kCtrlSplitTokens) gi_rows = size_t(kMaxCtrlSplit) * kCtrlSplitTokens;
   l.gi = take(gi_rows * 3 * c.ctrl_hidden * 4);
+  const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
+  l.cvec = take(rescore ? size_t(c.batch) * c.max_positions * c.ctrl_hidden * 4 : 0);
+  l.avec = take(rescore ? size_t(c.ctrl_hidden) * 4 : 0);
   l.total = off;
   return l;
 }
@@ -187,6 +192,8 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->init_res = reinterpret_cast<int32_t *>(base + l.init_res);
   ctx->att_part = reinterpret_cast<float *>(base + l.att_part);
   ctx->gi = reinterpret_cast<float *>(base + l.gi);
+  ctx->cvec = reinterpret_cast<float *>(base + l.cvec);
+  ctx->avec = reinterpret_cast<float *>(base + l.avec);
   ctx->inited = false;
   ctx->n = 0;
   ctx->occ = 0;
@@ -227,6 +234,8 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   if (!ctx || !prompt_k || !prompt_v || !hidden_store || !ctrl_input) return ADORE_E_INVALID;
   const adore_config &c = ctx->cfg;
   if (S < 1 || S >= c.max_positions) return ADORE_E_INVALID;
+  const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
+  if (rescore && score_override) return ADORE_E_INVALID;   // scores are recomputed at every step
   const size_t es = elem_size(c);
   const int m = c.cache_slots - c.rebuild_budget - 1;
   const int keep = S < m ? S : m;
@@ -246,6 +255,10 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
     int ksplit = 1;
     ADORE_TRY(launch_ctrl_input(ctx, st, x, c.batch * len, len, S, &ksplit));
     ADORE_TRY(launch_ctrl_cell(ctx, st, len, i0, score_override ? score_override + i0 : nullptr, S, ksplit));
+  }
+  if (rescore) {   // every prompt token as seen from the last one
+    ADORE_TRY(launch_ctrl_avec(ctx, st));
+    ADORE_TRY(launch_rescore(ctx, st, S - 1));
   }
   // slot map and reserved slot go to buffer `cur`, the rebuild lists to `cur ^ 1` (where a step's GEMM reads them)
   ADORE_TRY(launch_init_select(ctx, ctx->cur, ctx->cur ^ 1, S, keep, r0));
@@ -295,6 +308,7 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   int ksplit = 1;
   ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, 1, &ksplit));
   ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
+  if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
   // buffer `dst` was `cur` one step ago: the selections wait until that step's attention has read it
   if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
@@ -335,6 +349,7 @@ int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new
 int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
                    int32_t *released_pos, int32_t *rebuilt_pos) {
   if (!ctx || !x_n) return ADORE_E_INVALID;
+  if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->scheduled || ctx->n_attended != ctx->cfg.layers) return ADORE_E_STATE;
   return do_schedule(ctx, x_n, score_override, slot_map, released_pos, rebuilt_pos);
 }
@@ -351,6 +366,7 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
                       int32_t *slot_map) {
   if (!ctx || !q || !k_new || !v_new || !hidden_store || !x_n || !out) return ADORE_E_INVALID;
   if (ctx->cfg.layers != 1) return ADORE_E_INVALID;
+  if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
   // The selections do not depend on this step's attention: enqueue them first so that they start
@@ -387,6 +403,7 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
                     const void *cache_k, const void *cache_v, int32_t step) {
   if (!ctx || !slot_pos) return ADORE_E_INVALID;
   const adore_config &c = ctx->cfg;
+  if (c.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_UNSUPPORTED;   // the per-token vectors are not part of a snapshot
   if (step < 1 || step >= c.max_positions) return ADORE_E_INVALID;
   if (ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
   const size_t BH = size_t(c.batch) * c.heads;
@@ -470,6 +487,7 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_RELEASE: return "release";
     case ADORE_KERNEL_REBUILD_SELECT: return "rebuild_select";
     case ADORE_KERNEL_REBUILD_GEMM: return "rebuild_gemm";
+    case ADORE_KERNEL_RESCORE: return "rescore";
     default: return "?";
   }
 }
@@ -482,7 +500,7 @@ const char *adore_strerror(int code) {
     case ADORE_E_UNSUPPORTED:
       return "unsupported configuration (need head_dim in {64,128}, cache_slots <= 1024 or "
              "cache_slots - rebuild_budget - 1 >= max_positions, hidden % 8 == 0, max_positions <= 262144, "
-             "ctrl_hidden <= 1024)";
+             "ctrl_hidden <= 1024, ctrl_hidden % 4 == 0 in rescore mode; no set_state in rescore mode)";
     case ADORE_E_WORKSPACE: return "workspace too small or not 256-byte aligned";
     case ADORE_E_HIP: return "HIP runtime call failed";
     default: return "unknown error";

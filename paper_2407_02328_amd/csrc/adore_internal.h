@@ -56,6 +56,8 @@ struct adore_ctx {
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
+  float *cvec;               // rescore mode: [B][N_max][d']  W_1 (z_i + pos_b) + b_1 of every token
+  float *avec;               // rescore mode: [d']  W_1 pos_w  (what one unit of distance adds)
 
   // --- host-side step state ---
   bool inited;
@@ -124,5 +126,8 @@ hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int kee
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);
 hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t count);
+// rescore mode: the distance vector W_1 pos_w (once per init), and sigma of tokens 0..n seen from token n
+hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st);
+hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n);
 
 }  // namespace adore

@@ -138,6 +138,7 @@ struct CellArgs {
   const float *gi;             // [ksplit][B*nsteps][3d'], token (b, i) at row b*nsteps + i
   float *z;                    // [B][d']
   float *score;                // [B][N_max]
+  float *cvec;                 // rescore mode: [B][N_max][d'] interaction-layer pre-activation at distance 0; else null
   const float *override_;      // [B][override_stride] or null
   int override_stride;
   int dp, nsteps, pos0, N_max, ksplit, ntok;
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       const float u = sigmoidf_(g_u + gh[DP + tid]);
       const float cand = tanhf(g_n + r * gh[2 * DP + tid]);
       const float hnew = (1.0f - u) * cand + u * h[tid];
-      const float delta = float(a.pos0 + i) * a.pos_scale;
+      const float delta = a.cvec ? 0.f : float(a.pos0 + i) * a.pos_scale;   // rescore mode: distance to itself
       h[tid] = hnew;
       t_in[tid] = fmaf(a.pos_w[tid], delta, a.pos_b[tid]) + hnew;
     }
@@ -270,6 +271,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       rows_times_vec<float, 32>(a.W1, wave * 32, x0, x1, a.b1, u1, lane);
     }
     __syncthreads();
+    if (a.cvec && tid < DP) a.cvec[(size_t(b) * a.N_max + a.pos0 + i) * DP + tid] = u1[tid];
     if (wave == 0) {   // output layer and sigmoid
       float s = fmaf(a.out_w[lane], tanhf(u1[lane]), a.out_w[lane + 64] * tanhf(u1[lane + 64]));
       s = wave_sum(s);
@@ -312,7 +314,7 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
       if (lane == 0) gh[row] = s + a.b_hh[row];
     }
     __syncthreads();
-    const float delta = float(a.pos0 + i) * a.pos_scale;
+    const float delta = a.cvec ? 0.f : float(a.pos0 + i) * a.pos_scale;   // rescore mode: distance to itself
     for (int j = tid; j < dp; j += blockDim.x) {
       const float r = sigmoidf_(gi_sum(a, tok, j) + a.b_ih[j] + gh[j]);
       const float u = sigmoidf_(gi_sum(a, tok, dp + j) + a.b_ih[dp + j] + gh[dp + j]);
@@ -329,6 +331,7 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
       float s = 0.f;
       for (int t = lane; t < dp; t += 64) s = fmaf(a.W1[size_t(row) * dp + t], t_in[t], s);
       s = wave_sum(s);
+      if (a.cvec && lane == 0) a.cvec[(size_t(b) * a.N_max + a.pos0 + i) * dp + row] = s + a.b1[row];
       part = fmaf(a.out_w[row], tanhf(s + a.b1[row]), part);
     }
     if (lane == 0) red[wave] = part;
@@ -343,6 +346,48 @@ __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
     __syncthreads();
   }
   for (int j = tid; j < dp; j += blockDim.x) a.z[size_t(b) * dp + j] = h[j];
+}
+
+// ---- rescore mode -----------------------------------------------------------------
+// W_1 (pos_w * delta + pos_b + z_i) + b_1  =  c_i + delta * a   with  c_i = W_1 (z_i + pos_b) + b_1  kept per
+// token by the cell kernels and  a = W_1 pos_w:  scoring a token again costs d' tanh and one dot product.
+__global__ __launch_bounds__(256) void ctrl_avec_kernel(const float *__restrict__ W1,
+                                                        const float *__restrict__ pos_w,
+                                                        float *__restrict__ avec, int dp) {
+  for (int row = threadIdx.x; row < dp; row += blockDim.x) {
+    float s = 0.f;
+    for (int k = 0; k < dp; ++k) s = fmaf(W1[size_t(row) * dp + k], pos_w[k], s);
+    avec[row] = s;
+  }
+}
+
+// sigma_i(n) = sigmoid(out_w . tanh(c_i + (n - i) * pos_scale * a) + out_b) for i = 0..n.  16 lanes per
+// token, 16 tokens per workgroup; grid = (tokens / 16, B).
+__global__ __launch_bounds__(256) void rescore_kernel(const float *__restrict__ cvec,
+                                                      const float *__restrict__ avec,
+                                                      const float *__restrict__ out_w,
+                                                      const float *__restrict__ out_b,
+                                                      float *__restrict__ score, int n, int N_max, int dp,
+                                                      float pos_scale) {
+  const int b = blockIdx.y;
+  const int i = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int lig = threadIdx.x & 15;
+  const int ic = i <= n ? i : n;                 // lanes past the end redo the last token and store nothing
+  const float delta = float(n - ic) * pos_scale;
+  const float *c = cvec + (size_t(b) * N_max + ic) * dp;
+  float s = 0.f;
+  for (int e = lig * 4; e < dp; e += 64) {
+    const float4 cv = *reinterpret_cast<const float4 *>(c + e);
+    const float4 av = *reinterpret_cast<const float4 *>(avec + e);
+    const float4 wv = *reinterpret_cast<const float4 *>(out_w + e);
+    s = fmaf(wv.x, tanhf(fmaf(delta, av.x, cv.x)), s);
+    s = fmaf(wv.y, tanhf(fmaf(delta, av.y, cv.y)), s);
+    s = fmaf(wv.z, tanhf(fmaf(delta, av.z, cv.z)), s);
+    s = fmaf(wv.w, tanhf(fmaf(delta, av.w, cv.w)), s);
+  }
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (lig == 0 && i <= n) score[size_t(b) * N_max + i] = sigmoidf_(s + out_b[0]);
 }
 
 // Number of D-slices of the bf16 input projection: enough workgroups to cover the chip when
@@ -394,6 +439,7 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
   a.W1 = ctx->w.mlp_w1; a.b1 = ctx->w.mlp_b1;
   a.out_w = ctx->w.out_w; a.out_b = ctx->w.out_b;
   a.gi = ctx->gi; a.z = ctx->z; a.score = ctx->score;
+  a.cvec = c.score_mode == ADORE_SCORE_RESCORE ? ctx->cvec : nullptr;
   a.override_ = score_override; a.override_stride = override_stride;
   a.dp = c.ctrl_hidden; a.nsteps = nsteps; a.pos0 = pos0; a.N_max = c.max_positions;
   a.ksplit = ksplit; a.ntok = c.batch * nsteps;
@@ -413,6 +459,20 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
       ADORE_LAUNCH(t, (ctrl_cell_kernel<float>), dim3(c.batch), dim3(512), smem, st, a);
     }
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st) {
+  hipLaunchKernelGGL(ctrl_avec_kernel, dim3(1), dim3(256), 0, st, ctx->w.mlp_w1, ctx->w.pos_w, ctx->avec,
+                     ctx->cfg.ctrl_hidden);
+  return hipGetLastError();
+}
+
+hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n) {
+  const adore_config &c = ctx->cfg;
+  ScopedTimer t(ctx, ADORE_KERNEL_RESCORE, st);
+  ADORE_LAUNCH(t, rescore_kernel, dim3((n + 16) / 16, c.batch), dim3(256), 0, st, ctx->cvec, ctx->avec,
+               ctx->w.out_w, ctx->w.out_b, ctx->score, n, c.max_positions, c.ctrl_hidden, c.pos_scale);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def to_dev(a: np.ndarray, dtype) -> torch.Tensor:
 def adore_config(w: Workload):
     return make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
                        rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
-                       pos_scale=w.pos_scale)
+                       pos_scale=w.pos_scale, score_mode=1 if w.rescore else 0)
 
 
 def device_weights(w: Workload, wts):
@@ -68,7 +68,8 @@ class GpuJob:
             self.adore.rebuild(l, self.hidden[l])
         self.adore.get_state(scores=self.state["scores"])
         torch.cuda.synchronize()
-        score_n = self.state["scores"][:, n].cpu().numpy()
+        sc = self.state["scores"]
+        score_n = sc[:, :n + 1].cpu().numpy() if w.rescore else sc[:, n].cpu().numpy()
         return (self.out.cpu().numpy().astype(np.float64), self.slot_map.cpu().numpy(),
                 self.released.cpu().numpy(), self.rebuilt.cpu().numpy()[:, :w.R], score_n)
 
@@ -120,7 +121,9 @@ def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=No
         out_g, map_g, rel_g, rb_g, score_g = job.step(n, qkv, ov)
         out_o, map_o, rel_o, rb_o, own = orc.decode_step(*qkv, hs, hs[0][:, n],
                                                          score_override=score_g)
-        if override is None:
+        if w.rescore:     # every score of this step: the oracle's own values against the GPU's, then adopted
+            assert np.abs(orc.own_scores - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        elif override is None:
             assert np.abs(own - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
         else:
             assert np.array_equal(score_g, ov.astype(np.float32))

@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 1
+    assert lib.adore_abi_version() == 2
 
 
 def test_workspace_bytes(lib):
@@ -86,6 +86,19 @@ def test_create_rejects_bad_arguments(lib):
     over = cfg_for(w, cache_slots=2048, max_positions=2048 - w.R)
     big = lib.adore_workspace_bytes(ctypes.byref(over))
     assert lib.adore_create(ctypes.byref(over), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3
+    # rescore mode: unknown mode value, d' not a multiple of 4, no overrides, no set_state
+    assert lib.adore_create(ctypes.byref(cfg_for(w, score_mode=2)), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1
+    odd = cfg_for(w, score_mode=1, ctrl_hidden=6)
+    big = lib.adore_workspace_bytes(ctypes.byref(odd))
+    assert lib.adore_create(ctypes.byref(odd), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3
+    re = cfg_for(w, score_mode=1)
+    big = lib.adore_workspace_bytes(ctypes.byref(re))
+    assert big > n                                   # one d'-vector per token on top of the static layout
+    assert lib.adore_create(ctypes.byref(re), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
+    assert lib.adore_schedule(h, FAKE, FAKE, None, None, None) == -1
+    assert lib.adore_decode_step(h, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.adore_set_state(h, FAKE, None, None, None, None, 5) == -3
+    assert lib.adore_destroy(h) == 0
     wt2 = fake_weights()
     wt2.out_b = None
     assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt2), FAKE, n, None, ctypes.byref(h)) == -1

@@ -293,3 +293,71 @@ def test_stack32_reduced_all_layers():
     assert w.L == 32
     worst, job, _ = h.lockstep(w, steps=8, check_cache_every=4)
     job.adore.close()
+
+
+# ---- rescore mode: every token scored again at every step, relative position --------------------
+def test_rescore_mode_fp32_trajectory():
+    """d' = 128 (the specialised cell kernel keeps W_1 (z_i + pos_b) + b_1 per token), fp32: every score of
+    every step within 1e-5 of the oracle's, then identical slot maps, released and rebuilt positions."""
+    h = _harness()
+    w = Workload("rescore32", L=1, B=2, H=2, d=64, D=256, K=48, R=6, S=80, T=30, dtype="f32", dprime=128,
+                 act_std=0.125, w_std=0.125, pos_scale=2.0 ** -6, rescore=True)
+    worst, job, orc = h.lockstep(w, steps=w.T, check_cache_every=10)
+    assert np.array_equal(orc.score[:, :w.N_max], job.snapshot()["scores"][:, :w.N_max])
+    job.adore.close()
+
+
+def test_rescore_mode_bf16_generic_controller_and_warm_up():
+    """Any-d' cell kernel (d' = 32), bf16 storage, a prompt shorter than the cache so that the first steps
+    release nothing, 37 tokens per sequence at the end (the last workgroup of the rescore kernel is ragged)."""
+    h = _harness()
+    w = Workload("rescore16", L=2, B=3, H=2, d=128, D=256, K=24, R=4, S=9, T=28, dtype="bf16", dprime=32,
+                 pos_scale=2.0 ** -5, rescore=True)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=14)
+    job.adore.close()
+
+
+def test_rescore_mode_recency_weights_give_a_sliding_window_on_gpu():
+    """Zero GRU, identity interaction layer, negative position weight: the score falls with the distance to
+    the current token only, and the cache must hold exactly the last m tokens plus the R before them."""
+    h = _harness()
+    w = Workload("window", L=1, B=2, H=2, d=64, D=128, K=20, R=3, S=30, T=12, dtype="bf16", dprime=32,
+                 pos_scale=2.0 ** -6, rescore=True)
+    wts = SyntheticInputs(w).weights()
+    dp = w.dprime
+    wts = dict(wts, gru_w_ih=np.zeros_like(wts["gru_w_ih"]), gru_w_hh=np.zeros_like(wts["gru_w_hh"]),
+               gru_b_ih=np.zeros_like(wts["gru_b_ih"]), gru_b_hh=np.zeros_like(wts["gru_b_hh"]),
+               pos_w=np.full(dp, -1.0, dtype=np.float32), pos_b=np.zeros(dp, dtype=np.float32),
+               mlp_w1=np.eye(dp, dtype=np.float32), mlp_b1=np.zeros(dp, dtype=np.float32),
+               out_w=np.ones(dp, dtype=np.float32), out_b=np.zeros(1, dtype=np.float32))
+    worst, job, _ = h.lockstep(w, steps=w.T, wts=wts)
+    sm = job.slot_map.cpu().numpy()
+    n = w.S + w.T - 1
+    want = set(range(n - w.m - w.R + 1, n + 1))
+    for b in range(w.B):
+        for hh in range(w.H):
+            assert {int(p) for p in sm[b, hh] if p >= 0} == want
+    job.adore.close()
+
+
+def test_rescore_mode_rejects_overrides_and_restore():
+    h = _harness()
+    w = Workload("rescore_api", L=1, B=1, H=2, d=64, D=128, K=16, R=2, S=20, T=4, dtype="bf16", dprime=32,
+                 rescore=True)
+    job = h.GpuJob(w)
+    from paper_2407_02328_amd import AdoreError
+    with pytest.raises(AdoreError) as e:
+        job.init(score_override=np.zeros((w.B, w.S), dtype=np.float32))
+    assert e.value.code == -1
+    job.init()
+    q, k, v = (h.to_dev(a[0], job.st) for a in job.inp.step_qkv(w.S))
+    ov = torch.zeros(w.B, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(AdoreError) as e:
+        job.adore.decode_step(q, k, v, job.hidden[0], job.hidden[0][:, w.S].contiguous(), ov, job.out[0], None)
+    assert e.value.code == -1
+    with pytest.raises(AdoreError) as e:
+        job.adore.set_state(job.state["slot_pos"], None, None, None, None, w.S)
+    assert e.value.code == -3
+    job.adore.decode_step(q, k, v, job.hidden[0], job.hidden[0][:, w.S].contiguous(), None, job.out[0], None)
+    torch.cuda.synchronize()
+    job.adore.close()
