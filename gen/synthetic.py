@@ -25,6 +25,7 @@ _T_Q, _T_K, _T_V, _T_PK, _T_PV, _T_HID, _T_WKV = 1, 2, 3, 4, 5, 6, 7
 _T_GRU_IH, _T_GRU_HH, _T_GRU_BIH, _T_GRU_BHH = 8, 9, 10, 11
 _T_POS_W, _T_POS_B, _T_W1, _T_B1, _T_WO, _T_BO = 12, 13, 14, 15, 16, 17
 _T_SAL_PERM, _T_SAL_DIR = 18, 19
+_T_WQ, _T_WOUT = 20, 21
 
 
 def round_bf16(a: np.ndarray) -> np.ndarray:
@@ -145,6 +146,15 @@ class SyntheticInputs:
             "out_b": self._normal((1,), 0.1, _T_BO, storage=False),
         }
         return out
+
+    def forward_weights(self) -> Dict[str, np.ndarray]:
+        """Query and output projections of every layer, for the rebuild forward through a layer stack:
+        w_q [L, H*d, D], w_o [L, D, H*d] (rows of w_q grouped by head like W_k)."""
+        w = self.w
+        return {
+            "w_q": np.stack([self._normal((w.H * w.d, w.D), w.w_std, _T_WQ, l) for l in range(w.L)]),
+            "w_o": np.stack([self._normal((w.D, w.H * w.d), w.w_std, _T_WOUT, l) for l in range(w.L)]),
+        }
 
     # -- activations ----------------------------------------------------------
     def hidden_store_layer(self, layer: int) -> np.ndarray:

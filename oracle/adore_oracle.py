@@ -36,6 +36,16 @@ Readings of points the paper leaves open (each used exactly as stated here):
     state is removed).
   * Tokens released in this step may be rebuilt in this step (Sec. 2.3).
   * Ties on sigma are broken in favour of the lower position.
+  * Rebuild forward (Sec. 2.3 read in full: the rebuilt tokens are queries too and their
+    outputs feed the next layer): the paper prints no mask for the R+1 query rows; here a
+    row at position p attends to the cache rows at positions <= p (a decoder's causal
+    rule), so that a rebuilt state equals the state the token had when it was first
+    computed whenever all earlier tokens are present.  A layer is attention only:
+    x' = x + W_o . concat_h(attention output); norms and the feed-forward block belong to
+    the backbone, which is not available.  q, k, v, the attention output and x' are each
+    rounded once to the storage type.  K/V of the rebuilt tokens are written at the start
+    of the step that uses them (layer by layer), not at the end of the step that chose
+    them; the choice itself is unchanged.
   * Rows never move: a released row frees its slot; incoming rows take the
     lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
     token -> lowest free slot at its insert).
@@ -349,6 +359,105 @@ class AdoreOracle:
         self.n = n + 1
         self.last_probs = probs
         return out, self.slot_pos.copy(), released_pos, rebuilt_pos, own_score
+
+
+class AdoreForwardOracle(AdoreOracle):
+    """Sec. 2.3 in full: at step n the embeddings of the R tokens chosen in the previous step and of the
+    current token, X_{R+1}, go through every layer as R+1 query rows; each layer projects them to q, k, v,
+    puts k, v into the rows' slots, attends, and hands x + W_o o to the next layer.  The last layer's row
+    of the current token is the step's output.  Release and the choice of the next R tokens follow as in
+    the base class.  `weights` additionally holds w_q [L,H*d,D] and w_o [L,D,H*d]."""
+
+    def __init__(self, cfg: OracleConfig, weights: Dict[str, np.ndarray]):
+        super().__init__(cfg, weights)
+        self._wq64: Dict[int, np.ndarray] = {}
+        self._wo64: Dict[int, np.ndarray] = {}
+        self.pending: List[List[int]] = [[] for _ in range(cfg.B)]   # chosen last step, rebuilt in the next
+        self.last_rows = None            # [L+1][B] list of (positions, X) of the last step (diagnostics)
+
+    def _place_rebuilt(self, b, rebuilt, hidden_store):
+        """Slots are assigned now (rank rho -> rho-th lowest free slot); their K/V follow at the next step."""
+        c = self.cfg
+        for h in range(c.H):
+            free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]
+            for rho, pos in enumerate(rebuilt):
+                self.slot_pos[b, h, free[rho]] = pos
+        self.pending[b] = list(rebuilt)
+
+    def init_cache(self, prompt_k, prompt_v, hidden_store, ctrl_input, S, score_override=None):
+        return super().init_cache(prompt_k, prompt_v, None, ctrl_input, S, score_override)
+
+    def _w(self, cache, name, layer):
+        if layer not in cache:
+            cache[layer] = np.asarray(self.wts[name][layer], dtype=F64)
+        return cache[layer]
+
+    def forward_step(self, embed: np.ndarray, score_override: Optional[np.ndarray] = None):
+        """embed: [B, N_max, D] token embeddings (rows <= n valid).  Returns (x_out [B,D] fp64: last layer's
+        row of the current token, rows_out [B,R+1,D]: last layer's rows in rank order with the current token
+        last (unused rows zero), slot_map, released_pos, rebuilt_pos, own_score)."""
+        c = self.cfg
+        n = self.n
+        if n >= c.N_max:
+            raise RuntimeError("step past N_max")
+        Hd = c.H * c.d
+        released_pos = np.full((c.B, c.H, c.R + 1), -1, dtype=np.int32)
+        rebuilt_pos = np.full((c.B, c.R), -1, dtype=np.int32)
+        own_score = np.zeros(c.B, dtype=F64)
+        rows_out = np.zeros((c.B, c.R + 1, c.D), dtype=F64)
+        for b in range(c.B):
+            positions = list(self.pending[b]) + [n]                      # rank order, current token last
+            X = embed[b, positions, :].astype(F64)                       # X_{R+1}
+            # the current token takes the lowest free slot of every head (its k, v differ per layer)
+            cur_slot = []
+            for h in range(c.H):
+                free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]
+                self.slot_pos[b, h, free[0]] = n
+                cur_slot.append(free[0])
+            for l in range(c.L):
+                Wq = self._w(self._wq64, "w_q", l)
+                Wo = self._w(self._wo64, "w_o", l)
+                Q = round_to_storage(X @ Wq.T, c.dtype)                  # [r+1, H*d]
+                KV = self._project(l, X)                                 # [r+1, 2*H*d], rounded
+                O = np.zeros((len(positions), Hd), dtype=F64)
+                for h in range(c.H):
+                    slot_of = {int(p): k for k, p in enumerate(self.slot_pos[b, h]) if p >= 0}
+                    for j, pos in enumerate(positions):
+                        s = slot_of[pos]
+                        self.Kc[l, b, h, s] = KV[j, h * c.d:(h + 1) * c.d]
+                        self.Vc[l, b, h, s] = KV[j, Hd + h * c.d: Hd + (h + 1) * c.d]
+                    for j, pos in enumerate(positions):
+                        valid = np.nonzero((self.slot_pos[b, h] >= 0) & (self.slot_pos[b, h] <= pos))[0]
+                        O[j, h * c.d:(h + 1) * c.d], _ = attention_row(Q[j, h * c.d:(h + 1) * c.d],
+                                                                       self.Kc[l, b, h, valid],
+                                                                       self.Vc[l, b, h, valid])
+                O = round_to_storage(O, c.dtype)
+                X = round_to_storage(X + O @ Wo.T, c.dtype)
+            rows_out[b, :len(positions) - 1] = X[:-1]
+            rows_out[b, c.R] = X[-1]
+            # controller, release, choice of the next rebuild set: as in the base class
+            own_score[b] = self._controller(b, embed[b, n], n)
+            if c.rescore:
+                if b == 0:
+                    self.own_scores = np.zeros((c.B, n + 1), dtype=F64)
+                self.own_scores[b] = self._rescore(b, n)
+                self.score[b, :n + 1] = (self.own_scores[b].astype(np.float32) if score_override is None
+                                         else np.asarray(score_override[b], dtype=np.float32))
+            else:
+                self.score[b, n] = (np.float32(own_score[b]) if score_override is None
+                                    else np.float32(score_override[b]))
+            for h in range(c.H):
+                freed = release_lowest(self.slot_pos[b, h], self.score[b], n, c.m)
+                for j, s in enumerate(freed):
+                    released_pos[b, h, j] = self.slot_pos[b, h, s]
+                for s in freed:
+                    self.slot_pos[b, h, s] = -1
+            resident = [int(p) for p in self.slot_pos[b, 0] if p >= 0]
+            rebuilt = rebuild_choice(resident, n, self.score[b], c.R)
+            rebuilt_pos[b, :len(rebuilt)] = rebuilt
+            self._place_rebuilt(b, rebuilt, None)
+        self.n = n + 1
+        return rows_out[:, c.R].copy(), rows_out, self.slot_pos.copy(), released_pos, rebuilt_pos, own_score
 
 
 def full_attention(q: np.ndarray, Kall: np.ndarray, Vall: np.ndarray) -> np.ndarray:

@@ -445,6 +445,116 @@ def test_rescore_invariants_and_promotion_of_rebuilt_tokens():
     assert np.abs(want - orc.own_scores).max() < 1e-12
 
 
+# --------------------------------------------------------------------------
+# rebuild forward through a layer stack (Sec. 2.3 in full)
+# --------------------------------------------------------------------------
+def _forward_oracle(w, wts=None):
+    inp = SyntheticInputs(w)
+    wts = dict(inp.weights(), **inp.forward_weights()) if wts is None else wts
+    return O.AdoreForwardOracle(oracle_config(w), wts), inp, wts
+
+
+def _causal_stack_reference(E, wts, w):
+    """Textbook decoder stack of attention-only layers over the whole sequence, torch fp64:
+    x' = x + W_o . causal_attention(W_q x, W_k x, W_v x).  Returns (X_L [B,N,D], K [L,B,H,N,d], V)."""
+    X = torch.tensor(E.astype(np.float64))
+    B, N, _ = X.shape
+    Hd = w.H * w.d
+    Ks, Vs = [], []
+    for l in range(w.L):
+        Wq = torch.tensor(wts["w_q"][l].astype(np.float64))
+        Wkv = torch.tensor(wts["w_kv"][l].astype(np.float64))
+        Wo = torch.tensor(wts["w_o"][l].astype(np.float64))
+        heads = lambda t: t.reshape(B, N, w.H, w.d).transpose(1, 2)       # [B,H,N,d]
+        Q, K, V = heads(X @ Wq.T), heads(X @ Wkv[:Hd].T), heads(X @ Wkv[Hd:].T)
+        A = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=True)
+        X = X + A.transpose(1, 2).reshape(B, N, Hd) @ Wo.T
+        Ks.append(K.numpy()); Vs.append(V.numpy())
+    return X.numpy(), np.stack(Ks), np.stack(Vs)
+
+
+def test_forward_with_every_released_token_rebuilt_is_a_causal_decoder_stack():
+    """When R covers the whole pool, every token is in the cache at every step (as a resident or rebuilt), so
+    the rebuild forward must give what a plain causal decoder stack gives: the output row of the current
+    token, and the rows of the rebuilt tokens at their own positions.  This fixes the mask among the R+1
+    query rows (a rebuilt token that saw later tokens would get another state from layer 2 on), the residual,
+    the head layout of W_q / W_o, the order of the rows and the slot each K/V row lands in."""
+    w = Workload("fwd", L=3, B=2, H=2, d=8, D=16, K=17, R=8, S=10, T=6, dtype="f32", dprime=8,
+                 act_std=1.0, w_std=0.25)
+    orc, inp, wts = _forward_oracle(w)
+    E = inp.hidden_store_layer(0)                                         # [B, N_max, D] embeddings
+    XL, Kref, Vref = _causal_stack_reference(E, wts, w)
+    pk = O.round_to_storage(Kref[:, :, :, :w.S], "f32"); pv = O.round_to_storage(Vref[:, :, :, :w.S], "f32")
+    orc.init_cache(pk, pv, None, E[:, :w.S], w.S)
+    scale = np.abs(XL).max()
+    for t in range(w.T):
+        n = w.S + t
+        pending = [list(p) for p in orc.pending]
+        x_out, rows, slot_map, released, rebuilt, own = orc.forward_step(E)
+        assert np.abs(x_out - XL[:, n]).max() < 1e-5 * scale
+        for b in range(w.B):
+            held = {int(p) for p in slot_map[b, 0] if p >= 0}
+            assert held == set(range(n + 1))                              # nobody is missing
+            for rho, pos in enumerate(pending[b]):
+                assert np.abs(rows[b, rho] - XL[b, pos]).max() < 1e-5 * scale
+    # and the cache rows themselves are the reference K/V of their positions, layer by layer
+    for l in range(w.L):
+        for b in range(w.B):
+            for h in range(w.H):
+                for k, pos in enumerate(orc.slot_pos[b, h]):
+                    if pos >= 0 and pos not in orc.pending[b]:
+                        assert np.abs(orc.Kc[l, b, h, k] - Kref[l, b, h, pos]).max() < 1e-5 * np.abs(Kref).max()
+                        assert np.abs(orc.Vc[l, b, h, k] - Vref[l, b, h, pos]).max() < 1e-5 * np.abs(Vref).max()
+
+
+def test_forward_without_rebuild_budget_is_the_single_query_step():
+    """R = 0, one layer: the forward is the pinned single-query step with q, k, v = the projections of the
+    current token's embedding, followed by the residual output projection."""
+    w = small_workload(B=2, H=2, K=9, R=0, S=12, T=10, L=1)
+    fwd, inp, wts = _forward_oracle(w)
+    base, _, _ = make_oracle(w, wts)
+    E = inp.hidden_store_layer(0)
+    pk, pv = inp.prompt_kv()
+    fwd.init_cache(pk, pv, None, E[:, :w.S], w.S)
+    base.init_cache(pk, pv, inp.hidden_store(), E[:, :w.S], w.S)
+    Hd = w.H * w.d
+    Wq, Wkv, Wo = (wts[k][0].astype(np.float64) for k in ("w_q", "w_kv", "w_o"))
+    for t in range(w.T):
+        n = w.S + t
+        x = E[:, n].astype(np.float64)
+        q = O.round_to_storage(x @ Wq.T, w.dtype).reshape(1, w.B, w.H, w.d)
+        kv = O.round_to_storage(x @ Wkv.T, w.dtype)
+        k = kv[:, :Hd].reshape(1, w.B, w.H, w.d); v = kv[:, Hd:].reshape(1, w.B, w.H, w.d)
+        out, map_b, rel_b, rb_b, own_b = base.decode_step(q, k, v, inp.hidden_store(), E[:, n])
+        x_out, rows, map_f, rel_f, rb_f, own_f = fwd.forward_step(E)
+        want = O.round_to_storage(x + O.round_to_storage(out[0].reshape(w.B, Hd), w.dtype) @ Wo.T, w.dtype)
+        assert np.array_equal(map_b, map_f) and np.array_equal(rel_b, rel_f)
+        assert np.allclose(x_out, want, rtol=0, atol=1e-12)
+
+
+def test_forward_invariants_with_a_small_budget():
+    """R smaller than the pool: counts and residency as in the base step; the tokens rebuilt in a step are
+    the ones chosen in the step before; every output is finite."""
+    w = Workload("fwd2", L=2, B=2, H=3, d=8, D=16, K=10, R=2, S=14, T=12, dtype="bf16", dprime=8, w_std=0.25)
+    orc, inp, wts = _forward_oracle(w)
+    E = inp.hidden_store_layer(0)
+    pk, pv = inp.prompt_kv()
+    first = orc.init_cache(pk, pv, None, E[:, :w.S], w.S)
+    prev = [list(r) for r in first]
+    for t in range(w.T):
+        n = w.S + t
+        assert [list(p) for p in orc.pending] == prev
+        x_out, rows, slot_map, released, rebuilt, own = orc.forward_step(E)
+        assert np.isfinite(x_out).all()
+        for b in range(w.B):
+            for h in range(1, w.H):
+                assert np.array_equal(slot_map[b, h], slot_map[b, 0])
+            held = [int(p) for p in slot_map[b, 0] if p >= 0]
+            assert len(held) == len(set(held)) == w.K - 1 and n in held
+            assert np.all(rows[b, len(prev[b]):w.R] == 0)
+        prev = [[int(p) for p in rebuilt[b] if p >= 0] for b in range(w.B)]
+
+
 def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fits():
     """If the supplied K/V are the projections of the hidden states, a rebuilt row is identical to
     the row that was released; while |pool| <= R every token is present, so the output is Eq. 1
