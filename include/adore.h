@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 2
+#define ADORE_ABI_VERSION 3
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -127,8 +127,11 @@ int adore_destroy(adore_ctx *ctx);
  *   hidden_store        [L][B][N_max][D] storage type, rows < S valid
  *   ctrl_input          [B][S][D]        storage type (token embeddings x_i)
  *   score_override      [B][S] fp32 or NULL: if given, replaces the controller's sigma
+ * hidden_store == NULL prepares the context for adore_forward_step instead: the best min(R, rest)
+ * tokens are chosen and given their slots, but their K/V are computed by the first forward step.
  * Enqueues work; does not synchronise.  May be called again to restart.
- * Errors: E_INVALID (null, S < 1, S >= N_max). */
+ * Errors: E_INVALID (null, S < 1, S >= N_max), E_UNSUPPORTED (hidden_store == NULL and the
+ * configuration has no forward path: see adore_forward_step). */
 int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
                      const void *hidden_store, const void *ctrl_input,
                      const float *score_override, int32_t S);
@@ -175,6 +178,36 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
                       const void *hidden_store, const void *x_n, const float *score_override,
                       float *out, int32_t *slot_map);
 
+/* Rebuild forward through the layer stack (Sec. 2.3 in full: "the embeddings of the top-R released tokens
+ * are concatenated with the current token" and go through every layer as R+1 query rows, whose
+ * outputs are the next layer's inputs).  One call is one whole step for all L layers; it replaces
+ * attend / schedule / rebuild, which need the caller to supply per-layer hidden states.
+ * Rows of a sequence: the r tokens chosen by the previous step (or by adore_init_cache), by rank, then the
+ * current token n.  Per layer l, with x the rows entering the layer (layer 0: their embeddings):
+ *   q = round(W_q[l] x), [k; v] = round(W_kv[l] x)      k, v go to the rows' cache slots
+ *   o[j] = softmax over the slots whose position is <= position(j) of q[j] . Kc / sqrt(d), times Vc
+ *          (the paper prints no mask for these rows; a decoder's causal rule is used, so a rebuilt
+ *           state equals the state the token had when all earlier tokens are present)
+ *   x'   = round(x + W_o[l] round(o))                   a layer is attention + residual only: norms and
+ *                                                        feed-forward belong to the backbone model
+ * then the controller, the release and the choice of the next r tokens as in adore_schedule.
+ *   fw->w_q   [L][H*d][D]  storage type, rows grouped by head like W_k
+ *   fw->w_o   [L][D][H*d]  storage type
+ *   embed     [B][N_max][D] storage type: token embeddings, rows of all positions <= n valid
+ *   score_override, slot_map, released_pos, rebuilt_pos: as adore_schedule
+ *   rows_out  [B][R+1][D] storage type: the last layer's rows; rank j at [b][j], the current token
+ *             at [b][R]; rows of unused ranks are left untouched
+ * Requires a context initialised with hidden_store == NULL, bf16 storage, R + 1 <= 64, K <= 8192,
+ * H*d and D multiples of 64.  Enqueues work; does not synchronise.
+ * Errors: E_INVALID, E_STATE (not initialised for the forward, step past N_max). */
+typedef struct {
+  const void *w_q;
+  const void *w_o;
+} adore_forward_weights;
+int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const void *embed,
+                       const float *score_override, void *rows_out, int32_t *slot_map,
+                       int32_t *released_pos, int32_t *rebuilt_pos);
+
 /* Snapshot / restore between steps.  Any pointer may be NULL (skipped).
  *   slot_pos [B][H][K] i32; scores [B][N_max] fp32; z [B][d'] fp32;
  *   cache_k, cache_v [L][B][H][K][d] storage type; step: HOST pointer, the
@@ -202,6 +235,9 @@ enum {
   ADORE_KERNEL_REBUILD_SELECT,  /* per-sequence top-R select + slot assignment */
   ADORE_KERNEL_REBUILD_GEMM,    /* re-projection + scatter */
   ADORE_KERNEL_RESCORE,         /* RESCORE mode: sigma of every token for the current step */
+  ADORE_KERNEL_FWD_QKV,         /* rebuild forward: q, k, v projection of the R+1 rows + scatter */
+  ADORE_KERNEL_FWD_ATTEND,      /* rebuild forward: attention of the R+1 rows */
+  ADORE_KERNEL_FWD_OPROJ,       /* rebuild forward: output projection + residual */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

@@ -17,11 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libadore.so")
 
 ADORE_F32, ADORE_BF16 = 0, 1
 KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "rebuild_select", "rebuild_gemm",
-           "rescore"]
+           "rescore", "fwd_qkv", "fwd_attend", "fwd_oproj"]
 
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
-    "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_get_state", "adore_set_state",
+    "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_forward_step", "adore_get_state", "adore_set_state",
     "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
 ]
 
@@ -39,6 +39,10 @@ _WEIGHT_FIELDS = ["w_kv", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pos_w
 
 class AdoreWeights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+class AdoreForwardWeights(ctypes.Structure):
+    _fields_ = [("w_q", ctypes.c_void_p), ("w_o", ctypes.c_void_p)]
 
 
 class AdoreError(RuntimeError):
@@ -78,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.adore_rebuild.argtypes = [vp, i32, vp]
     lib.adore_decode_step.restype = ctypes.c_int
     lib.adore_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.adore_forward_step.restype = ctypes.c_int
+    lib.adore_forward_step.argtypes = [vp, ctypes.POINTER(AdoreForwardWeights), vp, vp, vp, vp, vp, vp]
     lib.adore_get_state.restype = ctypes.c_int
     lib.adore_get_state.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(i32)]
     lib.adore_set_state.restype = ctypes.c_int
@@ -170,7 +176,8 @@ class Adore:
             self.handle,
             self._ptr(prompt_k, (c.layers, c.batch, c.heads, S, c.head_dim), st, "prompt_k"),
             self._ptr(prompt_v, (c.layers, c.batch, c.heads, S, c.head_dim), st, "prompt_v"),
-            self._ptr(hidden_store, (c.layers, c.batch, c.max_positions, c.hidden), st, "hidden_store"),
+            self._ptr(hidden_store, (c.layers, c.batch, c.max_positions, c.hidden), st, "hidden_store",
+                      optional=True),                    # None: prepare for forward_step
             self._ptr(ctrl_input, (c.batch, S, c.hidden), st, "ctrl_input"),
             self._ptr(score_override, (c.batch, S), torch.float32, "score_override", optional=True), S))
 
@@ -209,6 +216,23 @@ class Adore:
             self._ptr(score_override, (c.batch,), torch.float32, "score_override", optional=True),
             self._ptr(out, shp, torch.float32, "out"),
             self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True)))
+
+    def forward_step(self, w_q, w_o, embed, score_override, rows_out, slot_map=None, released_pos=None,
+                     rebuilt_pos=None):
+        c, st = self.cfg, self.storage
+        Hd = c.heads * c.head_dim
+        fw = AdoreForwardWeights(self._ptr(w_q, (c.layers, Hd, c.hidden), st, "w_q"),
+                                 self._ptr(w_o, (c.layers, c.hidden, Hd), st, "w_o"))
+        _check(self.lib, self.lib.adore_forward_step(
+            self.handle, ctypes.byref(fw),
+            self._ptr(embed, (c.batch, c.max_positions, c.hidden), st, "embed"),
+            self._ptr(score_override, (c.batch,), torch.float32, "score_override", optional=True),
+            self._ptr(rows_out, (c.batch, c.rebuild_budget + 1, c.hidden), st, "rows_out"),
+            self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True),
+            self._ptr(released_pos, (c.batch, c.heads, c.rebuild_budget + 1), torch.int32, "released_pos",
+                      optional=True),
+            self._ptr(rebuilt_pos, (c.batch, max(c.rebuild_budget, 1)), torch.int32, "rebuilt_pos",
+                      optional=True)))
 
     def _state_ptrs(self, slot_pos, scores, z, cache_k, cache_v):
         c, st = self.cfg, self.storage

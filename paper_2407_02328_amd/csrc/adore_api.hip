@@ -48,7 +48,7 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
-      att_part, gi, cvec, avec, total;
+      att_part, gi, cvec, avec, fwd_q, fwd_o, fwd_x, total;
 };
 
 bool config_ok(const adore_config *c) {
@@ -96,6 +96,10 @@ Layout make_layout(const adore_config &c) {
   const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
   l.cvec = take(rescore ? size_t(c.batch) * c.max_positions * c.ctrl_hidden * 4 : 0);
   l.avec = take(rescore ? size_t(c.ctrl_hidden) * 4 : 0);
+  const size_t fwd_rows = size_t(c.batch) * R1;
+  l.fwd_q = take(fwd_rows * c.heads * c.head_dim * es);
+  l.fwd_o = take(fwd_rows * c.heads * c.head_dim * es);
+  l.fwd_x = take(fwd_rows * c.hidden * es);
   l.total = off;
   return l;
 }
@@ -194,6 +198,11 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->gi = reinterpret_cast<float *>(base + l.gi);
   ctx->cvec = reinterpret_cast<float *>(base + l.cvec);
   ctx->avec = reinterpret_cast<float *>(base + l.avec);
+  ctx->fwd_q = base + l.fwd_q;
+  ctx->fwd_o = base + l.fwd_o;
+  ctx->fwd_x = base + l.fwd_x;
+  ctx->forward = false;
+  ctx->r_pending = 0;
   ctx->inited = false;
   ctx->n = 0;
   ctx->occ = 0;
@@ -231,9 +240,12 @@ int adore_destroy(adore_ctx *ctx) {
 
 int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, const void *hidden_store,
                      const void *ctrl_input, const float *score_override, int32_t S) {
-  if (!ctx || !prompt_k || !prompt_v || !hidden_store || !ctrl_input) return ADORE_E_INVALID;
+  if (!ctx || !prompt_k || !prompt_v || !ctrl_input) return ADORE_E_INVALID;
   const adore_config &c = ctx->cfg;
   if (S < 1 || S >= c.max_positions) return ADORE_E_INVALID;
+  const bool forward = hidden_store == nullptr;
+  if (forward && !(fwd_gemm_supported(c) && c.rebuild_budget + 1 <= 64 && c.cache_slots <= fwd_attend_max_slots()))
+    return ADORE_E_UNSUPPORTED;
   const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
   if (rescore && score_override) return ADORE_E_INVALID;   // scores are recomputed at every step
   const size_t es = elem_size(c);
@@ -260,20 +272,24 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
     ADORE_TRY(launch_ctrl_avec(ctx, st));
     ADORE_TRY(launch_rescore(ctx, st, S - 1));
   }
-  // slot map and reserved slot go to buffer `cur`, the rebuild lists to `cur ^ 1` (where a step's GEMM reads them)
-  ADORE_TRY(launch_init_select(ctx, ctx->cur, ctx->cur ^ 1, S, keep, r0));
+  // slot map and reserved slot go to buffer `cur`, the rebuild lists to `cur ^ 1` (where a step's GEMM reads
+  // them); for the forward, whose first step rebuilds these tokens itself, the lists go to `cur` as well
+  ADORE_TRY(launch_init_select(ctx, ctx->cur, forward ? ctx->cur : ctx->cur ^ 1, S, keep, r0));
   ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
   const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
-  for (int l = 0; l < c.layers; ++l) {
+  for (int l = 0; l < c.layers && !forward; ++l) {
     ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur ^ 1, r0));
   }
   if (ctx->overlap) {   // the first step's selections overwrite the lists the GEMMs above read
     ADORE_TRY(hipEventRecord(ctx->ev_att[0], st));
     ADORE_TRY(hipEventRecord(ctx->ev_att[1], st));
   }
+  if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));   // the forward's first step waits for "its selections"
   ctx->n = S;
   ctx->occ = keep + r0;
   ctx->inited = true;
+  ctx->forward = forward;
+  ctx->r_pending = r0;
   reset_step(ctx);
   return ADORE_OK;
 }
@@ -341,7 +357,7 @@ int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new
                  float *out) {
   if (!ctx || !q || !k_new || !v_new || !out) return ADORE_E_INVALID;
   if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
-  if (!ctx->inited || ctx->scheduled || ctx->attended[layer] || ctx->n >= ctx->cfg.max_positions)
+  if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->attended[layer] || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
   return do_attend(ctx, layer, q, k_new, v_new, out);
 }
@@ -350,14 +366,14 @@ int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override,
                    int32_t *released_pos, int32_t *rebuilt_pos) {
   if (!ctx || !x_n) return ADORE_E_INVALID;
   if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
-  if (!ctx->inited || ctx->scheduled || ctx->n_attended != ctx->cfg.layers) return ADORE_E_STATE;
+  if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != ctx->cfg.layers) return ADORE_E_STATE;
   return do_schedule(ctx, x_n, score_override, slot_map, released_pos, rebuilt_pos);
 }
 
 int adore_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
   if (!ctx || !hidden_store_layer) return ADORE_E_INVALID;
   if (layer < 0 || layer >= ctx->cfg.layers) return ADORE_E_INVALID;
-  if (!ctx->inited || !ctx->scheduled || ctx->rebuilt[layer]) return ADORE_E_STATE;
+  if (!ctx->inited || ctx->forward || !ctx->scheduled || ctx->rebuilt[layer]) return ADORE_E_STATE;
   return do_rebuild(ctx, layer, hidden_store_layer);
 }
 
@@ -367,7 +383,7 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
   if (!ctx || !q || !k_new || !v_new || !hidden_store || !x_n || !out) return ADORE_E_INVALID;
   if (ctx->cfg.layers != 1) return ADORE_E_INVALID;
   if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
-  if (!ctx->inited || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
+  if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
   // The selections do not depend on this step's attention: enqueue them first so that they start
   // while the previous step's GEMM is still running.
@@ -376,6 +392,61 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
   rc = do_attend(ctx, 0, q, k_new, v_new, out);
   if (rc != ADORE_OK) return rc;
   return do_rebuild(ctx, 0, hidden_store);
+}
+
+int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const void *embed,
+                       const float *score_override, void *rows_out, int32_t *slot_map, int32_t *released_pos,
+                       int32_t *rebuilt_pos) {
+  if (!ctx || !fw || !fw->w_q || !fw->w_o || !embed || !rows_out) return ADORE_E_INVALID;
+  if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
+  if (!ctx->inited || !ctx->forward || ctx->n >= ctx->cfg.max_positions) return ADORE_E_STATE;
+  const adore_config &c = ctx->cfg;
+  const int r = ctx->r_pending;              // rows: r rebuilt tokens + the current one, per sequence
+  const int Hd = c.heads * c.head_dim;
+  const size_t es = elem_size(c);
+  // everything the layers read (slot map, slots of the rebuilt tokens and of the current one) was written
+  // by the previous step's selections
+  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+  // this step's controller and selections: they read the same lists and write the other buffer, so they
+  // run on the side stream next to the layers
+  const char *x_n = static_cast<const char *>(embed) + size_t(ctx->n) * c.hidden * es;
+  {
+    const int m = c.cache_slots - c.rebuild_budget - 1;
+    const int o = ctx->occ + 1;
+    const int x = o > m ? o - m : 0;
+    const int kept = o - x;
+    const int pool = ctx->n + 1 - kept;
+    const int r_next = pool < c.rebuild_budget ? pool : c.rebuild_budget;
+    const int src = ctx->cur, dst = ctx->cur ^ 1;
+    hipStream_t st = ctx->side;
+    int ksplit = 1;
+    ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, c.max_positions, &ksplit));
+    ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
+    if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
+    if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));   // the previous step's layers read `dst`
+    ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
+    ADORE_TRY(launch_rebuild_select(ctx, st, dst, r_next, slot_map, rebuilt_pos));
+    if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
+    ctx->r_step = r_next;
+    ctx->occ = kept + r_next;
+  }
+  const char *wq = static_cast<const char *>(fw->w_q);
+  const char *wo = static_cast<const char *>(fw->w_o);
+  for (int l = 0; l < c.layers; ++l) {
+    const void *x_rows = l == 0 ? embed : ctx->fwd_x;
+    const bool by_pos = l == 0;
+    const bool last = l == c.layers - 1;
+    ADORE_TRY(launch_fwd_qkv(ctx, l, wq + size_t(l) * Hd * c.hidden * es, x_rows, by_pos, r));
+    ADORE_TRY(launch_fwd_attend(ctx, l, r));
+    if (last && ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att[ctx->cur], ctx->stream));   // lists of `cur` read for the last time
+    ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,
+                               last ? c.rebuild_budget + 1 : r + 1, last ? c.rebuild_budget : r, r));
+  }
+  ctx->r_pending = ctx->r_step;
+  ctx->n++;
+  ctx->cur ^= 1;
+  reset_step(ctx);
+  return ADORE_OK;
 }
 
 int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, void *cache_k, void *cache_v,
@@ -405,7 +476,7 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   const adore_config &c = ctx->cfg;
   if (c.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_UNSUPPORTED;   // the per-token vectors are not part of a snapshot
   if (step < 1 || step >= c.max_positions) return ADORE_E_INVALID;
-  if (ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
+  if (ctx->scheduled || ctx->n_attended != 0 || ctx->forward) return ADORE_E_STATE;
   const size_t BH = size_t(c.batch) * c.heads;
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
   if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
@@ -488,6 +559,9 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_REBUILD_SELECT: return "rebuild_select";
     case ADORE_KERNEL_REBUILD_GEMM: return "rebuild_gemm";
     case ADORE_KERNEL_RESCORE: return "rescore";
+    case ADORE_KERNEL_FWD_QKV: return "fwd_qkv";
+    case ADORE_KERNEL_FWD_ATTEND: return "fwd_attend";
+    case ADORE_KERNEL_FWD_OPROJ: return "fwd_oproj";
     default: return "?";
   }
 }

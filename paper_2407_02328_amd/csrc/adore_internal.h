@@ -58,9 +58,13 @@ struct adore_ctx {
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
   float *cvec;               // rescore mode: [B][N_max][d']  W_1 (z_i + pos_b) + b_1 of every token
   float *avec;               // rescore mode: [d']  W_1 pos_w  (what one unit of distance adds)
+  void *fwd_q, *fwd_o;       // rebuild forward: [B*(R+1)][H*d] query rows / attention outputs of the layer in flight
+  void *fwd_x;               // rebuild forward: [B*(R+1)][D]   rows handed from layer to layer
 
   // --- host-side step state ---
   bool inited;
+  bool forward;              // initialised for the rebuild forward (adore_forward_step), not for attend/schedule/rebuild
+  int32_t r_pending;         // forward: tokens chosen by the previous step, rebuilt by the next
   int32_t cur;               // buffer index valid for the next attention
   int32_t n;                 // position of the current / next token
   int32_t occ;               // occupied slots per (b,h) between steps
@@ -129,5 +133,13 @@ hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t c
 // rescore mode: the distance vector W_1 pos_w (once per init), and sigma of tokens 0..n seen from token n
 hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st);
 hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n);
+// rebuild forward (one layer = qkv projection, attention of the r+1 rows, output projection with residual)
+bool fwd_gemm_supported(const adore_config &c);
+int fwd_attend_max_slots();
+hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, const void *x_rows, bool by_position,
+                          int r);
+hipError_t launch_fwd_attend(adore_ctx *ctx, int layer, int r);
+hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x_rows, bool by_position, void *out,
+                            int out_rps, int out_cur, int r);
 
 }  // namespace adore

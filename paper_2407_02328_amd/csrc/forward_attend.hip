@@ -1,0 +1,373 @@
+// Rebuild forward, attention of one layer (paper Sec. 2.3 read in full): the r tokens chosen for
+// rebuilding and the current token are all queries.  Every (sequence, head) has up to R+1 query
+// rows over its K cache slots; a row at position p sees the slots whose position is <= p.
+//
+//   O[j][:] = sum_k softmax_k(Q[j] . Kc[k] / sqrt(d)) Vc[k]     over slots k with 0 <= pos[k] <= pos(j)
+//
+// Still memory-bound (the cache is streamed once for all rows: about R+1 flops per byte), but far
+// too much arithmetic for the plain ALUs, so both products run on the matrix cores (16x16x32 bf16):
+//
+//   logits^T [slot][query] = Kc [slot][d] . Q^T     A = 16 cache rows, read from global memory straight
+//                                                   into the operand layout (8 consecutive d per lane)
+//   O^T [d][query]        += Vc^T [d][slot] . P^T   B = the probabilities exactly where the first product
+//                                                   left them (a lane holds one query and 4+4 slots of
+//                                                   two 16-slot blocks: that choice of 8 slots IS the
+//                                                   k-order of the second product); A = V transposed
+//                                                   through a wave-private LDS tile with the same k-order
+//
+// Probabilities enter the second product as two bf16 terms (upper 16 bits + rounded remainder), so
+// they carry 16 significant bits; sums are fp32; the output is rounded once to the storage type.
+// One workgroup of 4 waves per (sequence, head); each wave streams a quarter of the slots with an
+// online softmax (base 2), the four partial results are merged through LDS in a fixed order.
+#include "device_utils.h"
+
+namespace adore {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+struct FwdAttendArgs {
+  const bf16_t *Q;              // [B*nq][H*d]   query rows; row b*nq + j, j < r: rebuilt rank j, j == r: current token
+  const bf16_t *Kc, *Vc;        // [B*H][K][d]   this layer's cache (the rows of the nq tokens already written)
+  const int32_t *slot_pos;      // [B*H][K]      position per slot before this step's release; the current
+                                //               token's slot is still marked free there
+  const int32_t *insert_slot;   // [B*H]         the slot of the current token
+  const int32_t *rebuilt_pos;   // [B][Rdim]     positions of the rebuilt tokens, by rank
+  bf16_t *O;                    // [B*nq][H*d]
+  int H, K, Kp, nq, r, Rdim, n, chunk;   // Kp = K rounded up to 4*chunk; chunk = slots per wave, multiple of 32
+  float scale_log2;             // log2(e) / sqrt(d)
+};
+
+constexpr int kFwdWaves = 4;
+
+template <int DH, int NQB>
+constexpr int fwd_attend_lds_bytes(int Kp) {
+  constexpr int q = NQB * 16 * (DH * 2 + 16);
+  constexpr int ml = 2 * kFwdWaves * NQB * 16 * 4;
+  constexpr int v = kFwdWaves * 32 * (DH * 2 + 8);
+  constexpr int mrg = (DH / 16) * NQB * 64 * 16;
+  return Kp * 4 + q + ml + (v > mrg ? v : mrg);
+}
+
+template <int DH, int NQB>
+__global__ __launch_bounds__(256) void fwd_attend_kernel(const FwdAttendArgs a) {
+  constexpr int KT = DH / 32;         // matrix instructions along d per 16x16 logit block
+  constexpr int MB = DH / 16;         // 16-wide blocks of the head dimension
+  constexpr int OWN = MB / kFwdWaves; // blocks of the head dimension a wave finishes and stores
+  constexpr int VSTR = DH * 2 + 8;    // bytes per V row in LDS: 4 rows further = 32 bytes further in the banks
+  constexpr int QSTR = DH * 2 + 16;   // bytes per Q row in LDS
+  constexpr int LPR = DH / 8;         // lanes per cache row (16-byte loads)
+  constexpr int RPI = 64 / LPR;       // cache rows per load instruction
+  constexpr int NVL = 32 / RPI;       // V loads per lane and 32-slot block
+  constexpr int NQ16 = NQB * 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int32_t *s_pos = reinterpret_cast<int32_t *>(smem);                       // [Kp]
+  unsigned char *s_q = smem + a.Kp * 4;                                     // [NQ16][QSTR]
+  float *s_m = reinterpret_cast<float *>(s_q + NQ16 * QSTR);                // [4][NQ16]
+  float *s_l = s_m + kFwdWaves * NQ16;                                      // [4][NQ16]
+  unsigned char *s_big = reinterpret_cast<unsigned char *>(s_l + kFwdWaves * NQ16);
+
+  const int bh = blockIdx.x;
+  const int b = bh / a.H, h = bh - b * a.H;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int Hd = a.H * DH;
+
+  // ---- positions of the slots (the current token's slot patched in) and the query tile ----
+  {
+    const int32_t *sp = a.slot_pos + size_t(bh) * a.K;
+    const int s_ins = a.insert_slot[bh];
+    for (int k = tid; k < a.Kp; k += 256) s_pos[k] = k < a.K ? (k == s_ins ? a.n : sp[k]) : -1;
+    for (int idx = tid; idx < NQ16 * LPR; idx += 256) {
+      const int row = idx / LPR, ch = idx - row * LPR;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (row < a.nq) v = *reinterpret_cast<const u32x4 *>(a.Q + (size_t(b) * a.nq + row) * Hd + h * DH + ch * 8);
+      *reinterpret_cast<u32x4 *>(s_q + row * QSTR + ch * 16) = v;
+    }
+  }
+  // position of this lane's query in every query block; -1 = padding row (sees nothing)
+  int qpos[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int j = qb * 16 + c;
+    qpos[qb] = j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : (j == a.r ? a.n : -1);
+  }
+  __syncthreads();
+
+  const bf16_t *Kb = a.Kc + size_t(bh) * a.K * DH;
+  const bf16_t *Vb = a.Vc + size_t(bh) * a.K * DH;
+  unsigned char *s_v = s_big + wave * 32 * VSTR;     // this wave's V tile [32][VSTR]
+  const int vrow = lane / LPR, vch = lane - vrow * LPR;
+
+  float m[NQB], lsum[NQB];
+  f32x4 o[MB][NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m[qb] = -INFINITY;
+    lsum[qb] = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) o[mb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int begin = wave * a.chunk;
+  const int end = min(a.K, begin + a.chunk);
+  u32x4 kf[2][KT], vr[NVL];
+#define LOAD_K(BASE)                                                                        \
+  _Pragma("unroll") for (int sb = 0; sb < 2; ++sb) {                                        \
+    const int slot_ = min((BASE) + sb * 16 + c, a.K - 1);                                   \
+    _Pragma("unroll") for (int t = 0; t < KT; ++t)                                          \
+      kf[sb][t] = *reinterpret_cast<const u32x4 *>(Kb + size_t(slot_) * DH + (t * 4 + g) * 8); \
+  }
+#define LOAD_V(BASE)                                                                        \
+  _Pragma("unroll") for (int it = 0; it < NVL; ++it) {                                      \
+    const int slot_ = min((BASE) + it * RPI + vrow, a.K - 1);                               \
+    vr[it] = *reinterpret_cast<const u32x4 *>(Vb + size_t(slot_) * DH + vch * 8);           \
+  }
+  if (begin < end) {
+    LOAD_K(begin)
+    LOAD_V(begin)
+  }
+  for (int base = begin; base < end; base += 32) {
+    // ---- logits^T of 32 slots x all queries ----
+    f32x4 s[2][NQB];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) s[sb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        const u32x4 qv = *reinterpret_cast<const u32x4 *>(s_q + (qb * 16 + c) * QSTR + (t * 4 + g) * 16);
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          s[sb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&kf[sb][t]),
+                                                              *reinterpret_cast<const bf16x8 *>(&qv), s[sb][qb], 0, 0, 0);
+      }
+    const bool more = base + 32 < end;
+    if (more) { LOAD_K(base + 32) }
+
+    // ---- V rows of the block into this wave's LDS tile; rows of free slots as zeros (a free slot may
+    //      hold anything, and 0 x NaN would poison the product) ----
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the previous block's reads of the tile come first
+#pragma unroll
+    for (int it = 0; it < NVL; ++it) {
+      const int row = it * RPI + vrow;
+      const bool ok = s_pos[base + row] >= 0;
+      const u32x4 v = ok ? vr[it] : u32x4{0u, 0u, 0u, 0u};
+      u32x2 *dst = reinterpret_cast<u32x2 *>(s_v + row * VSTR + vch * 16);
+      dst[0] = u32x2{v.x, v.y};
+      dst[1] = u32x2{v.z, v.w};
+    }
+    if (more) { LOAD_V(base + 32) }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- online softmax; the probabilities become the B operand of the second product ----
+    // a lane holds, for its query, slots  base + g*4 + i  (sb = 0)  and  base + 16 + g*4 + i  (sb = 1)
+    i32x4 sp4[2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) sp4[sb] = *reinterpret_cast<const i32x4 *>(s_pos + base + sb * 16 + g * 4);
+    u32x4 bhi[NQB], blo[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      float x[8];
+      float bm = -INFINITY;
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ok = sp4[sb][i] >= 0 && sp4[sb][i] <= qpos[qb];
+          x[sb * 4 + i] = ok ? s[sb][qb][i] * a.scale_log2 : -INFINITY;
+          bm = fmaxf(bm, x[sb * 4 + i]);
+        }
+      bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+      const float mn = fmaxf(m[qb], bm);
+      const bool none = mn == -INFINITY;               // nothing visible to this query so far
+      const float alpha = none ? 1.f : __builtin_amdgcn_exp2f(m[qb] - mn);
+      float p[8], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = none ? 0.f : __builtin_amdgcn_exp2f(x[e] - mn);
+        psum += p[e];
+      }
+      lsum[qb] = lsum[qb] * alpha + psum;
+      m[qb] = mn;
+      uint32_t hi[8], lo[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t u = __float_as_uint(p[e]);
+        hi[e] = u & 0xffff0000u;
+        const uint32_t ul = __float_as_uint(p[e] - __uint_as_float(hi[e]));    // exact, >= 0
+        lo[e] = ul + 0x7fffu + ((ul >> 16) & 1u);
+      }
+      bhi[qb] = u32x4{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3], (hi[4] >> 16) | hi[5], (hi[6] >> 16) | hi[7]};
+      blo[qb] = u32x4{(lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u),
+                      (lo[4] >> 16) | (lo[5] & 0xffff0000u), (lo[6] >> 16) | (lo[7] & 0xffff0000u)};
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[mb][qb][i] *= alpha;
+      }
+    }
+
+    // ---- O^T += V^T . P^T ----
+    const uint16_t *vt = reinterpret_cast<const uint16_t *>(s_v);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const int e = e2 * 2;                                   // elements e, e+1 of the 8 k-values
+        const int slot0 = (e < 4 ? 0 : 16) + g * 4 + (e & 3);   // rows of the tile
+        const uint32_t lo16 = vt[(slot0 * VSTR) / 2 + mb * 16 + c];
+        const uint32_t hi16 = vt[((slot0 + 1) * VSTR) / 2 + mb * 16 + c];
+        w[e2] = lo16 | (hi16 << 16);
+      }
+      const u32x4 vf = u32x4{w[0], w[1], w[2], w[3]};
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf),
+                                                            *reinterpret_cast<const bf16x8 *>(&bhi[qb]), o[mb][qb], 0, 0, 0);
+        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf),
+                                                            *reinterpret_cast<const bf16x8 *>(&blo[qb]), o[mb][qb], 0, 0, 0);
+      }
+    }
+  }
+#undef LOAD_K
+#undef LOAD_V
+
+  // ---- merge the four waves: common maximum per query, then sums in wave order ----
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    float l = lsum[qb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    lsum[qb] = l;
+    if (g == 0) {
+      s_m[wave * NQ16 + qb * 16 + c] = m[qb];
+      s_l[wave * NQ16 + qb * 16 + c] = l;
+    }
+  }
+  __syncthreads();   // also: every wave is done with its V tile, which the merge buffer overlays
+  float inv_l[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kFwdWaves; ++w) M = fmaxf(M, s_m[w * NQ16 + qb * 16 + c]);
+    float L = 0.f, mine = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFwdWaves; ++w) {
+      const float mw = s_m[w * NQ16 + qb * 16 + c];
+      const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+      L += f * s_l[w * NQ16 + qb * 16 + c];
+      if (w == wave) mine = f;
+    }
+    inv_l[qb] = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[mb][qb][i] *= mine;
+  }
+  // wave w finishes head-dimension blocks w*OWN .. w*OWN+OWN-1: in round t wave t lays out its whole
+  // result, every wave adds its own blocks
+  f32x4 *s_mrg = reinterpret_cast<f32x4 *>(s_big);   // [MB][NQB][64 lanes]
+  f32x4 fin[OWN][NQB];
+#pragma unroll
+  for (int j = 0; j < OWN; ++j)
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) fin[j][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < kFwdWaves; ++t) {
+    if (wave == t) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) s_mrg[(mb * NQB + qb) * 64 + lane] = o[mb][qb];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < OWN; ++j)
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const f32x4 v = s_mrg[((wave * OWN + j) * NQB + qb) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fin[j][qb][i] += v[i];
+      }
+    __syncthreads();
+  }
+  // ---- normalise, round once, store: a lane holds 4 consecutive d of one query ----
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int j = qb * 16 + c;
+    if (j < a.nq) {
+      bf16_t *orow = a.O + (size_t(b) * a.nq + j) * Hd + h * DH;
+#pragma unroll
+      for (int jj = 0; jj < OWN; ++jj) {
+        const int d0 = (wave * OWN + jj) * 16 + g * 4;
+        uint32_t r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = f32_to_bf16_rne(fin[jj][qb][i] * inv_l[qb]);
+        *reinterpret_cast<u32x2 *>(orow + d0) = u32x2{r[0] | (r[1] << 16), r[2] | (r[3] << 16)};
+      }
+    }
+  }
+}
+
+template <int DH>
+hipError_t launch_dh(adore_ctx *ctx, const FwdAttendArgs &a, int rows) {
+  ScopedTimer t(ctx, ADORE_KERNEL_FWD_ATTEND, ctx->stream);
+  const dim3 grid(rows), block(64 * kFwdWaves);
+  const int nqb = (a.nq + 15) / 16;
+#define FWD_CASE(N)                                                                                       \
+  case N: {                                                                                               \
+    const int lds = fwd_attend_lds_bytes<DH, N>(a.Kp);                                                    \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_attend_kernel<DH, N>),          \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);                  \
+    if (e != hipSuccess) return e;                                                                        \
+    ADORE_LAUNCH(t, (fwd_attend_kernel<DH, N>), grid, block, lds, ctx->stream, a);                        \
+    break;                                                                                                \
+  }
+  switch (nqb) {
+    FWD_CASE(1)
+    FWD_CASE(2)
+    FWD_CASE(3)
+    FWD_CASE(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef FWD_CASE
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Largest cache the forward attention takes: the slot positions of a row sit in LDS next to the tiles.
+int fwd_attend_max_slots() { return 8192; }
+
+hipError_t launch_fwd_attend(adore_ctx *ctx, int layer, int r) {
+  const adore_config &c = ctx->cfg;
+  const size_t layer_elems = size_t(c.batch) * c.heads * c.cache_slots * c.head_dim;
+  FwdAttendArgs a;
+  a.Q = static_cast<const bf16_t *>(ctx->fwd_q);
+  a.Kc = reinterpret_cast<const bf16_t *>(ctx->cache_k) + layer * layer_elems;
+  a.Vc = reinterpret_cast<const bf16_t *>(ctx->cache_v) + layer * layer_elems;
+  a.slot_pos = ctx->slot_pos[ctx->cur];
+  a.insert_slot = ctx->insert_slot[ctx->cur];
+  a.rebuilt_pos = ctx->rebuilt_pos[ctx->cur];
+  a.O = static_cast<bf16_t *>(ctx->fwd_o);
+  a.H = c.heads; a.K = c.cache_slots; a.nq = r + 1; a.r = r; a.Rdim = max(c.rebuild_budget, 1); a.n = ctx->n;
+  a.chunk = ((c.cache_slots + kFwdWaves - 1) / kFwdWaves + 31) / 32 * 32;
+  a.Kp = a.chunk * kFwdWaves;
+  a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
+  const int rows = c.batch * c.heads;
+  return c.head_dim == 128 ? launch_dh<128>(ctx, a, rows) : launch_dh<64>(ctx, a, rows);
+}
+
+}  // namespace adore

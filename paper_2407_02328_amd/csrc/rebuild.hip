@@ -32,15 +32,37 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // plain vector: stays in registers
 
+// The same tile kernel serves the three projections of the path:
+//   REBUILD  C = X[b][rebuilt_pos] . W_kv^T         -> head slices scattered into the freed cache slots
+//   QKV      C = X_rows . [W_q ; W_kv]^T            -> query rows to a dense buffer, K/V slices scattered into the
+//            slots of the rebuilt tokens and of the current token (rebuild forward, Sec. 2.3)
+//   OPROJ    C = O_rows . W_o^T + X_rows (residual) -> dense rows, the next layer's input
+enum { MODE_REBUILD = 0, MODE_QKV = 1, MODE_OPROJ = 2 };
+
 struct GemmArgs {
-  const void *X;               // [B][N_max][D] hidden states entering this layer
-  const void *W;               // [N][D]
+  const void *X;               // A operand: [B][N_max][D] gathered by position, or dense rows [M][D]
+  const void *W;               // [N][D]  (QKV: W_kv, the rows of columns >= H*d)
+  const void *Wq;              // QKV: [H*d][D], the rows of columns < H*d
   void *Kc, *Vc;               // [B][H][K][d] of this layer
+  void *Out;                   // QKV: query rows [M][H*d]; OPROJ: output rows [.][N]
+  const void *Res;             // OPROJ: residual rows, gathered by position or dense like X
   const int32_t *rebuilt_pos;  // [B][Rdim]
   const int32_t *free_list;    // [B][H][R1]
-  int B, H, d, D, K, N_max, r, R1, Rdim, M, N;
+  const int32_t *insert_slot;  // [B][H]    QKV: the slot of the current token
+  int B, H, d, D, K, N_max, r, R1, Rdim, M, N;   // D = length of the contraction
   int tiles_m, tiles_n;
+  int rps;                     // rows per sequence: row mi = (b, j) = (mi / rps, mi % rps); j < r: rebuilt rank j,
+                               // j == r: the current token
+  int cur_pos;                 // position of the current token
+  int a_gather, res_gather;    // 1: the row of (b, j) is [b][position of j]; 0: it is row mi
+  int out_rps, out_cur;        // OPROJ: (b, j) is written to row b * out_rps + (j < r ? j : out_cur)
 };
+
+__device__ inline size_t row_by_position(const GemmArgs &a, int mi) {
+  const int b = mi / a.rps, j = mi - b * a.rps;
+  const int pos = j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : a.cur_pos;
+  return size_t(b) * a.N_max + pos;
+}
 
 // Workgroup = 8 waves on a BM x BN output tile, k-steps of BK.
 //   KG = 1: the waves form a WM x WN grid, each holding (BM/WM) x (BN/WN) of the tile.
@@ -53,7 +75,7 @@ struct GemmArgs {
 //                        fragments of the next step are fetched before the barrier.
 //   LDS -> fragments:    one 16-wide k-slice ahead of the MFMAs that use them
 // sched_barrier keeps the compiler from sinking the fragment loads below the MFMAs they overlap with.
-template <int BM, int BN, int BK, int KG, int WM, int WN, int LS, int NS>
+template <int MODE, int BM, int BN, int BK, int KG, int WM, int WN, int LS, int NS>
 __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   constexpr int CH = BK / 8;             // 16-byte chunks per tile row
   constexpr int RPP = 512 / CH;          // tile rows the workgroup loads per pass
@@ -74,7 +96,8 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   constexpr int NH_MAX = BN / 64 > 0 ? BN / 64 : 1;
   // one LDS block: the stages during the k-loop, then the upper k-group's accumulators, then the bf16 output tile
   __shared__ u32x4 smem[SMEM_BYTES / 16];
-  __shared__ long long s_dst[BM * NH_MAX];   // element offset of each output row slice in the cache, -1 = none
+  __shared__ long long s_dst[BM * NH_MAX];   // element offset of each output row slice in its destination, -1 = none
+  __shared__ long long s_res[MODE == MODE_OPROJ ? BM : 1];   // element offset of each row's residual, -1 = none
   // rows are 128 B (BK = 64) or 64 B (BK = 32): 16 consecutive rows at one chunk index hit 16 different bank groups
   auto swz = [](int row, int chunk) { return row * CH + (chunk ^ (CH == 8 ? (row >> 1) & 7 : (row >> 2) & 3)); };
 
@@ -90,40 +113,54 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
 
   // where every row of the output tile goes: looked up now, used after the k-loop
   const int Hd = a.H * a.d;
-  const int nh = BN / a.d > 0 ? BN / a.d : 1;     // head slices in one tile row
+  const int sw = MODE == MODE_OPROJ ? BN : a.d;   // width of a contiguous piece of an output row
+  const int nh = BN / sw > 0 ? BN / sw : 1;       // pieces in one tile row
+  const int section = MODE == MODE_OPROJ ? 0 : n0 / Hd;   // REBUILD: K, V; QKV: Q, K, V (a tile lies in one)
   for (int t = tid; t < BM * nh; t += 512) {
     const int row = t / nh, hh = t - row * nh;
     const int mi = m0 + row;
     long long off = -1;
     if (mi < a.M) {
-      const int b = mi / a.r, rho = mi - b * a.r;
-      const int nf = n0 + hh * a.d;
-      const int rem = nf % Hd;
-      const int h = rem / a.d;
-      const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
-      off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+      const int b = mi / a.rps, j = mi - b * a.rps;
+      if (MODE == MODE_OPROJ) {
+        off = (long long)(size_t(b) * a.out_rps + (j < a.r ? j : a.out_cur)) * a.N + n0;
+      } else {
+        const int rem = (n0 + hh * a.d) % Hd;
+        const int h = rem / a.d;
+        if (MODE == MODE_QKV && section == 0) {
+          off = (long long)mi * Hd + rem;
+        } else {
+          const int slot = j < a.r ? a.free_list[(size_t(b) * a.H + h) * a.R1 + j] : a.insert_slot[size_t(b) * a.H + h];
+          off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+        }
+      }
     }
     s_dst[t] = off;
+  }
+  if (MODE == MODE_OPROJ) {
+    for (int row = tid; row < BM; row += 512) {
+      const int mi = m0 + row;
+      s_res[row] = mi < a.M ? (long long)(a.res_gather ? row_by_position(a, mi) : size_t(mi)) * a.N + n0 : -1;
+    }
   }
   const int lchunk = tid % CH, lrow = tid / CH;   // rows lrow + RPP*i
   const bool b_on = BN >= RPP || lrow < BN;       // narrow tiles: only some threads load W rows
   const u32x4 *gA[NA], *gB[NB];
   const bf16_t *X = static_cast<const bf16_t *>(a.X);
-  const bf16_t *W = static_cast<const bf16_t *>(a.W);
+  const bf16_t *W = MODE == MODE_QKV ? (n0 < Hd ? static_cast<const bf16_t *>(a.Wq) + size_t(n0) * a.D
+                                                  : static_cast<const bf16_t *>(a.W) + size_t(n0 - Hd) * a.D)
+                                     : static_cast<const bf16_t *>(a.W) + size_t(n0) * a.D;
 #pragma unroll
   for (int i = 0; i < NA; ++i) {
     const int mi = m0 + lrow + RPP * i;
     size_t src_row = 0;
-    if (mi < a.M) {
-      const int b = mi / a.r, rho = mi - b * a.r;
-      src_row = size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + rho];
-    }
+    if (mi < a.M) src_row = a.a_gather ? row_by_position(a, mi) : size_t(mi);
     gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
   }
 #pragma unroll
   for (int i = 0; i < NB; ++i) {
     const int nrow = b_on ? lrow + RPP * i : 0;
-    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(n0 + nrow) * a.D) + lchunk;
+    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(nrow) * a.D) + lchunk;
   }
   const int nk = a.D / BK;
   u32x4 ra[NS][NA], rb[NS][NB];
@@ -268,19 +305,26 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
         for (int v = 0; v < 16; ++v) {
           const int row = (wm * TM + i) * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
           const int col = (wn * TN + j) * 32 + (lane & 31);
-          sOut[row * BN + col] = f32_to_bf16_rne(acc[i][j][v]);
+          float val = acc[i][j][v];
+          if (MODE == MODE_OPROJ) {   // the residual joins before the one rounding
+            const long long ro = s_res[row];
+            if (ro >= 0) val += to_float(static_cast<const bf16_t *>(a.Res)[ro + col]);
+          }
+          sOut[row * BN + col] = f32_to_bf16_rne(val);
         }
   }
   __syncthreads();
   // ---- scatter: every output row slice is contiguous in the cache; 16 bytes per lane ----
-  bf16_t *dst_half = static_cast<bf16_t *>(n0 >= Hd ? a.Vc : a.Kc);
+  bf16_t *dst_half = static_cast<bf16_t *>(MODE == MODE_OPROJ ? a.Out
+                                           : MODE == MODE_QKV ? (section == 0 ? a.Out : section == 1 ? a.Kc : a.Vc)
+                                                              : (section == 0 ? a.Kc : a.Vc));
   constexpr int VPR = BN / 8;   // 16-byte vectors per tile row
   for (int idx = tid; idx < BM * VPR; idx += 512) {
     const int row = idx / VPR, vec = idx - row * VPR;
-    const long long off = s_dst[row * nh + (vec * 8) / a.d];
+    const long long off = s_dst[row * nh + (vec * 8) / sw];
     if (off >= 0) {
       const u32x4 val = *reinterpret_cast<const u32x4 *>(sOut + row * BN + vec * 8);
-      *reinterpret_cast<u32x4 *>(dst_half + off + (vec * 8) % a.d) = val;
+      *reinterpret_cast<u32x4 *>(dst_half + off + (vec * 8) % sw) = val;
     }
   }
 }
@@ -323,9 +367,54 @@ struct TileShape {
 constexpr TileShape kTiles[] = {{256, 256, 32}, {256, 128, 64}, {128, 128, 64}, {128, 64, 64}, {128, 32, 64}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-bool tile_fits(const adore_config &c, const TileShape &t) {
-  const int Hd = c.heads * c.head_dim;
-  return c.hidden % t.bk == 0 && Hd % t.bn == 0 && (t.bn % c.head_dim == 0 || c.head_dim % t.bn == 0);
+// kdim = length of the contraction; scatter modes write head slices (section = H*d columns of one kind)
+bool tile_fits(const TileShape &t, int kdim, int section, int head_dim, bool dense) {
+  if (kdim % t.bk != 0 || section % t.bn != 0) return false;
+  return dense || t.bn % head_dim == 0 || head_dim % t.bn == 0;
+}
+
+// the largest tile that still gives each of the 256 compute units a workgroup; the smallest that fits otherwise
+int pick_tile(int M, int N, int kdim, int section, int head_dim, bool dense) {
+  int pick = -1;
+  for (int i = 0; i < kNumTiles; ++i) {
+    if (!tile_fits(kTiles[i], kdim, section, head_dim, dense)) continue;
+    pick = i;
+    const long long tiles = (long long)((M + kTiles[i].bm - 1) / kTiles[i].bm) * (N / kTiles[i].bn);
+    if (tiles >= 256) break;
+  }
+  if (const char *e = getenv("ADORE_GEMM_TILE")) {   // tuning runs: force a tile shape by index
+    const int v = atoi(e);
+    if (v >= 0 && v < kNumTiles && tile_fits(kTiles[v], kdim, section, head_dim, dense)) pick = v;
+  }
+  return pick;
+}
+
+template <int MODE>
+void launch_tile(ScopedTimer &t, hipStream_t stream, int pick, GemmArgs &a) {
+  a.tiles_m = (a.M + kTiles[pick].bm - 1) / kTiles[pick].bm;
+  a.tiles_n = a.N / kTiles[pick].bn;
+  const int total = a.tiles_m * a.tiles_n;
+  const dim3 grid((total + 7) / 8 * 8), block(512);
+  //                                              BM   BN  BK KG WM WN LS NS
+  switch (pick) {
+    case 0: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 256, 256, 32, 1, 2, 4, 4, 2>), grid, block, 0, stream, a); break;
+    case 1: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 256, 128, 64, 1, 4, 2, 3, 2>), grid, block, 0, stream, a); break;
+    case 2: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 128, 128, 64, 2, 2, 2, 3, 4>), grid, block, 0, stream, a); break;
+    case 3: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 128, 64, 64, 2, 2, 2, 3, 4>), grid, block, 0, stream, a); break;
+    default: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 128, 32, 64, 2, 4, 1, 3, 4>), grid, block, 0, stream, a); break;
+  }
+}
+
+void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
+  const adore_config &c = ctx->cfg;
+  a.Wq = nullptr; a.Out = nullptr; a.Res = nullptr;
+  a.rebuilt_pos = ctx->rebuilt_pos[lists];
+  a.free_list = ctx->free_list[lists];
+  a.insert_slot = ctx->insert_slot[lists];
+  a.B = c.batch; a.H = c.heads; a.d = c.head_dim; a.D = c.hidden; a.K = c.cache_slots;
+  a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
+  a.rps = r; a.cur_pos = 0; a.a_gather = 1; a.res_gather = 0; a.out_rps = 0; a.out_cur = 0;
+  a.tiles_m = a.tiles_n = 0;
 }
 
 }  // namespace
@@ -336,45 +425,17 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   const size_t es = elem_size(c);
   const size_t layer_bytes = size_t(c.batch) * c.heads * c.cache_slots * c.head_dim * es;
   GemmArgs a;
+  fill_common(ctx, a, lists, r);
   a.X = hidden_layer;
   a.W = static_cast<const char *>(ctx->w.w_kv) + size_t(layer) * 2 * c.heads * c.head_dim * c.hidden * es;
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
-  a.rebuilt_pos = ctx->rebuilt_pos[lists];
-  a.free_list = ctx->free_list[lists];
-  a.B = c.batch; a.H = c.heads; a.d = c.head_dim; a.D = c.hidden; a.K = c.cache_slots;
-  a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.M = c.batch * r; a.N = 2 * c.heads * c.head_dim;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM, ctx->stream);
-  // the largest tile that still gives each of the 256 compute units a workgroup; the smallest that fits otherwise
-  int pick = -1;
-  if (c.dtype == ADORE_BF16) {
-    for (int i = 0; i < kNumTiles; ++i) {
-      if (!tile_fits(c, kTiles[i])) continue;
-      pick = i;
-      const long long tiles = (long long)((a.M + kTiles[i].bm - 1) / kTiles[i].bm) * (a.N / kTiles[i].bn);
-      if (tiles >= 256) break;
-    }
-    if (const char *e = getenv("ADORE_GEMM_TILE")) {   // tuning runs: force a tile shape by index
-      const int v = atoi(e);
-      if (v >= 0 && v < kNumTiles && tile_fits(c, kTiles[v])) pick = v;
-    }
-  }
+  const int pick = c.dtype == ADORE_BF16 ? pick_tile(a.M, a.N, c.hidden, c.heads * c.head_dim, c.head_dim, false) : -1;
   if (pick >= 0) {
-    a.tiles_m = (a.M + kTiles[pick].bm - 1) / kTiles[pick].bm;
-    a.tiles_n = a.N / kTiles[pick].bn;
-    const int total = a.tiles_m * a.tiles_n;
-    const dim3 grid((total + 7) / 8 * 8), block(512);
-    //                                        BM   BN  BK KG WM WN LS NS
-    switch (pick) {
-      case 0: ADORE_LAUNCH(t, (rebuild_mfma_kernel<256, 256, 32, 1, 2, 4, 4, 2>), grid, block, 0, ctx->stream, a); break;
-      case 1: ADORE_LAUNCH(t, (rebuild_mfma_kernel<256, 128, 64, 1, 4, 2, 3, 2>), grid, block, 0, ctx->stream, a); break;
-      case 2: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 128, 64, 2, 2, 2, 3, 4>), grid, block, 0, ctx->stream, a); break;
-      case 3: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 64, 64, 2, 2, 2, 3, 4>), grid, block, 0, ctx->stream, a); break;
-      default: ADORE_LAUNCH(t, (rebuild_mfma_kernel<128, 32, 64, 2, 4, 1, 3, 4>), grid, block, 0, ctx->stream, a); break;
-    }
+    launch_tile<MODE_REBUILD>(t, ctx->stream, pick, a);
   } else {
-    a.tiles_m = a.tiles_n = 0;
     const size_t waves = size_t(a.M) * a.N;
     const unsigned blocks = unsigned((waves + 3) / 4);
     if (c.dtype == ADORE_BF16) {
@@ -383,6 +444,62 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
       ADORE_LAUNCH(t, (rebuild_dot_kernel<float>), dim3(blocks), dim3(256), 0, ctx->stream, a);
     }
   }
+  return hipGetLastError();
+}
+
+// ---- rebuild forward: the two projections around the attention of a layer ----------------------------
+// Whether the tile kernel takes both projections of this configuration (the forward has no other path).
+bool fwd_gemm_supported(const adore_config &c) {
+  const int Hd = c.heads * c.head_dim;
+  return c.dtype == ADORE_BF16 && pick_tile(1, 3 * Hd, c.hidden, Hd, c.head_dim, false) >= 0 &&
+         pick_tile(1, c.hidden, Hd, c.hidden, c.head_dim, true) >= 0;
+}
+
+// q, k, v of the r rebuilt tokens and the current token of every sequence.  x_rows: the rows entering this layer,
+// either the embedding table [B][N_max][D] (by_position) or the dense rows [B*(r+1)][D] the previous layer wrote.
+hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, const void *x_rows, bool by_position,
+                          int r) {
+  const adore_config &c = ctx->cfg;
+  const int Hd = c.heads * c.head_dim;
+  const size_t layer_bytes = size_t(c.batch) * Hd * c.cache_slots * 2;
+  GemmArgs a;
+  fill_common(ctx, a, ctx->cur, r);
+  a.X = x_rows;
+  a.W = static_cast<const char *>(ctx->w.w_kv) + size_t(layer) * 2 * Hd * c.hidden * 2;
+  a.Wq = w_q_layer;
+  a.Kc = ctx->cache_k + layer * layer_bytes;
+  a.Vc = ctx->cache_v + layer * layer_bytes;
+  a.Out = ctx->fwd_q;
+  a.rps = r + 1; a.cur_pos = ctx->n; a.a_gather = by_position ? 1 : 0;
+  a.M = c.batch * (r + 1); a.N = 3 * Hd;
+  ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
+  const int pick = pick_tile(a.M, a.N, c.hidden, Hd, c.head_dim, false);
+  if (pick < 0) return hipErrorInvalidValue;
+  launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
+  return hipGetLastError();
+}
+
+// x' = round(x + W_o . o): residual rows like launch_fwd_qkv's x_rows; output rows of (b, j) at
+// out[b * out_rps + (j < r ? j : out_cur)].
+hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x_rows, bool by_position, void *out,
+                            int out_rps, int out_cur, int r) {
+  const adore_config &c = ctx->cfg;
+  const int Hd = c.heads * c.head_dim;
+  GemmArgs a;
+  fill_common(ctx, a, ctx->cur, r);
+  a.X = ctx->fwd_o;
+  a.W = w_o_layer;
+  a.Kc = a.Vc = nullptr;
+  a.Out = out;
+  a.Res = x_rows;
+  a.D = Hd;
+  a.rps = r + 1; a.cur_pos = ctx->n; a.a_gather = 0; a.res_gather = by_position ? 1 : 0;
+  a.out_rps = out_rps; a.out_cur = out_cur;
+  a.M = c.batch * (r + 1); a.N = c.hidden;
+  ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
+  const int pick = pick_tile(a.M, a.N, Hd, c.hidden, c.head_dim, true);
+  if (pick < 0) return hipErrorInvalidValue;
+  launch_tile<MODE_OPROJ>(t, ctx->stream, pick, a);
   return hipGetLastError();
 }
 

@@ -153,3 +153,73 @@ def compare_cache(w: Workload, snap, orc):
                 assert np.all(np.abs(g - r) <= ulp * 1.0001 + 2e-5 * np.abs(r).max()), name
             else:
                 assert np.all(np.abs(g - r) <= 2e-6 * np.maximum(np.abs(r).max(), 1e-30)), name
+
+
+# ---------------------------------------------------------------------------------------------
+# rebuild forward through the layer stack
+# ---------------------------------------------------------------------------------------------
+def forward_tol(w: Workload) -> float:
+    """Bound on |got - want| / max|want| per output row of the forward.  Every row of q, k, v, the attention
+    output and x' is rounded once to bf16 on both sides; the GPU accumulates in fp32 (and carries the
+    probabilities with 16 bits), the oracle in fp64, so a value near a rounding boundary may land on the
+    neighbouring bf16 value (2^-8 of its binade).  Such a flip upstream moves an entry of x' by about one
+    unit in the last place again, hence one unit per rounding stage that feeds the row: L layers and the
+    cache rows written in earlier steps, (L + 1) * 2^-8 of the row's largest entry."""
+    return (w.L + 1) * 2.0 ** -8
+
+
+def forward_lockstep(w: Workload, steps: int, override=None):
+    """adore_forward_step next to the forward oracle: identical selections (the oracle adopts the GPU's
+    sigma bits after checking them), output rows within forward_tol.  Returns (worst, mean) row errors."""
+    from oracle.adore_oracle import AdoreForwardOracle
+    from tests.helpers import oracle_config
+    inp = SyntheticInputs(w)
+    wts = dict(inp.weights(), **inp.forward_weights())
+    orc = AdoreForwardOracle(oracle_config(w), wts)
+    st = storage_dtype(w)
+    adore = Adore(adore_config(w), device_weights(w, {k: v for k, v in wts.items() if k not in ("w_q", "w_o")}), DEV)
+    wq, wo = to_dev(wts["w_q"], st), to_dev(wts["w_o"], st)
+    E = inp.hidden_store_layer(0)
+    Ed = to_dev(E, st)
+    pk, pv = inp.prompt_kv()
+    ov0 = None if override is None else to_dev(override[:, :w.S], torch.float32)
+    adore.init_cache(to_dev(pk, st), to_dev(pv, st), None, Ed[:, :w.S].contiguous(), ov0, w.S)
+    state = adore.empty_state()
+    adore.get_state(slot_pos=state["slot_pos"], scores=state["scores"])
+    torch.cuda.synchronize()
+    gpu_scores = state["scores"][:, :w.S].cpu().numpy()
+    orc.init_cache(pk, pv, None, E[:, :w.S], w.S, score_override=None if override is None else override[:, :w.S])
+    assert np.abs(gpu_scores.astype(np.float64) - orc.score[:, :w.S].astype(np.float64)).max() < 1e-5
+    if override is None and not np.array_equal(gpu_scores, orc.score[:, :w.S]):
+        orc.init_cache(pk, pv, None, E[:, :w.S], w.S, score_override=gpu_scores)
+    assert np.array_equal(state["slot_pos"].cpu().numpy(), orc.slot_pos), "slot map after init"
+    rows = torch.zeros((w.B, w.R + 1, w.D), dtype=st, device=DEV)
+    slot_map = torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=DEV)
+    released = torch.empty((w.B, w.H, w.R + 1), dtype=torch.int32, device=DEV)
+    rebuilt = torch.empty((w.B, max(w.R, 1)), dtype=torch.int32, device=DEV)
+    worst, mean = 0.0, 0.0
+    for t in range(steps):
+        n = w.S + t
+        npend = [len(p) for p in orc.pending]
+        ov = None if override is None else to_dev(np.asarray(override[:, n], dtype=np.float32), torch.float32)
+        adore.forward_step(wq, wo, Ed, ov, rows, slot_map, released, rebuilt)
+        adore.get_state(scores=state["scores"])
+        torch.cuda.synchronize()
+        score_g = state["scores"][:, n].cpu().numpy()
+        x_o, rows_o, map_o, rel_o, rb_o, own = orc.forward_step(E, score_override=score_g)
+        if override is None:
+            assert np.abs(own - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        assert np.array_equal(slot_map.cpu().numpy(), map_o), f"slot map at n={n}"
+        assert np.array_equal(released.cpu().numpy(), rel_o), f"released at n={n}"
+        assert np.array_equal(rebuilt.cpu().numpy()[:, :w.R], rb_o), f"rebuilt at n={n}"
+        got = rows.float().cpu().numpy().astype(np.float64)
+        for b in range(w.B):
+            used = list(range(npend[b])) + [w.R]
+            g, want = got[b, used], rows_o[b, used]
+            assert np.isfinite(g).all(), f"output rows at n={n}"
+            err = np.abs(g - want).max(axis=-1) / np.abs(want).max(axis=-1)
+            assert err.max() < forward_tol(w), f"output rows at n={n}, b={b}: {err.max()}"
+            worst = max(worst, float(err.max()))
+            mean = max(mean, float(np.abs(g - want).mean() / np.abs(want).max()))
+    adore.close()
+    return worst, mean

@@ -361,3 +361,25 @@ def test_rescore_mode_rejects_overrides_and_restore():
     job.adore.decode_step(q, k, v, job.hidden[0], job.hidden[0][:, w.S].contiguous(), None, job.out[0], None)
     torch.cuda.synchronize()
     job.adore.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# rebuild forward through the layer stack (R+1 query rows per layer)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,kw", [
+    # one 16-row query block, head_dim 64, three layers, a prompt shorter than the cache (rebuild set grows from 0)
+    ("r8_d64", dict(L=3, B=2, H=4, d=64, D=256, K=64, R=8, S=40, T=40)),
+    # 33 rows (three query blocks, the last with one row), head_dim 128, a slot count that is no multiple of 128
+    ("r32_d128", dict(L=2, B=2, H=4, d=128, D=512, K=160, R=32, S=200, T=12)),
+    # two and four query blocks
+    ("r20_d64", dict(L=1, B=3, H=2, d=64, D=128, K=96, R=20, S=100, T=10)),
+    ("r63_d128", dict(L=1, B=1, H=2, d=128, D=256, K=200, R=63, S=260, T=6)),
+    # no rebuild budget: the forward is the single-query step with projections around it
+    ("r0", dict(L=2, B=2, H=2, d=64, D=128, K=48, R=0, S=60, T=10)),
+])
+def test_forward_step_matches_the_forward_oracle(name, kw):
+    h = _harness()
+    w = Workload("fwd_" + name, dtype="bf16", dprime=32, w_std=0.06, **kw)
+    worst, mean = h.forward_lockstep(w, w.T)
+    print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    assert mean < 2.0 ** -10
