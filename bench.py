@@ -185,6 +185,86 @@ def run_stack(w, steps, warmup, prof_steps):
     return el_s, us_s, el_f, us_f
 
 
+def run_forward(w, steps, warmup, prof_steps):
+    """Rebuild forward through the layer stack: every step is one adore_forward_step (per layer: q/k/v
+    projection of the R+1 rows of every sequence with scatter into the cache, attention of the R+1 rows,
+    output projection with residual; once per step: controller and the two selections).  Large tensors
+    are drawn on the device from a seeded torch generator, as in run_stack."""
+    import torch
+    from gen import SyntheticInputs
+    from paper_2407_02328_amd import Adore, make_config
+    from tests.gpu_harness import DEV, storage_dtype, to_dev
+    st = storage_dtype(w)
+    total = warmup + steps + prof_steps
+    assert w.S + total <= w.N_max, "not enough positions for this many steps"
+    g = torch.Generator(device=DEV)
+    g.manual_seed(w.seed)
+
+    def randn(shape, std=1.0):
+        return (torch.randn(shape, generator=g, device=DEV, dtype=torch.float32) * std).to(st)
+
+    Hd = w.H * w.d
+    small = SyntheticInputs(w.scaled(L=1, H=1, d=64, B=1)).weights()
+    wts = {k: to_dev(v, st if k in ("gru_w_ih", "gru_w_hh") else torch.float32) for k, v in small.items() if k != "w_kv"}
+    wts["w_kv"] = randn((w.L, 2 * Hd, w.D), w.w_std)
+    w_q, w_o = randn((w.L, Hd, w.D), w.w_std), randn((w.L, w.D, Hd), w.w_std)
+    embed = randn((w.B, w.N_max, w.D))
+    prompt_k = randn((w.L, w.B, w.H, w.S, w.d)); prompt_v = randn((w.L, w.B, w.H, w.S, w.d))
+    cfg = make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
+                      rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
+                      pos_scale=w.pos_scale)
+    a = Adore(cfg, wts, DEV)
+    a.init_cache(prompt_k, prompt_v, None, embed[:, :w.S].contiguous(), None, w.S)
+    rows = torch.zeros((w.B, w.R + 1, w.D), dtype=st, device=DEV)
+    torch.cuda.synchronize()
+    for t in range(warmup):
+        a.forward_step(w_q, w_o, embed, None, rows)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for t in range(steps):
+        a.forward_step(w_q, w_o, embed, None, rows)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    a.set_timing(True)
+    for t in range(prof_steps):
+        a.forward_step(w_q, w_o, embed, None, rows)
+    timing = a.read_timing()
+    a.set_timing(False)
+    assert bool(torch.isfinite(rows.float()).all())
+    a.close()
+    return elapsed, {k: (1e3 * ms / cnt if cnt else 0.0) for k, (ms, cnt) in timing.items()}
+
+
+def forward_line(w, args):
+    """JSON line of the rebuild-forward workload (tokens/s per layer = B * L * steps / elapsed)."""
+    elapsed, us = run_forward(w, args.steps, args.warmup, args.profile_steps)
+    es, BH, Hd, M = 2, w.B * w.H, w.H * w.d, w.B * (w.R + 1)
+    att_bytes = 2 * BH * w.K * w.d * es + BH * w.K * 4 + 2 * M * Hd * es
+    qkv_flops, o_flops = 2.0 * M * w.D * 3 * Hd, 2.0 * M * Hd * w.D
+    roof = lambda name, work, t, peak, unit, scale, bound: dict(
+        kernel=name, bound=bound, achieved=round(work / (t * 1e-6) / scale, 1) if t else 0.0, peak=peak, unit=unit,
+        frac=round(work / (t * 1e-6) / scale / peak, 4) if t else 0.0, traffic=None, us_per_launch=round(t, 2))
+    roofs = {"roofline_fwd_attend": roof("fwd_attend", att_bytes, us["fwd_attend"], HBM_PEAK_GBS, "GB/s", 1e9, "hbm"),
+             # each projection = the tile kernel (rebuilt tokens' rows) + the skinny kernel (current tokens' rows)
+             "roofline_fwd_qkv": roof("fwd_qkv+fwd_qkv_cur", qkv_flops, us["fwd_qkv"] + us["fwd_qkv_cur"],
+                                      MFMA_PEAK_TFLOPS["bf16"], "TFLOP/s", 1e12, "mfma"),
+             "roofline_fwd_oproj": roof("fwd_oproj+fwd_oproj_cur", o_flops, us["fwd_oproj"] + us["fwd_oproj_cur"],
+                                        MFMA_PEAK_TFLOPS["bf16"], "TFLOP/s", 1e12, "mfma")}
+    dominant = max(roofs.values(), key=lambda r: r["us_per_launch"])
+    return {
+        "metric": "decoded tokens/sec per decode layer at cache K", "value": round(w.B * w.L * args.steps / elapsed, 1),
+        "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * elapsed / args.steps / w.L, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "_forward", "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
+                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
+                   "path": "rebuild forward: R+1 query rows through every layer"},
+        "roofline": dominant, **roofs,
+        "kernel_us": {k: round(v, 2) for k, v in us.items()},
+        "ms_per_step_all_layers": round(1e3 * elapsed / args.steps, 4),
+    }
+
+
 def run_cpu_baseline(w, seqs=16, steps=40):
     """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
     from threadpoolctl import threadpool_info
@@ -220,6 +300,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rescore", action="store_true",
                     help="controller scores every token again at every step (relative position)")
+    ap.add_argument("--forward", type=int, default=0, metavar="LAYERS",
+                    help="time the rebuild forward (adore_forward_step) through this many layers of the workload's shape")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (the decode step shards by "
@@ -231,6 +313,9 @@ def main():
     w = workload(args.workload)
     if args.rescore:
         w = w.scaled(rescore=True)
+    if args.forward:
+        print(json.dumps(forward_line(w.scaled(L=args.forward), args)), flush=True)
+        return
     work = algorithmic_work(w)
     stack = None
     if w.L != 1:

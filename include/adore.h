@@ -198,7 +198,7 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
  *   rows_out  [B][R+1][D] storage type: the last layer's rows; rank j at [b][j], the current token
  *             at [b][R]; rows of unused ranks are left untouched
  * Requires a context initialised with hidden_store == NULL, bf16 storage, R + 1 <= 64, K <= 8192,
- * H*d and D multiples of 64.  Enqueues work; does not synchronise.
+ * H*d and D multiples of 128.  Enqueues work; does not synchronise.
  * Errors: E_INVALID, E_STATE (not initialised for the forward, step past N_max). */
 typedef struct {
   const void *w_q;
@@ -235,9 +235,11 @@ enum {
   ADORE_KERNEL_REBUILD_SELECT,  /* per-sequence top-R select + slot assignment */
   ADORE_KERNEL_REBUILD_GEMM,    /* re-projection + scatter */
   ADORE_KERNEL_RESCORE,         /* RESCORE mode: sigma of every token for the current step */
-  ADORE_KERNEL_FWD_QKV,         /* rebuild forward: q, k, v projection of the R+1 rows + scatter */
+  ADORE_KERNEL_FWD_QKV,         /* rebuild forward: q, k, v projection of the rebuilt tokens' rows + scatter */
+  ADORE_KERNEL_FWD_QKV_CUR,     /* rebuild forward: the same for the current tokens' rows (one per sequence) */
   ADORE_KERNEL_FWD_ATTEND,      /* rebuild forward: attention of the R+1 rows */
-  ADORE_KERNEL_FWD_OPROJ,       /* rebuild forward: output projection + residual */
+  ADORE_KERNEL_FWD_OPROJ,       /* rebuild forward: output projection + residual, rebuilt tokens' rows */
+  ADORE_KERNEL_FWD_OPROJ_CUR,   /* rebuild forward: the same for the current tokens' rows */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libadore.so")
 
 ADORE_F32, ADORE_BF16 = 0, 1
 KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "rebuild_select", "rebuild_gemm",
-           "rescore", "fwd_qkv", "fwd_attend", "fwd_oproj"]
+           "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur"]
 
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",

@@ -560,8 +560,10 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_REBUILD_GEMM: return "rebuild_gemm";
     case ADORE_KERNEL_RESCORE: return "rescore";
     case ADORE_KERNEL_FWD_QKV: return "fwd_qkv";
+    case ADORE_KERNEL_FWD_QKV_CUR: return "fwd_qkv_cur";
     case ADORE_KERNEL_FWD_ATTEND: return "fwd_attend";
     case ADORE_KERNEL_FWD_OPROJ: return "fwd_oproj";
+    case ADORE_KERNEL_FWD_OPROJ_CUR: return "fwd_oproj_cur";
     default: return "?";
   }
 }

@@ -15,7 +15,7 @@
 //                                                   k-order of the second product); A = V transposed
 //                                                   through a wave-private LDS tile with the same k-order
 //
-// Probabilities enter the second product as two bf16 terms (upper 16 bits + rounded remainder), so
+// Probabilities enter the second product as two bf16 terms (upper 16 bits + the next 16 bits), so
 // they carry 16 significant bits; sums are fp32; the output is rounded once to the storage type.
 // One workgroup of 4 waves per (sequence, head); each wave streams a quarter of the slots with an
 // online softmax (base 2), the four partial results are merged through LDS in a fixed order.
@@ -55,7 +55,7 @@ constexpr int fwd_attend_lds_bytes(int Kp) {
 }
 
 template <int DH, int NQB>
-__global__ __launch_bounds__(256) void fwd_attend_kernel(const FwdAttendArgs a) {
+__global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_attend_kernel(const FwdAttendArgs a) {
   constexpr int KT = DH / 32;         // matrix instructions along d per 16x16 logit block
   constexpr int MB = DH / 16;         // 16-wide blocks of the head dimension
   constexpr int OWN = MB / kFwdWaves; // blocks of the head dimension a wave finishes and stores
@@ -90,12 +90,14 @@ __global__ __launch_bounds__(256) void fwd_attend_kernel(const FwdAttendArgs a) 
       *reinterpret_cast<u32x4 *>(s_q + row * QSTR + ch * 16) = v;
     }
   }
-  // position of this lane's query in every query block; -1 = padding row (sees nothing)
-  int qpos[NQB];
+  // position of this lane's query in every query block (padding rows: any value, their results are dropped).
+  // A slot at position p is visible to a query at position P iff 0 <= p <= P: one unsigned comparison, a
+  // free slot's -1 being the largest unsigned value.
+  uint32_t qpos[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int j = qb * 16 + c;
-    qpos[qb] = j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : (j == a.r ? a.n : -1);
+    qpos[qb] = uint32_t(j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : a.n);
   }
   __syncthreads();
 
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(256) void fwd_attend_kernel(const FwdAttendArgs a) 
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const bool ok = sp4[sb][i] >= 0 && sp4[sb][i] <= qpos[qb];
+          const bool ok = uint32_t(sp4[sb][i]) <= qpos[qb];
           x[sb * 4 + i] = ok ? s[sb][qb][i] * a.scale_log2 : -INFINITY;
           bm = fmaxf(bm, x[sb * 4 + i]);
         }
@@ -199,17 +201,18 @@ __global__ __launch_bounds__(256) void fwd_attend_kernel(const FwdAttendArgs a) 
       }
       lsum[qb] = lsum[qb] * alpha + psum;
       m[qb] = mn;
+      // two bf16 terms per probability: the upper 16 bits, and the upper 16 bits of what is left (16
+      // significant bits in all, rounded down); the upper halves of two floats are packed by one byte permute
       uint32_t hi[8], lo[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const uint32_t u = __float_as_uint(p[e]);
-        hi[e] = u & 0xffff0000u;
-        const uint32_t ul = __float_as_uint(p[e] - __uint_as_float(hi[e]));    // exact, >= 0
-        lo[e] = ul + 0x7fffu + ((ul >> 16) & 1u);
+        hi[e] = __float_as_uint(p[e]);
+        lo[e] = __float_as_uint(p[e] - __uint_as_float(hi[e] & 0xffff0000u));    // exact, >= 0
       }
-      bhi[qb] = u32x4{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3], (hi[4] >> 16) | hi[5], (hi[6] >> 16) | hi[7]};
-      blo[qb] = u32x4{(lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u),
-                      (lo[4] >> 16) | (lo[5] & 0xffff0000u), (lo[6] >> 16) | (lo[7] & 0xffff0000u)};
+#define PACK_HI(A, B) __builtin_amdgcn_perm(B, A, 0x07060302u)   /* (A >> 16) | (B & 0xffff0000) */
+      bhi[qb] = u32x4{PACK_HI(hi[0], hi[1]), PACK_HI(hi[2], hi[3]), PACK_HI(hi[4], hi[5]), PACK_HI(hi[6], hi[7])};
+      blo[qb] = u32x4{PACK_HI(lo[0], lo[1]), PACK_HI(lo[2], lo[3]), PACK_HI(lo[4], lo[5]), PACK_HI(lo[6], lo[7])};
+#undef PACK_HI
       if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)

@@ -51,17 +51,17 @@ struct GemmArgs {
   const int32_t *insert_slot;  // [B][H]    QKV: the slot of the current token
   int B, H, d, D, K, N_max, r, R1, Rdim, M, N;   // D = length of the contraction
   int tiles_m, tiles_n;
-  int rps;                     // rows per sequence: row mi = (b, j) = (mi / rps, mi % rps); j < r: rebuilt rank j,
-                               // j == r: the current token
+  // Rows.  The tile kernel takes the rebuilt tokens: row mi = (b, j) = (mi / r, mi % r), rank j of sequence b.
+  // The current token of every sequence (one row each) goes through cur_rows_kernel.  Dense row buffers hold
+  // xrps rows per sequence: rank j at row b * xrps + j, the current token at row b * xrps + r.
+  int xrps;
   int cur_pos;                 // position of the current token
-  int a_gather, res_gather;    // 1: the row of (b, j) is [b][position of j]; 0: it is row mi
-  int out_rps, out_cur;        // OPROJ: (b, j) is written to row b * out_rps + (j < r ? j : out_cur)
+  int a_gather, res_gather;    // 1: the row of a token is [b][its position]; 0: its row in a dense buffer
+  int out_rps, out_cur;        // OPROJ: rank j is written to row b * out_rps + j, the current token to b * out_rps + out_cur
 };
 
-__device__ inline size_t row_by_position(const GemmArgs &a, int mi) {
-  const int b = mi / a.rps, j = mi - b * a.rps;
-  const int pos = j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : a.cur_pos;
-  return size_t(b) * a.N_max + pos;
+__device__ inline size_t row_by_position(const GemmArgs &a, int b, int j) {
+  return size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + j];
 }
 
 // Workgroup = 8 waves on a BM x BN output tile, k-steps of BK.
@@ -121,16 +121,16 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
     const int mi = m0 + row;
     long long off = -1;
     if (mi < a.M) {
-      const int b = mi / a.rps, j = mi - b * a.rps;
+      const int b = mi / a.r, j = mi - b * a.r;
       if (MODE == MODE_OPROJ) {
-        off = (long long)(size_t(b) * a.out_rps + (j < a.r ? j : a.out_cur)) * a.N + n0;
+        off = (long long)(size_t(b) * a.out_rps + j) * a.N + n0;
       } else {
         const int rem = (n0 + hh * a.d) % Hd;
         const int h = rem / a.d;
         if (MODE == MODE_QKV && section == 0) {
-          off = (long long)mi * Hd + rem;
+          off = (long long)(size_t(b) * a.xrps + j) * Hd + rem;
         } else {
-          const int slot = j < a.r ? a.free_list[(size_t(b) * a.H + h) * a.R1 + j] : a.insert_slot[size_t(b) * a.H + h];
+          const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + j];
           off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
         }
       }
@@ -140,7 +140,12 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   if (MODE == MODE_OPROJ) {
     for (int row = tid; row < BM; row += 512) {
       const int mi = m0 + row;
-      s_res[row] = mi < a.M ? (long long)(a.res_gather ? row_by_position(a, mi) : size_t(mi)) * a.N + n0 : -1;
+      long long ro = -1;
+      if (mi < a.M) {
+        const int b = mi / a.r, j = mi - b * a.r;
+        ro = (long long)(a.res_gather ? row_by_position(a, b, j) : size_t(b) * a.xrps + j) * a.N + n0;
+      }
+      s_res[row] = ro;
     }
   }
   const int lchunk = tid % CH, lrow = tid / CH;   // rows lrow + RPP*i
@@ -154,7 +159,10 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   for (int i = 0; i < NA; ++i) {
     const int mi = m0 + lrow + RPP * i;
     size_t src_row = 0;
-    if (mi < a.M) src_row = a.a_gather ? row_by_position(a, mi) : size_t(mi);
+    if (mi < a.M) {
+      const int b = mi / a.r, j = mi - b * a.r;
+      src_row = a.a_gather ? row_by_position(a, b, j) : size_t(b) * a.xrps + j;
+    }
     gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
   }
 #pragma unroll
@@ -360,6 +368,91 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
   }
 }
 
+// The current token's row of every sequence (rebuild forward): B rows against the same weights, a skinny product
+// that only streams W.  One workgroup owns 16 sequences x NC*16 output columns; its 4 waves cut the contraction
+// into quarters (summed through LDS in a fixed order).  16x16x32 tiles; lane (c, g) holds, for matrix instruction
+// s, the 8 values at k = (4*s + g)*8 of its quarter for row c, so every row is read in 64-byte runs (both operands
+// use the same assignment, so the order of k does not matter).  Epilogue as in the tile kernel.
+template <int MODE, int NC>
+__global__ __launch_bounds__(256) void cur_rows_kernel(const GemmArgs a) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int j0 = blockIdx.x * (16 * NC), t0 = blockIdx.y * 16;
+  const int Hd = a.H * a.d;
+  const int kw = a.D / 4;                               // k-range of one wave, a multiple of 32
+  const int bb = min(t0 + c, a.B - 1);                  // padded rows read a valid sequence; dropped at the store
+  const size_t xrow = a.a_gather ? size_t(bb) * a.N_max + a.cur_pos : size_t(bb) * a.xrps + a.r;
+  const u32x4 *pa = reinterpret_cast<const u32x4 *>(static_cast<const bf16_t *>(a.X) + xrow * a.D + wave * kw) + g;
+  const u32x4 *pb[NC];
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc) {
+    const int n = j0 + nc * 16 + c;                     // N is a multiple of 16 * NC
+    const bf16_t *wrow = MODE == MODE_QKV && n < Hd ? static_cast<const bf16_t *>(a.Wq) + size_t(n) * a.D
+                         : MODE == MODE_QKV         ? static_cast<const bf16_t *>(a.W) + size_t(n - Hd) * a.D
+                                                    : static_cast<const bf16_t *>(a.W) + size_t(n) * a.D;
+    pb[nc] = reinterpret_cast<const u32x4 *>(wrow + wave * kw) + g;
+  }
+  f32x4 acc[NC];
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc) acc[nc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int steps = kw / 32;
+#define CUR_STEP(VA, VB)                                                                                     \
+  _Pragma("unroll") for (int nc = 0; nc < NC; ++nc)                                                          \
+    acc[nc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&(VA)),              \
+                                                      *reinterpret_cast<const bf16x8 *>(&(VB)[nc]), acc[nc], 0, 0, 0);
+  int s = 0;
+  for (; s + 4 <= steps; s += 4) {          // four steps' loads in flight
+    u32x4 va[4], vb[4][NC];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      va[u] = pa[(s + u) * 4];
+#pragma unroll
+      for (int nc = 0; nc < NC; ++nc) vb[u][nc] = pb[nc][(s + u) * 4];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { CUR_STEP(va[u], vb[u]) }
+  }
+  for (; s < steps; ++s) {
+    u32x4 va = pa[s * 4], vb[NC];
+#pragma unroll
+    for (int nc = 0; nc < NC; ++nc) vb[nc] = pb[nc][s * 4];
+    CUR_STEP(va, vb)
+  }
+#undef CUR_STEP
+  // accumulator element v of lane (c, g): sequence 4*g + v, column c
+  __shared__ float red[4][NC][16][17];
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][nc][4 * g + v][c] = acc[nc][v];
+  __syncthreads();
+  const int m = tid >> 4, nn = tid & 15;
+  const int b = t0 + m;
+  if (b >= a.B) return;
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc) {
+    float val = (red[0][nc][m][nn] + red[1][nc][m][nn]) + (red[2][nc][m][nn] + red[3][nc][m][nn]);
+    const int n = j0 + nc * 16 + nn;
+    bf16_t *dst;
+    if (MODE == MODE_OPROJ) {
+      const size_t rrow = a.res_gather ? size_t(b) * a.N_max + a.cur_pos : size_t(b) * a.xrps + a.r;
+      val += to_float(static_cast<const bf16_t *>(a.Res)[rrow * a.N + n]);
+      dst = static_cast<bf16_t *>(a.Out) + (size_t(b) * a.out_rps + a.out_cur) * a.N + n;
+    } else {
+      const int section = n / Hd, rem = n - section * Hd;
+      const int h = rem / a.d;
+      if (section == 0) {
+        dst = static_cast<bf16_t *>(a.Out) + (size_t(b) * a.xrps + a.r) * Hd + rem;
+      } else {
+        const int slot = a.insert_slot[size_t(b) * a.H + h];
+        dst = static_cast<bf16_t *>(section == 1 ? a.Kc : a.Vc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+      }
+    }
+    dst->bits = f32_to_bf16_rne(val);
+  }
+}
+
 // The tile shapes the launcher chooses from, largest first.
 struct TileShape {
   int bm, bn, bk;
@@ -413,7 +506,7 @@ void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
   a.insert_slot = ctx->insert_slot[lists];
   a.B = c.batch; a.H = c.heads; a.d = c.head_dim; a.D = c.hidden; a.K = c.cache_slots;
   a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
-  a.rps = r; a.cur_pos = 0; a.a_gather = 1; a.res_gather = 0; a.out_rps = 0; a.out_cur = 0;
+  a.xrps = r; a.cur_pos = 0; a.a_gather = 1; a.res_gather = 0; a.out_rps = 0; a.out_cur = 0;
   a.tiles_m = a.tiles_n = 0;
 }
 
@@ -448,15 +541,30 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
 }
 
 // ---- rebuild forward: the two projections around the attention of a layer ----------------------------
-// Whether the tile kernel takes both projections of this configuration (the forward has no other path).
+// Whether the kernels take both projections of this configuration (the forward has no other path).
 bool fwd_gemm_supported(const adore_config &c) {
   const int Hd = c.heads * c.head_dim;
-  return c.dtype == ADORE_BF16 && pick_tile(1, 3 * Hd, c.hidden, Hd, c.head_dim, false) >= 0 &&
+  return c.dtype == ADORE_BF16 && c.hidden % 128 == 0 && Hd % 128 == 0 &&
+         pick_tile(1, 3 * Hd, c.hidden, Hd, c.head_dim, false) >= 0 &&
          pick_tile(1, c.hidden, Hd, c.hidden, c.head_dim, true) >= 0;
 }
 
+namespace {
+
+template <int MODE>
+void launch_cur_rows(ScopedTimer &t, hipStream_t stream, const GemmArgs &a) {
+  const int seq_blocks = (a.B + 15) / 16;
+  if (a.N % 32 == 0 && (a.N / 32) * seq_blocks >= 256) {
+    ADORE_LAUNCH(t, (cur_rows_kernel<MODE, 2>), dim3(a.N / 32, seq_blocks), dim3(256), 0, stream, a);
+  } else {
+    ADORE_LAUNCH(t, (cur_rows_kernel<MODE, 1>), dim3(a.N / 16, seq_blocks), dim3(256), 0, stream, a);
+  }
+}
+
+}  // namespace
+
 // q, k, v of the r rebuilt tokens and the current token of every sequence.  x_rows: the rows entering this layer,
-// either the embedding table [B][N_max][D] (by_position) or the dense rows [B*(r+1)][D] the previous layer wrote.
+// either the embedding table [B][N_max][D] (by_position) or the dense rows [B][r+1][D] the previous layer wrote.
 hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, const void *x_rows, bool by_position,
                           int r) {
   const adore_config &c = ctx->cfg;
@@ -470,17 +578,23 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
   a.Out = ctx->fwd_q;
-  a.rps = r + 1; a.cur_pos = ctx->n; a.a_gather = by_position ? 1 : 0;
-  a.M = c.batch * (r + 1); a.N = 3 * Hd;
-  ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
-  const int pick = pick_tile(a.M, a.N, c.hidden, Hd, c.head_dim, false);
-  if (pick < 0) return hipErrorInvalidValue;
-  launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
+  a.xrps = r + 1; a.cur_pos = ctx->n; a.a_gather = by_position ? 1 : 0;
+  a.M = c.batch * r; a.N = 3 * Hd;
+  if (r > 0) {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
+    const int pick = pick_tile(a.M, a.N, c.hidden, Hd, c.head_dim, false);
+    if (pick < 0) return hipErrorInvalidValue;
+    launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
+  }
+  {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV_CUR, ctx->stream);
+    launch_cur_rows<MODE_QKV>(t, ctx->stream, a);
+  }
   return hipGetLastError();
 }
 
-// x' = round(x + W_o . o): residual rows like launch_fwd_qkv's x_rows; output rows of (b, j) at
-// out[b * out_rps + (j < r ? j : out_cur)].
+// x' = round(x + W_o . o): residual rows like launch_fwd_qkv's x_rows; output rows at out[b * out_rps + j] for
+// rank j and out[b * out_rps + out_cur] for the current token.
 hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x_rows, bool by_position, void *out,
                             int out_rps, int out_cur, int r) {
   const adore_config &c = ctx->cfg;
@@ -493,13 +607,19 @@ hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x
   a.Out = out;
   a.Res = x_rows;
   a.D = Hd;
-  a.rps = r + 1; a.cur_pos = ctx->n; a.a_gather = 0; a.res_gather = by_position ? 1 : 0;
+  a.xrps = r + 1; a.cur_pos = ctx->n; a.a_gather = 0; a.res_gather = by_position ? 1 : 0;
   a.out_rps = out_rps; a.out_cur = out_cur;
-  a.M = c.batch * (r + 1); a.N = c.hidden;
-  ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
-  const int pick = pick_tile(a.M, a.N, Hd, c.hidden, c.head_dim, true);
-  if (pick < 0) return hipErrorInvalidValue;
-  launch_tile<MODE_OPROJ>(t, ctx->stream, pick, a);
+  a.M = c.batch * r; a.N = c.hidden;
+  if (r > 0) {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
+    const int pick = pick_tile(a.M, a.N, Hd, c.hidden, c.head_dim, true);
+    if (pick < 0) return hipErrorInvalidValue;
+    launch_tile<MODE_OPROJ>(t, ctx->stream, pick, a);
+  }
+  {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ_CUR, ctx->stream);
+    launch_cur_rows<MODE_OPROJ>(t, ctx->stream, a);
+  }
   return hipGetLastError();
 }
 
