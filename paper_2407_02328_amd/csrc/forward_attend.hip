@@ -44,6 +44,8 @@ struct FwdAttendArgs {
 };
 
 constexpr int kFwdWaves = 4;
+constexpr float kNoMax = -1.0e30f;   // running maximum before anything has been seen (finite on purpose)
+constexpr float kLazy = 8.f;         // the reference moves only when the maximum grows by more than 2^kLazy
 
 template <int DH, int NQB>
 constexpr int fwd_attend_lds_bytes(int Kp) {
@@ -78,44 +80,10 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
   const int c = lane & 15, g = lane >> 4;
   const int Hd = a.H * DH;
 
-  // ---- positions of the slots (the current token's slot patched in) and the query tile ----
-  {
-    const int32_t *sp = a.slot_pos + size_t(bh) * a.K;
-    const int s_ins = a.insert_slot[bh];
-    for (int k = tid; k < a.Kp; k += 256) s_pos[k] = k < a.K ? (k == s_ins ? a.n : sp[k]) : -1;
-    for (int idx = tid; idx < NQ16 * LPR; idx += 256) {
-      const int row = idx / LPR, ch = idx - row * LPR;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (row < a.nq) v = *reinterpret_cast<const u32x4 *>(a.Q + (size_t(b) * a.nq + row) * Hd + h * DH + ch * 8);
-      *reinterpret_cast<u32x4 *>(s_q + row * QSTR + ch * 16) = v;
-    }
-  }
-  // position of this lane's query in every query block (padding rows: any value, their results are dropped).
-  // A slot at position p is visible to a query at position P iff 0 <= p <= P: one unsigned comparison, a
-  // free slot's -1 being the largest unsigned value.
-  uint32_t qpos[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int j = qb * 16 + c;
-    qpos[qb] = uint32_t(j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : a.n);
-  }
-  __syncthreads();
-
   const bf16_t *Kb = a.Kc + size_t(bh) * a.K * DH;
   const bf16_t *Vb = a.Vc + size_t(bh) * a.K * DH;
   unsigned char *s_v = s_big + wave * 32 * VSTR;     // this wave's V tile [32][VSTR]
   const int vrow = lane / LPR, vch = lane - vrow * LPR;
-
-  float m[NQB], lsum[NQB];
-  f32x4 o[MB][NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m[qb] = -INFINITY;
-    lsum[qb] = 0.f;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) o[mb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
   const int begin = wave * a.chunk;
   const int end = min(a.K, begin + a.chunk);
   u32x4 kf[2][KT], vr[NVL];
@@ -130,10 +98,67 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
     const int slot_ = min((BASE) + it * RPI + vrow, a.K - 1);                               \
     vr[it] = *reinterpret_cast<const u32x4 *>(Vb + size_t(slot_) * DH + vch * 8);           \
   }
+
+  // ---- every global read of the set-up is issued before any of them is waited for (a read of what the
+  //      previous kernel wrote comes from memory, not from this XCD's cache: one round trip, not six) ----
+  // positions of the slots (the current token's slot patched in), the query tile, the first cache block
+  constexpr int QIT = (NQ16 * LPR + 255) / 256;      // query-tile vectors per thread
+  constexpr int PIT = 4;                             // slot positions per thread and batch
+  const int32_t *sp = a.slot_pos + size_t(bh) * a.K;
+  const int s_ins = a.insert_slot[bh];
+  u32x4 qv[QIT];
+#pragma unroll
+  for (int i = 0; i < QIT; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx / LPR, ch = idx - row * LPR;
+    qv[i] = u32x4{0u, 0u, 0u, 0u};
+    if (idx < NQ16 * LPR && row < a.nq)
+      qv[i] = *reinterpret_cast<const u32x4 *>(a.Q + (size_t(b) * a.nq + row) * Hd + h * DH + ch * 8);
+  }
+  // position of this lane's query in every query block (padding rows: any value, their results are dropped).
+  // A slot at position p is visible to a query at position P iff 0 <= p <= P: one unsigned comparison, a
+  // free slot's -1 being the largest unsigned value.
+  uint32_t qpos[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int j = qb * 16 + c;
+    qpos[qb] = uint32_t(j < a.r ? a.rebuilt_pos[size_t(b) * a.Rdim + j] : a.n);
+  }
+  int32_t pv[PIT];
+#pragma unroll
+  for (int i = 0; i < PIT; ++i) {
+    const int k = tid + i * 256;
+    pv[i] = k < a.K ? sp[k] : -1;
+  }
   if (begin < end) {
     LOAD_K(begin)
     LOAD_V(begin)
   }
+#pragma unroll
+  for (int i = 0; i < PIT; ++i) {
+    const int k = tid + i * 256;
+    if (k < a.Kp) s_pos[k] = k == s_ins ? a.n : pv[i];
+  }
+  for (int k = tid + PIT * 256; k < a.Kp; k += 256) s_pos[k] = k < a.K ? (k == s_ins ? a.n : sp[k]) : -1;   // K > 1024
+#pragma unroll
+  for (int i = 0; i < QIT; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx / LPR, ch = idx - row * LPR;
+    if (idx < NQ16 * LPR) *reinterpret_cast<u32x4 *>(s_q + row * QSTR + ch * 16) = qv[i];
+  }
+  __syncthreads();
+
+  float m[NQB], lsum[NQB];
+  f32x4 o[MB][NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m[qb] = kNoMax;
+    lsum[qb] = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) o[mb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const float lazy_raw = kLazy / a.scale_log2;
   for (int base = begin; base < end; base += 32) {
     // ---- logits^T of 32 slots x all queries ----
     f32x4 s[2][NQB];
@@ -171,7 +196,11 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
     __builtin_amdgcn_wave_barrier();
 
     // ---- online softmax; the probabilities become the B operand of the second product ----
-    // a lane holds, for its query, slots  base + g*4 + i  (sb = 0)  and  base + 16 + g*4 + i  (sb = 1)
+    // a lane holds, for its query, slots  base + g*4 + i  (sb = 0)  and  base + 16 + g*4 + i  (sb = 1).
+    // The running maximum m (in units of the raw dot product) only moves when the block's maximum exceeds
+    // it by more than kLazy / scale: until then probabilities are taken against the old reference (they
+    // stay below 2^kLazy) and the accumulators need no rescaling.  m starts at a large negative finite
+    // value, so that no case distinction for "nothing visible yet" is needed: exp2(-inf) = 0.
     i32x4 sp4[2];
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) sp4[sb] = *reinterpret_cast<const i32x4 *>(s_pos + base + sb * 16 + g * 4);
@@ -184,23 +213,29 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const bool ok = uint32_t(sp4[sb][i]) <= qpos[qb];
-          x[sb * 4 + i] = ok ? s[sb][qb][i] * a.scale_log2 : -INFINITY;
+          x[sb * 4 + i] = uint32_t(sp4[sb][i]) <= qpos[qb] ? s[sb][qb][i] : -INFINITY;
           bm = fmaxf(bm, x[sb * 4 + i]);
         }
       bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
       bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-      const float mn = fmaxf(m[qb], bm);
-      const bool none = mn == -INFINITY;               // nothing visible to this query so far
-      const float alpha = none ? 1.f : __builtin_amdgcn_exp2f(m[qb] - mn);
+      const bool move = bm > m[qb] + lazy_raw;          // the same in the four lanes of a query
+      if (__builtin_amdgcn_ballot_w64(move) != 0) {
+        const float alpha = move ? __builtin_amdgcn_exp2f((m[qb] - bm) * a.scale_log2) : 1.f;
+        m[qb] = move ? bm : m[qb];
+        lsum[qb] *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[mb][qb][i] *= alpha;
+      }
+      const float neg_m = -m[qb] * a.scale_log2;
       float p[8], psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = none ? 0.f : __builtin_amdgcn_exp2f(x[e] - mn);
+        p[e] = __builtin_amdgcn_exp2f(fmaf(x[e], a.scale_log2, neg_m));
         psum += p[e];
       }
-      lsum[qb] = lsum[qb] * alpha + psum;
-      m[qb] = mn;
+      lsum[qb] += psum;
       // two bf16 terms per probability: the upper 16 bits, and the upper 16 bits of what is left (16
       // significant bits in all, rounded down); the upper halves of two floats are packed by one byte permute
       uint32_t hi[8], lo[8];
@@ -213,36 +248,40 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
       bhi[qb] = u32x4{PACK_HI(hi[0], hi[1]), PACK_HI(hi[2], hi[3]), PACK_HI(hi[4], hi[5]), PACK_HI(hi[6], hi[7])};
       blo[qb] = u32x4{PACK_HI(lo[0], lo[1]), PACK_HI(lo[2], lo[3]), PACK_HI(lo[4], lo[5]), PACK_HI(lo[6], lo[7])};
 #undef PACK_HI
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) o[mb][qb][i] *= alpha;
-      }
     }
 
     // ---- O^T += V^T . P^T ----
+    // the V^T fragment of the next 16 head dimensions is fetched from LDS before the matrix instructions of
+    // the current ones; the two terms of a probability go to the same accumulator NQB instructions apart
     const uint16_t *vt = reinterpret_cast<const uint16_t *>(s_v);
+#define VT_FRAG(DST, MBI)                                                                          \
+  {                                                                                                \
+    uint32_t w_[4];                                                                                \
+    _Pragma("unroll") for (int e2 = 0; e2 < 4; ++e2) {                                             \
+      const int slot0_ = (e2 < 2 ? 0 : 16) + g * 4 + (e2 & 1) * 2;   /* k-values 2*e2, 2*e2+1 */   \
+      const uint32_t lo16_ = vt[(slot0_ * VSTR) / 2 + (MBI) * 16 + c];                             \
+      const uint32_t hi16_ = vt[((slot0_ + 1) * VSTR) / 2 + (MBI) * 16 + c];                       \
+      w_[e2] = lo16_ | (hi16_ << 16);                                                              \
+    }                                                                                              \
+    DST = u32x4{w_[0], w_[1], w_[2], w_[3]};                                                       \
+  }
+    u32x4 vf[2];
+    VT_FRAG(vf[0], 0)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      uint32_t w[4];
+      if (mb + 1 < MB) { VT_FRAG(vf[(mb + 1) & 1], mb + 1) }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const int e = e2 * 2;                                   // elements e, e+1 of the 8 k-values
-        const int slot0 = (e < 4 ? 0 : 16) + g * 4 + (e & 3);   // rows of the tile
-        const uint32_t lo16 = vt[(slot0 * VSTR) / 2 + mb * 16 + c];
-        const uint32_t hi16 = vt[((slot0 + 1) * VSTR) / 2 + mb * 16 + c];
-        w[e2] = lo16 | (hi16 << 16);
-      }
-      const u32x4 vf = u32x4{w[0], w[1], w[2], w[3]};
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf),
+      for (int qb = 0; qb < NQB; ++qb)
+        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf[mb & 1]),
                                                             *reinterpret_cast<const bf16x8 *>(&bhi[qb]), o[mb][qb], 0, 0, 0);
-        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf),
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+        o[mb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&vf[mb & 1]),
                                                             *reinterpret_cast<const bf16x8 *>(&blo[qb]), o[mb][qb], 0, 0, 0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+#undef VT_FRAG
   }
 #undef LOAD_K
 #undef LOAD_V
@@ -263,14 +302,13 @@ __global__ __launch_bounds__(256, (DH == 128 && NQB == 4) ? 1 : 2) void fwd_atte
   float inv_l[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    float M = -INFINITY;
+    float M = kNoMax;
 #pragma unroll
     for (int w = 0; w < kFwdWaves; ++w) M = fmaxf(M, s_m[w * NQ16 + qb * 16 + c]);
     float L = 0.f, mine = 0.f;
 #pragma unroll
     for (int w = 0; w < kFwdWaves; ++w) {
-      const float mw = s_m[w * NQ16 + qb * 16 + c];
-      const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+      const float f = __builtin_amdgcn_exp2f((s_m[w * NQ16 + qb * 16 + c] - M) * a.scale_log2);   // 0 for a wave that saw nothing
       L += f * s_l[w * NQ16 + qb * 16 + c];
       if (w == wave) mine = f;
     }
