@@ -84,8 +84,10 @@ def run_gpu(w, steps, warmup, prof_steps):
     t1 = time.perf_counter()
     for t in range(warmup, warmup + steps):
         step(t)
+    host = time.perf_counter() - t1             # the host's share: all launches enqueued
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
+    log(f"host enqueue {1e6 * host / steps:.1f} us per step, step {1e6 * elapsed / steps:.1f} us")
 
     # per-kernel durations, HIP events on the library's stream around every launch
     job.adore.set_timing(True)

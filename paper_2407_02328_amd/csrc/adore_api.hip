@@ -9,10 +9,15 @@
 // Two streams.  Attention and the rebuild GEMM run on the caller's stream.  The controller and the
 // two selections run on a side stream owned by the context: they depend on neither the attention
 // output nor the cache contents, only on the previous step's selections, so the chain of step n+1
-// runs under the GEMM of step n (and the attention of step n+1).  What makes this safe is the
-// double buffering of slot_pos / insert_slot / free_list / rebuilt_pos by step parity and three
-// events: the chain of a step waits for the previous step's attention (which reads the buffer the
-// chain is about to overwrite), and the GEMM waits for its own step's chain.
+// runs under the GEMM of step n (and the attention of step n+1).  The GEMM waits for its own step's
+// chain (an event per step: a true dependency).  In the other direction there is only a hazard: the
+// chain must not overwrite lists that an attention still reads.  slot_pos / insert_slot / free_list /
+// rebuilt_pos are therefore rings of kRing copies: the chain of step n writes copy (n + 1) % kRing,
+// whose last reader was the attention of step n - kRing + 1, and the side stream waits for the
+// caller's stream only once in kSyncEvery steps: at a step n that is a multiple of kSyncEvery it waits
+// for the attention of step n - 2, which covers the chains of steps n .. n + kSyncEvery - 1 as long as
+// n + kSyncEvery - 1 - (kRing - 1) <= n - 2.  (Every cross-stream event costs several microseconds on
+// the GPU and on the host; with one wait per step in each direction they added up to 9 us per step.)
 // ADORE_NO_OVERLAP=1 puts everything on the caller's stream.
 #include <cmath>
 #include <cstdlib>
@@ -81,13 +86,13 @@ Layout make_layout(const adore_config &c) {
   };
   l.cache_k = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
   l.cache_v = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
-  l.slot_pos = take(2 * BH * c.cache_slots * 4);
+  l.slot_pos = take(kRing * BH * c.cache_slots * 4);
   l.score = take(size_t(c.batch) * c.max_positions * 4);
   l.z = take(size_t(c.batch) * c.ctrl_hidden * 4);
-  l.insert_slot = take(2 * align_up(BH * 4));
-  l.free_list = take(2 * align_up(BH * R1 * 4));
+  l.insert_slot = take(kRing * align_up(BH * 4));
+  l.free_list = take(kRing * align_up(BH * R1 * 4));
   l.released_pos = take(BH * R1 * 4);
-  l.rebuilt_pos = take(2 * align_up(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4));
+  l.rebuilt_pos = take(kRing * align_up(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4));
   l.init_res = take(size_t(c.batch) * c.cache_slots * 4);
   l.att_part = take(BH * kMaxSplits * (size_t(c.head_dim) + 2) * 4);
   size_t gi_rows = size_t(c.batch) * kPromptChunk;
@@ -137,8 +142,7 @@ void choose_split(adore_ctx *ctx) {
 int ensure_side_stream(adore_ctx *ctx) {
   if (!ctx->overlap || ctx->side_ready) return ADORE_OK;
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_att[0], hipEventDisableTiming) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_att[1], hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_att, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
   if (!ok) return ADORE_E_HIP;
   ctx->side_ready = true;
@@ -184,7 +188,7 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   const size_t BH = size_t(cfg->batch) * cfg->heads;
   const size_t R1 = size_t(cfg->rebuild_budget) + 1;
   const size_t Rdim = cfg->rebuild_budget > 0 ? cfg->rebuild_budget : 1;
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < kRing; ++i) {
     ctx->slot_pos[i] = reinterpret_cast<int32_t *>(base + l.slot_pos + i * BH * cfg->cache_slots * 4);
     ctx->insert_slot[i] = reinterpret_cast<int32_t *>(base + l.insert_slot + i * align_up(BH * 4));
     ctx->free_list[i] = reinterpret_cast<int32_t *>(base + l.free_list + i * align_up(BH * R1 * 4));
@@ -210,7 +214,8 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   const char *no = getenv("ADORE_NO_OVERLAP");
   ctx->overlap = !(no && atoi(no) != 0);
   ctx->side = ctx->stream;
-  ctx->ev_att[0] = ctx->ev_att[1] = ctx->ev_join = nullptr;
+  ctx->ev_att = ctx->ev_join = nullptr;
+  ctx->steps_done = 0;
   ctx->side_ready = false;
   ctx->attended.assign(cfg->layers, 0);
   ctx->rebuilt.assign(cfg->layers, 0);
@@ -231,7 +236,7 @@ int adore_destroy(adore_ctx *ctx) {
   if (ctx->overlap && ctx->side_ready) {
     (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamDestroy(ctx->side);
-    for (hipEvent_t e : {ctx->ev_att[0], ctx->ev_att[1], ctx->ev_join})
+    for (hipEvent_t e : {ctx->ev_att, ctx->ev_join})
       if (e) (void)hipEventDestroy(e);
   }
   delete ctx;
@@ -272,18 +277,16 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
     ADORE_TRY(launch_ctrl_avec(ctx, st));
     ADORE_TRY(launch_rescore(ctx, st, S - 1));
   }
-  // slot map and reserved slot go to buffer `cur`, the rebuild lists to `cur ^ 1` (where a step's GEMM reads
+  // slot map and reserved slot go to copy `cur`, the rebuild lists to `cur + 1` (where a step's GEMM reads
   // them); for the forward, whose first step rebuilds these tokens itself, the lists go to `cur` as well
-  ADORE_TRY(launch_init_select(ctx, ctx->cur, forward ? ctx->cur : ctx->cur ^ 1, S, keep, r0));
+  ADORE_TRY(launch_init_select(ctx, ctx->cur, forward ? ctx->cur : ctx->cur + 1, S, keep, r0));
   ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
   const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
   for (int l = 0; l < c.layers && !forward; ++l) {
-    ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur ^ 1, r0));
+    ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur + 1, r0));
   }
-  if (ctx->overlap) {   // the first step's selections overwrite the lists the GEMMs above read
-    ADORE_TRY(hipEventRecord(ctx->ev_att[0], st));
-    ADORE_TRY(hipEventRecord(ctx->ev_att[1], st));
-  }
+  if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, st));   // the first selections wait for everything above
+  ctx->steps_done = 0;
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));   // the forward's first step waits for "its selections"
   ctx->n = S;
   ctx->occ = keep + r0;
@@ -301,8 +304,8 @@ namespace {
 int do_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out) {
   ADORE_TRY(launch_attend(ctx, layer, q, k_new, v_new, out));
   ctx->attended[layer] = 1;
-  if (++ctx->n_attended == ctx->cfg.layers && ctx->overlap) {
-    ADORE_TRY(hipEventRecord(ctx->ev_att[ctx->cur], ctx->stream));   // buffer `cur` has been read for the last time
+  if (++ctx->n_attended == ctx->cfg.layers && ctx->overlap && (ctx->steps_done + 2) % kSyncEvery == 0) {
+    ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));   // what the side stream waits for two steps from now
   }
   return ADORE_OK;
 }
@@ -316,7 +319,7 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   const int kept = o - x;
   const int pool = ctx->n + 1 - kept;
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
-  const int src = ctx->cur, dst = ctx->cur ^ 1;
+  const int src = ctx->cur, dst = (ctx->cur + 1) % kRing;
   hipStream_t st = ctx->side;
 
   // the controller touches only its own state and the score array: it may run as early as the
@@ -325,8 +328,8 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, 1, &ksplit));
   ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
   if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
-  // buffer `dst` was `cur` one step ago: the selections wait until that step's attention has read it
-  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));
+  // copy `dst` was `cur` kRing - 1 steps ago: see the note on the ring at the top of this file
+  if (ctx->overlap && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
   ADORE_TRY(launch_rebuild_select(ctx, st, dst, r, slot_map, rebuilt_pos));
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
@@ -341,11 +344,12 @@ int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
     // from here on the caller's stream sees everything the selections wrote, outputs included
     ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
   }
-  ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, ctx->cur ^ 1, ctx->r_step));
+  ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, (ctx->cur + 1) % kRing, ctx->r_step));
   ctx->rebuilt[layer] = 1;
   if (++ctx->n_rebuilt == ctx->cfg.layers) {
     ctx->n++;
-    ctx->cur ^= 1;
+    ctx->steps_done++;
+    ctx->cur = (ctx->cur + 1) % kRing;
     reset_step(ctx);
   }
   return ADORE_OK;
@@ -417,13 +421,13 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const int kept = o - x;
     const int pool = ctx->n + 1 - kept;
     const int r_next = pool < c.rebuild_budget ? pool : c.rebuild_budget;
-    const int src = ctx->cur, dst = ctx->cur ^ 1;
+    const int src = ctx->cur, dst = (ctx->cur + 1) % kRing;
     hipStream_t st = ctx->side;
     int ksplit = 1;
     ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, c.max_positions, &ksplit));
     ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
     if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
-    if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att[dst], 0));   // the previous step's layers read `dst`
+    if (ctx->overlap && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));   // see the note on the ring
     ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
     ADORE_TRY(launch_rebuild_select(ctx, st, dst, r_next, slot_map, rebuilt_pos));
     if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
@@ -438,13 +442,14 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const bool last = l == c.layers - 1;
     ADORE_TRY(launch_fwd_qkv(ctx, l, wq + size_t(l) * Hd * c.hidden * es, x_rows, by_pos, r));
     ADORE_TRY(launch_fwd_attend(ctx, l, r));
-    if (last && ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att[ctx->cur], ctx->stream));   // lists of `cur` read for the last time
+    if (last && ctx->overlap && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,
                                last ? c.rebuild_budget + 1 : r + 1, last ? c.rebuild_budget : r, r));
   }
   ctx->r_pending = ctx->r_step;
   ctx->n++;
-  ctx->cur ^= 1;
+  ctx->steps_done++;
+  ctx->cur = (ctx->cur + 1) % kRing;
   reset_step(ctx);
   return ADORE_OK;
 }
@@ -511,10 +516,8 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   if (cache_k) ADORE_TRY(hipMemcpyAsync(ctx->cache_k, cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_v) ADORE_TRY(hipMemcpyAsync(ctx->cache_v, cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   ADORE_TRY(hipStreamSynchronize(ctx->stream));   // `ins` lives on this stack frame
-  if (ctx->overlap) {   // the next selections may start at once
-    ADORE_TRY(hipEventRecord(ctx->ev_att[0], ctx->stream));
-    ADORE_TRY(hipEventRecord(ctx->ev_att[1], ctx->stream));
-  }
+  if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));   // the next selections may start at once
+  ctx->steps_done = 0;
   ctx->n = step;
   ctx->occ = occ;
   ctx->inited = true;

@@ -23,6 +23,9 @@ constexpr int kMaxPositions = 1 << 18; // residency bitmap of a sequence lives i
 constexpr int kPromptChunk = 512;     // tokens per GRU input-projection launch at init
 constexpr int kMaxCtrlSplit = 16;     // D-slices of the GRU input projection
 constexpr int kCtrlSplitTokens = 256; // the projection is only sliced for launches of at most this many tokens
+constexpr int kRing = 8;              // copies of the per-step lists (slot map, reserved slot, free slots, rebuilt tokens)
+constexpr int kSyncEvery = 4;         // the side stream waits for the caller's stream once in this many steps
+static_assert(kSyncEvery + 3 <= kRing, "a list is rewritten kRing - 1 steps after its last reader; see adore_api.hip");
 
 struct TimedLaunch {
   int kernel;
@@ -36,23 +39,23 @@ struct adore_ctx {
   adore_weights w;
   hipStream_t stream;        // the caller's stream: attention and the rebuild GEMM
   hipStream_t side;          // controller and selections; equals `stream` when overlap is off
-  hipEvent_t ev_att[2];      // recorded on `stream` after the last attention of a step (by step parity)
+  hipEvent_t ev_att;         // recorded on `stream` after the last attention of a step, once in kSyncEvery steps
   hipEvent_t ev_join;        // recorded on `side` after the selections of a step
   bool overlap;              // two-stream mode requested
   bool side_ready;           // side stream and events exist (made on first GPU use)
 
   // --- workspace sections (device) ---
-  // Arrays marked x2 are double-buffered by step parity `cur`: a step's attention reads [cur] while
-  // its selections write [cur ^ 1], so the selections of step n+1 may run while the GEMM of step n
-  // still reads the lists of step n.
+  // Arrays marked xR are rings of kRing copies indexed by `cur`: a step's attention reads [cur] while its
+  // selections write [cur + 1], so the selections of step n+1 may run while the GEMM of step n still
+  // reads the lists of step n, and the side stream may run a few steps ahead of the caller's stream.
   char *cache_k, *cache_v;   // [L][B][H][K][d] storage type
-  int32_t *slot_pos[2];      // x2 [B][H][K]   position per slot, -1 = free
+  int32_t *slot_pos[adore::kRing];     // xR [B][H][K]   position per slot, -1 = free
   float *score;              // [B][N_max]  sigma_i
   float *z;                  // [B][d']     GRU state
-  int32_t *insert_slot[2];   // x2 [B][H]      slot reserved for the next token
-  int32_t *free_list[2];     // x2 [B][H][R+1] ascending free slots after the release
+  int32_t *insert_slot[adore::kRing];  // xR [B][H]      slot reserved for the next token
+  int32_t *free_list[adore::kRing];    // xR [B][H][R+1] ascending free slots after the release
   int32_t *released_pos;     // [B][H][R+1]
-  int32_t *rebuilt_pos[2];   // x2 [B][max(R,1)]
+  int32_t *rebuilt_pos[adore::kRing];  // xR [B][max(R,1)]
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
@@ -65,7 +68,8 @@ struct adore_ctx {
   bool inited;
   bool forward;              // initialised for the rebuild forward (adore_forward_step), not for attend/schedule/rebuild
   int32_t r_pending;         // forward: tokens chosen by the previous step, rebuilt by the next
-  int32_t cur;               // buffer index valid for the next attention
+  int32_t cur;               // ring index valid for the next attention
+  int32_t steps_done;        // steps since the last init / set_state
   int32_t n;                 // position of the current / next token
   int32_t occ;               // occupied slots per (b,h) between steps
   int32_t r_step;            // rebuilt tokens chosen by this step's schedule

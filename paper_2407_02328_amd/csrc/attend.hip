@@ -30,7 +30,7 @@ struct AttendArgs {
 };
 
 template <typename T, int DH, int U, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) {
+__global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs a) {
   constexpr int EPL = Vec16<T>::EPL;    // elements per lane
   constexpr int LPR = DH / EPL;         // lanes per cache row
   constexpr int RPW = 64 / LPR;         // rows per wave and load
@@ -53,6 +53,9 @@ __global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) 
   Vec16<T>::load(static_cast<const T *>(a.q) + size_t(bh) * DH + lig * EPL, qf);
 #pragma unroll
   for (int e = 0; e < EPL; ++e) qf[e] *= a.scale_log2;
+  // the current token's k, v: every lane group holds them, the one that meets the reserved slot uses them
+  const typename Vec16<T>::Raw kn = Vec16<T>::load_raw(static_cast<const T *>(a.k_new) + size_t(bh) * DH + lig * EPL);
+  const typename Vec16<T>::Raw vn = Vec16<T>::load_raw(static_cast<const T *>(a.v_new) + size_t(bh) * DH + lig * EPL);
 
   const int begin = sp * a.chunk;
   const int end = min(a.K, begin + a.chunk);
@@ -61,38 +64,46 @@ __global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) 
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
+  // cache rows are read whatever they hold (no read waits for the reserved slot's index to arrive), one
+  // iteration ahead of their use; the row of the reserved slot is then replaced by the current token's k, v,
+  // which are also stored (the slot is marked occupied by the release kernel, which knows the reserved slot too)
+  typename Vec16<T>::Raw kr[U], vr[U];
+  int spv[U];
+#define ATTEND_FETCH(BASE)                                                        \
+  _Pragma("unroll") for (int u = 0; u < U; ++u) {                                 \
+    const int slot_ = min((BASE) + u * G + grp, end - 1);                         \
+    kr[u] = Vec16<T>::load_raw(Kb + size_t(slot_) * DH + lig * EPL);              \
+    vr[u] = Vec16<T>::load_raw(Vb + size_t(slot_) * DH + lig * EPL);              \
+    spv[u] = sp_row[slot_];                                                       \
+  }
+  if (begin < end) { ATTEND_FETCH(begin) }
   for (int base = begin; base < end; base += G * U) {
-    float kf[U][EPL], vf[U][EPL], logit[U];
+    float logit[U];
     bool valid[U];
+    typename Vec16<T>::Raw kc[U], vc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int slot = base + u * G + grp;
       const bool inr = slot < end;
       const bool ins = inr && slot == s_ins;
-      valid[u] = false;
       if (ins) {
-        // the current token: take k, v from the step inputs and store them in the cache (its slot is
-        // marked occupied by the release kernel, which also knows the reserved slot)
-        const T *kn = static_cast<const T *>(a.k_new) + size_t(bh) * DH + lig * EPL;
-        const T *vn = static_cast<const T *>(a.v_new) + size_t(bh) * DH + lig * EPL;
-        Vec16<T>::load(kn, kf[u]);
-        Vec16<T>::load(vn, vf[u]);
-        Vec16<T>::copy(const_cast<T *>(Kb) + size_t(slot) * DH + lig * EPL, kn);
-        Vec16<T>::copy(const_cast<T *>(Vb) + size_t(slot) * DH + lig * EPL, vn);
-        valid[u] = true;
-      } else if (inr) {
-        Vec16<T>::load(Kb + size_t(slot) * DH + lig * EPL, kf[u]);
-        Vec16<T>::load(Vb + size_t(slot) * DH + lig * EPL, vf[u]);
-        valid[u] = sp_row[slot] >= 0;
+        Vec16<T>::store_raw(const_cast<T *>(Kb) + size_t(slot) * DH + lig * EPL, kn);
+        Vec16<T>::store_raw(const_cast<T *>(Vb) + size_t(slot) * DH + lig * EPL, vn);
       }
+      kc[u] = ins ? kn : kr[u];
+      vc[u] = ins ? vn : vr[u];
+      valid[u] = inr && (ins || spv[u] >= 0);
     }
+    if (base + G * U < end) { ATTEND_FETCH(base + G * U) }
     float mb = m;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float dot = 0.f;
       if (valid[u]) {
+        float kf[EPL];
+        Vec16<T>::values(kc[u], kf);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], kf[u][e], dot);
+        for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
       }
 #pragma unroll
       for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
@@ -109,12 +120,16 @@ __global__ __launch_bounds__(64 * WAVES) void attend_kernel(const AttendArgs a) 
       if (valid[u]) {
         const float p = exp2f(logit[u] - mb);
         l += p;
+        float vf[EPL];
+        Vec16<T>::values(vc[u], vf);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[u][e], acc[e]);
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
       }
     }
     m = mb;
   }
+
+#undef ATTEND_FETCH
 
   // ---- merge the G lane groups of this workgroup ----
   __shared__ float s_m[G], s_l[G];

@@ -34,6 +34,7 @@ __global__ __launch_bounds__(256) void ctrl_input_mfma_kernel(const bf16_t *__re
                                                               const bf16_t *__restrict__ x,
                                                               float *__restrict__ part, int D, int G3, int ntok,
                                                               int per_seq, int seq_rows, int kslice) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j0 = blockIdx.x * 16, t0 = blockIdx.y * 16;
   const int kw = kslice / 4;                       // k-range of one wave, a multiple of 32
@@ -228,6 +229,7 @@ __device__ inline void rows_times_vec(const T *W, int row0, float x0, float x1, 
 
 template <typename T>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void ctrl_cell128_kernel(const CellArgs a) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   constexpr int DP = 128;
   __shared__ float h[DP];        // z_{i-1}, then z_i
   __shared__ float t_in[DP];     // p_i + z_i
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // One workgroup per sequence; loops over `nsteps` consecutive tokens starting at position pos0.
 template <typename T>
 __global__ __launch_bounds__(512) void ctrl_cell_kernel(const CellArgs a) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   extern __shared__ float smem[];
   const int dp = a.dp;
   float *h = smem;            // [dp]   z_{i-1}, then z_i
@@ -369,6 +372,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const float *__restrict__ 
                                                       const float *__restrict__ out_b,
                                                       float *__restrict__ score, int n, int N_max, int dp,
                                                       float pos_scale) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   const int b = blockIdx.y;
   const int i = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int lig = threadIdx.x & 15;

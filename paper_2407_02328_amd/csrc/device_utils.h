@@ -23,6 +23,13 @@ struct Vec16<float> {
   __device__ static inline void copy(float *dst, const float *src) {
     *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
   }
+  // the same in two steps: the 16 bytes as they are, and their values
+  typedef float4 Raw;
+  __device__ static inline Raw load_raw(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+  __device__ static inline void store_raw(float *p, const Raw &v) { *reinterpret_cast<float4 *>(p) = v; }
+  __device__ static inline void values(const Raw &v, float (&f)[4]) {
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
 };
 
 template <>
@@ -37,6 +44,15 @@ struct Vec16<bf16_t> {
   }
   __device__ static inline void copy(bf16_t *dst, const bf16_t *src) {
     *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+  }
+  typedef uint4 Raw;
+  __device__ static inline Raw load_raw(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+  __device__ static inline void store_raw(bf16_t *p, const Raw &v) { *reinterpret_cast<uint4 *>(p) = v; }
+  __device__ static inline void values(const Raw &v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
   }
 };
 

@@ -117,6 +117,7 @@ __global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict_
                                                       int32_t *__restrict__ map_out,
                                                       int32_t *__restrict__ rel_out, int rows, int K,
                                                       int H, int N_max, int n, int x, int R1) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;                      // whole wave leaves together
   const int lane = threadIdx.x & 63;
@@ -272,6 +273,7 @@ struct RebuildSelectArgs {
 };
 
 __global__ __launch_bounds__(1024) void rebuild_select_kernel(const RebuildSelectArgs a) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   extern __shared__ uint64_t smem64[];
   uint64_t *s_keys = smem64;                                    // [max(r,1)]
   uint64_t *s_ctl = s_keys + max(a.r, 1);                       // [4]
