@@ -41,10 +41,10 @@ def algorithmic_work(w):
     return dict(attend_bytes=att_bytes, gemm_flops=gemm_flops, ctrl_flops=ctrl_flops, select_bytes=sel_bytes)
 
 
-def recorded_traffic(w):
+def recorded_traffic(w, path_name="decode_step"):
     """HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE / WRITE_SIZE scaled by a copy
     kernel of known size); recorded in profiles/ because bench.py cannot run the profiler on itself."""
-    path = os.path.join(ROOT, "profiles", f"decode_step_{w.name}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{path_name}_{w.name}_hbm_traffic.txt")
     out = {}
     if os.path.exists(path):
         for line in open(path):
@@ -243,9 +243,11 @@ def forward_line(w, args):
     es, BH, Hd, M = 2, w.B * w.H, w.H * w.d, w.B * (w.R + 1)
     att_bytes = 2 * BH * w.K * w.d * es + BH * w.K * 4 + 2 * M * Hd * es
     qkv_flops, o_flops = 2.0 * M * w.D * 3 * Hd, 2.0 * M * Hd * w.D
+    traffic = recorded_traffic(w, "forward_step")      # per projection: tile kernel + skinny kernel together
     roof = lambda name, work, t, peak, unit, scale, bound: dict(
         kernel=name, bound=bound, achieved=round(work / (t * 1e-6) / scale, 1) if t else 0.0, peak=peak, unit=unit,
-        frac=round(work / (t * 1e-6) / scale / peak, 4) if t else 0.0, traffic=None, us_per_launch=round(t, 2))
+        frac=round(work / (t * 1e-6) / scale / peak, 4) if t else 0.0, traffic=traffic.get(name.split("+")[0]),
+        us_per_launch=round(t, 2))
     roofs = {"roofline_fwd_attend": roof("fwd_attend", att_bytes, us["fwd_attend"], HBM_PEAK_GBS, "GB/s", 1e9, "hbm"),
              # each projection = the tile kernel (rebuilt tokens' rows) + the skinny kernel (current tokens' rows)
              "roofline_fwd_qkv": roof("fwd_qkv+fwd_qkv_cur", qkv_flops, us["fwd_qkv"] + us["fwd_qkv_cur"],

@@ -111,8 +111,75 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kgrp = wave / (WM * WN), wm = (wave / WN) % WM, wn = wave % WN;
 
-  // where every row of the output tile goes: looked up now, used after the k-loop
   const int Hd = a.H * a.d;
+  const int lchunk = tid % CH, lrow = tid / CH;   // rows lrow + RPP*i
+  const bool b_on = BN >= RPP || lrow < BN;       // narrow tiles: only some threads load W rows
+  const u32x4 *gA[NA], *gB[NB];
+  const bf16_t *X = static_cast<const bf16_t *>(a.X);
+  const bf16_t *W = MODE == MODE_QKV ? (n0 < Hd ? static_cast<const bf16_t *>(a.Wq) + size_t(n0) * a.D
+                                                  : static_cast<const bf16_t *>(a.W) + size_t(n0 - Hd) * a.D)
+                                     : static_cast<const bf16_t *>(a.W) + size_t(n0) * a.D;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int nrow = b_on ? lrow + RPP * i : 0;
+    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(nrow) * a.D) + lchunk;
+  }
+  const int nk = a.D / BK;
+  u32x4 ra[NS][NA], rb[NS][NB];
+#define SA(ST) (smem + (ST) * STAGE)
+#define SB(ST) (smem + (ST) * STAGE + BM * CH)
+#define GLOAD_A(SET, KS) { _Pragma("unroll") for (int i = 0; i < NA; ++i) ra[SET][i] = gA[i][(KS) * CH]; }
+#define GLOAD_B(SET, KS) { _Pragma("unroll") for (int i = 0; i < NB; ++i) rb[SET][i] = gB[i][(KS) * CH]; }
+#define GLOAD(SET, KS) { GLOAD_A(SET, KS) GLOAD_B(SET, KS) }
+#define LSTORE(SET, ST)                                                                  \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                       \
+      SA(ST)[swz(lrow + RPP * i, lchunk)] = ra[SET][i];                                  \
+    if (b_on) {                                                                          \
+      _Pragma("unroll") for (int i = 0; i < NB; ++i)                                     \
+        SB(ST)[swz(lrow + RPP * i, lchunk)] = rb[SET][i];                                \
+    }                                                                                    \
+  }
+#define FRAGS(BUF, ST, KK)                                                               \
+  {                                                                                      \
+    const int ch_ = (KK) * 2 + (lane >> 5);                                              \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
+      const u32x4 va_ = SA(ST)[swz((wm * TM + i) * 32 + (lane & 31), ch_)];              \
+      fa[BUF][i] = *reinterpret_cast<const bf16x8 *>(&va_);                              \
+    }                                                                                    \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
+      const u32x4 vb_ = SB(ST)[swz((wn * TN + j) * 32 + (lane & 31), ch_)];              \
+      fb[BUF][j] = *reinterpret_cast<const bf16x8 *>(&vb_);                              \
+    }                                                                                    \
+  }
+#define MFMAS(BUF)                                                                       \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                       \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[BUF][i], fb[BUF][j], acc[i][j], 0, 0, 0);
+
+  // prologue: tiles 0 .. LEAD-1 to LDS, tiles LEAD .. LEAD+NS-1 into the register sets (set of tile t = t % NS).
+  // Everything read from memory here is issued before anything is waited for: the W rows of the first NS tiles
+  // (they depend on nothing), the positions of the gathered rows, the A rows, the destination slots.  (A read of
+  // what the previous kernel wrote takes a microsecond or two; one after the other they cost a tenth of the launch.)
+#pragma unroll
+  for (int t = 0; t < NS; ++t) {
+    if (t < nk) { GLOAD_B(t, t) }
+  }
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int mi = m0 + lrow + RPP * i;
+    size_t src_row = 0;
+    if (mi < a.M) {
+      const int b = mi / a.r, j = mi - b * a.r;
+      src_row = a.a_gather ? row_by_position(a, b, j) : size_t(b) * a.xrps + j;
+    }
+    gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
+  }
+#pragma unroll
+  for (int t = 0; t < NS; ++t) {
+    if (t < nk) { GLOAD_A(t, t) }
+  }
+  // where every row of the output tile goes: looked up now, used after the k-loop
   const int sw = MODE == MODE_OPROJ ? BN : a.d;   // width of a contiguous piece of an output row
   const int nh = BN / sw > 0 ? BN / sw : 1;       // pieces in one tile row
   const int section = MODE == MODE_OPROJ ? 0 : n0 / Hd;   // REBUILD: K, V; QKV: Q, K, V (a tile lies in one)
@@ -148,74 +215,10 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
       s_res[row] = ro;
     }
   }
-  const int lchunk = tid % CH, lrow = tid / CH;   // rows lrow + RPP*i
-  const bool b_on = BN >= RPP || lrow < BN;       // narrow tiles: only some threads load W rows
-  const u32x4 *gA[NA], *gB[NB];
-  const bf16_t *X = static_cast<const bf16_t *>(a.X);
-  const bf16_t *W = MODE == MODE_QKV ? (n0 < Hd ? static_cast<const bf16_t *>(a.Wq) + size_t(n0) * a.D
-                                                  : static_cast<const bf16_t *>(a.W) + size_t(n0 - Hd) * a.D)
-                                     : static_cast<const bf16_t *>(a.W) + size_t(n0) * a.D;
-#pragma unroll
-  for (int i = 0; i < NA; ++i) {
-    const int mi = m0 + lrow + RPP * i;
-    size_t src_row = 0;
-    if (mi < a.M) {
-      const int b = mi / a.r, j = mi - b * a.r;
-      src_row = a.a_gather ? row_by_position(a, b, j) : size_t(b) * a.xrps + j;
-    }
-    gA[i] = reinterpret_cast<const u32x4 *>(X + src_row * a.D) + lchunk;
-  }
-#pragma unroll
-  for (int i = 0; i < NB; ++i) {
-    const int nrow = b_on ? lrow + RPP * i : 0;
-    gB[i] = reinterpret_cast<const u32x4 *>(W + size_t(nrow) * a.D) + lchunk;
-  }
-  const int nk = a.D / BK;
-  u32x4 ra[NS][NA], rb[NS][NB];
-#define SA(ST) (smem + (ST) * STAGE)
-#define SB(ST) (smem + (ST) * STAGE + BM * CH)
-#define GLOAD(SET, KS)                                                                   \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i) ra[SET][i] = gA[i][(KS) * CH];        \
-    _Pragma("unroll") for (int i = 0; i < NB; ++i) rb[SET][i] = gB[i][(KS) * CH];        \
-  }
-#define LSTORE(SET, ST)                                                                  \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                       \
-      SA(ST)[swz(lrow + RPP * i, lchunk)] = ra[SET][i];                                  \
-    if (b_on) {                                                                          \
-      _Pragma("unroll") for (int i = 0; i < NB; ++i)                                     \
-        SB(ST)[swz(lrow + RPP * i, lchunk)] = rb[SET][i];                                \
-    }                                                                                    \
-  }
-#define FRAGS(BUF, ST, KK)                                                               \
-  {                                                                                      \
-    const int ch_ = (KK) * 2 + (lane >> 5);                                              \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
-      const u32x4 va_ = SA(ST)[swz((wm * TM + i) * 32 + (lane & 31), ch_)];              \
-      fa[BUF][i] = *reinterpret_cast<const bf16x8 *>(&va_);                              \
-    }                                                                                    \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
-      const u32x4 vb_ = SB(ST)[swz((wn * TN + j) * 32 + (lane & 31), ch_)];              \
-      fb[BUF][j] = *reinterpret_cast<const bf16x8 *>(&vb_);                              \
-    }                                                                                    \
-  }
-#define MFMAS(BUF)                                                                       \
-  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                       \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[BUF][i], fb[BUF][j], acc[i][j], 0, 0, 0);
-
-  // prologue: tiles 0 .. LEAD-1 to LDS, tiles LEAD .. LEAD+NS-1 into the register sets (set of tile t = t % NS)
 #pragma unroll
   for (int t = 0; t < LEAD; ++t) {
-    if (t < nk) {
-      GLOAD(t % NS, t)
-      LSTORE(t % NS, t)
-    }
-  }
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    if (s + LEAD < nk) { GLOAD((s + LEAD) % NS, s + LEAD) }
+    if (t < nk) { LSTORE(t % NS, t) }
+    if (t + NS < nk) { GLOAD(t % NS, t + NS) }   // the set just stored takes the tile NS further on
   }
   __syncthreads();
 
@@ -273,6 +276,8 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
 #undef ALWAYS
 #undef GUARDED
 #undef GLOAD
+#undef GLOAD_A
+#undef GLOAD_B
 #undef LSTORE
 #undef FRAGS
 #undef MFMAS
