@@ -116,7 +116,7 @@ class ScopedTimer {
   } while (0)
 
 // Launchers.  Each validates nothing (the API did) and returns the launch status.  `st` is the
-// stream to launch on; `src` / `dst` are buffer indices of the double-buffered arrays.
+// stream to launch on; `src` / `dst` are indices into the rings of per-step lists.
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
                          const void *v_new, float *out);
 hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int ntok, int per_seq,

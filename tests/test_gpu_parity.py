@@ -383,3 +383,14 @@ def test_forward_step_matches_the_forward_oracle(name, kw):
     worst, mean = h.forward_lockstep(w, w.T)
     print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
     assert mean < 2.0 ** -10
+
+
+def test_forward_step_llama7b_layer_full_size():
+    """The rebuild forward at the benchmark shape and in the launch configuration `bench.py --forward` times
+    (B16 H32 d128 D4096 K512 R32, prompt 1024: 33 rows per sequence, 512 + 16 rows per projection), two
+    layers: init plus three steps, every selection and every output row against the forward oracle."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(L=2, T=4)
+    worst, mean = h.forward_lockstep(w, 3)
+    print(f"forward llama7b_layer x2: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    assert mean < 2.0 ** -10
