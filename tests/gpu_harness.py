@@ -205,9 +205,12 @@ def forward_lockstep(w: Workload, steps: int, override=None):
         adore.forward_step(wq, wo, Ed, ov, rows, slot_map, released, rebuilt)
         adore.get_state(scores=state["scores"])
         torch.cuda.synchronize()
-        score_g = state["scores"][:, n].cpu().numpy()
+        sc = state["scores"]
+        score_g = sc[:, :n + 1].cpu().numpy() if w.rescore else sc[:, n].cpu().numpy()
         x_o, rows_o, map_o, rel_o, rb_o, own = orc.forward_step(E, score_override=score_g)
-        if override is None:
+        if w.rescore:     # every score of this step: the oracle's own values against the GPU's, then adopted
+            assert np.abs(orc.own_scores - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        elif override is None:
             assert np.abs(own - score_g.astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
         assert np.array_equal(slot_map.cpu().numpy(), map_o), f"slot map at n={n}"
         assert np.array_equal(released.cpu().numpy(), rel_o), f"released at n={n}"

@@ -126,6 +126,16 @@ def test_calls_out_of_order_are_state_errors(lib):
         assert lib.adore_init_cache(h, None, FAKE, FAKE, FAKE, None, 4) == -1
         assert lib.adore_set_state(h, None, None, None, None, None, 5) == -1
         assert lib.adore_set_state(h, FAKE, None, None, None, None, 0) == -1
+        # the rebuild forward: null arguments, a context not initialised for it, a configuration without
+        # a forward path (fp32 storage) -- all caught on the host
+        from paper_2407_02328_amd.binding import AdoreForwardWeights
+        fw = AdoreForwardWeights(FAKE, FAKE)
+        assert lib.adore_forward_step(h, None, FAKE, None, FAKE, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), None, None, FAKE, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, None, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(AdoreForwardWeights(None, FAKE)), FAKE, None, FAKE, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, FAKE, None, None, None) == -2
+        assert lib.adore_init_cache(h, FAKE, FAKE, None, FAKE, None, 4) == -3     # tiny is fp32: no forward path
     finally:
         assert lib.adore_destroy(h) == 0
     assert lib.adore_destroy(None) == -1

@@ -394,3 +394,23 @@ def test_forward_step_llama7b_layer_full_size():
     worst, mean = h.forward_lockstep(w, 3)
     print(f"forward llama7b_layer x2: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
     assert mean < 2.0 ** -10
+
+
+def test_forward_step_with_rescoring_controller():
+    """The rebuild forward with the controller that rates every token again at every step (relative
+    position): promotions and demotions change which tokens are rebuilt from step to step."""
+    h = _harness()
+    w = Workload("fwd_rescore", L=2, B=2, H=4, d=64, D=256, K=48, R=6, S=60, T=24, dtype="bf16", dprime=32,
+                 w_std=0.06, rescore=True)
+    worst, mean = h.forward_lockstep(w, w.T)
+    assert mean < 2.0 ** -10
+
+
+def test_forward_step_with_injected_ties():
+    """Scores given from outside with many equal values: ties go to the lower position in the forward too."""
+    h = _harness()
+    w = Workload("fwd_ties", L=1, B=2, H=2, d=64, D=128, K=40, R=5, S=50, T=16, dtype="bf16", dprime=32, w_std=0.06)
+    rng = np.random.default_rng(7)
+    override = rng.integers(0, 4, size=(w.B, w.N_max)).astype(np.float32) / 4.0
+    worst, mean = h.forward_lockstep(w, w.T, override=override)
+    assert mean < 2.0 ** -10
