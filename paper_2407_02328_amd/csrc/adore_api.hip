@@ -207,12 +207,18 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->fwd_x = base + l.fwd_x;
   ctx->forward = false;
   ctx->r_pending = 0;
+  ctx->ins_stride = 1;
+  ctx->ins_off = 0;
+  ctx->ins_from_list = false;
+  ctx->rode = false;
   ctx->inited = false;
   ctx->n = 0;
   ctx->occ = 0;
   ctx->cur = 0;
   const char *no = getenv("ADORE_NO_OVERLAP");
   ctx->overlap = !(no && atoi(no) != 0);
+  const char *nr = getenv("ADORE_NO_RIDE");
+  ctx->ride = ctx->overlap && !(nr && atoi(nr) != 0);
   ctx->side = ctx->stream;
   ctx->ev_att = ctx->ev_join = nullptr;
   ctx->steps_done = 0;
@@ -293,6 +299,10 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   ctx->inited = true;
   ctx->forward = forward;
   ctx->r_pending = r0;
+  ctx->ins_stride = 1;
+  ctx->ins_off = 0;
+  ctx->ins_from_list = false;
+  ctx->rode = false;
   reset_step(ctx);
   return ADORE_OK;
 }
@@ -321,6 +331,13 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
   const int src = ctx->cur, dst = (ctx->cur + 1) % kRing;
   hipStream_t st = ctx->side;
+  if (ctx->rode && ctx->overlap) {
+    // the steps before this one ran their selections on the caller's stream: the side stream catches up once
+    ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
+    ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
+    ctx->steps_done = 1;   // the next regular wait is due at a multiple of kSyncEvery, covered by this one until then
+  }
+  ctx->rode = false;
 
   // the controller touches only its own state and the score array: it may run as early as the
   // previous step's selections are done
@@ -350,8 +367,47 @@ int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
     ctx->n++;
     ctx->steps_done++;
     ctx->cur = (ctx->cur + 1) % kRing;
+    ctx->ins_stride = 1;       // this step's per-sequence choice wrote insert_slot
+    ctx->ins_off = 0;
+    ctx->ins_from_list = false;
     reset_step(ctx);
   }
+  return ADORE_OK;
+}
+
+// The whole step of one layer with the two selections riding in the attention launch (static score mode).
+// Neither selection of step n looks at the current token's score, so only the controller stays on the side
+// stream; what it writes (the score of token n) is first needed by the selections of step n+1, which is
+// what the one wait at the top is for.  No other event, and no kernel of the selections runs next to the GEMM.
+int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new, const void *hidden_store,
+                   const void *x_n, const float *score_override, float *out, int32_t *slot_map) {
+  const adore_config &c = ctx->cfg;
+  const int m = c.cache_slots - c.rebuild_budget - 1;
+  const int o = ctx->occ + 1;
+  const int x = o > m ? o - m : 0;
+  const int kept = o - x;
+  const int pool = ctx->n + 1 - kept;
+  const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
+  const int dst = (ctx->cur + 1) % kRing;
+  ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));   // the controller of the step before
+  int ksplit = 1;
+  ADORE_TRY(launch_ctrl_input(ctx, ctx->side, x_n, c.batch, 1, 1, &ksplit));
+  ADORE_TRY(launch_ctrl_cell(ctx, ctx->side, 1, ctx->n, score_override, 1, ksplit));
+  ADORE_TRY(hipEventRecord(ctx->ev_join, ctx->side));
+  RidingSelections sel;
+  sel.dst = dst; sel.x = x; sel.r = r;
+  sel.map_out = slot_map; sel.rel_out = nullptr; sel.rb_out = nullptr;
+  ADORE_TRY(launch_attend(ctx, 0, q, k_new, v_new, out, &sel));
+  ADORE_TRY(launch_rebuild_gemm(ctx, 0, hidden_store, dst, r, ctx->slot_pos[dst], slot_map));
+  ctx->occ = kept + r;
+  ctx->n++;
+  ctx->steps_done++;
+  ctx->cur = dst;
+  ctx->ins_stride = c.rebuild_budget + 1;   // the slot behind the rebuilt tokens' slots in the free list
+  ctx->ins_off = r;
+  ctx->ins_from_list = true;
+  ctx->rode = true;
+  reset_step(ctx);
   return ADORE_OK;
 }
 
@@ -389,6 +445,12 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
   if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
+  // the riding selections keep a sequence's scores and ranking keys in LDS (12 bytes per position)
+  const bool fits_lds = size_t(ctx->cfg.max_positions) * 12 + size_t(ctx->cfg.cache_slots) * 4 <= 56 * 1024;
+  if (ctx->ride && ctx->cfg.score_mode == ADORE_SCORE_STATIC && ctx->cfg.cache_slots <= kMaxSlots && fits_lds) {
+    if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
+    return do_ridden_step(ctx, q, k_new, v_new, hidden_store, x_n, score_override, out, slot_map);
+  }
   // The selections do not depend on this step's attention: enqueue them first so that they start
   // while the previous step's GEMM is still running.
   int rc = do_schedule(ctx, x_n, score_override, slot_map, nullptr, nullptr);
@@ -462,6 +524,7 @@ int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, 
   const size_t BH = size_t(c.batch) * c.heads;
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
   if (step) *step = ctx->n;
+  if (ctx->overlap && ctx->side_ready) ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));   // the controller's last score
   if (slot_pos)
     ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos[ctx->cur], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
                              ctx->stream));
@@ -521,6 +584,10 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   ctx->n = step;
   ctx->occ = occ;
   ctx->inited = true;
+  ctx->ins_stride = 1;
+  ctx->ins_off = 0;
+  ctx->ins_from_list = false;
+  ctx->rode = false;
   reset_step(ctx);
   return ADORE_OK;
 }

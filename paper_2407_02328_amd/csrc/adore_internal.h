@@ -68,6 +68,14 @@ struct adore_ctx {
   bool inited;
   bool forward;              // initialised for the rebuild forward (adore_forward_step), not for attend/schedule/rebuild
   int32_t r_pending;         // forward: tokens chosen by the previous step, rebuilt by the next
+  // where the slot reserved for the next token of (b,h) is found: insert_slot[cur][b*H + h] (stride 1, offset 0)
+  // after an init, a set_state or a step through the stand-alone selection kernels; after a step whose
+  // selections rode in the attention launch it is the entry behind the rebuilt tokens' slots in
+  // free_list[cur][(b*H + h) * (R+1) + r]
+  int32_t ins_stride, ins_off;
+  bool ins_from_list;
+  bool ride;                 // decode_step lets the selections ride in the attention launch when it can
+  bool rode;                 // the last step did
   int32_t cur;               // ring index valid for the next attention
   int32_t steps_done;        // steps since the last init / set_state
   int32_t n;                 // position of the current / next token
@@ -90,6 +98,11 @@ struct adore_ctx {
 namespace adore {
 
 inline size_t elem_size(const adore_config &c) { return c.dtype == ADORE_BF16 ? 2 : 4; }
+
+// The array that holds the reserved slots of ring copy `idx` (see adore_ctx::ins_stride).
+inline const int32_t *reserved_slots(const adore_ctx *ctx, int idx) {
+  return ctx->ins_from_list ? ctx->free_list[idx] : ctx->insert_slot[idx];
+}
 
 // Per-kernel timing.  When timing is on, the kernel is launched with hipExtLaunchKernelGGL, which ties
 // the two events to the dispatch itself (its begin and end time stamps), so the elapsed time is the
@@ -117,8 +130,14 @@ class ScopedTimer {
 
 // Launchers.  Each validates nothing (the API did) and returns the launch status.  `st` is the
 // stream to launch on; `src` / `dst` are indices into the rings of per-step lists.
+// The selections of a step when they ride in the attention launch instead of running as kernels of their own.
+struct RidingSelections {
+  int dst;                 // ring copy they write
+  int x, r;                // rows to release per (b,h), tokens to rebuild per sequence
+  int32_t *map_out, *rel_out, *rb_out;   // the caller's copies, or null
+};
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
-                         const void *v_new, float *out);
+                         const void *v_new, float *out, const RidingSelections *sel = nullptr);
 hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int ntok, int per_seq,
                              int seq_rows, int *ksplit_out);
 hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0,
@@ -129,7 +148,10 @@ hipError_t launch_release(adore_ctx *ctx, hipStream_t st, int src, int dst, int 
                           int32_t *rel_out);
 hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r, int32_t *map_out,
                                  int32_t *rb_out);
-hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r);
+// map_dst / map_out: null, or the slot map (ring copy and the caller's) into which the kernel enters the rebuilt
+// tokens' positions itself (when the per-sequence choice did not do it)
+hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r,
+                               int32_t *map_dst = nullptr, int32_t *map_out = nullptr);
 hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep, int r0);
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);

@@ -12,22 +12,79 @@
 // whole L2 and costs far more than the extra launch).  When there are enough
 // rows, one workgroup of up to 16 waves takes a whole row and no merge kernel
 // runs.  Softmax runs online in fp32, base 2.
-#include "device_utils.h"
+#include "select_device.h"
 
 namespace adore {
 
 namespace {
 
+// The step's two selections as extra workgroups of the attention launch (static score mode: neither selection
+// of step n looks at the current token's score, so they depend on nothing this launch computes, and nothing in
+// this launch depends on them).  Per sequence: rel_wgs workgroups release heads 1 .. H-1 (one wave per head),
+// one more releases head 0 and then chooses the tokens to rebuild from the positions head 0 keeps.
+// The chosen positions are entered into the slot maps by the kernel that writes their rows.
+struct SchedArgs {
+  int kpl, rel_wgs;                 // keys per lane of a row (K / 64 rounded up to 2, 4, 8, 16); 0 workgroups = off
+  const int32_t *slot_src;          // [B*H][K]
+  int32_t *slot_dst;                // [B*H][K]
+  const float *score;               // [B][N_max]
+  int32_t *free_list;               // [B*H][R1]
+  int32_t *released_pos, *map_out, *rel_out;
+  int H, K, N_max, n, x, R1;
+  RebuildSelectArgs sel;
+};
+
 struct AttendArgs {
   const void *q, *k_new, *v_new;   // [B*H][d]
   void *Kc, *Vc;                   // [B*H][K][d] of this layer
   const int32_t *slot_pos;         // [B*H][K]
-  const int32_t *insert_slot;      // [B*H]
+  const int32_t *insert_slot;      // the reserved slot of row bh is insert_slot[bh * ins_stride + ins_off]
+  int ins_stride, ins_off;
+  int n_att;                       // attention workgroups; the ones behind them carry the selections
+  SchedArgs s;
   float *part;                     // [B*H][nsplit][d+2]
   float *out;                      // [B*H][d]
   int K, chunk, nsplit;
   float scale_log2;                // log2(e) / sqrt(d)
 };
+
+// Dynamic LDS of a workgroup in this role: [scores of the sequence, n + 1 floats][head 0's row, K ints][choice].
+// The scores are copied once and the rows are read at the same time, so that afterwards the ranking keys come
+// from LDS: under the attention's traffic every dependent trip to memory costs five to seven microseconds.
+template <int WAVES, int KPL>
+__device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn) {
+  const SchedArgs &s = a.s;
+  const int per_seq = s.rel_wgs + 1;
+  const int b = e / per_seq, part = e - b * per_seq;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  __builtin_amdgcn_s_setprio(3);   // few waves with a long chain of dependent steps: they go first on their SIMD
+  float *s_score = reinterpret_cast<float *>(dyn);
+  const int h = part < s.rel_wgs ? 1 + part * WAVES + wave : 0;
+  const bool releases = part < s.rel_wgs ? h < s.H : wave == 0;   // whole waves
+  const int row = b * s.H + (h < s.H ? h : 0);
+  const int s_ins = a.insert_slot[size_t(row) * a.ins_stride + a.ins_off];
+  int raw[KPL];
+  if (releases) release_fetch<KPL>(row, s.slot_src, s.K, raw);
+  const float *sc = s.score + size_t(b) * s.N_max;
+  for (int i = tid; i <= s.n; i += 64 * WAVES) s_score[i] = sc[i];
+  __syncthreads();
+  if (part < s.rel_wgs) {
+    if (releases)
+      release_row<KPL>(row, s_ins, s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
+                       s.rel_out, s.K, s.n, s.x, s.R1, nullptr, raw);
+    return;
+  }
+  int32_t *row_copy = reinterpret_cast<int32_t *>(dyn + (s.n + 2) / 2);   // head 0's positions after the release
+  uint64_t *choice = dyn + (s.n + 2) / 2 + (s.K + 1) / 2;
+  if (wave == 0) {
+    release_row<KPL>(row, s_ins, s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
+                     s.rel_out, s.K, s.n, s.x, s.R1, row_copy, raw);
+  } else {
+    choice_fill_keys(s_score, s.n, choice, tid - 64, 64 * (WAVES - 1));   // the other waves meanwhile
+  }
+  __syncthreads();
+  choice_from_keys(s.sel, b, row_copy, choice);
+}
 
 template <typename T, int DH, int U, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs a) {
@@ -37,6 +94,17 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
   constexpr int G = WAVES * RPW;        // lane groups (rows in flight) per workgroup
   static_assert(LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must be a power-of-two lane group");
 
+  if (int(blockIdx.x) >= a.n_att) {   // uniform over the workgroup
+    extern __shared__ uint64_t dyn_smem[];
+    const int e = blockIdx.x - a.n_att;
+    switch (a.s.kpl) {
+      case 2: selections_role<WAVES, 2>(a, e, dyn_smem); break;
+      case 4: selections_role<WAVES, 4>(a, e, dyn_smem); break;
+      case 8: selections_role<WAVES, 8>(a, e, dyn_smem); break;
+      default: selections_role<WAVES, 16>(a, e, dyn_smem); break;
+    }
+    return;
+  }
   const int bh = blockIdx.x / a.nsplit;
   const int sp = blockIdx.x - bh * a.nsplit;
   const int tid = threadIdx.x;
@@ -47,7 +115,7 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
   const T *Kb = static_cast<const T *>(a.Kc) + size_t(bh) * a.K * DH;
   const T *Vb = static_cast<const T *>(a.Vc) + size_t(bh) * a.K * DH;
   const int32_t *sp_row = a.slot_pos + size_t(bh) * a.K;
-  const int s_ins = a.insert_slot[bh];
+  const int s_ins = a.insert_slot[size_t(bh) * a.ins_stride + a.ins_off];
 
   float qf[EPL];
   Vec16<T>::load(static_cast<const T *>(a.q) + size_t(bh) * DH + lig * EPL, qf);
@@ -182,16 +250,16 @@ __global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, f
 }
 
 template <typename T, int DH>
-hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
+hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows, int waves, int extra_wgs, size_t dyn_lds) {
   {
     ScopedTimer t(ctx, ADORE_KERNEL_ATTEND, ctx->stream);
-    const dim3 grid(rows * a.nsplit);
-    if (ctx->attend_waves == 16)
-      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 16>), grid, dim3(1024), 0, ctx->stream, a);
-    else if (ctx->attend_waves == 8)
-      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 8>), grid, dim3(512), 0, ctx->stream, a);
+    const dim3 grid(rows * a.nsplit + extra_wgs);
+    if (waves == 16)
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 16>), grid, dim3(1024), dyn_lds, ctx->stream, a);
+    else if (waves == 8)
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 8>), grid, dim3(512), dyn_lds, ctx->stream, a);
     else
-      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 4>), grid, dim3(256), 0, ctx->stream, a);
+      ADORE_LAUNCH(t, (attend_kernel<T, DH, 4, 4>), grid, dim3(256), dyn_lds, ctx->stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -206,8 +274,9 @@ hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows) {
 
 }  // namespace
 
+// sel: null, or the selections of this step to carry in the same launch (see SchedArgs).
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new,
-                         float *out) {
+                         float *out, const RidingSelections *sel) {
   const adore_config &c = ctx->cfg;
   const size_t layer_bytes = size_t(c.batch) * c.heads * c.cache_slots * c.head_dim * elem_size(c);
   AttendArgs a;
@@ -215,16 +284,45 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
   a.slot_pos = ctx->slot_pos[ctx->cur];
-  a.insert_slot = ctx->insert_slot[ctx->cur];
+  a.insert_slot = reserved_slots(ctx, ctx->cur);
+  a.ins_stride = ctx->ins_stride; a.ins_off = ctx->ins_off;
   a.part = ctx->att_part;
   a.out = out;
   a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
   const int rows = c.batch * c.heads;
-  if (c.dtype == ADORE_BF16) {
-    return c.head_dim == 128 ? launch_typed<bf16_t, 128>(ctx, a, rows) : launch_typed<bf16_t, 64>(ctx, a, rows);
+  a.n_att = rows * a.nsplit;
+  a.s.rel_wgs = 0;
+  int waves = ctx->attend_waves, extra = 0;
+  size_t dyn = 0;
+  if (sel) {
+    // 4 waves per workgroup: half of a compute unit's wave slots and registers then stay free, so the extra
+    // workgroups start at once next to the attention's instead of waiting for a round of them to end
+    waves = 4;
+    SchedArgs &s = a.s;
+    s.kpl = c.cache_slots <= 128 ? 2 : c.cache_slots <= 256 ? 4 : c.cache_slots <= 512 ? 8 : 16;
+    s.rel_wgs = (c.heads - 1 + waves - 1) / waves;
+    s.slot_src = ctx->slot_pos[ctx->cur]; s.slot_dst = ctx->slot_pos[sel->dst];
+    s.score = ctx->score; s.free_list = ctx->free_list[sel->dst];
+    s.released_pos = ctx->released_pos; s.map_out = sel->map_out; s.rel_out = sel->rel_out;
+    s.H = c.heads; s.K = c.cache_slots; s.N_max = c.max_positions; s.n = ctx->n; s.x = sel->x;
+    s.R1 = c.rebuild_budget + 1;
+    RebuildSelectArgs &r = s.sel;
+    r.slot_pos = ctx->slot_pos[sel->dst]; r.score = ctx->score; r.free_list = ctx->free_list[sel->dst];
+    r.rebuilt_pos = ctx->rebuilt_pos[sel->dst]; r.insert_slot = nullptr;
+    r.map_out = sel->map_out; r.rb_out = sel->rb_out;
+    r.K = c.cache_slots; r.H = c.heads; r.N_max = c.max_positions; r.n = ctx->n; r.r = sel->r;
+    r.R1 = c.rebuild_budget + 1; r.Rdim = max(c.rebuild_budget, 1);
+    r.words = (c.max_positions + 31) / 32;
+    extra = c.batch * (s.rel_wgs + 1);
+    dyn = size_t((ctx->n + 2) / 2) * 8 + size_t((c.cache_slots + 1) / 2) * 8 + ridden_choice_lds_bytes(sel->r, ctx->n);
   }
-  return c.head_dim == 128 ? launch_typed<float, 128>(ctx, a, rows) : launch_typed<float, 64>(ctx, a, rows);
+  if (c.dtype == ADORE_BF16) {
+    return c.head_dim == 128 ? launch_typed<bf16_t, 128>(ctx, a, rows, waves, extra, dyn)
+                             : launch_typed<bf16_t, 64>(ctx, a, rows, waves, extra, dyn);
+  }
+  return c.head_dim == 128 ? launch_typed<float, 128>(ctx, a, rows, waves, extra, dyn)
+                           : launch_typed<float, 64>(ctx, a, rows, waves, extra, dyn);
 }
 
 }  // namespace adore

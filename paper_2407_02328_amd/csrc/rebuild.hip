@@ -49,6 +49,7 @@ struct GemmArgs {
   const int32_t *rebuilt_pos;  // [B][Rdim]
   const int32_t *free_list;    // [B][H][R1]
   const int32_t *insert_slot;  // [B][H]    QKV: the slot of the current token
+  int32_t *map_dst, *map_out;  // REBUILD: slot maps [B][H][K] that get the rebuilt tokens' positions, or null
   int B, H, d, D, K, N_max, r, R1, Rdim, M, N;   // D = length of the contraction
   int tiles_m, tiles_n;
   // Rows.  The tile kernel takes the rebuilt tokens: row mi = (b, j) = (mi / r, mi % r), rank j of sequence b.
@@ -199,6 +200,11 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
         } else {
           const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + j];
           off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+          if (MODE == MODE_REBUILD && a.map_dst && section == 0) {   // the K half's tiles visit every (token, head)
+            const int pos = a.rebuilt_pos[size_t(b) * a.Rdim + j];
+            a.map_dst[(size_t(b) * a.H + h) * a.K + slot] = pos;
+            if (a.map_out) a.map_out[(size_t(b) * a.H + h) * a.K + slot] = pos;
+          }
         }
       }
     }
@@ -370,6 +376,10 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
     const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
     T *dst = static_cast<T *>(half ? a.Vc : a.Kc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + cc;
     store_elem(dst, s);
+    if (a.map_dst && half == 0 && cc == 0) {
+      a.map_dst[(size_t(b) * a.H + h) * a.K + slot] = pos;
+      if (a.map_out) a.map_out[(size_t(b) * a.H + h) * a.K + slot] = pos;
+    }
   }
 }
 
@@ -514,7 +524,7 @@ void launch_tile(ScopedTimer &t, hipStream_t stream, int pick, GemmArgs &a) {
 
 void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
   const adore_config &c = ctx->cfg;
-  a.Wq = nullptr; a.Out = nullptr; a.Res = nullptr;
+  a.Wq = nullptr; a.Out = nullptr; a.Res = nullptr; a.map_dst = a.map_out = nullptr;
   a.rebuilt_pos = ctx->rebuilt_pos[lists];
   a.free_list = ctx->free_list[lists];
   a.insert_slot = ctx->insert_slot[lists];
@@ -526,7 +536,8 @@ void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
 
 }  // namespace
 
-hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r) {
+hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r,
+                               int32_t *map_dst, int32_t *map_out) {
   const adore_config &c = ctx->cfg;
   if (r <= 0) return hipSuccess;
   const size_t es = elem_size(c);
@@ -538,6 +549,7 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
   a.M = c.batch * r; a.N = 2 * c.heads * c.head_dim;
+  a.map_dst = map_dst; a.map_out = map_out;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM, ctx->stream);
   const int pick = c.dtype == ADORE_BF16 ? pick_tile(a.M, a.N, c.hidden, c.heads * c.head_dim, c.head_dim, false) : -1;
   if (pick >= 0) {

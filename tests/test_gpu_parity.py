@@ -414,3 +414,40 @@ def test_forward_step_with_injected_ties():
     override = rng.integers(0, 4, size=(w.B, w.N_max)).astype(np.float32) / 4.0
     worst, mean = h.forward_lockstep(w, w.T, override=override)
     assert mean < 2.0 ** -10
+
+
+# ---- adore_decode_step: the selections ride in the attention launch --------------------------------
+@pytest.mark.parametrize("name,kw,steps", [
+    ("tiny", None, 40),                                                                        # fp32, d = 64, K = 64
+    ("bf16_k200", dict(L=1, B=3, H=4, d=128, D=512, K=200, R=5, S=260, T=30, dtype="bf16"), 30),  # ragged K, split rows
+    ("bf16_h9", dict(L=1, B=2, H=9, d=64, D=256, K=130, R=12, S=20, T=40, dtype="bf16", dprime=32), 40),  # warm-up from a
+    # short prompt (x = 0, then r < R), 9 heads = one full and one nearly empty release workgroup per sequence
+    ("bf16_k1024", dict(L=1, B=1, H=4, d=128, D=256, K=1024, R=40, S=1100, T=8, dtype="bf16", dprime=32), 8),
+])
+def test_decode_step_call_matches_the_oracle(name, kw, steps):
+    """Every step through adore_decode_step: slot maps, outputs and cache rows against the oracle."""
+    h = _harness()
+    w = workload("tiny") if kw is None else Workload("ds_" + name, **kw)
+    worst, job, _ = h.lockstep(w, steps=steps, check_cache_every=5, whole=lambda t: True)
+    job.adore.close()
+
+
+def test_decode_step_call_mixed_with_fine_grained_calls():
+    """Steps alternate in blocks between adore_decode_step and attend / schedule / rebuild: the reserved slot is
+    handed over correctly in both directions and the side stream catches up when the selections move back to it."""
+    h = _harness()
+    w = Workload("ds_mixed", L=1, B=2, H=4, d=128, D=256, K=96, R=8, S=120, T=36, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=lambda t: (t // 3) % 2 == 0)
+    job.adore.close()
+    rng = np.random.default_rng(11)
+    ties = rng.integers(0, 3, size=(w.B, w.N_max)).astype(np.float32) / 2.0
+    worst, job, _ = h.lockstep(w, steps=20, override=ties, whole=lambda t: t % 2 == 1)
+    job.adore.close()
+
+
+def test_decode_step_call_at_the_benchmark_shape():
+    """llama7b_layer at full size through adore_decode_step, the call bench.py times."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(T=8)
+    worst, job, _ = h.lockstep(w, steps=6, check_cache_every=3, whole=lambda t: True)
+    job.adore.close()
