@@ -40,7 +40,8 @@ struct AttendArgs {
   const int32_t *slot_pos;         // [B*H][K]
   const int32_t *insert_slot;      // the reserved slot of row bh is insert_slot[bh * ins_stride + ins_off]
   int ins_stride, ins_off;
-  int n_att;                       // attention workgroups; the ones behind them carry the selections
+  int n_sel;                       // the first n_sel workgroups carry the selections (they start first: their chain
+                                   // of dependent steps is the longest), the attention's come behind them
   SchedArgs s;
   float *part;                     // [B*H][nsplit][d+2]
   float *out;                      // [B*H][d]
@@ -94,9 +95,9 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
   constexpr int G = WAVES * RPW;        // lane groups (rows in flight) per workgroup
   static_assert(LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must be a power-of-two lane group");
 
-  if (int(blockIdx.x) >= a.n_att) {   // uniform over the workgroup
+  if (int(blockIdx.x) < a.n_sel) {   // uniform over the workgroup
     extern __shared__ uint64_t dyn_smem[];
-    const int e = blockIdx.x - a.n_att;
+    const int e = blockIdx.x;
     switch (a.s.kpl) {
       case 2: selections_role<WAVES, 2>(a, e, dyn_smem); break;
       case 4: selections_role<WAVES, 4>(a, e, dyn_smem); break;
@@ -105,8 +106,9 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
     }
     return;
   }
-  const int bh = blockIdx.x / a.nsplit;
-  const int sp = blockIdx.x - bh * a.nsplit;
+  const int wg = blockIdx.x - a.n_sel;
+  const int bh = wg / a.nsplit;
+  const int sp = wg - bh * a.nsplit;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int grp = (tid >> 6) * RPW + lane / LPR;
@@ -291,7 +293,7 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
   a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
   const int rows = c.batch * c.heads;
-  a.n_att = rows * a.nsplit;
+  a.n_sel = 0;
   a.s.rel_wgs = 0;
   int waves = ctx->attend_waves, extra = 0;
   size_t dyn = 0;
@@ -315,6 +317,7 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
     r.R1 = c.rebuild_budget + 1; r.Rdim = max(c.rebuild_budget, 1);
     r.words = (c.max_positions + 31) / 32;
     extra = c.batch * (s.rel_wgs + 1);
+    a.n_sel = extra;
     dyn = size_t((ctx->n + 2) / 2) * 8 + size_t((c.cache_slots + 1) / 2) * 8 + ridden_choice_lds_bytes(sel->r, ctx->n);
   }
   if (c.dtype == ADORE_BF16) {
