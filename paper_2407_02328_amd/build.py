@@ -8,7 +8,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libadore.so")
 SOURCES = ["adore_api.hip", "attend.hip", "controller.hip", "select.hip", "rebuild.hip", "forward_attend.hip"]
-HEADERS = ["adore_internal.h", "device_utils.h"]
+HEADERS = ["adore_internal.h", "device_utils.h", "select_device.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
