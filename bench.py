@@ -4,7 +4,10 @@
 A "step" is one pass of the whole hot path (insert + sparse attention, controller, release select,
 rebuild select, re-projection GEMM + scatter) for one batch of B sequences of one decoder layer, in
 steady state (cache full, R tokens rebuilt per sequence and step).  All inputs are generated from a
-seed, uploaded, and resident in HBM before the timed region.
+seed, uploaded, and resident in HBM before the timed region; the library is told so
+(adore_set_input_order(0): its side stream need not wait for the caller's stream before it reads a
+step's inputs).  The step with that wait in place (the library's default, for inputs produced by work
+still queued on the stream) is timed as well and reported as "ordered_inputs".
 
 Prints ONE JSON line: tokens/s per layer for the whole job, per-kernel times measured live with HIP
 events on the library's stream, the roofline fraction of the dominant kernel, and the CPU oracle
@@ -24,6 +27,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+INPUTS_ORDERED = False          # --input-order; see the module docstring
 
 
 def log(msg):
@@ -54,16 +60,18 @@ def recorded_traffic(w, path_name="decode_step"):
     return out
 
 
-def run_gpu(w, steps, warmup, prof_steps):
+def run_gpu(w, steps, warmup, prof_steps, ordered_steps=0):
     import torch
     from gen import SyntheticInputs
     from tests.gpu_harness import GpuJob, to_dev
     t0 = time.time()
     inp = SyntheticInputs(w)
-    job = GpuJob(w, inp)
+    job = GpuJob(w, inp, ordered=INPUTS_ORDERED)
     log(f"inputs generated and uploaded in {time.time() - t0:.1f}s")
     job.init()
-    total = warmup + steps + prof_steps
+    if w.S + warmup + steps + prof_steps + ordered_steps > w.N_max:
+        ordered_steps = 0
+    total = warmup + steps + prof_steps + ordered_steps
     assert w.S + total <= w.N_max, "not enough positions for this many steps"
     qkv = []
     for t in range(total):
@@ -91,14 +99,29 @@ def run_gpu(w, steps, warmup, prof_steps):
 
     # per-kernel durations, HIP events on the library's stream around every launch
     job.adore.set_timing(True)
-    for t in range(warmup + steps, total):
+    for t in range(warmup + steps, warmup + steps + prof_steps):
         step(t)
     timing = job.adore.read_timing()
     job.adore.set_timing(False)
     per_kernel_us = {k: (1e3 * ms / cnt if cnt else 0.0) for k, (ms, cnt) in timing.items()}
+
+    # the same step in the other input order
+    other = None
+    if ordered_steps > warmup:
+        job.adore.set_input_order(not INPUTS_ORDERED)
+        t0 = warmup + steps + prof_steps
+        for t in range(t0, t0 + warmup):
+            step(t)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for t in range(t0 + warmup, total):
+            step(t)
+        torch.cuda.synchronize()
+        other = (time.perf_counter() - t1) / (ordered_steps - warmup)
+        log(f"step with input order {'off' if INPUTS_ORDERED else 'on'}: {1e6 * other:.1f} us")
     assert bool(torch.isfinite(out).all())
     job.adore.close()
-    return elapsed, per_kernel_us
+    return elapsed, per_kernel_us, other
 
 
 def run_stack(w, steps, warmup, prof_steps):
@@ -148,6 +171,7 @@ def run_stack(w, steps, warmup, prof_steps):
                           rebuild_budget=R, max_positions=w.N_max, ctrl_hidden=dp, dtype=w.dtype,
                           pos_scale=w.pos_scale)
         a = Adore(cfg, wts, DEV)
+        a.set_input_order(INPUTS_ORDERED)
         a.init_cache(prompt_k, prompt_v, hidden, ctrl_in, None, w.S)
         torch.cuda.synchronize()
         return a
@@ -216,6 +240,7 @@ def run_forward(w, steps, warmup, prof_steps):
                       rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
                       pos_scale=w.pos_scale)
     a = Adore(cfg, wts, DEV)
+    a.set_input_order(INPUTS_ORDERED)
     a.init_cache(prompt_k, prompt_v, None, embed[:, :w.S].contiguous(), None, w.S)
     rows = torch.zeros((w.B, w.R + 1, w.D), dtype=st, device=DEV)
     torch.cuda.synchronize()
@@ -306,7 +331,12 @@ def main():
                     help="controller scores every token again at every step (relative position)")
     ap.add_argument("--forward", type=int, default=0, metavar="LAYERS",
                     help="time the rebuild forward (adore_forward_step) through this many layers of the workload's shape")
+    ap.add_argument("--input-order", choices=["ready", "stream"], default="ready",
+                    help="ready: inputs are complete in memory at every call (they are, here); stream: the library "
+                         "orders its side stream behind the caller's stream at every step (its default)")
     args = ap.parse_args()
+    global INPUTS_ORDERED
+    INPUTS_ORDERED = args.input_order == "stream"
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (the decode step shards by "
                  "sequence or by head with no exchange; see DESIGN.md). Run with --gpus 1.")
@@ -335,7 +365,8 @@ def main():
         elapsed /= w.L                       # the metric is per decode layer
         args.no_cpu_baseline = True          # the oracle sample is defined on the single-layer workloads
     else:
-        elapsed, per_kernel_us = run_gpu(w, args.steps, args.warmup, args.profile_steps)
+        elapsed, per_kernel_us, other = run_gpu(w, args.steps, args.warmup, args.profile_steps,
+                                                ordered_steps=args.warmup + args.steps // 2)
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.B * args.steps / elapsed
 
@@ -360,12 +391,15 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
                    "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
-                   "score_mode": "rescore" if w.rescore else "static"},
+                   "score_mode": "rescore" if w.rescore else "static", "input_order": args.input_order},
         "roofline": dominant,
         "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
         "kernel_us_sum": round(sum(per_kernel_us.values()), 2),
     }
+    if w.L == 1 and other:
+        line["stream_ordered_inputs" if not INPUTS_ORDERED else "ready_inputs"] = {
+            "ms_per_step": round(1e3 * other, 4), "value": round(w.B / other, 1)}
     if stack:
         line["stack"] = stack
     if not args.no_cpu_baseline:

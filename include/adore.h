@@ -32,7 +32,9 @@
  *   - attend / schedule / rebuild / decode_step only enqueue work on the
  *     context's stream and never synchronise it: outputs are valid once the
  *     caller has synchronised that stream.  Input buffers must stay unchanged
- *     until then.
+ *     until then.  Inputs may be produced by work enqueued on that stream before
+ *     the call (see adore_set_input_order for the one exception a caller can
+ *     ask for).
  *   - The return value is the only error channel.  Arguments are validated on
  *     the host before anything is enqueued: a call that fails has no effect.
  *   - A context is bound to one stream and is not thread-safe.  Contexts are
@@ -50,7 +52,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 3
+#define ADORE_ABI_VERSION 4
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -220,6 +222,19 @@ int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z,
                     void *cache_k, void *cache_v, int32_t *step);
 int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores,
                     const float *z, const void *cache_k, const void *cache_v, int32_t step);
+
+/* Input order.  The controller and the selections of a step run on a stream of the
+ * context's own, next to the attention and the rebuild; they read x_n / embed and
+ * score_override.  ordered != 0 (the default): they start behind everything that was
+ * enqueued on the context's stream before the call, so those inputs may come from
+ * kernels enqueued there, at the price of one more cross-stream event per step.
+ * ordered == 0: the caller guarantees that x_n (embed) and score_override of a step
+ * are complete in memory when the step's call is made (say, the token's embedding
+ * was gathered before the stream was last synchronised); that event is dropped and
+ * the side work of later steps may start early.  All other inputs are read on the
+ * context's stream in either mode.  HOST call between steps.
+ * Errors: E_INVALID, E_STATE (in the middle of a step). */
+int adore_set_input_order(adore_ctx *ctx, int32_t ordered);
 
 /* Per-kernel timing with HIP events on the context's stream (for benchmarks).
  * While enabled, every kernel launch is bracketed by two events.

@@ -22,7 +22,7 @@ KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "re
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
     "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_forward_step", "adore_get_state", "adore_set_state",
-    "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
+    "adore_set_input_order", "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
 ]
 
 
@@ -88,6 +88,8 @@ def load_library() -> ctypes.CDLL:
     lib.adore_get_state.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(i32)]
     lib.adore_set_state.restype = ctypes.c_int
     lib.adore_set_state.argtypes = [vp, vp, vp, vp, vp, vp, i32]
+    lib.adore_set_input_order.restype = ctypes.c_int
+    lib.adore_set_input_order.argtypes = [vp, i32]
     lib.adore_set_timing.restype = ctypes.c_int
     lib.adore_set_timing.argtypes = [vp, i32]
     lib.adore_read_timing.restype = ctypes.c_int
@@ -252,6 +254,9 @@ class Adore:
     def set_state(self, slot_pos, scores, z, cache_k, cache_v, step: int):
         _check(self.lib, self.lib.adore_set_state(self.handle, *self._state_ptrs(slot_pos, scores, z, cache_k, cache_v),
                                                   step))
+
+    def set_input_order(self, ordered: bool):
+        _check(self.lib, self.lib.adore_set_input_order(self.handle, int(ordered)))
 
     def set_timing(self, enable: bool):
         _check(self.lib, self.lib.adore_set_timing(self.handle, int(enable)))

@@ -18,6 +18,11 @@
 // for the attention of step n - 2, which covers the chains of steps n .. n + kSyncEvery - 1 as long as
 // n + kSyncEvery - 1 - (kRing - 1) <= n - 2.  (Every cross-stream event costs several microseconds on
 // the GPU and on the host; with one wait per step in each direction they added up to 9 us per step.)
+// Inputs.  The side kernels read what the caller passes to a step (x_n, score_override).  By default
+// (adore_set_input_order(ctx, 1)) the side stream therefore starts a step's work behind an event recorded
+// on the caller's stream at the top of the call, like any work on the caller's stream itself; the side
+// stream then never runs ahead and the periodic wait above is not needed.  A caller whose inputs are
+// complete in memory when the call is made switches this off and saves that event.
 // ADORE_NO_OVERLAP=1 puts everything on the caller's stream.
 #include <cmath>
 #include <cstdlib>
@@ -144,10 +149,22 @@ int ensure_side_stream(adore_ctx *ctx) {
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_att, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming) == hipSuccess;
   if (!ok) return ADORE_E_HIP;
   ctx->side_ready = true;
   return ADORE_OK;
 }
+
+// Ordered inputs: the side stream starts a step's work behind everything the caller's stream holds now.
+hipError_t order_side_after_caller(adore_ctx *ctx) {
+  if (!ctx->overlap || !ctx->ordered) return hipSuccess;
+  hipError_t e = hipEventRecord(ctx->ev_in, ctx->stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_in, 0);
+  return e;
+}
+
+// Whether the side stream may run ahead of the caller's stream (and so needs the periodic wait of the ring).
+bool runs_ahead(const adore_ctx *ctx) { return ctx->overlap && !ctx->ordered; }
 
 void reset_step(adore_ctx *ctx) {
   std::fill(ctx->attended.begin(), ctx->attended.end(), 0);
@@ -220,7 +237,8 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   const char *nr = getenv("ADORE_NO_RIDE");
   ctx->ride = ctx->overlap && !(nr && atoi(nr) != 0);
   ctx->side = ctx->stream;
-  ctx->ev_att = ctx->ev_join = nullptr;
+  ctx->ev_att = ctx->ev_join = ctx->ev_in = nullptr;
+  ctx->ordered = true;
   ctx->steps_done = 0;
   ctx->side_ready = false;
   ctx->attended.assign(cfg->layers, 0);
@@ -242,7 +260,7 @@ int adore_destroy(adore_ctx *ctx) {
   if (ctx->overlap && ctx->side_ready) {
     (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamDestroy(ctx->side);
-    for (hipEvent_t e : {ctx->ev_att, ctx->ev_join})
+    for (hipEvent_t e : {ctx->ev_att, ctx->ev_join, ctx->ev_in})
       if (e) (void)hipEventDestroy(e);
   }
   delete ctx;
@@ -314,7 +332,7 @@ namespace {
 int do_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out) {
   ADORE_TRY(launch_attend(ctx, layer, q, k_new, v_new, out));
   ctx->attended[layer] = 1;
-  if (++ctx->n_attended == ctx->cfg.layers && ctx->overlap && (ctx->steps_done + 2) % kSyncEvery == 0) {
+  if (++ctx->n_attended == ctx->cfg.layers && runs_ahead(ctx) && (ctx->steps_done + 2) % kSyncEvery == 0) {
     ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));   // what the side stream waits for two steps from now
   }
   return ADORE_OK;
@@ -331,7 +349,8 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
   const int src = ctx->cur, dst = (ctx->cur + 1) % kRing;
   hipStream_t st = ctx->side;
-  if (ctx->rode && ctx->overlap) {
+  ADORE_TRY(order_side_after_caller(ctx));
+  if (ctx->rode && runs_ahead(ctx)) {
     // the steps before this one ran their selections on the caller's stream: the side stream catches up once
     ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
@@ -346,7 +365,7 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
   if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
   // copy `dst` was `cur` kRing - 1 steps ago: see the note on the ring at the top of this file
-  if (ctx->overlap && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
+  if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
   ADORE_TRY(launch_rebuild_select(ctx, st, dst, r, slot_map, rebuilt_pos));
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
@@ -389,6 +408,7 @@ int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void 
   const int pool = ctx->n + 1 - kept;
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
   const int dst = (ctx->cur + 1) % kRing;
+  ADORE_TRY(order_side_after_caller(ctx));
   ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));   // the controller of the step before
   int ksplit = 1;
   ADORE_TRY(launch_ctrl_input(ctx, ctx->side, x_n, c.batch, 1, 1, &ksplit));
@@ -472,6 +492,7 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
   const size_t es = elem_size(c);
   // everything the layers read (slot map, slots of the rebuilt tokens and of the current one) was written
   // by the previous step's selections
+  ADORE_TRY(order_side_after_caller(ctx));
   if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
   // this step's controller and selections: they read the same lists and write the other buffer, so they
   // run on the side stream next to the layers
@@ -489,7 +510,7 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, c.max_positions, &ksplit));
     ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
     if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
-    if (ctx->overlap && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));   // see the note on the ring
+    if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));   // see the note on the ring
     ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
     ADORE_TRY(launch_rebuild_select(ctx, st, dst, r_next, slot_map, rebuilt_pos));
     if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));
@@ -504,7 +525,7 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const bool last = l == c.layers - 1;
     ADORE_TRY(launch_fwd_qkv(ctx, l, wq + size_t(l) * Hd * c.hidden * es, x_rows, by_pos, r));
     ADORE_TRY(launch_fwd_attend(ctx, l, r));
-    if (last && ctx->overlap && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
+    if (last && runs_ahead(ctx) && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,
                                last ? c.rebuild_budget + 1 : r + 1, last ? c.rebuild_budget : r, r));
   }
@@ -589,6 +610,22 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   ctx->ins_from_list = false;
   ctx->rode = false;
   reset_step(ctx);
+  return ADORE_OK;
+}
+
+int adore_set_input_order(adore_ctx *ctx, int32_t ordered) {
+  if (!ctx) return ADORE_E_INVALID;
+  if (ctx->scheduled || ctx->n_attended != 0) return ADORE_E_STATE;
+  const bool on = ordered != 0;
+  if (on == ctx->ordered) return ADORE_OK;
+  if (!on && ctx->overlap && ctx->side_ready) {
+    // from here on the side stream runs ahead again: start its periodic wait like after an init
+    ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
+    ADORE_TRY(hipStreamWaitEvent(ctx->side, ctx->ev_att, 0));
+    ctx->steps_done = 0;
+    ctx->rode = false;
+  }
+  ctx->ordered = on;
   return ADORE_OK;
 }
 

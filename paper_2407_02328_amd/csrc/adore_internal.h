@@ -41,6 +41,8 @@ struct adore_ctx {
   hipStream_t side;          // controller and selections; equals `stream` when overlap is off
   hipEvent_t ev_att;         // recorded on `stream` after the last attention of a step, once in kSyncEvery steps
   hipEvent_t ev_join;        // recorded on `side` after the selections of a step
+  hipEvent_t ev_in;          // ordered inputs: recorded on `stream` at the top of a step, the side stream starts behind it
+  bool ordered;              // the side stream reads a step's inputs behind everything enqueued on `stream` before the call
   bool overlap;              // two-stream mode requested
   bool side_ready;           // side stream and events exist (made on first GPU use)
 

@@ -31,13 +31,16 @@ def device_weights(w: Workload, wts):
 class GpuJob:
     """Device-side twin of an oracle run: same workload, same inputs, uploaded byte for byte."""
 
-    def __init__(self, w: Workload, inp: SyntheticInputs = None, wts=None, hidden=None, prompt=None):
+    def __init__(self, w: Workload, inp: SyntheticInputs = None, wts=None, hidden=None, prompt=None, ordered=True):
         self.w = w
+        self.ordered = ordered     # False: inputs are complete in memory at every call (synchronised first)
         self.inp = inp or SyntheticInputs(w)
         self.wts = wts if wts is not None else self.inp.weights()
         st = storage_dtype(w)
         self.st = st
         self.adore = Adore(adore_config(w), device_weights(w, self.wts), DEV)
+        if not ordered:
+            self.adore.set_input_order(False)
         self.hidden_np = self.inp.hidden_store() if hidden is None else hidden
         self.hidden = to_dev(self.hidden_np, st)
         self.prompt_np = self.inp.prompt_kv() if prompt is None else prompt
@@ -55,20 +58,24 @@ class GpuJob:
                               self.hidden[0][:, :w.S].contiguous(), ov, w.S)
         torch.cuda.synchronize()
 
-    def step(self, n, qkv=None, override=None, whole=False):
+    def step(self, n, qkv=None, override=None, whole=False, x_n=None):
         """One step through the fine-grained calls, or (whole, L = 1) through adore_decode_step, which reports
-        the slot map only.  Returns numpy (out, slot_map, released, rebuilt, score_n)."""
+        the slot map only.  x_n: a device buffer to pass as the controller input instead of a fresh copy of the
+        token's row.  Returns numpy (out, slot_map, released, rebuilt, score_n)."""
         w = self.w
         q, k, v = self.inp.step_qkv(n) if qkv is None else qkv
         qd, kd, vd = (to_dev(a, self.st) for a in (q, k, v))
         ov = None if override is None else to_dev(np.asarray(override, dtype=np.float32), torch.float32)
+        if x_n is None:
+            x_n = self.hidden[0][:, n].contiguous()  # a copy kernel on the stream the context is bound to
+        if not self.ordered:
+            torch.cuda.synchronize()
         if whole:
-            self.adore.decode_step(qd[0], kd[0], vd[0], self.hidden[0], self.hidden[0][:, n].contiguous(), ov,
-                                   self.out[0], self.slot_map)
+            self.adore.decode_step(qd[0], kd[0], vd[0], self.hidden[0], x_n, ov, self.out[0], self.slot_map)
         else:
             for l in range(w.L):
                 self.adore.attend(l, qd[l], kd[l], vd[l], self.out[l])
-            self.adore.schedule(self.hidden[0][:, n].contiguous(), ov, self.slot_map, self.released, self.rebuilt)
+            self.adore.schedule(x_n, ov, self.slot_map, self.released, self.rebuilt)
             for l in range(w.L):
                 self.adore.rebuild(l, self.hidden[l])
         self.adore.get_state(scores=self.state["scores"])
@@ -96,7 +103,7 @@ def out_tol(w: Workload) -> float:
     return 2e-3 if w.dtype == "bf16" else 1e-5
 
 
-def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=None, whole=None):
+def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=None, whole=None, ordered=True):
     """Free-running GPU trajectory with the oracle in lockstep.  whole: None = every step through attend /
     schedule / rebuild; otherwise a function of the step index that says which steps go through
     adore_decode_step (released and rebuilt positions are then checked through the slot map only).
@@ -104,9 +111,11 @@ def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=No
     Each step the oracle computes its own sigma_n, which must agree with the GPU's to 1e-5; it then
     adopts the GPU's bits so that both sides select from identical keys.  Slot maps, released and
     rebuilt positions must be identical; outputs within the storage type's tolerance.
+    ordered: True / False = the context's input order for the whole run; a function of the step index
+    switches it from step to step (inputs are then complete at every call).
     """
     orc, inp, wts = make_oracle(w, wts)
-    job = GpuJob(w, inp, wts)
+    job = GpuJob(w, inp, wts, ordered=ordered if isinstance(ordered, bool) else False)
     hs = job.hidden_np
     pk, pv = job.prompt_np
     job.init(None if override is None else override[:, :w.S])
@@ -126,6 +135,8 @@ def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=No
         qkv = inp.step_qkv(n)
         ov = None if override is None else override[:, n]
         one_call = whole is not None and bool(whole(t))
+        if not isinstance(ordered, bool):
+            job.adore.set_input_order(bool(ordered(t)))
         out_g, map_g, rel_g, rb_g, score_g = job.step(n, qkv, ov, whole=one_call)
         out_o, map_o, rel_o, rb_o, own = orc.decode_step(*qkv, hs, hs[0][:, n],
                                                          score_override=score_g)
@@ -177,7 +188,7 @@ def forward_tol(w: Workload) -> float:
     return (w.L + 1) * 2.0 ** -8
 
 
-def forward_lockstep(w: Workload, steps: int, override=None):
+def forward_lockstep(w: Workload, steps: int, override=None, ordered=True):
     """adore_forward_step next to the forward oracle: identical selections (the oracle adopts the GPU's
     sigma bits after checking them), output rows within forward_tol.  Returns (worst, mean) row errors."""
     from oracle.adore_oracle import AdoreForwardOracle
@@ -187,6 +198,8 @@ def forward_lockstep(w: Workload, steps: int, override=None):
     orc = AdoreForwardOracle(oracle_config(w), wts)
     st = storage_dtype(w)
     adore = Adore(adore_config(w), device_weights(w, {k: v for k, v in wts.items() if k not in ("w_q", "w_o")}), DEV)
+    if not ordered:
+        adore.set_input_order(False)
     wq, wo = to_dev(wts["w_q"], st), to_dev(wts["w_o"], st)
     E = inp.hidden_store_layer(0)
     Ed = to_dev(E, st)
@@ -211,6 +224,8 @@ def forward_lockstep(w: Workload, steps: int, override=None):
         n = w.S + t
         npend = [len(p) for p in orc.pending]
         ov = None if override is None else to_dev(np.asarray(override[:, n], dtype=np.float32), torch.float32)
+        if not ordered:
+            torch.cuda.synchronize()
         adore.forward_step(wq, wo, Ed, ov, rows, slot_map, released, rebuilt)
         adore.get_state(scores=state["scores"])
         torch.cuda.synchronize()

@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 3
+    assert lib.adore_abi_version() == 4
 
 
 def test_workspace_bytes(lib):
@@ -126,6 +126,10 @@ def test_calls_out_of_order_are_state_errors(lib):
         assert lib.adore_init_cache(h, None, FAKE, FAKE, FAKE, None, 4) == -1
         assert lib.adore_set_state(h, None, None, None, None, None, 5) == -1
         assert lib.adore_set_state(h, FAKE, None, None, None, None, 0) == -1
+        # the input-order switch is host state only until a GPU call has made the side stream
+        assert lib.adore_set_input_order(None, 0) == -1
+        assert lib.adore_set_input_order(h, 0) == 0
+        assert lib.adore_set_input_order(h, 1) == 0
         # the rebuild forward: null arguments, a context not initialised for it, a configuration without
         # a forward path (fp32 storage) -- all caught on the host
         from paper_2407_02328_amd.binding import AdoreForwardWeights

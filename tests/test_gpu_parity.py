@@ -445,9 +445,78 @@ def test_decode_step_call_mixed_with_fine_grained_calls():
     job.adore.close()
 
 
-def test_decode_step_call_at_the_benchmark_shape():
-    """llama7b_layer at full size through adore_decode_step, the call bench.py times."""
+@pytest.mark.parametrize("ordered", [True, False])
+def test_decode_step_call_at_the_benchmark_shape(ordered):
+    """llama7b_layer at full size through adore_decode_step, the call bench.py times, in both input orders."""
     h = _harness()
     w = workload("llama7b_layer").scaled(T=8)
-    worst, job, _ = h.lockstep(w, steps=6, check_cache_every=3, whole=lambda t: True)
+    worst, job, _ = h.lockstep(w, steps=6, check_cache_every=3, whole=lambda t: True, ordered=ordered)
     job.adore.close()
+
+
+# ---- input order: adore_set_input_order --------------------------------------------------------------
+ORDER_W = dict(L=1, B=2, H=4, d=128, D=256, K=96, R=8, S=120, T=36, dtype="bf16", dprime=32)
+
+
+@pytest.mark.parametrize("calls", ["whole", "fine", "mixed"])
+def test_inputs_complete_at_call_time(calls):
+    """With the input order switched off the side stream runs ahead of the caller's stream (its lists are rings);
+    the trajectory is the oracle's all the same.  The harness synchronises before every call, as that mode asks."""
+    h = _harness()
+    w = Workload("order_" + calls, **ORDER_W)
+    whole = {"whole": lambda t: True, "fine": None, "mixed": lambda t: (t // 3) % 2 == 0}[calls]
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=whole, ordered=False)
+    job.adore.close()
+
+
+def test_input_order_switched_between_steps():
+    h = _harness()
+    w = Workload("order_switch", **ORDER_W)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=lambda t: (t // 3) % 2 == 0,
+                               ordered=lambda t: (t // 5) % 2 == 0)
+    job.adore.close()
+
+
+def test_inputs_complete_at_call_time_two_layers_rescore_and_forward():
+    h = _harness()
+    w = Workload("order_l2", L=2, B=2, H=4, d=64, D=128, K=72, R=6, S=90, T=20, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5, ordered=False)
+    job.adore.close()
+    w = Workload("order_rescore", L=1, B=2, H=2, d=64, D=64, K=40, R=4, S=50, T=20, dtype="f32", dprime=16,
+                 pos_scale=2.0 ** -5, rescore=True)
+    worst, job, _ = h.lockstep(w, steps=w.T, ordered=False)
+    job.adore.close()
+    w = Workload("order_fwd", L=2, B=2, H=2, d=128, D=256, K=64, R=7, S=80, T=10, dtype="bf16", dprime=32)
+    h.forward_lockstep(w, w.T, ordered=False)
+
+
+def test_inputs_produced_on_the_stream_are_waited_for():
+    """Default input order: x_n and score_override may be written by work that is still queued on the context's
+    stream when the call is made.  One job gets its inputs complete; its twin gets them from copies enqueued
+    behind milliseconds of other work into buffers that hold NaN until then.  Same bits in both."""
+    import torch
+    h = _harness()
+    w = Workload("order_lazy", **dict(ORDER_W, T=12))
+    ref = h.GpuJob(w)
+    lazy = h.GpuJob(w, ref.inp, ref.wts)
+    ref.init()
+    lazy.init()
+    rng = np.random.default_rng(5)
+    busy = torch.randn((4096, 4096), device=h.DEV)
+    x_buf = torch.empty((w.B, w.D), dtype=ref.st, device=h.DEV)
+    for t in range(w.T):
+        n = w.S + t
+        whole = t % 2 == 0
+        want = ref.step(n, whole=whole)
+        x_buf.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for _ in range(4):
+            busy = torch.tanh(busy @ busy)          # a few milliseconds on the context's stream
+        x_buf.copy_(lazy.hidden[0][:, n])
+        got = lazy.step(n, whole=whole, x_n=x_buf)
+        for g, r, what in zip(got, want, ("out", "slot map", "released", "rebuilt", "sigma")):
+            if what in ("released", "rebuilt") and whole:
+                continue                            # not reported by adore_decode_step
+            assert np.array_equal(g, r), f"{what} at n={n}"
+    ref.adore.close()
+    lazy.adore.close()
