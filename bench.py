@@ -294,6 +294,59 @@ def forward_line(w, args):
     }
 
 
+def prefill_line(w, args):
+    """JSON line of the prompt side: adore_init_cache over the workload's S-token prompt (controller over every
+    prompt token: input projection, recurrence, scoring; choice and fill of the residents; first rebuild)."""
+    import torch
+    from gen import SyntheticInputs
+    from tests.gpu_harness import GpuJob, to_dev
+    inp = SyntheticInputs(w)
+    job = GpuJob(w, inp)
+    pk, pv = (to_dev(a, job.st) for a in job.prompt_np)
+    ctrl_in = job.hidden[0][:, :w.S].contiguous()
+    reps, warm = max(3, min(args.steps, 20)), 2
+    torch.cuda.synchronize()
+    for _ in range(warm):
+        job.adore.init_cache(pk, pv, job.hidden, ctrl_in, None, w.S)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        job.adore.init_cache(pk, pv, job.hidden, ctrl_in, None, w.S)
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t1) / reps
+    job.adore.set_timing(True)
+    job.adore.init_cache(pk, pv, job.hidden, ctrl_in, None, w.S)
+    timing = job.adore.read_timing()
+    job.adore.set_timing(False)
+    us = {k: 1e3 * ms for k, (ms, cnt) in timing.items() if cnt}      # per init: all launches of a kernel together
+    scores = job.snapshot()["scores"][:, :w.S]
+    assert np.isfinite(scores).all()
+    job.adore.close()
+    # the recurrence: 2 * 3d' * d' flops per token, one sequence per workgroup, tokens one after the other
+    cell_flops = 2.0 * w.B * w.S * (3 * w.dprime * w.dprime + w.dprime * w.dprime)
+    in_flops = 2.0 * w.B * w.S * w.D * 3 * w.dprime
+    roof_cell = dict(kernel="ctrl_cell", bound="alu", achieved=round(cell_flops / (us["ctrl_cell"] * 1e-6) / 1e12, 3),
+                     peak=MFMA_PEAK_TFLOPS["f32"], unit="TFLOP/s",
+                     frac=round(cell_flops / (us["ctrl_cell"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["f32"], 5),
+                     traffic=None, us_per_launch=round(us["ctrl_cell"], 1),
+                     note="a recurrence: one workgroup per sequence, so at most B of the 256 compute units work on it")
+    roof_in = dict(kernel="ctrl_input", bound="mfma", achieved=round(in_flops / (us["ctrl_input"] * 1e-6) / 1e12, 1),
+                   peak=MFMA_PEAK_TFLOPS.get(w.dtype, 157.3), unit="TFLOP/s",
+                   frac=round(in_flops / (us["ctrl_input"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS.get(w.dtype, 157.3), 4),
+                   traffic=None, us_per_launch=round(us["ctrl_input"], 1))
+    return {
+        "metric": "prompt tokens/sec through cache initialisation", "value": round(w.B * w.S / elapsed, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": warm, "ms_per_step": round(1e3 * elapsed, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "_prefill", "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
+                   "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
+                   "path": "adore_init_cache: controller over the prompt, residents chosen and filled, first rebuild"},
+        "roofline": roof_cell if us["ctrl_cell"] >= us["ctrl_input"] else roof_in,
+        "roofline_ctrl_cell": roof_cell, "roofline_ctrl_input": roof_in,
+        "kernel_us": {k: round(v, 1) for k, v in us.items()},
+    }
+
+
 def run_cpu_baseline(w, seqs=16, steps=40):
     """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
     from threadpoolctl import threadpool_info
@@ -334,6 +387,8 @@ def main():
     ap.add_argument("--input-order", choices=["ready", "stream"], default="ready",
                     help="ready: inputs are complete in memory at every call (they are, here); stream: the library "
                          "orders its side stream behind the caller's stream at every step (its default)")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time adore_init_cache over the workload's prompt instead of decode steps")
     args = ap.parse_args()
     global INPUTS_ORDERED
     INPUTS_ORDERED = args.input_order == "stream"
@@ -349,6 +404,9 @@ def main():
         w = w.scaled(rescore=True)
     if args.forward:
         print(json.dumps(forward_line(w.scaled(L=args.forward), args)), flush=True)
+        return
+    if args.prefill:
+        print(json.dumps(prefill_line(w, args)), flush=True)
         return
     work = algorithmic_work(w)
     stack = None

@@ -58,7 +58,7 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
-      att_part, gi, cvec, avec, fwd_q, fwd_o, fwd_x, total;
+      att_part, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, total;
 };
 
 bool config_ok(const adore_config *c) {
@@ -103,6 +103,7 @@ Layout make_layout(const adore_config &c) {
   size_t gi_rows = size_t(c.batch) * kPromptChunk;
   if (gi_rows < size_t(kMaxCtrlSplit) * kCtrlSplitTokens) gi_rows = size_t(kMaxCtrlSplit) * kCtrlSplitTokens;
   l.gi = take(gi_rows * 3 * c.ctrl_hidden * 4);
+  l.zseq = take(size_t(c.batch) * kPromptChunk * c.ctrl_hidden * 4);
   const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
   l.cvec = take(rescore ? size_t(c.batch) * c.max_positions * c.ctrl_hidden * 4 : 0);
   l.avec = take(rescore ? size_t(c.ctrl_hidden) * 4 : 0);
@@ -217,6 +218,7 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->init_res = reinterpret_cast<int32_t *>(base + l.init_res);
   ctx->att_part = reinterpret_cast<float *>(base + l.att_part);
   ctx->gi = reinterpret_cast<float *>(base + l.gi);
+  ctx->zseq = reinterpret_cast<float *>(base + l.zseq);
   ctx->cvec = reinterpret_cast<float *>(base + l.cvec);
   ctx->avec = reinterpret_cast<float *>(base + l.avec);
   ctx->fwd_q = base + l.fwd_q;

@@ -61,6 +61,7 @@ struct adore_ctx {
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
+  float *zseq;               // [B][kPromptChunk][d'] GRU states of a prompt chunk, between its scan and its scoring
   float *cvec;               // rescore mode: [B][N_max][d']  W_1 (z_i + pos_b) + b_1 of every token
   float *avec;               // rescore mode: [d']  W_1 pos_w  (what one unit of distance adds)
   void *fwd_q, *fwd_o;       // rebuild forward: [B*(R+1)][H*d] query rows / attention outputs of the layer in flight

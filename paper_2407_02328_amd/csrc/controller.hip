@@ -67,6 +67,96 @@ __global__ __launch_bounds__(256) void ctrl_input_mfma_kernel(const bf16_t *__re
   }
 }
 
+// ---- input projection of a prompt chunk, bf16, matrix cores ---------------------------
+// Thousands of tokens at once: a workgroup owns 64 tokens x 64 gate rows (4 x 4 tiles of the shape above)
+// and the whole of D; its 4 waves cut D and keep all 16 tiles each, so a wave multiplies 16 tiles with
+// 4 + 4 operand loads per step (the 16-token tile above re-reads W_ih once per 16 tokens and x once per
+// 16 gate rows: at 8192 tokens that was 800 us).  The waves' sums are added in a fixed order.
+// grid (ceil(3d'/64), ceil(ntok/64)), 256 threads.  gi[tok][j] (one D-slice).
+__global__ __launch_bounds__(256) void ctrl_input_prompt_kernel(const bf16_t *__restrict__ W_ih,
+                                                                const bf16_t *__restrict__ x,
+                                                                float *__restrict__ gi, int D, int G3, int ntok,
+                                                                int per_seq, int seq_rows) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j0 = blockIdx.x * 64, t0 = blockIdx.y * 64;
+  const int kw = D / 4;                            // k-range of one wave, a multiple of 32
+  // a step of 32 k is one contiguous 64-byte run of every row, lane group g = lane/16 taking its g-th quarter
+  // (with thousands of rows in flight, rows walked in four places at once would not stay in the L1)
+  const int kbeg = wave * kw + (lane >> 4) * 8;
+  const u32x4 *pa[4], *pb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int tok = t0 + 16 * i + (lane & 15);
+    if (tok >= ntok) tok = ntok - 1;               // padded rows read a valid token; dropped at the store
+    const size_t xrow = size_t(tok / per_seq) * seq_rows + tok % per_seq;
+    pa[i] = reinterpret_cast<const u32x4 *>(x + xrow * D + kbeg);
+    int j = j0 + 16 * i + (lane & 15);
+    if (j >= G3) j = G3 - 1;
+    pb[i] = reinterpret_cast<const u32x4 *>(W_ih + size_t(j) * D + kbeg);
+  }
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[i][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int steps = kw / 32;
+#define PROMPT_STEP(VA, VB)                                                                                   \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                               \
+    _Pragma("unroll") for (int jj = 0; jj < 4; ++jj)                                                          \
+      acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&VA[i]),         \
+                                                           *reinterpret_cast<const bf16x8 *>(&VB[jj]), acc[i][jj], 0, 0, 0);
+  int s = 0;
+  for (; s + 2 <= steps; s += 2) {          // two steps' loads in flight
+    u32x4 va[2][4], vb[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { va[u][i] = pa[i][(s + u) * 4]; vb[u][i] = pb[i][(s + u) * 4]; }
+    PROMPT_STEP(va[0], vb[0])
+    PROMPT_STEP(va[1], vb[1])
+  }
+  for (; s < steps; ++s) {
+    u32x4 va[4], vb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { va[i] = pa[i][s * 4]; vb[i] = pb[i][s * 4]; }
+    PROMPT_STEP(va, vb)
+  }
+#undef PROMPT_STEP
+  // waves 3, 2, 1 hand their tiles to wave 0 through LDS, one after the other
+  __shared__ float red[16][4][64];   // [tile][v][lane]: conflict-free, lane-private
+  for (int w = 3; w >= 1; --w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) red[i * 4 + jj][v][lane] = acc[i][jj][v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[i][jj][v] += red[i * 4 + jj][v][lane];
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {   // accumulator element v of lane L: token 4*(L/16) + v, gate row L%16 of its tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int tok = t0 + 16 * i + 4 * (lane >> 4) + v, j = j0 + 16 * jj + (lane & 15);
+          if (tok < ntok && j < G3) gi[size_t(tok) * G3 + j] = acc[i][jj][v];
+        }
+  }
+}
+
 // ---- input projection, any storage type, plain ALUs ---------------------------------
 constexpr int JT = 4;  // gate rows per workgroup
 constexpr int NB = 8;  // tokens per workgroup
@@ -287,6 +377,164 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   if (tid < DP) a.z[size_t(b) * DP + tid] = h[tid];
 }
 
+// ---- a prompt chunk, d' = 128: the recurrence alone, then the layers above it for all tokens at once ----
+// Only z_i = GRU(x_i, z_{i-1}) ties a token to the one before it; the position, interaction and output layers
+// do not.  The scan therefore does nothing but the recurrence, one workgroup of 4 waves per sequence, with W_hh
+// in registers as fp32 for the whole chunk: wave w keeps columns 32w .. 32w+31 of all 384 rows (lane l: rows
+// l, l+64, .., l+320), so a token costs a wave 8 16-byte reads of the state from LDS (same address in every
+// lane) and 192 multiply-adds per lane on each of the four SIMDs; the four partial sums of a row meet in LDS,
+// 128 threads apply the gates.  Two barriers and no memory round trip per token.  The gates use the hardware's exp2 and reciprocal
+// (about 2e-7 absolute); z_i goes to zseq[b * nsteps + i][128] for the kernel below.
+__device__ inline float scan_sigmoid(float a) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * a));
+}
+__device__ inline float scan_tanh(float a) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008f * a));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ctrl_scan128_kernel(const CellArgs a, float *__restrict__ zseq) {
+  constexpr int DP = 128, KW = 32, RPL = 6;               // columns per wave, rows per lane
+  constexpr int TB = 16, GPT = TB * (3 * DP / 4) / 256;   // tokens per block of input pre-activations; float4 per thread
+  __shared__ __attribute__((aligned(16))) float h[DP];   // z_{i-1}, then z_i
+  __shared__ float part[4][3 * DP];                        // the waves' partial sums of W_hh h
+  __shared__ float4 gbuf[2][TB * (3 * DP / 4)];            // input pre-activations of two blocks of tokens
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float w[RPL][KW];
+  {
+    constexpr int EPL = Vec16<T>::EPL;
+#pragma unroll
+    for (int m = 0; m < RPL; ++m) {
+      const T *row = static_cast<const T *>(a.W_hh) + size_t(lane + 64 * m) * DP + wave * KW;
+#pragma unroll
+      for (int c = 0; c < KW; c += EPL) {
+        float f[EPL];
+        Vec16<T>::load(row + c, f);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) w[m][c + e] = f[e];
+      }
+    }
+  }
+  float b_r = 0.f, b_u = 0.f, b_in = 0.f, b_hn = 0.f, hcur = 0.f;
+  if (tid < DP) {
+    hcur = a.z[size_t(b) * DP + tid];
+    h[tid] = hcur;
+    b_r = a.b_ih[tid] + a.b_hh[tid];
+    b_u = a.b_ih[DP + tid] + a.b_hh[DP + tid];
+    b_in = a.b_ih[2 * DP + tid];
+    b_hn = a.b_hh[2 * DP + tid];
+  }
+  // The input pre-activations reach the gates through LDS, TB tokens at a time: the rows of block j+1 are
+  // fetched (all threads, 16 bytes each, the D-slices added up) while block j is worked through, so the
+  // recurrence never waits for memory.
+  const int nblk = (a.nsteps + TB - 1) / TB;
+  const float4 *gsrc = reinterpret_cast<const float4 *>(a.gi) + size_t(b) * a.nsteps * (3 * DP / 4);
+  const size_t slice4 = size_t(a.ntok) * (3 * DP / 4);   // distance between two D-slices
+  float4 stage[GPT];
+  auto fetch = [&](int blk) {
+    const int rows = a.nsteps - blk * TB < TB ? a.nsteps - blk * TB : TB;
+#pragma unroll
+    for (int q = 0; q < GPT; ++q) {
+      const int idx = tid + 256 * q;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (idx < rows * (3 * DP / 4)) {
+        const float4 *p = gsrc + size_t(blk) * TB * (3 * DP / 4) + idx;
+        v = p[0];
+        for (int k = 1; k < a.ksplit; ++k) {
+          const float4 t = p[size_t(k) * slice4];
+          v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+        }
+      }
+      stage[q] = v;
+    }
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int q = 0; q < GPT; ++q) gbuf[buf][tid + 256 * q] = stage[q];
+  };
+  if (nblk > 0) {
+    fetch(0);
+    park(0);
+  }
+  __syncthreads();
+  for (int blk = 0; blk < nblk; ++blk) {
+    if (blk + 1 < nblk) fetch(blk + 1);
+    const float *g = reinterpret_cast<const float *>(gbuf[blk & 1]);
+    const int rows = a.nsteps - blk * TB < TB ? a.nsteps - blk * TB : TB;
+    for (int ii = 0; ii < rows; ++ii) {
+      const size_t tok = size_t(b) * a.nsteps + blk * TB + ii;
+      float acc[RPL];
+#pragma unroll
+      for (int m = 0; m < RPL; ++m) acc[m] = 0.f;
+#pragma unroll
+      for (int k = 0; k < KW; k += 4) {
+        const float4 hv = *reinterpret_cast<const float4 *>(&h[wave * KW + k]);
+#pragma unroll
+        for (int m = 0; m < RPL; ++m) {
+          acc[m] = fmaf(w[m][k], hv.x, acc[m]);
+          acc[m] = fmaf(w[m][k + 1], hv.y, acc[m]);
+          acc[m] = fmaf(w[m][k + 2], hv.z, acc[m]);
+          acc[m] = fmaf(w[m][k + 3], hv.w, acc[m]);
+        }
+      }
+#pragma unroll
+      for (int m = 0; m < RPL; ++m) part[wave][lane + 64 * m] = acc[m];
+      __syncthreads();
+      if (tid < DP) {
+        const float s_r = (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]);
+        const float s_u = (part[0][DP + tid] + part[1][DP + tid]) + (part[2][DP + tid] + part[3][DP + tid]);
+        const float s_n = (part[0][2 * DP + tid] + part[1][2 * DP + tid]) + (part[2][2 * DP + tid] + part[3][2 * DP + tid]);
+        const float *gt = g + ii * 3 * DP;
+        const float r = scan_sigmoid(gt[tid] + b_r + s_r);
+        const float u = scan_sigmoid(gt[DP + tid] + b_u + s_u);
+        const float cand = scan_tanh(gt[2 * DP + tid] + b_in + r * (s_n + b_hn));
+        hcur = (1.0f - u) * cand + u * hcur;
+        h[tid] = hcur;
+        zseq[tok * DP + tid] = hcur;
+      }
+      __syncthreads();
+    }
+    if (blk + 1 < nblk) park((blk + 1) & 1);   // read next after at least one more barrier
+  }
+  if (tid < DP) a.z[size_t(b) * DP + tid] = hcur;
+}
+
+// sigma_i = sigmoid(out_w . tanh(W_1 (p_i + z_i) + b_1) + out_b) for the tokens of a chunk, from the z_i the scan
+// left.  grid (ceil(nsteps / 16), B), 4 waves, 4 tokens per wave one after the other; the arithmetic is the cell
+// kernel's (rows_times_vec, same order), so a token scored here and one scored by a step agree bit for bit
+// given the same z_i.
+__global__ __launch_bounds__(256) void ctrl_mlp128_kernel(const CellArgs a, const float *__restrict__ zseq) {
+  constexpr int DP = 128;
+  __shared__ float u1[4][DP];
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int q = 0; q < 4; ++q) {
+    const int i = blockIdx.x * 16 + wave * 4 + q;
+    const bool on = i < a.nsteps;                      // uniform over the wave; the barriers are not skipped
+    const size_t tok = size_t(b) * a.nsteps + (on ? i : 0);
+    const float delta = a.cvec ? 0.f : float(a.pos0 + i) * a.pos_scale;   // rescore mode: distance to itself
+    const float x0 = fmaf(a.pos_w[2 * lane], delta, a.pos_b[2 * lane]) + zseq[tok * DP + 2 * lane];
+    const float x1 = fmaf(a.pos_w[2 * lane + 1], delta, a.pos_b[2 * lane + 1]) + zseq[tok * DP + 2 * lane + 1];
+#pragma unroll 1
+    for (int part = 0; part < 4; ++part) rows_times_vec<float, 32>(a.W1, part * 32, x0, x1, a.b1, u1[wave], lane);
+    __syncthreads();
+    if (on) {
+      if (a.cvec) {
+        float *c = a.cvec + (size_t(b) * a.N_max + a.pos0 + i) * DP;
+        c[lane] = u1[wave][lane];
+        c[lane + 64] = u1[wave][lane + 64];
+      }
+      float s = fmaf(a.out_w[lane], tanhf(u1[wave][lane]), a.out_w[lane + 64] * tanhf(u1[wave][lane + 64]));
+      s = wave_sum(s);
+      if (lane == 0) {
+        float sig = sigmoidf_(s + a.out_b[0]);
+        if (a.override_) sig = a.override_[size_t(b) * a.override_stride + i];
+        a.score[size_t(b) * a.N_max + a.pos0 + i] = sig;
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // ---- cell, any d' -------------------------------------------------------------------
 // One workgroup per sequence; loops over `nsteps` consecutive tokens starting at position pos0.
 template <typename T>
@@ -412,7 +660,12 @@ hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int 
   const int G3 = 3 * c.ctrl_hidden;
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_INPUT, st);
   *ksplit_out = 1;
-  if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0) {
+  if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0 && ntok > kCtrlSplitTokens) {
+    dim3 grid((G3 + 63) / 64, (ntok + 63) / 64);
+    ADORE_LAUNCH(t, ctrl_input_prompt_kernel, grid, dim3(256), 0, st,
+                       static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,
+                       c.hidden, G3, ntok, per_seq, seq_rows);
+  } else if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0) {
     const int ks = ctrl_input_ksplit(c, ntok);
     *ksplit_out = ks;
     dim3 grid((G3 + 15) / 16, (ntok + 15) / 16, ks);
@@ -448,6 +701,20 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
   a.dp = c.ctrl_hidden; a.nsteps = nsteps; a.pos0 = pos0; a.N_max = c.max_positions;
   a.ksplit = ksplit; a.ntok = c.batch * nsteps;
   a.pos_scale = c.pos_scale;
+  if (c.ctrl_hidden == 128 && nsteps > 1) {   // a prompt chunk: the recurrence, then the layers above it
+    {
+      ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
+      if (c.dtype == ADORE_BF16) {
+        ADORE_LAUNCH(t, (ctrl_scan128_kernel<bf16_t>), dim3(c.batch), dim3(256), 0, st, a, ctx->zseq);
+      } else {
+        ADORE_LAUNCH(t, (ctrl_scan128_kernel<float>), dim3(c.batch), dim3(256), 0, st, a, ctx->zseq);
+      }
+    }
+    ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
+    ADORE_LAUNCH(t, ctrl_mlp128_kernel, dim3((nsteps + 15) / 16, c.batch), dim3(256), 0, st, a,
+                 static_cast<const float *>(ctx->zseq));
+    return hipGetLastError();
+  }
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
   if (c.ctrl_hidden == 128) {
     if (c.dtype == ADORE_BF16) {
