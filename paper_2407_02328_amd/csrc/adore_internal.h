@@ -155,6 +155,8 @@ hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r,
 // tokens' positions itself (when the per-sequence choice did not do it)
 hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_layer, int lists, int r,
                                int32_t *map_dst = nullptr, int32_t *map_out = nullptr);
+bool launch_plain_projection(adore_ctx *ctx, ScopedTimer &t, hipStream_t st, const void *x, const void *W, float *out,
+                             int ntok, int per_seq, int seq_rows, int N, int D);
 hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep, int r0);
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);

@@ -660,7 +660,10 @@ hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int 
   const int G3 = 3 * c.ctrl_hidden;
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_INPUT, st);
   *ksplit_out = 1;
-  if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0 && ntok > kCtrlSplitTokens) {
+  if (ntok > kCtrlSplitTokens &&
+      launch_plain_projection(ctx, t, st, x, ctx->w.gru_w_ih, ctx->gi, ntok, per_seq, seq_rows, G3, c.hidden)) {
+    // a prompt chunk on the rebuild's 128x128 tile (3d' a multiple of 128, D of 64)
+  } else if (c.dtype == ADORE_BF16 && c.hidden % 128 == 0 && ntok > kCtrlSplitTokens) {
     dim3 grid((G3 + 63) / 64, (ntok + 63) / 64);
     ADORE_LAUNCH(t, ctrl_input_prompt_kernel, grid, dim3(256), 0, st,
                        static_cast<const bf16_t *>(ctx->w.gru_w_ih), static_cast<const bf16_t *>(x), ctx->gi,

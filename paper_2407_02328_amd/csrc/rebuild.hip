@@ -37,14 +37,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // plain vector: s
 //   QKV      C = X_rows . [W_q ; W_kv]^T            -> query rows to a dense buffer, K/V slices scattered into the
 //            slots of the rebuilt tokens and of the current token (rebuild forward, Sec. 2.3)
 //   OPROJ    C = O_rows . W_o^T + X_rows (residual) -> dense rows, the next layer's input
-enum { MODE_REBUILD = 0, MODE_QKV = 1, MODE_OPROJ = 2 };
+// and one more product of the same shape family, the controller's input projection over a prompt chunk:
+//   PLAIN    C = X_rows . W^T                        -> dense fp32 rows, no rounding
+enum { MODE_REBUILD = 0, MODE_QKV = 1, MODE_OPROJ = 2, MODE_PLAIN = 3 };
 
 struct GemmArgs {
   const void *X;               // A operand: [B][N_max][D] gathered by position, or dense rows [M][D]
   const void *W;               // [N][D]  (QKV: W_kv, the rows of columns >= H*d)
   const void *Wq;              // QKV: [H*d][D], the rows of columns < H*d
   void *Kc, *Vc;               // [B][H][K][d] of this layer
-  void *Out;                   // QKV: query rows [M][H*d]; OPROJ: output rows [.][N]
+  void *Out;                   // QKV: query rows [M][H*d]; OPROJ: output rows [.][N]; PLAIN: fp32 rows [M][N]
   const void *Res;             // OPROJ: residual rows, gathered by position or dense like X
   const int32_t *rebuilt_pos;  // [B][Rdim]
   const int32_t *free_list;    // [B][H][R1]
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   const int sw = MODE == MODE_OPROJ ? BN : a.d;   // width of a contiguous piece of an output row
   const int nh = BN / sw > 0 ? BN / sw : 1;       // pieces in one tile row
   const int section = MODE == MODE_OPROJ ? 0 : n0 / Hd;   // REBUILD: K, V; QKV: Q, K, V (a tile lies in one)
-  for (int t = tid; t < BM * nh; t += 512) {
+  for (int t = tid; MODE != MODE_PLAIN && t < BM * nh; t += 512) {
     const int row = t / nh, hh = t - row * nh;
     const int mi = m0 + row;
     long long off = -1;
@@ -311,6 +313,21 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
           for (int v = 0; v < 16; ++v) acc[i][j][v] += red[((i * TN + j) * 16 + v) * 64];
     }
     __syncthreads();   // the output tile below overwrites what was just read
+  }
+  if (MODE == MODE_PLAIN) {   // fp32 rows straight from the accumulators: 32 consecutive columns per row and block
+    float *out = static_cast<float *>(a.Out);
+    if (kgrp == 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int mi = m0 + (wm * TM + i) * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            if (mi < a.M) out[size_t(mi) * a.N + n0 + (wn * TN + j) * 32 + (lane & 31)] = acc[i][j][v];
+          }
+    }
+    return;
   }
   // ---- round once to bf16 into a row-major LDS tile ----
   // accumulator element v of lane L: row 8*(v/4) + 4*(L/32) + v%4, column L%32 of its 32x32 block
@@ -647,6 +664,25 @@ hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x
     launch_cur_rows<MODE_OPROJ>(t, ctx->stream, a);
   }
   return hipGetLastError();
+}
+
+// gi[tok][j] = W_ih[j][:] . x_tok for the ntok tokens of a prompt chunk (token b * per_seq + i at row
+// b * seq_rows + i of x), fp32, on the 128x128 tile.  False if the shape does not fit that tile.
+bool launch_plain_projection(adore_ctx *ctx, ScopedTimer &t, hipStream_t st, const void *x, const void *W, float *out,
+                             int ntok, int per_seq, int seq_rows, int N, int D) {
+  constexpr int kTile = 2;   // 128 x 128 x 64
+  if (ctx->cfg.dtype != ADORE_BF16 || N % kTiles[kTile].bn != 0 || D % kTiles[kTile].bk != 0) return false;
+  GemmArgs a;
+  fill_common(ctx, a, 0, per_seq);
+  a.X = x; a.W = W; a.Out = out;
+  a.Kc = a.Vc = nullptr;
+  a.D = D; a.M = ntok; a.N = N;
+  a.xrps = seq_rows; a.a_gather = 0;
+  a.tiles_m = (a.M + kTiles[kTile].bm - 1) / kTiles[kTile].bm;
+  a.tiles_n = a.N / kTiles[kTile].bn;
+  const dim3 grid((a.tiles_m * a.tiles_n + 7) / 8 * 8), block(512);
+  ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE_PLAIN, 128, 128, 64, 2, 2, 2, 3, 4>), grid, block, 0, st, a);
+  return true;
 }
 
 }  // namespace adore

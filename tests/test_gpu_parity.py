@@ -490,6 +490,29 @@ def test_inputs_complete_at_call_time_two_layers_rescore_and_forward():
     h.forward_lockstep(w, w.T, ordered=False)
 
 
+@pytest.mark.parametrize("env", ["ADORE_NO_RIDE", "ADORE_NO_OVERLAP"])
+@pytest.mark.parametrize("ordered", [True, False])
+def test_decode_step_call_with_the_selections_as_kernels_of_their_own(env, ordered, monkeypatch):
+    """adore_decode_step with the riding switched off (selections and controller on the side stream) and with the
+    side stream switched off (everything on the caller's stream), mixed with the fine-grained calls."""
+    monkeypatch.setenv(env, "1")
+    h = _harness()
+    w = Workload("ds_" + env.lower(), **ORDER_W)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=lambda t: (t // 3) % 2 == 0, ordered=ordered)
+    job.adore.close()
+
+
+@pytest.mark.parametrize("ordered", [True, False])
+def test_decode_step_call_with_the_rescoring_controller(ordered):
+    """RESCORE mode never rides (every score changes at every step): adore_decode_step enqueues the side chain
+    first, then the attention, then the rebuild."""
+    h = _harness()
+    w = Workload("ds_rescore", L=1, B=2, H=2, d=64, D=256, K=48, R=6, S=60, T=24, dtype="bf16", dprime=128,
+                 pos_scale=2.0 ** -6, rescore=True)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=6, whole=lambda t: t % 3 != 2, ordered=ordered)
+    job.adore.close()
+
+
 def test_inputs_produced_on_the_stream_are_waited_for():
     """Default input order: x_n and score_override may be written by work that is still queued on the context's
     stream when the call is made.  One job gets its inputs complete; its twin gets them from copies enqueued
