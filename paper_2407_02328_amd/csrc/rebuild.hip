@@ -61,10 +61,139 @@ struct GemmArgs {
   int cur_pos;                 // position of the current token
   int a_gather, res_gather;    // 1: the row of a token is [b][its position]; 0: its row in a dense buffer
   int out_rps, out_cur;        // OPROJ: rank j is written to row b * out_rps + j, the current token to b * out_rps + out_cur
+  int n_cur;                   // QKV / OPROJ: the first n_cur workgroups of the tile launch take the current tokens' rows
+  int cur_ks;                  // ... with the contraction cut over cur_ks (1, 2, 4, 8) of a workgroup's waves
 };
 
 __device__ inline size_t row_by_position(const GemmArgs &a, int b, int j) {
   return size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + j];
+}
+
+// The current token's row of every sequence (rebuild forward) as workgroups of the tile kernel's launch.  B rows
+// against the same weights are a skinny product that only streams W; the tile launches of the forward leave a
+// fifth or more of the compute units without a tile, and these workgroups take them (one workgroup per unit:
+// the kernel's LDS sees to that), so the rows cost no launch and no time of their own.  A wave multiplies 16
+// sequences x 32 output columns; the 8 waves of a workgroup are cur_ks wide along the contraction and 8 / cur_ks
+// wide along the columns (partial sums added through LDS in a fixed order), so that the launcher can make as
+// many workgroups as there are units without a tile: what one unit can stream is bounded by what it can keep
+// in flight (about 36 GB/s next to the tiles' traffic).  With so few units at work the rows of W must arrive as whole cache lines (operands loaded
+// straight into the 16x16x32 operand layout cost the L1 a tag look-up per lane, about 25 GB/s per unit): a wave
+// reads its 32 rows x 64 k as four coalesced 16-byte loads per lane, six such chunks in flight, and turns them
+// into operands through 4 KB of LDS of its own (XOR-swizzled; only the wave itself reads and writes it, so no
+// barrier).  Epilogue as in the tile kernel, one rounding.
+constexpr int kCurCols = 256;   // output columns per workgroup in this role when the contraction is not cut
+
+template <int MODE>
+__device__ inline void cur_rows_role(const GemmArgs &a, int e, u32x4 *smem) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  constexpr int U = 6;                                  // chunks of 64 k in flight
+  const int ks = a.cur_ks;
+  const int wg_cols = kCurCols / ks;
+  const int wgs_n = a.N / wg_cols;
+  const int sb = e / wgs_n, jn = e - sb * wgs_n;
+  const int t0 = sb * 16;
+  if (t0 >= a.B) return;                                // workgroups that only pad the launch
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int kpart = wave % ks;                          // this wave's part of the contraction
+  const int j0 = jn * wg_cols + (wave / ks) * 32;
+  const int Hd = a.H * a.d;
+  const int bb = min(t0 + c, a.B - 1);                  // padded rows read a valid sequence; dropped at the store
+  const size_t xrow = a.a_gather ? size_t(bb) * a.N_max + a.cur_pos : size_t(bb) * a.xrps + a.r;
+  const u32x4 *pa = reinterpret_cast<const u32x4 *>(static_cast<const bf16_t *>(a.X) + xrow * a.D) + g;
+  // W: lane (row8 = lane / 8, chunk = lane % 8) loads 16 bytes of row 8 i + row8 of the wave's 32 rows
+  const int lrow = lane >> 3, lch = lane & 7;
+  const u32x4 *pw[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int n = j0 + 8 * i + lrow;
+    const bf16_t *wrow = MODE == MODE_QKV && n < Hd ? static_cast<const bf16_t *>(a.Wq) + size_t(n) * a.D
+                         : MODE == MODE_QKV         ? static_cast<const bf16_t *>(a.W) + size_t(n - Hd) * a.D
+                                                    : static_cast<const bf16_t *>(a.W) + size_t(n) * a.D;
+    pw[i] = reinterpret_cast<const u32x4 *>(wrow) + lch;
+  }
+  u32x4 *tile = smem + wave * (32 * 8);                 // [32 rows][8 chunks of 16 bytes]
+  auto swz = [](int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); };
+  f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  const int nchunks = a.D / 64 / ks;                    // chunks of this wave: kpart * nchunks ...
+  const int chunk0 = kpart * nchunks;
+  u32x4 vw[U][4], va[U][2];
+#define CUR_LOAD(SET, CH)                                                                \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) vw[SET][i] = pw[i][(chunk0 + (CH)) * 8]; \
+    va[SET][0] = pa[(chunk0 + (CH)) * 8];                                                \
+    va[SET][1] = pa[(chunk0 + (CH)) * 8 + 4];                                            \
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (u < nchunks) CUR_LOAD(u, u)
+  }
+  for (int ch0 = 0; ch0 < nchunks; ch0 += U) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ch = ch0 + u;
+      if (ch < nchunks) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[swz(8 * i + lrow, lch)] = vw[u][i];
+        u32x4 fb[2][2];   // [step of 32 k][tile of 16 columns]
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int nc = 0; nc < 2; ++nc) fb[st][nc] = tile[swz(nc * 16 + c, st * 4 + g)];
+        const u32x4 fa0 = va[u][0], fa1 = va[u][1];
+        if (ch + U < nchunks) CUR_LOAD(u, ch + U)
+#pragma unroll
+        for (int nc = 0; nc < 2; ++nc) {
+          acc[nc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&fa0),
+                                                            *reinterpret_cast<const bf16x8 *>(&fb[0][nc]), acc[nc], 0, 0, 0);
+          acc[nc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(&fa1),
+                                                            *reinterpret_cast<const bf16x8 *>(&fb[1][nc]), acc[nc], 0, 0, 0);
+        }
+      }
+    }
+  }
+#undef CUR_LOAD
+  if (ks > 1) {   // the parts of the contraction meet in the wave that holds part 0, in order
+    float *red = reinterpret_cast<float *>(smem + 8 * (32 * 8));   // [8 waves][2][4][64], behind the waves' tiles
+#pragma unroll
+    for (int nc = 0; nc < 2; ++nc)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[((wave * 2 + nc) * 4 + v) * 64 + lane] = acc[nc][v];
+    __syncthreads();
+    if (kpart != 0) return;
+    for (int p = 1; p < ks; ++p)
+#pragma unroll
+      for (int nc = 0; nc < 2; ++nc)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[nc][v] += red[(((wave + p) * 2 + nc) * 4 + v) * 64 + lane];
+  }
+  // accumulator element v of lane (c, g): sequence 4*g + v of the block, column c of the tile
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int b = t0 + 4 * g + v;
+    if (b >= a.B) continue;
+#pragma unroll
+    for (int nc = 0; nc < 2; ++nc) {
+      float val = acc[nc][v];
+      const int n = j0 + nc * 16 + c;
+      bf16_t *dst;
+      if (MODE == MODE_OPROJ) {
+        const size_t rrow = a.res_gather ? size_t(b) * a.N_max + a.cur_pos : size_t(b) * a.xrps + a.r;
+        val += to_float(static_cast<const bf16_t *>(a.Res)[rrow * a.N + n]);
+        dst = static_cast<bf16_t *>(a.Out) + (size_t(b) * a.out_rps + a.out_cur) * a.N + n;
+      } else {
+        const int section = n / Hd, rem = n - section * Hd;
+        const int h = rem / a.d;
+        if (section == 0) {
+          dst = static_cast<bf16_t *>(a.Out) + (size_t(b) * a.xrps + a.r) * Hd + rem;
+        } else {
+          const int slot = a.insert_slot[size_t(b) * a.H + h];
+          dst = static_cast<bf16_t *>(section == 1 ? a.Kc : a.Vc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+        }
+      }
+      dst->bits = f32_to_bf16_rne(val);
+    }
+  }
 }
 
 // Workgroup = 8 waves on a BM x BN output tile, k-steps of BK.
@@ -104,9 +233,17 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   // rows are 128 B (BK = 64) or 64 B (BK = 32): 16 consecutive rows at one chunk index hit 16 different bank groups
   auto swz = [](int row, int chunk) { return row * CH + (chunk ^ (CH == 8 ? (row >> 1) & 7 : (row >> 2) & 3)); };
 
+  int bx = blockIdx.x;
+  if constexpr (MODE == MODE_QKV || MODE == MODE_OPROJ) {
+    if (bx < a.n_cur) {   // uniform over the workgroup; n_cur is a multiple of 8, so the tiles keep their XCDs
+      cur_rows_role<MODE>(a, bx, smem);
+      return;
+    }
+    bx -= a.n_cur;
+  }
   const int total = a.tiles_m * a.tiles_n;
   const int per_xcd = (total + 7) / 8;
-  const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int lin = (bx & 7) * per_xcd + (bx >> 3);
   if (lin >= total) return;
   const int tn = lin / a.tiles_m, tm = lin - tn * a.tiles_m;
   const int m0 = tm * BM, n0 = tn * BN;
@@ -504,13 +641,14 @@ bool tile_fits(const TileShape &t, int kdim, int section, int head_dim, bool den
 // 64 us) beats one that fills all of them one and a half times (128x128: 384 tiles, 88 us).
 constexpr float kTileMicros[kNumTiles] = {125.f, 66.f, 41.f, 40.f, 25.f};
 
-int pick_tile(int M, int N, int kdim, int section, int head_dim, bool dense) {
+// extra: workgroups that ride in the launch and need a compute unit each (the current tokens' rows)
+int pick_tile(int M, int N, int kdim, int section, int head_dim, bool dense, int extra = 0) {
   int pick = -1;
   float best = 0.f;
   for (int i = 0; i < kNumTiles; ++i) {
     if (!tile_fits(kTiles[i], kdim, section, head_dim, dense)) continue;
     const long long tiles = (long long)((M + kTiles[i].bm - 1) / kTiles[i].bm) * (N / kTiles[i].bn);
-    const float est = float((tiles + 255) / 256) * kTileMicros[i];
+    const float est = float((tiles + extra + 255) / 256) * kTileMicros[i];
     if (pick < 0 || est < best) {
       pick = i;
       best = est;
@@ -528,7 +666,7 @@ void launch_tile(ScopedTimer &t, hipStream_t stream, int pick, GemmArgs &a) {
   a.tiles_m = (a.M + kTiles[pick].bm - 1) / kTiles[pick].bm;
   a.tiles_n = a.N / kTiles[pick].bn;
   const int total = a.tiles_m * a.tiles_n;
-  const dim3 grid((total + 7) / 8 * 8), block(512);
+  const dim3 grid((total + 7) / 8 * 8 + a.n_cur), block(512);
   //                                              BM   BN  BK KG WM WN LS NS
   switch (pick) {
     case 0: ADORE_LAUNCH(t, (rebuild_mfma_kernel<MODE, 256, 256, 32, 1, 2, 4, 4, 2>), grid, block, 0, stream, a); break;
@@ -549,6 +687,8 @@ void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
   a.N_max = c.max_positions; a.r = r; a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.xrps = r; a.cur_pos = 0; a.a_gather = 1; a.res_gather = 0; a.out_rps = 0; a.out_cur = 0;
   a.tiles_m = a.tiles_n = 0;
+  a.n_cur = 0;
+  a.cur_ks = 1;
 }
 
 }  // namespace
@@ -594,6 +734,35 @@ bool fwd_gemm_supported(const adore_config &c) {
 
 namespace {
 
+// Workgroups that take the current tokens' rows inside the tile launch (a multiple of 8; see cur_rows_role) when
+// the contraction is cut ks ways inside a workgroup, or 0 when the rows go through a launch of their own: a
+// width that is no multiple of the role's 256 columns, or ADORE_FWD_CUR_SEPARATE=1 (for comparison runs).
+int cur_row_riders(const GemmArgs &a, int ks) {
+  if (a.N % kCurCols != 0 || a.D % (64 * ks) != 0) return 0;
+  if (const char *e = getenv("ADORE_FWD_CUR_SEPARATE")) {
+    if (atoi(e) != 0) return 0;
+  }
+  const int n = ((a.B + 15) / 16) * (a.N / (kCurCols / ks));
+  return (n + 7) / 8 * 8;
+}
+
+// Tile shape and cut for a forward projection: the cheapest launch by pick_tile's estimate, with the rows of the
+// current tokens spread over as many of the remaining units as a cut of the contraction allows.
+int pick_with_riders(GemmArgs &a, int kdim, int section, int head_dim, bool dense) {
+  a.n_cur = 0;
+  a.cur_ks = 1;
+  const int base = cur_row_riders(a, 1);
+  const int pick = pick_tile(a.M, a.N, kdim, section, head_dim, dense, base);
+  if (pick < 0 || base == 0) return pick;
+  const int tiles = ((a.M + kTiles[pick].bm - 1) / kTiles[pick].bm) * (a.N / kTiles[pick].bn);
+  const int rounds = (tiles + base + 255) / 256;
+  int ks = 1;
+  while (ks < 8 && cur_row_riders(a, ks * 2) > 0 && (tiles + cur_row_riders(a, ks * 2) + 255) / 256 <= rounds) ks *= 2;
+  a.cur_ks = ks;
+  a.n_cur = cur_row_riders(a, ks);
+  return pick;
+}
+
 template <int MODE>
 void launch_cur_rows(ScopedTimer &t, hipStream_t stream, const GemmArgs &a) {
   const int seq_blocks = (a.B + 15) / 16;
@@ -625,11 +794,11 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
   a.M = c.batch * r; a.N = 3 * Hd;
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
-    const int pick = pick_tile(a.M, a.N, c.hidden, Hd, c.head_dim, false);
+    const int pick = pick_with_riders(a, c.hidden, Hd, c.head_dim, false);
     if (pick < 0) return hipErrorInvalidValue;
     launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
   }
-  {
+  if (a.n_cur == 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV_CUR, ctx->stream);
     launch_cur_rows<MODE_QKV>(t, ctx->stream, a);
   }
@@ -655,17 +824,16 @@ hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x
   a.M = c.batch * r; a.N = c.hidden;
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
-    const int pick = pick_tile(a.M, a.N, Hd, c.hidden, c.head_dim, true);
+    const int pick = pick_with_riders(a, Hd, c.hidden, c.head_dim, true);
     if (pick < 0) return hipErrorInvalidValue;
     launch_tile<MODE_OPROJ>(t, ctx->stream, pick, a);
   }
-  {
+  if (a.n_cur == 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ_CUR, ctx->stream);
     launch_cur_rows<MODE_OPROJ>(t, ctx->stream, a);
   }
   return hipGetLastError();
 }
-
 // gi[tok][j] = W_ih[j][:] . x_tok for the ntok tokens of a prompt chunk (token b * per_seq + i at row
 // b * seq_rows + i of x), fp32, on the 128x128 tile.  False if the shape does not fit that tile.
 bool launch_plain_projection(adore_ctx *ctx, ScopedTimer &t, hipStream_t st, const void *x, const void *W, float *out,

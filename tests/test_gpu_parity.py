@@ -376,12 +376,24 @@ def test_rescore_mode_rejects_overrides_and_restore():
     ("r63_d128", dict(L=1, B=1, H=2, d=128, D=256, K=200, R=63, S=260, T=6)),
     # no rebuild budget: the forward is the single-query step with projections around it
     ("r0", dict(L=2, B=2, H=2, d=64, D=128, K=48, R=0, S=60, T=10)),
+    # more than 16 sequences: two blocks of current-token rows, the second nearly empty
+    ("b18", dict(L=2, B=18, H=2, d=128, D=256, K=64, R=4, S=70, T=5)),
 ])
 def test_forward_step_matches_the_forward_oracle(name, kw):
     h = _harness()
     w = Workload("fwd_" + name, dtype="bf16", dprime=32, w_std=0.06, **kw)
     worst, mean = h.forward_lockstep(w, w.T)
     print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    assert mean < 2.0 ** -10
+
+
+def test_forward_step_with_the_current_rows_in_a_launch_of_their_own(monkeypatch):
+    """Widths that are multiples of 256 let the current tokens' rows ride in the tile launches (the cases above
+    with H*d = 256 and 512; r20_d64 and r0 do not); here they are kept out of them at such a width."""
+    monkeypatch.setenv("ADORE_FWD_CUR_SEPARATE", "1")
+    h = _harness()
+    w = Workload("fwd_sep", dtype="bf16", dprime=32, w_std=0.06, L=2, B=2, H=4, d=128, D=512, K=160, R=32, S=200, T=6)
+    worst, mean = h.forward_lockstep(w, w.T)
     assert mean < 2.0 ** -10
 
 
