@@ -16,8 +16,8 @@
 // 16-byte vectors with no transposes.  One kernel template covers a family of
 // output tiles; the launcher takes the largest tile that still gives every compute
 // unit a workgroup (M = 512 at the 7B shape: 128x128, one tile per unit;
-// M >= 2048: 256x256; M <= 128: 128x32).  Larger tiles move fewer LDS bytes per
-// flop, and LDS bandwidth is what the 128x128 tile runs into first.  LDS stages
+// M >= 2048: 256x256; M <= 128: 128x32).  Larger tiles move fewer bytes per flop, from the
+// L2 to the compute unit and through LDS, and that path is what the 128x128 tile runs into first.  LDS stages
 // are XOR-swizzled (conflict-free for 16-byte reads and writes).  The output tile
 // is rounded to bf16 into LDS and leaves as 16-byte vectors: a row of the tile is
 // a run of contiguous head slices of cache rows.
