@@ -158,6 +158,55 @@ def lockstep(w: Workload, steps: int, override=None, check_cache_every=0, wts=No
     return worst, job, orc
 
 
+def sampled_lockstep(w: Workload, steps: int, seqs, whole=lambda t: True):
+    """A workload at its full size on the GPU, the oracle on a few of its sequences.  Sequences do not interact, so
+    an oracle built for the sampled sequences alone (same weights, their rows of every input) must agree with those
+    rows of the full run: scores within 1e-5 and then adopted, slot maps (released and rebuilt positions where the
+    call reports them) identical, outputs and occupied cache rows within the storage type's tolerance."""
+    from oracle.adore_oracle import AdoreOracle
+    from tests.helpers import oracle_config
+    seqs = list(seqs)
+    inp = SyntheticInputs(w)
+    wts = inp.weights()
+    job = GpuJob(w, inp, wts)
+    ws = w.scaled(B=len(seqs))
+    orc = AdoreOracle(oracle_config(ws), wts)
+    hs = job.hidden_np[:, seqs]
+    pk, pv = (a[:, seqs] for a in job.prompt_np)
+    job.init()
+
+    def sampled_snapshot():
+        snap = job.snapshot()
+        return {k: (v[:, seqs] if k.startswith("cache") else v[seqs]) for k, v in snap.items()}
+
+    snap = sampled_snapshot()
+    orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S)
+    gpu_scores = snap["scores"][:, :w.S]
+    assert np.abs(gpu_scores.astype(np.float64) - orc.score[:, :w.S].astype(np.float64)).max() < 1e-5
+    if not np.array_equal(gpu_scores, orc.score[:, :w.S]):
+        orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S, score_override=gpu_scores)
+    assert np.array_equal(snap["slot_pos"], orc.slot_pos), "slot map after init"
+    compare_cache(ws, snap, orc)
+    worst = 0.0
+    for t in range(steps):
+        n = w.S + t
+        qkv = inp.step_qkv(n)
+        one_call = bool(whole(t))
+        out_g, map_g, rel_g, rb_g, score_g = job.step(n, qkv, whole=one_call)
+        out_o, map_o, rel_o, rb_o, own = orc.decode_step(*(a[:, seqs] for a in qkv), hs, hs[0][:, n],
+                                                         score_override=score_g[seqs])
+        assert np.abs(own - score_g[seqs].astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        assert np.array_equal(map_g[seqs], map_o), f"slot map at n={n}"
+        if not one_call:
+            assert np.array_equal(rel_g[seqs], rel_o), f"released at n={n}"
+            assert np.array_equal(rb_g[seqs], rb_o), f"rebuilt at n={n}"
+        err = row_rel_err(out_g[:, seqs], out_o)
+        worst = max(worst, err)
+        assert err < out_tol(w), f"attention output at n={n}: {err}"
+    compare_cache(ws, sampled_snapshot(), orc)
+    return worst, job, orc
+
+
 def compare_cache(w: Workload, snap, orc):
     """Occupied rows of the GPU cache against the oracle's: inserted rows are copies (exact);
     rebuilt rows are fp32-accumulated and rounded once, so a value may land on the neighbouring

@@ -284,6 +284,28 @@ def test_high_batch_reduced():
     job.adore.close()
 
 
+@pytest.mark.timeout(300)
+def test_high_batch_full_size_sampled_sequences():
+    """high_batch at its full size (B128 H32 d128 D4096 K256 R16, prompt 512) through adore_decode_step and, every
+    third step, the fine-grained calls; the oracle follows sequences 0, 77 and 127."""
+    h = _harness()
+    w = workload("high_batch").scaled(T=8)
+    worst, job, _ = h.sampled_lockstep(w, steps=6, seqs=[0, 77, 127], whole=lambda t: t % 3 != 2)
+    print(f"high_batch (full size, 3 of 128 sequences): worst output error {worst:.3e}")
+    job.adore.close()
+
+
+@pytest.mark.timeout(300)
+def test_long_context_full_size_sampled_sequences():
+    """long_context at its full size (B4 H32 d128 D4096 K1024 R32, prompt 8192, Zipf salience): sixteen prompt
+    chunks through the scan, 8000 candidates for the rebuild choice; the oracle follows sequences 1 and 3."""
+    h = _harness()
+    w = workload("long_context").scaled(T=8)
+    worst, job, _ = h.sampled_lockstep(w, steps=5, seqs=[1, 3], whole=lambda t: t % 2 == 0)
+    print(f"long_context (full size, 2 of 4 sequences): worst output error {worst:.3e}")
+    job.adore.close()
+
+
 def test_stack32_reduced_all_layers():
     """The 32-layer stack (attend x 32, one schedule, rebuild x 32 through the fine-grained calls) with small
     heads and hidden size: every layer's outputs, slot maps and cache rows over eight steps, so that a wrong
