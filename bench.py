@@ -140,17 +140,11 @@ def run_stack(w, steps, warmup, prof_steps):
     st = storage_dtype(w)
     total = warmup + steps + prof_steps
     assert w.S + total <= w.N_max, "not enough positions for this many steps"
-    g = torch.Generator(device=DEV)
-    g.manual_seed(w.seed)
+    from gen import DeviceNormals
+    drawer = DeviceNormals(w.seed, DEV)
 
     def randn(shape, std=1.0):
-        out = torch.empty(shape, dtype=st, device=DEV)
-        flat = out.view(-1)
-        piece = 1 << 28
-        for i in range(0, flat.numel(), piece):         # bounded temporaries
-            n = min(piece, flat.numel() - i)
-            flat[i:i + n] = (torch.randn(n, generator=g, device=DEV, dtype=torch.float32) * std).to(st)
-        return out
+        return drawer.normal(shape, std, st)
 
     t0 = time.time()
     dp = w.dprime

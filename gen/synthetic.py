@@ -203,3 +203,26 @@ class SyntheticInputs:
             ks.append(self._store(k))
             vs.append(self._normal((w.B, w.H, w.d), w.act_std, _T_V, l, n))
         return np.stack(qs), np.stack(ks), np.stack(vs)
+
+
+class DeviceNormals:
+    """Large tensors drawn on the GPU from one seeded torch generator (tens of GB, which the host generator above
+    would take minutes to produce).  N(0, std) rounded to the storage type; draws come in a fixed order, in
+    pieces, so the temporaries stay bounded."""
+
+    def __init__(self, seed: int, device: str):
+        import torch
+        self.torch = torch
+        self.device = device
+        self.g = torch.Generator(device=device)
+        self.g.manual_seed(seed)
+
+    def normal(self, shape, std, dtype):
+        torch = self.torch
+        out = torch.empty(shape, dtype=dtype, device=self.device)
+        flat = out.view(-1)
+        piece = 1 << 28
+        for i in range(0, flat.numel(), piece):
+            n = min(piece, flat.numel() - i)
+            flat[i:i + n] = (torch.randn(n, generator=self.g, device=self.device, dtype=torch.float32) * std).to(dtype)
+        return out

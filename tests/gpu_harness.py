@@ -207,6 +207,85 @@ def sampled_lockstep(w: Workload, steps: int, seqs, whole=lambda t: True):
     return worst, job, orc
 
 
+def stack_sampled(w: Workload, steps: int, seqs):
+    """A layer stack too large for host-side inputs, at its full size: W_kv, hidden states and prompt K/V are drawn
+    on the device (gen.DeviceNormals) and only the rows of the sampled sequences (and W_kv) come back for the
+    oracle.  Every step through attend x L, schedule, rebuild x L.  Checks as in sampled_lockstep, every layer."""
+    from gen import DeviceNormals
+    from oracle.adore_oracle import AdoreOracle
+    from tests.helpers import oracle_config
+    seqs = list(seqs)
+    st = storage_dtype(w)
+    drawer = DeviceNormals(w.seed, DEV)
+    small = SyntheticInputs(w.scaled(L=1, H=1, d=64, B=1)).weights()   # controller tensors do not depend on L, H, d, B
+    dev_w = {k: to_dev(v, st if k in ("gru_w_ih", "gru_w_hh") else torch.float32) for k, v in small.items() if k != "w_kv"}
+    dev_w["w_kv"] = drawer.normal((w.L, 2 * w.H * w.d, w.D), w.w_std, st)
+    hidden = drawer.normal((w.L, w.B, w.N_max, w.D), w.act_std, st)
+    prompt_k = drawer.normal((w.L, w.B, w.H, w.S, w.d), w.act_std, st)
+    prompt_v = drawer.normal((w.L, w.B, w.H, w.S, w.d), w.act_std, st)
+    adore = Adore(adore_config(w), dev_w, DEV)
+    adore.init_cache(prompt_k, prompt_v, hidden, hidden[0][:, :w.S].contiguous(), None, w.S)
+    state = adore.empty_state()
+    out = torch.empty((w.L, w.B, w.H, w.d), dtype=torch.float32, device=DEV)
+    slot_map = torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=DEV)
+    released = torch.empty((w.B, w.H, w.R + 1), dtype=torch.int32, device=DEV)
+    rebuilt = torch.empty((w.B, max(w.R, 1)), dtype=torch.int32, device=DEV)
+
+    def host(t):
+        return t.float().cpu().numpy() if t.dtype.is_floating_point else t.cpu().numpy()
+
+    def sampled_state():
+        adore.get_state(**state)
+        torch.cuda.synchronize()
+        return {k: host(v[:, seqs] if k.startswith("cache") else v[seqs]) for k, v in state.items()}
+
+    ws = w.scaled(B=len(seqs))
+    wts = dict(small, w_kv=host(dev_w["w_kv"]))
+    orc = AdoreOracle(oracle_config(ws), wts)
+    hs = host(hidden[:, seqs])
+    pk, pv = host(prompt_k[:, seqs]), host(prompt_v[:, seqs])
+    snap = sampled_state()
+    orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S)
+    gpu_scores = snap["scores"][:, :w.S]
+    assert np.abs(gpu_scores.astype(np.float64) - orc.score[:, :w.S].astype(np.float64)).max() < 1e-5
+    if not np.array_equal(gpu_scores, orc.score[:, :w.S]):
+        orc.init_cache(pk, pv, hs, hs[0][:, :w.S], w.S, score_override=gpu_scores)
+    assert np.array_equal(snap["slot_pos"], orc.slot_pos), "slot map after init"
+    compare_cache(ws, snap, orc)
+    inp = SyntheticInputs(w)
+    worst = 0.0
+    for t in range(steps):
+        n = w.S + t
+        q, k, v = inp.step_qkv(n)
+        qd, kd, vd = (to_dev(a, st) for a in (q, k, v))
+        for l in range(w.L):
+            adore.attend(l, qd[l], kd[l], vd[l], out[l])
+        adore.schedule(hidden[0][:, n].contiguous(), None, slot_map, released, rebuilt)
+        for l in range(w.L):
+            adore.rebuild(l, hidden[l])
+        adore.get_state(scores=state["scores"])
+        torch.cuda.synchronize()
+        score_g = state["scores"][:, n].cpu().numpy()
+        out_o, map_o, rel_o, rb_o, own = orc.decode_step(q[:, seqs], k[:, seqs], v[:, seqs], hs, hs[0][:, n],
+                                                         score_override=score_g[seqs])
+        assert np.abs(own - score_g[seqs].astype(np.float64)).max() < 1e-5, f"sigma at n={n}"
+        assert np.array_equal(slot_map.cpu().numpy()[seqs], map_o), f"slot map at n={n}"
+        assert np.array_equal(released.cpu().numpy()[seqs], rel_o), f"released at n={n}"
+        assert np.array_equal(rebuilt.cpu().numpy()[seqs][:, :w.R], rb_o), f"rebuilt at n={n}"
+        # Thousands of rows per step.  A rebuilt cache row may differ from the oracle's by one unit in the last place
+        # (compare_cache: fp32 against fp64 accumulation, one rounding each), 2^-7 of the entry; a row of the output
+        # whose softmax sits on such a row inherits up to that much on top of the attention's own 2e-3.  So: every
+        # row within 2e-3 + 2^-7, and all but a handful within 2e-3.
+        got = out.cpu().numpy().astype(np.float64)[:, seqs]
+        e = np.abs(got - out_o).max(axis=-1) / np.maximum(np.abs(out_o).max(axis=-1), 1e-30)
+        worst = max(worst, float(e.max()))
+        assert e.max() < out_tol(w) + 2.0 ** -7, f"attention output at n={n}: {e.max()}"
+        assert (e >= out_tol(w)).mean() <= 0.005, f"attention output at n={n}: {(e >= out_tol(w)).sum()} rows beyond {out_tol(w)}"
+    compare_cache(ws, sampled_state(), orc)
+    adore.close()
+    return worst
+
+
 def compare_cache(w: Workload, snap, orc):
     """Occupied rows of the GPU cache against the oracle's: inserted rows are copies (exact);
     rebuilt rows are fp32-accumulated and rounded once, so a value may land on the neighbouring

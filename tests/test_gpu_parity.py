@@ -306,6 +306,17 @@ def test_long_context_full_size_sampled_sequences():
     job.adore.close()
 
 
+@pytest.mark.timeout(900)
+def test_stack32_full_size_sampled_sequences():
+    """stack32 at its full size (L32 B32 H32 d128 D4096 K512 R32, prompt 2048: 9 GB of cache, 21 GB of hidden
+    states, offsets beyond 32 bits in every layer-indexed tensor), inputs drawn on the device; the oracle follows
+    sequences 5 and 31 through every layer."""
+    h = _harness()
+    w = workload("stack32").scaled(T=3)
+    worst = h.stack_sampled(w, steps=2, seqs=[5, 31])
+    print(f"stack32 (full size, 2 of 32 sequences): worst output error {worst:.3e}")
+
+
 def test_stack32_reduced_all_layers():
     """The 32-layer stack (attend x 32, one schedule, rebuild x 32 through the fine-grained calls) with small
     heads and hidden size: every layer's outputs, slot maps and cache rows over eight steps, so that a wrong
