@@ -151,6 +151,61 @@ def test_decode_step_entry_point_and_determinism():
         assert np.array_equal(s0, s1), key
 
 
+def test_two_contexts_interleaved_do_not_disturb_each_other():
+    """Contexts are independent: a job stepped alone and the same job stepped in turns with a second context of
+    another shape (same stream, one with the whole-step call, one with the fine-grained calls, no synchronisation
+    between them) give the same bits."""
+    h = _harness()
+    wa = Workload("ctx_a", L=1, B=2, H=4, d=128, D=256, K=72, R=6, S=90, T=10, dtype="bf16", dprime=128)
+    wb = Workload("ctx_b", L=2, B=3, H=2, d=64, D=128, K=40, R=9, S=30, T=10, dtype="bf16", dprime=32)
+    ia, ib = SyntheticInputs(wa), SyntheticInputs(wb)
+
+    def step_a(job, n):
+        q, k, v = (h.to_dev(a[0], job.st) for a in ia.step_qkv(n))
+        job.adore.decode_step(q, k, v, job.hidden[0], job.hidden[0][:, n].contiguous(), None, job.out[0], job.slot_map)
+
+    def step_b(job, n):
+        q, k, v = (h.to_dev(a, job.st) for a in ib.step_qkv(n))
+        for l in range(wb.L):
+            job.adore.attend(l, q[l], k[l], v[l], job.out[l])
+        job.adore.schedule(job.hidden[0][:, n].contiguous(), None, job.slot_map, job.released, job.rebuilt)
+        for l in range(wb.L):
+            job.adore.rebuild(l, job.hidden[l])
+
+    alone = h.GpuJob(wa, ia)
+    alone.init()
+    for t in range(wa.T):
+        step_a(alone, wa.S + t)
+    want = alone.snapshot()
+    want_out = alone.out.cpu().numpy().copy()
+    alone.adore.close()
+
+    a, b = h.GpuJob(wa, ia), h.GpuJob(wb, ib)
+    a.init()
+    b.init()
+    for t in range(wa.T):
+        step_a(a, wa.S + t)
+        step_b(b, wb.S + t)
+    got = a.snapshot()
+    assert np.array_equal(a.out.cpu().numpy(), want_out)
+    occ = want["slot_pos"] >= 0
+    assert np.array_equal(got["slot_pos"], want["slot_pos"])
+    assert np.array_equal(got["scores"][:, :wa.S + wa.T], want["scores"][:, :wa.S + wa.T])
+    assert np.array_equal(got["z"], want["z"])
+    for key in ("cache_k", "cache_v"):
+        assert np.array_equal(got[key][0][occ], want[key][0][occ]), key
+    # and the second context followed its own oracle meanwhile: its trajectory alone, for comparison
+    b2 = h.GpuJob(wb, ib)
+    b2.init()
+    for t in range(wb.T):
+        step_b(b2, wb.S + t)
+    sb, sb2 = b.snapshot(), b2.snapshot()
+    assert np.array_equal(sb["slot_pos"], sb2["slot_pos"])
+    assert np.array_equal(b.out.cpu().numpy(), b2.out.cpu().numpy())
+    for j in (a, b, b2):
+        j.adore.close()
+
+
 def test_state_snapshot_and_restore():
     h = _harness()
     w = Workload("snap", L=1, B=2, H=2, d=64, D=128, K=40, R=4, S=60, T=12, dtype="bf16", dprime=32)
