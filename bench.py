@@ -69,7 +69,10 @@ def run_gpu(w, steps, warmup, prof_steps, ordered_steps=0):
     job = GpuJob(w, inp, ordered=INPUTS_ORDERED)
     log(f"inputs generated and uploaded in {time.time() - t0:.1f}s")
     job.init()
-    if w.S + warmup + steps + prof_steps + ordered_steps > w.N_max:
+    room = w.N_max - w.S - warmup - steps          # positions left for the untimed extras
+    assert room >= 0, "not enough positions for this many steps"
+    prof_steps = min(prof_steps, room)
+    if ordered_steps > room - prof_steps:
         ordered_steps = 0
     total = warmup + steps + prof_steps + ordered_steps
     assert w.S + total <= w.N_max, "not enough positions for this many steps"
@@ -417,6 +420,11 @@ def main():
         elapsed /= w.L                       # the metric is per decode layer
         args.no_cpu_baseline = True          # the oracle sample is defined on the single-layer workloads
     else:
+        extra = args.profile_steps + args.warmup + args.steps // 2
+        if args.warmup + args.steps + extra > w.T:
+            # a longer run than the workload's T decode steps: more positions (the shapes stay; the riding
+            # selections keep a sequence's scores in LDS, which bounds the positions at about 4400)
+            w = w.scaled(T=max(w.T, min(args.warmup + args.steps + extra, 4400 - w.S)))
         elapsed, per_kernel_us, other = run_gpu(w, args.steps, args.warmup, args.profile_steps,
                                                 ordered_steps=args.warmup + args.steps // 2)
     ms_per_step = 1e3 * elapsed / args.steps
