@@ -643,3 +643,81 @@ def test_inputs_produced_on_the_stream_are_waited_for():
             assert np.array_equal(g, r), f"{what} at n={n}"
     ref.adore.close()
     lazy.adore.close()
+
+
+# ---- a sweep of random small shapes ----------------------------------------------------------------------
+def _random_workloads(count, seed):
+    """Small shapes drawn at random within what the library documents as supported: every axis ragged against the
+    kernels' tiles (K against 64 slots per wave, B against 16 sequences per controller tile, H against 4 heads per
+    release workgroup, R + 1 against the free list, S on both sides of the cache size)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        d = int(rng.choice([64, 128]))
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        K = int(rng.integers(4, 260))
+        R = int(rng.integers(0, min(K - 2, 40) + 1))
+        L = int(rng.choice([1, 1, 2, 3]))
+        S = int(rng.integers(1, 2 * K + 2))
+        kw = dict(L=L, B=int(rng.integers(1, 6)), H=int(rng.integers(1, 7)), d=d,
+                  D=int(rng.choice([64, 128, 192, 256, 384])), K=K, R=R, S=S, T=int(rng.integers(6, 14)),
+                  dtype=dtype, dprime=int(rng.choice([8, 32, 128])))
+        out.append((f"rand{i}", kw, str(rng.choice(["fine", "whole", "mixed"])) if L == 1 else "fine",
+                    bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("name,kw,calls,ordered", _random_workloads(64, 20240702))
+def test_random_small_configurations(name, kw, calls, ordered):
+    h = _harness()
+    w = Workload(name, **kw)
+    whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=3, whole=whole, ordered=ordered)
+    job.adore.close()
+
+
+def _random_rescore_workloads(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        K = int(rng.integers(6, 120))
+        out.append((f"rrand{i}", dict(L=int(rng.choice([1, 2])), B=int(rng.integers(1, 4)), H=int(rng.integers(1, 5)),
+                                      d=int(rng.choice([64, 128])), D=int(rng.choice([64, 128, 256])), K=K,
+                                      R=int(rng.integers(0, min(K - 2, 12) + 1)), S=int(rng.integers(1, 2 * K)),
+                                      T=int(rng.integers(6, 12)), dtype=str(rng.choice(["bf16", "f32"])),
+                                      dprime=int(rng.choice([8, 32, 128])), pos_scale=2.0 ** -int(rng.integers(3, 8)),
+                                      rescore=True)))
+    return out
+
+
+@pytest.mark.parametrize("name,kw", _random_rescore_workloads(12, 7))
+def test_random_small_configurations_rescore(name, kw):
+    h = _harness()
+    w = Workload(name, **kw)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=(lambda t: t % 2 == 0) if w.L == 1 else None)
+    job.adore.close()
+
+
+def _random_forward_workloads(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        d = int(rng.choice([64, 128]))
+        H = int(rng.choice([2, 4, 6] if d == 64 else [1, 2, 3, 4]))
+        K = int(rng.integers(8, 220))
+        out.append((f"frand{i}", dict(L=int(rng.choice([1, 2, 3])), B=int(rng.integers(1, 20)), H=H, d=d,
+                                      D=int(rng.choice([128, 256, 384, 512])), K=K,
+                                      R=int(rng.integers(0, min(K - 2, 63) + 1)), S=int(rng.integers(1, 2 * K)),
+                                      T=int(rng.integers(4, 9)))))
+    return out
+
+
+@pytest.mark.parametrize("name,kw", _random_forward_workloads(16, 11))
+def test_random_small_configurations_forward(name, kw):
+    h = _harness()
+    # weights scaled with the width (each projection about norm-preserving, as in the fixed cases above at D = 256):
+    # with larger ones the rows grow from layer to layer, the softmax sharpens, and what the test then measures is
+    # how three layers amplify a one-unit rounding difference, not whether a layer is computed correctly
+    w = Workload(name, dtype="bf16", dprime=32, w_std=0.96 / np.sqrt(kw["D"]), **kw)
+    worst, mean = h.forward_lockstep(w, w.T)
+    assert mean < 2.0 ** -10
