@@ -721,3 +721,27 @@ def test_random_small_configurations_forward(name, kw):
     w = Workload(name, dtype="bf16", dprime=32, w_std=0.96 / np.sqrt(kw["D"]), **kw)
     worst, mean = h.forward_lockstep(w, w.T)
     assert mean < 2.0 ** -10
+
+
+def _random_medium_workloads(count, seed):
+    """Shapes between the small cases and the benchmark's: several GEMM tiles per axis (all five tile shapes get
+    picked across the sweep), rows of up to 1024 slots, more than 16 sequences."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        K = int(rng.integers(200, 1025))
+        R = int(rng.integers(8, 49))
+        out.append((f"mrand{i}", dict(L=1, B=int(rng.integers(1, 25)), H=int(rng.integers(4, 17)), d=128,
+                                      D=int(rng.choice([512, 1024, 2048])), K=K, R=R,
+                                      S=int(rng.integers(K // 2, 2 * K)), T=5, dtype="bf16", dprime=128),
+                    str(rng.choice(["fine", "whole", "mixed"])), bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("name,kw,calls,ordered", _random_medium_workloads(10, 3))
+def test_random_medium_configurations(name, kw, calls, ordered):
+    h = _harness()
+    w = Workload(name, **kw)
+    whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=2, whole=whole, ordered=ordered)
+    job.adore.close()
