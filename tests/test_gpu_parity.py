@@ -532,6 +532,16 @@ def test_decode_step_call_matches_the_oracle(name, kw, steps):
     job.adore.close()
 
 
+def test_decode_step_call_on_long_sequences():
+    """Beyond about 4500 positions a sequence's scores and ranking keys no longer fit the LDS of the riding selections,
+    and adore_decode_step goes through the selection kernels on the side stream.  5000-token prompts, rows of 300
+    slots, 9 heads; whole-step calls mixed with the fine-grained ones."""
+    h = _harness()
+    w = Workload("ds_long", L=1, B=2, H=9, d=64, D=128, K=300, R=20, S=5000, T=10, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5, whole=lambda t: t % 4 != 3)
+    job.adore.close()
+
+
 def test_decode_step_call_mixed_with_fine_grained_calls():
     """Steps alternate in blocks between adore_decode_step and attend / schedule / rebuild: the reserved slot is
     handed over correctly in both directions and the side stream catches up when the selections move back to it."""
