@@ -6,16 +6,17 @@
 // (n, S, K, R), so the host knows every launch shape without reading results
 // back:  o = occupied_before + 1,  x = max(0, o - m),  r = min(R, n + 1 - min(o, m)).
 //
-// Two streams.  Attention and the rebuild GEMM run on the caller's stream.  The controller and the
-// two selections run on a side stream owned by the context: they depend on neither the attention
-// output nor the cache contents, only on the previous step's selections, so the chain of step n+1
-// runs under the GEMM of step n (and the attention of step n+1).  The GEMM waits for its own step's
-// chain (an event per step: a true dependency).  In the other direction there is only a hazard: the
-// chain must not overwrite lists that an attention still reads.  slot_pos / insert_slot / free_list /
-// rebuilt_pos are therefore rings of kRing copies: the chain of step n writes copy (n + 1) % kRing,
-// whose last reader was the attention of step n - kRing + 1, and the side stream waits for the
-// caller's stream only once in kSyncEvery steps: at a step n that is a multiple of kSyncEvery it waits
-// for the attention of step n - 2, which covers the chains of steps n .. n + kSyncEvery - 1 as long as
+// Streams.  Attention and the rebuild GEMM run on the caller's stream.  The two selections run on a side stream
+// owned by the context, and the controller on a second one (static scores; in RESCORE mode it runs on the
+// selections' stream ahead of them): they depend on neither the attention output nor the cache contents.  The
+// selections of step n rank the tokens before n, so they wait for the controller of step n-1 (ev_ctrl), not
+// for their own step's; the chain of step n+1 runs under the GEMM of step n (and the attention of step n+1).
+// The GEMM waits for its own step's selections (ev_join, one event per step: a true dependency).  In the other
+// direction there is only a hazard: the selections must not overwrite lists that an attention still reads.
+// slot_pos / insert_slot / free_list / rebuilt_pos are therefore rings of kRing copies: the selections of step n
+// write copy (n + 1) % kRing, whose last reader was the attention of step n - kRing + 1, and their stream waits
+// for the caller's stream only once in kSyncEvery steps: at a step n that is a multiple of kSyncEvery it waits
+// for the attention of step n - 2, which covers the steps n .. n + kSyncEvery - 1 as long as
 // n + kSyncEvery - 1 - (kRing - 1) <= n - 2.  (Every cross-stream event costs several microseconds on
 // the GPU and on the host; with one wait per step in each direction they added up to 9 us per step.)
 // Inputs.  The side kernels read what the caller passes to a step (x_n, score_override).  By default
@@ -148,6 +149,8 @@ void choose_split(adore_ctx *ctx) {
 int ensure_side_stream(adore_ctx *ctx) {
   if (!ctx->overlap || ctx->side_ready) return ADORE_OK;
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_ctrl, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_att, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming) == hipSuccess;
@@ -161,11 +164,27 @@ hipError_t order_side_after_caller(adore_ctx *ctx) {
   if (!ctx->overlap || !ctx->ordered) return hipSuccess;
   hipError_t e = hipEventRecord(ctx->ev_in, ctx->stream);
   if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_in, 0);
+  if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side2, ctx->ev_in, 0);
   return e;
 }
 
 // Whether the side stream may run ahead of the caller's stream (and so needs the periodic wait of the ring).
 bool runs_ahead(const adore_ctx *ctx) { return ctx->overlap && !ctx->ordered; }
+
+// The controller of the current step.  Static scores: on its own stream, so that the selections of the next step
+// wait for it (ev_ctrl) but those of this step do not queue behind it; they do not need its score (the current
+// token is exempt from release and holds a row).  RESCORE mode: on the selections' stream, ahead of them.
+hipError_t launch_controller(adore_ctx *ctx, const void *x_n, int seq_rows, const float *score_override) {
+  const adore_config &c = ctx->cfg;
+  const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
+  hipStream_t st = rescore ? ctx->side : ctx->side2;
+  int ksplit = 1;
+  hipError_t e = launch_ctrl_input(ctx, st, x_n, c.batch, 1, seq_rows, &ksplit);
+  if (e == hipSuccess) e = launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit);
+  if (e == hipSuccess && rescore) e = launch_rescore(ctx, st, ctx->n);
+  if (e == hipSuccess && ctx->overlap) e = hipEventRecord(ctx->ev_ctrl, st);
+  return e;
+}
 
 void reset_step(adore_ctx *ctx) {
   std::fill(ctx->attended.begin(), ctx->attended.end(), 0);
@@ -238,7 +257,8 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->overlap = !(no && atoi(no) != 0);
   const char *nr = getenv("ADORE_NO_RIDE");
   ctx->ride = ctx->overlap && !(nr && atoi(nr) != 0);
-  ctx->side = ctx->stream;
+  ctx->side = ctx->side2 = ctx->stream;
+  ctx->ev_ctrl = nullptr;
   ctx->ev_att = ctx->ev_join = ctx->ev_in = nullptr;
   ctx->ordered = true;
   ctx->steps_done = 0;
@@ -261,8 +281,10 @@ int adore_destroy(adore_ctx *ctx) {
   for (auto &e : ctx->event_pool) (void)hipEventDestroy(e);
   if (ctx->overlap && ctx->side_ready) {
     (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamSynchronize(ctx->side2);
     (void)hipStreamDestroy(ctx->side);
-    for (hipEvent_t e : {ctx->ev_att, ctx->ev_join, ctx->ev_in})
+    (void)hipStreamDestroy(ctx->side2);
+    for (hipEvent_t e : {ctx->ev_att, ctx->ev_join, ctx->ev_in, ctx->ev_ctrl})
       if (e) (void)hipEventDestroy(e);
   }
   delete ctx;
@@ -287,7 +309,10 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
 
   // init runs on the caller's stream only; anything a previous job left on the side stream ends first
   if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
-  if (ctx->overlap) ADORE_TRY(hipStreamSynchronize(ctx->side));
+  if (ctx->overlap) {
+    ADORE_TRY(hipStreamSynchronize(ctx->side));
+    ADORE_TRY(hipStreamSynchronize(ctx->side2));
+  }
   hipStream_t st = ctx->stream;
   ctx->cur = 0;
   // controller over the prompt: z_{-1} = 0, tokens in order, in chunks
@@ -313,7 +338,10 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   }
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, st));   // the first selections wait for everything above
   ctx->steps_done = 0;
-  if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_join, st));   // the forward's first step waits for "its selections"
+  if (ctx->overlap) {   // what the first step waits for is all above
+    ADORE_TRY(hipEventRecord(ctx->ev_join, st));
+    ADORE_TRY(hipEventRecord(ctx->ev_ctrl, st));
+  }
   ctx->n = S;
   ctx->occ = keep + r0;
   ctx->inited = true;
@@ -360,12 +388,10 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   }
   ctx->rode = false;
 
-  // the controller touches only its own state and the score array: it may run as early as the
-  // previous step's selections are done
-  int ksplit = 1;
-  ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, 1, &ksplit));
-  ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
-  if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
+  // the selections rank the tokens before the current one: they wait for the previous step's controller, not for
+  // this step's (which touches only its own state and the score array and may run as early as its inputs allow)
+  if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_ctrl, 0));
+  ADORE_TRY(launch_controller(ctx, x_n, 1, score_override));
   // copy `dst` was `cur` kRing - 1 steps ago: see the note on the ring at the top of this file
   if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
@@ -397,7 +423,7 @@ int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
 }
 
 // The whole step of one layer with the two selections riding in the attention launch (static score mode).
-// Neither selection of step n looks at the current token's score, so only the controller stays on the side
+// Neither selection of step n looks at the current token's score, so only the controller stays on a side
 // stream; what it writes (the score of token n) is first needed by the selections of step n+1, which is
 // what the one wait at the top is for.  No other event, and no kernel of the selections runs next to the GEMM.
 int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new, const void *hidden_store,
@@ -411,11 +437,8 @@ int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void 
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
   const int dst = (ctx->cur + 1) % kRing;
   ADORE_TRY(order_side_after_caller(ctx));
-  ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));   // the controller of the step before
-  int ksplit = 1;
-  ADORE_TRY(launch_ctrl_input(ctx, ctx->side, x_n, c.batch, 1, 1, &ksplit));
-  ADORE_TRY(launch_ctrl_cell(ctx, ctx->side, 1, ctx->n, score_override, 1, ksplit));
-  ADORE_TRY(hipEventRecord(ctx->ev_join, ctx->side));
+  ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_ctrl, 0));   // the controller of the step before
+  ADORE_TRY(launch_controller(ctx, x_n, 1, score_override));
   RidingSelections sel;
   sel.dst = dst; sel.x = x; sel.r = r;
   sel.map_out = slot_map; sel.rel_out = nullptr; sel.rb_out = nullptr;
@@ -508,10 +531,8 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const int r_next = pool < c.rebuild_budget ? pool : c.rebuild_budget;
     const int src = ctx->cur, dst = (ctx->cur + 1) % kRing;
     hipStream_t st = ctx->side;
-    int ksplit = 1;
-    ADORE_TRY(launch_ctrl_input(ctx, st, x_n, c.batch, 1, c.max_positions, &ksplit));
-    ADORE_TRY(launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit));
-    if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n));
+    if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_ctrl, 0));   // the previous step's controller
+    ADORE_TRY(launch_controller(ctx, x_n, c.max_positions, score_override));
     if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));   // see the note on the ring
     ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
     ADORE_TRY(launch_rebuild_select(ctx, st, dst, r_next, slot_map, rebuilt_pos));
@@ -547,7 +568,10 @@ int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, 
   const size_t BH = size_t(c.batch) * c.heads;
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
   if (step) *step = ctx->n;
-  if (ctx->overlap && ctx->side_ready) ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));   // the controller's last score
+  if (ctx->overlap && ctx->side_ready) {   // the last selections and the controller's last score
+    ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+    ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_ctrl, 0));
+  }
   if (slot_pos)
     ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos[ctx->cur], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
                              ctx->stream));
@@ -571,7 +595,10 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
   const size_t BH = size_t(c.batch) * c.heads;
   const size_t cache_bytes = size_t(c.layers) * BH * c.cache_slots * c.head_dim * elem_size(c);
   if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
-  if (ctx->overlap) ADORE_TRY(hipStreamSynchronize(ctx->side));
+  if (ctx->overlap) {
+    ADORE_TRY(hipStreamSynchronize(ctx->side));
+    ADORE_TRY(hipStreamSynchronize(ctx->side2));
+  }
   // count the occupied slots and find the reserved slot of every row on the host
   std::vector<int32_t> host(BH * c.cache_slots);
   ADORE_TRY(hipMemcpyAsync(host.data(), slot_pos, host.size() * 4, hipMemcpyDeviceToHost, ctx->stream));
@@ -640,7 +667,10 @@ int adore_set_timing(adore_ctx *ctx, int32_t enable) {
 int adore_read_timing(adore_ctx *ctx, float *ms, int32_t *launches) {
   if (!ctx || !ms || !launches) return ADORE_E_INVALID;
   ADORE_TRY(hipStreamSynchronize(ctx->stream));
-  if (ctx->overlap && ctx->side_ready) ADORE_TRY(hipStreamSynchronize(ctx->side));
+  if (ctx->overlap && ctx->side_ready) {
+    ADORE_TRY(hipStreamSynchronize(ctx->side));
+    ADORE_TRY(hipStreamSynchronize(ctx->side2));
+  }
   for (int i = 0; i < ADORE_N_KERNELS; ++i) {
     ms[i] = 0.f;
     launches[i] = 0;

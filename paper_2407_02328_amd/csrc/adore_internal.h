@@ -38,7 +38,9 @@ struct adore_ctx {
   adore_config cfg;
   adore_weights w;
   hipStream_t stream;        // the caller's stream: attention and the rebuild GEMM
-  hipStream_t side;          // controller and selections; equals `stream` when overlap is off
+  hipStream_t side;          // the selections (and, in RESCORE mode, the controller before them); equals `stream` when overlap is off
+  hipStream_t side2;         // static scores: the controller, off the selections' chain; equals `stream` when overlap is off
+  hipEvent_t ev_ctrl;        // recorded behind the controller of a step (on whichever stream ran it)
   hipEvent_t ev_att;         // recorded on `stream` after the last attention of a step, once in kSyncEvery steps
   hipEvent_t ev_join;        // recorded on `side` after the selections of a step
   hipEvent_t ev_in;          // ordered inputs: recorded on `stream` at the top of a step, the side stream starts behind it
