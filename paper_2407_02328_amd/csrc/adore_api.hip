@@ -160,11 +160,12 @@ int ensure_side_stream(adore_ctx *ctx) {
 }
 
 // Ordered inputs: the side stream starts a step's work behind everything the caller's stream holds now.
-hipError_t order_side_after_caller(adore_ctx *ctx) {
+// selections: the step has work on the selections' stream as well (not when they ride in the attention launch).
+hipError_t order_side_after_caller(adore_ctx *ctx, bool selections = true) {
   if (!ctx->overlap || !ctx->ordered) return hipSuccess;
   hipError_t e = hipEventRecord(ctx->ev_in, ctx->stream);
-  if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_in, 0);
-  if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side2, ctx->ev_in, 0);
+  if (e == hipSuccess && selections) e = hipStreamWaitEvent(ctx->side, ctx->ev_in, 0);
+  if (e == hipSuccess && ctx->side2 != ctx->side) e = hipStreamWaitEvent(ctx->side2, ctx->ev_in, 0);
   return e;
 }
 
@@ -436,7 +437,7 @@ int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void 
   const int pool = ctx->n + 1 - kept;
   const int r = pool < c.rebuild_budget ? pool : c.rebuild_budget;
   const int dst = (ctx->cur + 1) % kRing;
-  ADORE_TRY(order_side_after_caller(ctx));
+  ADORE_TRY(order_side_after_caller(ctx, false));
   ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_ctrl, 0));   // the controller of the step before
   ADORE_TRY(launch_controller(ctx, x_n, 1, score_override));
   RidingSelections sel;
