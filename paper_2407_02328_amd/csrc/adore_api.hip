@@ -7,8 +7,7 @@
 // back:  o = occupied_before + 1,  x = max(0, o - m),  r = min(R, n + 1 - min(o, m)).
 //
 // Streams.  Attention and the rebuild GEMM run on the caller's stream.  The two selections run on a side stream
-// owned by the context, and the controller on a second one (static scores; in RESCORE mode it runs on the
-// selections' stream ahead of them): they depend on neither the attention output nor the cache contents.  The
+// owned by the context, and the controller on a second one: they depend on neither the attention output nor the cache contents.  The
 // selections of step n rank the tokens before n, so they wait for the controller of step n-1 (ev_ctrl), not
 // for their own step's; the chain of step n+1 runs under the GEMM of step n (and the attention of step n+1).
 // The GEMM waits for its own step's selections (ev_join, one event per step: a true dependency).  In the other
@@ -172,17 +171,16 @@ hipError_t order_side_after_caller(adore_ctx *ctx, bool selections = true) {
 // Whether the side stream may run ahead of the caller's stream (and so needs the periodic wait of the ring).
 bool runs_ahead(const adore_ctx *ctx) { return ctx->overlap && !ctx->ordered; }
 
-// The controller of the current step.  Static scores: on its own stream, so that the selections of the next step
-// wait for it (ev_ctrl) but those of this step do not queue behind it; they do not need its score (the current
-// token is exempt from release and holds a row).  RESCORE mode: on the selections' stream, ahead of them.
+// The controller of the current step, on a stream of its own: the selections of the next step wait for it
+// (ev_ctrl), those of this step do not queue behind it.  They do not need its score: the current token is exempt
+// from release and holds a row.  (In RESCORE mode it also writes the current token's score at distance 0 and the
+// vector the later rescorings start from; the tokens before it are rescored on the selections' stream.)
 hipError_t launch_controller(adore_ctx *ctx, const void *x_n, int seq_rows, const float *score_override) {
   const adore_config &c = ctx->cfg;
-  const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
-  hipStream_t st = rescore ? ctx->side : ctx->side2;
+  hipStream_t st = ctx->side2;
   int ksplit = 1;
   hipError_t e = launch_ctrl_input(ctx, st, x_n, c.batch, 1, seq_rows, &ksplit);
   if (e == hipSuccess) e = launch_ctrl_cell(ctx, st, 1, ctx->n, score_override, 1, ksplit);
-  if (e == hipSuccess && rescore) e = launch_rescore(ctx, st, ctx->n);
   if (e == hipSuccess && ctx->overlap) e = hipEventRecord(ctx->ev_ctrl, st);
   return e;
 }
@@ -327,7 +325,7 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   }
   if (rescore) {   // every prompt token as seen from the last one
     ADORE_TRY(launch_ctrl_avec(ctx, st));
-    ADORE_TRY(launch_rescore(ctx, st, S - 1));
+    ADORE_TRY(launch_rescore(ctx, st, S - 1, S - 1));
   }
   // slot map and reserved slot go to copy `cur`, the rebuild lists to `cur + 1` (where a step's GEMM reads
   // them); for the forward, whose first step rebuilds these tokens itself, the lists go to `cur` as well
@@ -393,6 +391,7 @@ int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, in
   // this step's (which touches only its own state and the score array and may run as early as its inputs allow)
   if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_ctrl, 0));
   ADORE_TRY(launch_controller(ctx, x_n, 1, score_override));
+  if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n, ctx->n - 1));
   // copy `dst` was `cur` kRing - 1 steps ago: see the note on the ring at the top of this file
   if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));
   ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
@@ -534,6 +533,7 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     hipStream_t st = ctx->side;
     if (ctx->overlap) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_ctrl, 0));   // the previous step's controller
     ADORE_TRY(launch_controller(ctx, x_n, c.max_positions, score_override));
+    if (c.score_mode == ADORE_SCORE_RESCORE) ADORE_TRY(launch_rescore(ctx, st, ctx->n, ctx->n - 1));
     if (runs_ahead(ctx) && ctx->steps_done % kSyncEvery == 0) ADORE_TRY(hipStreamWaitEvent(st, ctx->ev_att, 0));   // see the note on the ring
     ADORE_TRY(launch_release(ctx, st, src, dst, x, slot_map, released_pos));
     ADORE_TRY(launch_rebuild_select(ctx, st, dst, r_next, slot_map, rebuilt_pos));

@@ -38,8 +38,8 @@ struct adore_ctx {
   adore_config cfg;
   adore_weights w;
   hipStream_t stream;        // the caller's stream: attention and the rebuild GEMM
-  hipStream_t side;          // the selections (and, in RESCORE mode, the controller before them); equals `stream` when overlap is off
-  hipStream_t side2;         // static scores: the controller, off the selections' chain; equals `stream` when overlap is off
+  hipStream_t side;          // the selections (in RESCORE mode the rescoring ahead of them); equals `stream` when overlap is off
+  hipStream_t side2;         // the controller, off the selections' chain; equals `stream` when overlap is off
   hipEvent_t ev_ctrl;        // recorded behind the controller of a step (on whichever stream ran it)
   hipEvent_t ev_att;         // recorded on `stream` after the last attention of a step, once in kSyncEvery steps
   hipEvent_t ev_join;        // recorded on `side` after the selections of a step
@@ -163,9 +163,9 @@ hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int kee
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);
 hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t count);
-// rescore mode: the distance vector W_1 pos_w (once per init), and sigma of tokens 0..n seen from token n
+// rescore mode: the distance vector W_1 pos_w (once per init), and sigma of tokens 0..upto seen from token n
 hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st);
-hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n);
+hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n, int upto);
 // rebuild forward (one layer = qkv projection, attention of the r+1 rows, output projection with residual)
 bool fwd_gemm_supported(const adore_config &c);
 int fwd_attend_max_slots();

@@ -612,19 +612,20 @@ __global__ __launch_bounds__(256) void ctrl_avec_kernel(const float *__restrict_
   }
 }
 
-// sigma_i(n) = sigmoid(out_w . tanh(c_i + (n - i) * pos_scale * a) + out_b) for i = 0..n.  16 lanes per
-// token, 16 tokens per workgroup; grid = (tokens / 16, B).
+// sigma_i(n) = sigmoid(out_w . tanh(c_i + (n - i) * pos_scale * a) + out_b) for i = 0..upto.  16 lanes per
+// token, 16 tokens per workgroup; grid = (tokens / 16, B).  In a step upto = n - 1: the current token's score (distance
+// 0) is the cell kernel's, which runs next to this one.
 __global__ __launch_bounds__(256) void rescore_kernel(const float *__restrict__ cvec,
                                                       const float *__restrict__ avec,
                                                       const float *__restrict__ out_w,
                                                       const float *__restrict__ out_b,
-                                                      float *__restrict__ score, int n, int N_max, int dp,
-                                                      float pos_scale) {
+                                                      float *__restrict__ score, int n, int upto, int N_max,
+                                                      int dp, float pos_scale) {
   __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
   const int b = blockIdx.y;
   const int i = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int lig = threadIdx.x & 15;
-  const int ic = i <= n ? i : n;                 // lanes past the end redo the last token and store nothing
+  const int ic = i <= upto ? i : upto;           // lanes past the end redo the last token and store nothing
   const float delta = float(n - ic) * pos_scale;
   const float *c = cvec + (size_t(b) * N_max + ic) * dp;
   float s = 0.f;
@@ -639,7 +640,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const float *__restrict__ 
   }
 #pragma unroll
   for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-  if (lig == 0 && i <= n) score[size_t(b) * N_max + i] = sigmoidf_(s + out_b[0]);
+  if (lig == 0 && i <= upto) score[size_t(b) * N_max + i] = sigmoidf_(s + out_b[0]);
 }
 
 // Number of D-slices of the bf16 input projection: enough workgroups to cover the chip when
@@ -742,11 +743,12 @@ hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n) {
+hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n, int upto) {
   const adore_config &c = ctx->cfg;
+  if (upto < 0) return hipSuccess;
   ScopedTimer t(ctx, ADORE_KERNEL_RESCORE, st);
-  ADORE_LAUNCH(t, rescore_kernel, dim3((n + 16) / 16, c.batch), dim3(256), 0, st, ctx->cvec, ctx->avec,
-               ctx->w.out_w, ctx->w.out_b, ctx->score, n, c.max_positions, c.ctrl_hidden, c.pos_scale);
+  ADORE_LAUNCH(t, rescore_kernel, dim3((upto + 16) / 16, c.batch), dim3(256), 0, st, ctx->cvec, ctx->avec,
+               ctx->w.out_w, ctx->w.out_b, ctx->score, n, upto, c.max_positions, c.ctrl_hidden, c.pos_scale);
   return hipGetLastError();
 }
 
