@@ -145,14 +145,18 @@ void choose_split(adore_ctx *ctx) {
 
 // The side stream and its events are made on the first call that touches the GPU, so that a
 // context can be created (and its host-side checks exercised) on a machine without one.
+// The context's events only order its streams against each other on one device: no timing, and no system-scope
+// fence (cache write-back and invalidation for the host's and other devices' sake) when they complete.
+constexpr unsigned kSyncEventFlags = hipEventDisableTiming | hipEventDisableSystemFence;
+
 int ensure_side_stream(adore_ctx *ctx) {
   if (!ctx->overlap || ctx->side_ready) return ADORE_OK;
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_ctrl, hipEventDisableTiming) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_att, hipEventDisableTiming) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_ctrl, kSyncEventFlags) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_att, kSyncEventFlags) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_join, kSyncEventFlags) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->ev_in, kSyncEventFlags) == hipSuccess;
   if (!ok) return ADORE_E_HIP;
   ctx->side_ready = true;
   return ADORE_OK;
