@@ -372,8 +372,8 @@ def run_cpu_baseline(w, seqs=16, steps=40):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--profile-steps", type=int, default=50, help="extra steps with per-kernel events")
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
