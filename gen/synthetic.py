@@ -55,6 +55,7 @@ class Workload:
     w_std: float = 0.02      # W_kv
     salience: bool = False   # heavy-tailed per-token offset (long-context workload)
     rescore: bool = False    # controller scores every token again at every step (relative position)
+    rope_base: float = 0.0   # > 0: rotary position embedding with this base on keys/queries made from hidden states
     seed: int = BASE_SEED
 
     @property

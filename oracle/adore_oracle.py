@@ -46,6 +46,15 @@ Readings of points the paper leaves open (each used exactly as stated here):
     rounded once to the storage type.  K/V of the rebuilt tokens are written at the start
     of the step that uses them (layer by layer), not at the end of the step that chose
     them; the choice itself is unchanged.
+  * Rotary position embedding (the paper names it only in its related work on length
+    extrapolation, but the backbones it evaluates rotate q and k by the token's position
+    before the product, so a key that is rebuilt from a hidden state has to be rotated to the
+    position the token had, or it cannot stand next to the cached keys): optional, off when
+    `rope_base` is 0.  The pairing is the half-split one (element j < d/2 of a head and
+    element j + d/2 span a plane that is turned by pos * rope_base**(-2j/d)); the rotation
+    is applied to the unrounded projection, so a rebuilt key is still rounded once.  Keys
+    and queries the caller supplies are taken as they are.  In the rebuild forward the
+    queries of the R+1 rows are rotated as well.
   * Rows never move: a released row frees its slot; incoming rows take the
     lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
     token -> lowest free slot at its insert).
@@ -163,6 +172,27 @@ def rebuild_choice(resident: Sequence[int], n: int, score: np.ndarray, R: int) -
 
 
 # --------------------------------------------------------------------------
+# rotary position embedding (optional; see the readings in the header)
+# --------------------------------------------------------------------------
+def rotary(rows: np.ndarray, positions: Sequence[int], base: float) -> np.ndarray:
+    """rows [r, ..., d] (any number of head axes in between), positions [r]: every vector of
+    row i turned by its position.  With t_j = positions[i] * base**(-2j/d) for j < d/2:
+        out[j]       = x[j] cos t_j - x[j + d/2] sin t_j
+        out[j + d/2] = x[j] sin t_j + x[j + d/2] cos t_j"""
+    x = np.asarray(rows, dtype=F64)
+    d = x.shape[-1]
+    half = d // 2
+    out = np.empty_like(x)
+    for i, pos in enumerate(positions):
+        for j in range(half):
+            t = F64(pos) * F64(base) ** (F64(-2.0) * j / d)
+            lo, hi = x[i, ..., j], x[i, ..., j + half]
+            out[i, ..., j] = lo * np.cos(t) - hi * np.sin(t)
+            out[i, ..., j + half] = lo * np.sin(t) + hi * np.cos(t)
+    return out
+
+
+# --------------------------------------------------------------------------
 # the whole path
 # --------------------------------------------------------------------------
 @dataclass
@@ -179,6 +209,7 @@ class OracleConfig:
     dtype: str            # "f32" | "bf16"
     pos_scale: float
     rescore: bool = False # score every token again at every step, with its distance to the current token
+    rope_base: float = 0.0  # > 0: keys (and, in the rebuild forward, queries) made from hidden states are rotated
 
     @property
     def m(self) -> int:
@@ -233,18 +264,24 @@ class AdoreOracle:
         return out
 
     # -- rebuild ------------------------------------------------------------
-    def _project(self, layer: int, x_rows: np.ndarray) -> np.ndarray:
-        """K/V states of tokens from their hidden states: one rounding of x W_kv^T."""
+    def _project(self, layer: int, x_rows: np.ndarray, positions: Sequence[int]) -> np.ndarray:
+        """K/V states of tokens from their hidden states: one rounding of x W_kv^T, the key half turned
+        to the tokens' positions first when the rotary embedding is on."""
+        c = self.cfg
         if layer not in self._wkv64:                     # [2*H*d, D], rows 0..H*d-1 = W_k
             self._wkv64[layer] = np.asarray(self.wts["w_kv"][layer], dtype=F64)
-        return round_to_storage(x_rows.astype(F64) @ self._wkv64[layer].T, self.cfg.dtype)
+        kv = x_rows.astype(F64) @ self._wkv64[layer].T
+        if c.rope_base > 0:
+            Hd = c.H * c.d
+            kv[:, :Hd] = rotary(kv[:, :Hd].reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd)
+        return round_to_storage(kv, c.dtype)
 
     def _place_rebuilt(self, b: int, rebuilt: List[int], hidden_store: np.ndarray) -> None:
         c = self.cfg
         if not rebuilt:
             return
         for l in range(c.L):
-            kv = self._project(l, hidden_store[l, b, rebuilt, :])           # [r, 2*H*d]
+            kv = self._project(l, hidden_store[l, b, rebuilt, :], rebuilt)  # [r, 2*H*d]
             for h in range(c.H):
                 free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]    # ascending
                 for rho, pos in enumerate(rebuilt):
@@ -417,8 +454,11 @@ class AdoreForwardOracle(AdoreOracle):
             for l in range(c.L):
                 Wq = self._w(self._wq64, "w_q", l)
                 Wo = self._w(self._wo64, "w_o", l)
-                Q = round_to_storage(X @ Wq.T, c.dtype)                  # [r+1, H*d]
-                KV = self._project(l, X)                                 # [r+1, 2*H*d], rounded
+                Q = X @ Wq.T                                             # [r+1, H*d]
+                if c.rope_base > 0:
+                    Q = rotary(Q.reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd)
+                Q = round_to_storage(Q, c.dtype)
+                KV = self._project(l, X, positions)                      # [r+1, 2*H*d], rounded
                 O = np.zeros((len(positions), Hd), dtype=F64)
                 for h in range(c.H):
                     slot_of = {int(p): k for k, p in enumerate(self.slot_pos[b, h]) if p >= 0}

@@ -11,7 +11,8 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def oracle_config(w: Workload) -> OracleConfig:
     return OracleConfig(L=w.L, B=w.B, H=w.H, d=w.d, D=w.D, K=w.K, R=w.R, N_max=w.N_max,
-                        dprime=w.dprime, dtype=w.dtype, pos_scale=w.pos_scale, rescore=w.rescore)
+                        dprime=w.dprime, dtype=w.dtype, pos_scale=w.pos_scale, rescore=w.rescore,
+                        rope_base=w.rope_base)
 
 
 def make_oracle(w: Workload, weights=None):

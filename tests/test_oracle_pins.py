@@ -454,9 +454,20 @@ def _forward_oracle(w, wts=None):
     return O.AdoreForwardOracle(oracle_config(w), wts), inp, wts
 
 
+def _rotate_complex(t, base):
+    """Rotary embedding written with complex numbers (torch): the pair (x[j], x[j + d/2]) is the complex
+    number x[j] + i x[j + d/2], multiplied by exp(i pos base^(-2j/d)).  t: [..., N, d], positions 0..N-1."""
+    N, d = t.shape[-2], t.shape[-1]
+    freq = torch.tensor(float(base), dtype=torch.float64) ** (-torch.arange(0, d, 2, dtype=torch.float64) / d)
+    ang = torch.arange(N, dtype=torch.float64)[:, None] * freq[None, :]
+    z = torch.complex(t[..., :d // 2], t[..., d // 2:]) * torch.polar(torch.ones_like(ang), ang)
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
 def _causal_stack_reference(E, wts, w):
     """Textbook decoder stack of attention-only layers over the whole sequence, torch fp64:
-    x' = x + W_o . causal_attention(W_q x, W_k x, W_v x).  Returns (X_L [B,N,D], K [L,B,H,N,d], V)."""
+    x' = x + W_o . causal_attention(W_q x, W_k x, W_v x), q and k rotated by their positions when the
+    workload asks for the rotary embedding.  Returns (X_L [B,N,D], K [L,B,H,N,d], V)."""
     X = torch.tensor(E.astype(np.float64))
     B, N, _ = X.shape
     Hd = w.H * w.d
@@ -467,20 +478,23 @@ def _causal_stack_reference(E, wts, w):
         Wo = torch.tensor(wts["w_o"][l].astype(np.float64))
         heads = lambda t: t.reshape(B, N, w.H, w.d).transpose(1, 2)       # [B,H,N,d]
         Q, K, V = heads(X @ Wq.T), heads(X @ Wkv[:Hd].T), heads(X @ Wkv[Hd:].T)
+        if w.rope_base > 0:
+            Q, K = _rotate_complex(Q, w.rope_base), _rotate_complex(K, w.rope_base)
         A = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=True)
         X = X + A.transpose(1, 2).reshape(B, N, Hd) @ Wo.T
         Ks.append(K.numpy()); Vs.append(V.numpy())
     return X.numpy(), np.stack(Ks), np.stack(Vs)
 
 
-def test_forward_with_every_released_token_rebuilt_is_a_causal_decoder_stack():
+@pytest.mark.parametrize("rope_base", [0.0, 50.0])
+def test_forward_with_every_released_token_rebuilt_is_a_causal_decoder_stack(rope_base):
     """When R covers the whole pool, every token is in the cache at every step (as a resident or rebuilt), so
     the rebuild forward must give what a plain causal decoder stack gives: the output row of the current
     token, and the rows of the rebuilt tokens at their own positions.  This fixes the mask among the R+1
     query rows (a rebuilt token that saw later tokens would get another state from layer 2 on), the residual,
     the head layout of W_q / W_o, the order of the rows and the slot each K/V row lands in."""
     w = Workload("fwd", L=3, B=2, H=2, d=8, D=16, K=17, R=8, S=10, T=6, dtype="f32", dprime=8,
-                 act_std=1.0, w_std=0.25)
+                 act_std=1.0, w_std=0.25, rope_base=rope_base)
     orc, inp, wts = _forward_oracle(w)
     E = inp.hidden_store_layer(0)                                         # [B, N_max, D] embeddings
     XL, Kref, Vref = _causal_stack_reference(E, wts, w)
@@ -555,18 +569,23 @@ def test_forward_invariants_with_a_small_budget():
         prev = [[int(p) for p in rebuilt[b] if p >= 0] for b in range(w.B)]
 
 
-def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fits():
-    """If the supplied K/V are the projections of the hidden states, a rebuilt row is identical to
-    the row that was released; while |pool| <= R every token is present, so the output is Eq. 1
-    over all tokens."""
-    w = small_workload(B=1, H=2, K=12, R=5, S=4, T=7, dtype="f32")     # m = 6; pool <= 5 up to n = 10
+@pytest.mark.parametrize("rope_base", [0.0, 10000.0])
+def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fits(rope_base):
+    """If the supplied K/V are the projections of the hidden states (the keys turned to their positions when
+    the rotary embedding is on, here by torch complex arithmetic), a rebuilt row is identical to the row that
+    was released; while |pool| <= R every token is present, so the output is Eq. 1 over all tokens."""
+    w = small_workload(B=1, H=2, K=12, R=5, S=4, T=7, dtype="f32", rope_base=rope_base)   # m = 6; pool <= 5 up to n = 10
     orc, inp, wts = make_oracle(w)
     hs = inp.hidden_store()
     W = wts["w_kv"][0].astype(np.float64)
-    kv_all = (hs[0].astype(np.float64) @ W.T).astype(np.float32).astype(np.float64)    # [B,N,2Hd]
+    kv_all = hs[0].astype(np.float64) @ W.T                                            # [B,N,2Hd]
     Hd = w.H * w.d
     k_all = kv_all[:, :, :Hd].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)    # [B,H,N,d]
     v_all = kv_all[:, :, Hd:].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)
+    if rope_base > 0:
+        k_all = _rotate_complex(torch.tensor(np.ascontiguousarray(k_all)), rope_base).numpy()
+    k_all = k_all.astype(np.float32).astype(np.float64)
+    v_all = v_all.astype(np.float32).astype(np.float64)
     orc.init_cache(k_all[None, :, :, :w.S], v_all[None, :, :, :w.S], hs, hs[0][:, :w.S], w.S)
     for n in range(w.S, w.S + w.T):
         q, _, _ = inp.step_qkv(n)
@@ -578,8 +597,8 @@ def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fit
         for h in range(w.H):
             for s in range(w.K):
                 p = slot_map[0, h, s]
-                if p >= 0:
-                    assert np.array_equal(orc.Kc[0, 0, h, s], k_all[0, h, p])
+                if p >= 0:      # with the rotation two fp64 evaluation orders meet: equal up to the fp32 rounding
+                    assert np.abs(orc.Kc[0, 0, h, s] - k_all[0, h, p]).max() <= (2e-7 * np.abs(k_all).max() if rope_base else 0)
                     assert np.array_equal(orc.Vc[0, 0, h, s], v_all[0, h, p])
     assert (rebuilt >= 0).sum() == 5        # the last step did rebuild R tokens
 
@@ -588,7 +607,7 @@ def test_projection_matches_triple_loop_and_torch_matmul():
     w = small_workload(B=1, H=2, d=4, D=6, dtype="bf16")
     orc, inp, wts = make_oracle(w)
     x = inp.hidden_store()[0, 0, :3]
-    got = orc._project(0, x)
+    got = orc._project(0, x, [0, 1, 2])
     W = wts["w_kv"][0]
     naive = np.zeros((3, 2 * w.H * w.d))
     for i in range(3):
@@ -614,3 +633,72 @@ def test_oracle_rejects_bad_budget_and_overrun():
     q, k, v = inp.step_qkv(w.S)
     with pytest.raises(RuntimeError):
         orc.decode_step(q, k, v, inp.hidden_store(), inp.hidden_store()[0][:, 0])
+
+
+# --------------------------------------------------------------------------
+# rotary position embedding (optional reading, see the oracle's header)
+# --------------------------------------------------------------------------
+def test_rotary_is_identity_at_position_zero_and_keeps_lengths():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((4, 3, 16))
+    out = O.rotary(x, [0, 1, 7, 1000], 10000.0)
+    assert np.array_equal(out[0], x[0])
+    np.testing.assert_allclose(np.linalg.norm(out, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-13)
+    assert np.abs(out[1:] - x[1:]).max() > 0.1
+
+
+def test_rotary_in_two_dimensions_is_the_plane_rotation_by_the_position():
+    x = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -3.0]])
+    out = O.rotary(x, [1, 2, 5], 77.0)                   # d = 2: one plane, frequency base^0 = 1
+    for row, p, got in zip(x, [1, 2, 5], out):
+        Rm = np.array([[np.cos(p), -np.sin(p)], [np.sin(p), np.cos(p)]])
+        np.testing.assert_allclose(got, Rm @ row, rtol=0, atol=1e-15)
+
+
+def test_rotary_matches_complex_multiplication_in_torch():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((9, 2, 3, 12))               # positions 0..8, two head axes
+    want = _rotate_complex(torch.tensor(x).permute(1, 2, 0, 3), 500.0).permute(2, 0, 1, 3).numpy()
+    np.testing.assert_allclose(O.rotary(x, list(range(9)), 500.0), want, rtol=0, atol=1e-14)
+
+
+def test_rotary_products_depend_on_the_distance_only():
+    """<rot(q, m), rot(k, n)> = <rot(q, m + s), rot(k, n + s)>: the property the embedding exists for."""
+    rng = np.random.default_rng(7)
+    q, k = rng.standard_normal((1, 32)), rng.standard_normal((1, 32))
+    base = 10000.0
+    ref = float(O.rotary(q, [9], base)[0] @ O.rotary(k, [4], base)[0])
+    for s in (1, 13, 700):
+        assert abs(float(O.rotary(q, [9 + s], base)[0] @ O.rotary(k, [4 + s], base)[0]) - ref) < 1e-11
+    assert abs(float(O.rotary(q, [9], base)[0] @ O.rotary(k, [5], base)[0]) - ref) > 1e-3
+
+
+def test_decode_oracle_rotates_only_the_rebuilt_keys():
+    """Same job with and without the embedding: value rows, supplied rows and all selections are the same;
+    a rebuilt key row is the unrotated projection turned to its token's position."""
+    w0 = small_workload(B=1, H=2, K=10, R=3, S=12, T=6, dtype="f32")
+    w1 = w0.scaled(rope_base=100.0)
+    a, inp, wts = make_oracle(w0)
+    b, _, _ = make_oracle(w1, wts)
+    pk, pv = inp.prompt_kv()
+    hs = inp.hidden_store()
+    for o in (a, b):
+        o.init_cache(pk, pv, hs, hs[0][:, :w0.S], w0.S)
+    seen = 0
+    for n in range(w0.S, w0.S + w0.T):
+        q, k, v = inp.step_qkv(n)
+        ra = a.decode_step(q, k, v, hs, hs[0][:, n])
+        rb = b.decode_step(q, k, v, hs, hs[0][:, n])
+        assert np.array_equal(ra[1], rb[1]) and np.array_equal(ra[3], rb[3])
+        assert np.array_equal(a.Vc, b.Vc)
+        for h in range(w0.H):
+            for s, pos in enumerate(a.slot_pos[0, h]):
+                if pos in ra[3][0]:
+                    raw = hs[0, 0, pos].astype(np.float64) @ wts["w_kv"][0][h * w0.d:(h + 1) * w0.d].astype(np.float64).T
+                    want = O.rotary(raw[None], [int(pos)], 100.0)[0].astype(np.float32)
+                    assert np.array_equal(b.Kc[0, 0, h, s], want.astype(np.float64))
+                    seen += 1
+                elif pos >= 0 and not np.array_equal(a.Kc[0, 0, h, s], b.Kc[0, 0, h, s]):
+                    # rebuilt in an earlier step and still resident
+                    assert pos < n
+    assert seen > 0
