@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 4
+#define ADORE_ABI_VERSION 5
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -83,6 +83,14 @@ typedef struct {
   int32_t dtype;                                      /* ADORE_F32 | ADORE_BF16 */
   float pos_scale;                                    /* position feature of token i = (float)i * pos_scale */
   int32_t score_mode;                                 /* ADORE_SCORE_STATIC | ADORE_SCORE_RESCORE */
+  float rope_base;                                    /* 0: off.  > 0: rotary position embedding (the one the paper's
+                                                         backbones apply to q and k; the paper names it in its related
+                                                         work on length extrapolation) on every key the library makes
+                                                         from a hidden state, and on the queries of the rebuild forward:
+                                                         the projection is rounded to the storage type, elements j and
+                                                         j + d/2 of each head are turned by pos * rope_base^(-2j/d), and
+                                                         the result is rounded again.  Keys and queries the caller
+                                                         supplies (prompt_k, k_new, q) are taken as they are. */
 } adore_config;
 
 /* Device pointers, caller-owned, read-only, must outlive the context. */
@@ -255,6 +263,7 @@ enum {
   ADORE_KERNEL_FWD_ATTEND,      /* rebuild forward: attention of the R+1 rows */
   ADORE_KERNEL_FWD_OPROJ,       /* rebuild forward: output projection + residual, rebuilt tokens' rows */
   ADORE_KERNEL_FWD_OPROJ_CUR,   /* rebuild forward: the same for the current tokens' rows */
+  ADORE_KERNEL_ROPE,            /* rotary embedding of the rows a projection just wrote (rope_base > 0) */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

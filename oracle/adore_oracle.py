@@ -51,9 +51,10 @@ Readings of points the paper leaves open (each used exactly as stated here):
     before the product, so a key that is rebuilt from a hidden state has to be rotated to the
     position the token had, or it cannot stand next to the cached keys): optional, off when
     `rope_base` is 0.  The pairing is the half-split one (element j < d/2 of a head and
-    element j + d/2 span a plane that is turned by pos * rope_base**(-2j/d)); the rotation
-    is applied to the unrounded projection, so a rebuilt key is still rounded once.  Keys
-    and queries the caller supplies are taken as they are.  In the rebuild forward the
+    element j + d/2 span a plane that is turned by pos * rope_base**(-2j/d)).  As in those
+    backbones the projection leaves the matrix product in the storage type and the
+    rotation works on that: a rotated row is rounded twice, once as a projection and once
+    after the rotation.  Keys and queries the caller supplies are taken as they are.  In the rebuild forward the
     queries of the R+1 rows are rotated as well.
   * Rows never move: a released row frees its slot; incoming rows take the
     lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
@@ -265,16 +266,17 @@ class AdoreOracle:
 
     # -- rebuild ------------------------------------------------------------
     def _project(self, layer: int, x_rows: np.ndarray, positions: Sequence[int]) -> np.ndarray:
-        """K/V states of tokens from their hidden states: one rounding of x W_kv^T, the key half turned
-        to the tokens' positions first when the rotary embedding is on."""
+        """K/V states of tokens from their hidden states: one rounding of x W_kv^T; when the rotary
+        embedding is on, the rounded key half is then turned to the tokens' positions and rounded again."""
         c = self.cfg
         if layer not in self._wkv64:                     # [2*H*d, D], rows 0..H*d-1 = W_k
             self._wkv64[layer] = np.asarray(self.wts["w_kv"][layer], dtype=F64)
-        kv = x_rows.astype(F64) @ self._wkv64[layer].T
+        kv = round_to_storage(x_rows.astype(F64) @ self._wkv64[layer].T, c.dtype)
         if c.rope_base > 0:
             Hd = c.H * c.d
-            kv[:, :Hd] = rotary(kv[:, :Hd].reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd)
-        return round_to_storage(kv, c.dtype)
+            kv[:, :Hd] = round_to_storage(
+                rotary(kv[:, :Hd].reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd), c.dtype)
+        return kv
 
     def _place_rebuilt(self, b: int, rebuilt: List[int], hidden_store: np.ndarray) -> None:
         c = self.cfg
@@ -454,10 +456,10 @@ class AdoreForwardOracle(AdoreOracle):
             for l in range(c.L):
                 Wq = self._w(self._wq64, "w_q", l)
                 Wo = self._w(self._wo64, "w_o", l)
-                Q = X @ Wq.T                                             # [r+1, H*d]
+                Q = round_to_storage(X @ Wq.T, c.dtype)                  # [r+1, H*d]
                 if c.rope_base > 0:
-                    Q = rotary(Q.reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd)
-                Q = round_to_storage(Q, c.dtype)
+                    Q = round_to_storage(rotary(Q.reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd),
+                                         c.dtype)
                 KV = self._project(l, X, positions)                      # [r+1, 2*H*d], rounded
                 O = np.zeros((len(positions), Hd), dtype=F64)
                 for h in range(c.H):

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libadore.so")
 
 ADORE_F32, ADORE_BF16 = 0, 1
 KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "rebuild_select", "rebuild_gemm",
-           "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur"]
+           "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur", "rope"]
 
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
@@ -30,7 +30,8 @@ class AdoreConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("layers", "batch", "heads", "head_dim", "hidden", "cache_slots", "rebuild_budget",
                  "max_positions", "ctrl_hidden", "dtype")] + [("pos_scale", ctypes.c_float),
-                                                              ("score_mode", ctypes.c_int32)]
+                                                              ("score_mode", ctypes.c_int32),
+                                                              ("rope_base", ctypes.c_float)]
 
 
 _WEIGHT_FIELDS = ["w_kv", "gru_w_ih", "gru_w_hh", "gru_b_ih", "gru_b_hh", "pos_w", "pos_b", "mlp_w1",
@@ -110,10 +111,10 @@ def _check(lib, rc: int):
 
 
 def make_config(*, layers, batch, heads, head_dim, hidden, cache_slots, rebuild_budget, max_positions,
-                ctrl_hidden, dtype, pos_scale, score_mode=0) -> AdoreConfig:
+                ctrl_hidden, dtype, pos_scale, score_mode=0, rope_base=0.0) -> AdoreConfig:
     code = {"f32": ADORE_F32, "bf16": ADORE_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
     return AdoreConfig(layers, batch, heads, head_dim, hidden, cache_slots, rebuild_budget, max_positions,
-                       ctrl_hidden, code, pos_scale, int(score_mode))
+                       ctrl_hidden, code, pos_scale, int(score_mode), float(rope_base))
 
 
 class Adore:

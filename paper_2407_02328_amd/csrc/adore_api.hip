@@ -58,7 +58,7 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
-      att_part, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, total;
+      att_part, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, rope, total;
 };
 
 bool config_ok(const adore_config *c) {
@@ -66,7 +66,7 @@ bool config_ok(const adore_config *c) {
          c->cache_slots >= 2 && c->rebuild_budget >= 0 && c->rebuild_budget <= c->cache_slots - 2 &&
          c->max_positions >= 2 && c->ctrl_hidden > 0 && (c->dtype == ADORE_F32 || c->dtype == ADORE_BF16) &&
          (c->score_mode == ADORE_SCORE_STATIC || c->score_mode == ADORE_SCORE_RESCORE) &&
-         std::isfinite(c->pos_scale);
+         std::isfinite(c->pos_scale) && std::isfinite(c->rope_base) && c->rope_base >= 0.f;
 }
 
 bool config_supported(const adore_config *c) {
@@ -111,6 +111,7 @@ Layout make_layout(const adore_config &c) {
   l.fwd_q = take(fwd_rows * c.heads * c.head_dim * es);
   l.fwd_o = take(fwd_rows * c.heads * c.head_dim * es);
   l.fwd_x = take(fwd_rows * c.hidden * es);
+  l.rope = take(c.rope_base > 0.f ? size_t(c.max_positions) * (c.head_dim / 2) * 16 : 0);
   l.total = off;
   return l;
 }
@@ -246,6 +247,7 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->fwd_q = base + l.fwd_q;
   ctx->fwd_o = base + l.fwd_o;
   ctx->fwd_x = base + l.fwd_x;
+  ctx->rope = base + l.rope;
   ctx->forward = false;
   ctx->r_pending = 0;
   ctx->ins_stride = 1;
@@ -318,6 +320,7 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   }
   hipStream_t st = ctx->stream;
   ctx->cur = 0;
+  ADORE_TRY(launch_rope_table(ctx));
   // controller over the prompt: z_{-1} = 0, tokens in order, in chunks
   ADORE_TRY(launch_fill_i32(ctx, reinterpret_cast<int32_t *>(ctx->z), 0, size_t(c.batch) * c.ctrl_hidden));
   for (int i0 = 0; i0 < S; i0 += kPromptChunk) {
@@ -338,6 +341,7 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
   for (int l = 0; l < c.layers && !forward; ++l) {
     ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur + 1, r0));
+    ADORE_TRY(launch_rope_rebuilt(ctx, l, ctx->cur + 1, r0));
   }
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, st));   // the first selections wait for everything above
   ctx->steps_done = 0;
@@ -413,6 +417,7 @@ int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
     ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
   }
   ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, (ctx->cur + 1) % kRing, ctx->r_step));
+  ADORE_TRY(launch_rope_rebuilt(ctx, layer, (ctx->cur + 1) % kRing, ctx->r_step));
   ctx->rebuilt[layer] = 1;
   if (++ctx->n_rebuilt == ctx->cfg.layers) {
     ctx->n++;
@@ -448,6 +453,7 @@ int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void 
   sel.map_out = slot_map; sel.rel_out = nullptr; sel.rb_out = nullptr;
   ADORE_TRY(launch_attend(ctx, 0, q, k_new, v_new, out, &sel));
   ADORE_TRY(launch_rebuild_gemm(ctx, 0, hidden_store, dst, r, ctx->slot_pos[dst], slot_map));
+  ADORE_TRY(launch_rope_rebuilt(ctx, 0, dst, r));
   ctx->occ = kept + r;
   ctx->n++;
   ctx->steps_done++;
@@ -552,6 +558,7 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const bool by_pos = l == 0;
     const bool last = l == c.layers - 1;
     ADORE_TRY(launch_fwd_qkv(ctx, l, wq + size_t(l) * Hd * c.hidden * es, x_rows, by_pos, r));
+    ADORE_TRY(launch_rope_forward(ctx, l, r));
     ADORE_TRY(launch_fwd_attend(ctx, l, r));
     if (last && runs_ahead(ctx) && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,
@@ -708,6 +715,7 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_FWD_ATTEND: return "fwd_attend";
     case ADORE_KERNEL_FWD_OPROJ: return "fwd_oproj";
     case ADORE_KERNEL_FWD_OPROJ_CUR: return "fwd_oproj_cur";
+    case ADORE_KERNEL_ROPE: return "rope";
     default: return "?";
   }
 }

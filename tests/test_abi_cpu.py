@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 4
+    assert lib.adore_abi_version() == 5
 
 
 def test_workspace_bytes(lib):
@@ -98,6 +98,17 @@ def test_create_rejects_bad_arguments(lib):
     assert lib.adore_schedule(h, FAKE, FAKE, None, None, None) == -1
     assert lib.adore_decode_step(h, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
     assert lib.adore_set_state(h, FAKE, None, None, None, None, 5) == -3
+    assert lib.adore_destroy(h) == 0
+    # rotary embedding: a negative or non-finite base is invalid; a positive one adds the angle table
+    for bad_base in (-1.0, float("nan"), float("inf")):
+        assert lib.adore_workspace_bytes(ctypes.byref(cfg_for(w, rope_base=bad_base))) == 0
+        assert lib.adore_create(ctypes.byref(cfg_for(w, rope_base=bad_base)), ctypes.byref(wt), FAKE, n, None,
+                                ctypes.byref(h)) == -1
+    rp = cfg_for(w, rope_base=10000.0)
+    big = lib.adore_workspace_bytes(ctypes.byref(rp))
+    assert n + w.N_max * (w.d // 2) * 16 <= big < n + w.N_max * (w.d // 2) * 16 + 512
+    assert lib.adore_create(ctypes.byref(rp), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -4
+    assert lib.adore_create(ctypes.byref(rp), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
     assert lib.adore_destroy(h) == 0
     wt2 = fake_weights()
     wt2.out_b = None

@@ -755,3 +755,69 @@ def test_random_medium_configurations(name, kw, calls, ordered):
     whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
     worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=2, whole=whole, ordered=ordered)
     job.adore.close()
+
+
+# ---- rotary position embedding on the keys (and forward queries) the library makes ------------------
+@pytest.mark.parametrize("name,kw,calls", [
+    # fp32, one wave per output element, head_dim 64
+    ("f32_d64", dict(L=1, B=2, H=2, d=64, D=128, K=40, R=6, S=50, T=20, dtype="f32", dprime=16), "fine"),
+    # fp32, head_dim 128, the whole-step call
+    ("f32_d128", dict(L=1, B=2, H=2, d=128, D=128, K=80, R=4, S=100, T=16, dtype="f32", act_std=0.3, w_std=0.1), "whole"),
+    # bf16 on the tile kernel, ragged tiles, two layers through the fine-grained calls
+    ("bf16_d64_l2", dict(L=2, B=2, H=4, d=64, D=256, K=96, R=8, S=120, T=24, dtype="bf16", dprime=32), "fine"),
+    # bf16, d = 128, the whole-step call with the selections riding; positions beyond 1000
+    ("bf16_d128", dict(L=1, B=3, H=4, d=128, D=512, K=200, R=20, S=1050, T=20, dtype="bf16", dprime=32), "whole"),
+    # a prompt shorter than the cache: the rebuild set grows from nothing
+    ("bf16_warm", dict(L=1, B=2, H=9, d=64, D=256, K=130, R=12, S=20, T=40, dtype="bf16", dprime=32), "whole"),
+])
+def test_rotary_embedding_on_rebuilt_keys(name, kw, calls):
+    """rope_base = 10000: every rebuilt key row is the rounded projection turned to its token's position; slot
+    maps, outputs and cache rows against the oracle (its rotation is pinned on the CPU)."""
+    h = _harness()
+    w = Workload("rope_" + name, rope_base=10000.0, **kw)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=(lambda t: True) if calls == "whole" else None)
+    print(f"rope {name}: worst output error {worst:.3e}", flush=True)
+    job.adore.close()
+
+
+def test_rotary_embedding_changes_the_keys_and_nothing_else():
+    """The same job with and without the embedding on the GPU: selections and value rows agree, rebuilt key
+    rows differ (so the tests above do not pass by the rotation being skipped on both sides)."""
+    h = _harness()
+    kw = dict(L=1, B=2, H=4, d=128, D=256, K=96, R=8, S=120, T=10, dtype="bf16", dprime=32)
+    snaps = []
+    for base in (0.0, 500.0):
+        w = Workload("rope_onoff", rope_base=base, **kw)
+        worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5)
+        snaps.append(job.snapshot())
+        job.adore.close()
+    a, b = snaps
+    assert np.array_equal(a["slot_pos"], b["slot_pos"]) and np.array_equal(a["cache_v"], b["cache_v"])
+    assert not np.array_equal(a["cache_k"], b["cache_k"])
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("r8_d64", dict(L=3, B=2, H=4, d=64, D=256, K=64, R=8, S=40, T=30)),
+    ("r32_d128", dict(L=2, B=2, H=4, d=128, D=512, K=160, R=32, S=200, T=10)),
+    ("r0", dict(L=2, B=2, H=2, d=64, D=128, K=48, R=0, S=60, T=8)),
+    ("b18", dict(L=2, B=18, H=2, d=128, D=256, K=64, R=4, S=70, T=5)),
+])
+def test_forward_step_with_rotary_embedding(name, kw):
+    """Rebuild forward with rope_base = 10000: queries and keys of the R+1 rows of every layer are turned to
+    their positions (rebuilt tokens: their own; current token: n)."""
+    h = _harness()
+    w = Workload("fwd_rope_" + name, dtype="bf16", dprime=32, w_std=0.06, rope_base=10000.0, **kw)
+    worst, mean = h.forward_lockstep(w, w.T)
+    print(f"forward rope {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    assert mean < 2.0 ** -10
+
+
+def test_rotary_embedding_at_the_benchmark_shape():
+    """llama7b_layer with the embedding on, in the launch configuration bench.py times: init and four steps
+    through adore_decode_step, everything against the oracle (16384 rebuilt key rows per step: the row check of
+    the full-size runs)."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(T=6, rope_base=10000.0)
+    worst, job, _ = h.lockstep(w, steps=4, check_cache_every=2, whole=lambda t: True, full_size_rows=True)
+    print(f"rope llama7b_layer: worst output error {worst:.3e}", flush=True)
+    job.adore.close()

@@ -582,10 +582,11 @@ def test_rebuilt_rows_equal_original_rows_and_full_attention_when_everything_fit
     Hd = w.H * w.d
     k_all = kv_all[:, :, :Hd].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)    # [B,H,N,d]
     v_all = kv_all[:, :, Hd:].reshape(w.B, w.N_max, w.H, w.d).transpose(0, 2, 1, 3)
-    if rope_base > 0:
-        k_all = _rotate_complex(torch.tensor(np.ascontiguousarray(k_all)), rope_base).numpy()
     k_all = k_all.astype(np.float32).astype(np.float64)
     v_all = v_all.astype(np.float32).astype(np.float64)
+    if rope_base > 0:       # rounded projection, turned, rounded again
+        k_all = _rotate_complex(torch.tensor(np.ascontiguousarray(k_all)), rope_base).numpy()
+        k_all = k_all.astype(np.float32).astype(np.float64)
     orc.init_cache(k_all[None, :, :, :w.S], v_all[None, :, :, :w.S], hs, hs[0][:, :w.S], w.S)
     for n in range(w.S, w.S + w.T):
         q, _, _ = inp.step_qkv(n)
@@ -695,7 +696,7 @@ def test_decode_oracle_rotates_only_the_rebuilt_keys():
             for s, pos in enumerate(a.slot_pos[0, h]):
                 if pos in ra[3][0]:
                     raw = hs[0, 0, pos].astype(np.float64) @ wts["w_kv"][0][h * w0.d:(h + 1) * w0.d].astype(np.float64).T
-                    want = O.rotary(raw[None], [int(pos)], 100.0)[0].astype(np.float32)
+                    want = O.rotary(raw.astype(np.float32)[None], [int(pos)], 100.0)[0].astype(np.float32)
                     assert np.array_equal(b.Kc[0, 0, h, s], want.astype(np.float64))
                     seen += 1
                 elif pos >= 0 and not np.array_equal(a.Kc[0, 0, h, s], b.Kc[0, 0, h, s]):
