@@ -166,7 +166,7 @@ def run_stack(w, steps, warmup, prof_steps):
     def make(K, R):
         cfg = make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=K,
                           rebuild_budget=R, max_positions=w.N_max, ctrl_hidden=dp, dtype=w.dtype,
-                          pos_scale=w.pos_scale)
+                          pos_scale=w.pos_scale, rope_base=w.rope_base)
         a = Adore(cfg, wts, DEV)
         a.set_input_order(INPUTS_ORDERED)
         a.init_cache(prompt_k, prompt_v, hidden, ctrl_in, None, w.S)
@@ -235,7 +235,7 @@ def run_forward(w, steps, warmup, prof_steps):
     prompt_k = randn((w.L, w.B, w.H, w.S, w.d)); prompt_v = randn((w.L, w.B, w.H, w.S, w.d))
     cfg = make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
                       rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
-                      pos_scale=w.pos_scale)
+                      pos_scale=w.pos_scale, rope_base=w.rope_base)
     a = Adore(cfg, wts, DEV)
     a.set_input_order(INPUTS_ORDERED)
     a.init_cache(prompt_k, prompt_v, None, embed[:, :w.S].contiguous(), None, w.S)
@@ -379,6 +379,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rescore", action="store_true",
                     help="controller scores every token again at every step (relative position)")
+    ap.add_argument("--rope-base", type=float, default=0.0,
+                    help="rotary position embedding with this base on the keys (and forward queries) the library makes")
     ap.add_argument("--forward", type=int, default=0, metavar="LAYERS",
                     help="time the rebuild forward (adore_forward_step) through this many layers of the workload's shape")
     ap.add_argument("--input-order", choices=["ready", "stream"], default="ready",
@@ -399,6 +401,8 @@ def main():
     w = workload(args.workload)
     if args.rescore:
         w = w.scaled(rescore=True)
+    if args.rope_base:
+        w = w.scaled(rope_base=args.rope_base)
     if args.forward:
         print(json.dumps(forward_line(w.scaled(L=args.forward), args)), flush=True)
         return
@@ -451,7 +455,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
                    "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
-                   "score_mode": "rescore" if w.rescore else "static", "input_order": args.input_order},
+                   "score_mode": "rescore" if w.rescore else "static", "input_order": args.input_order,
+                   "rope_base": w.rope_base},
         "roofline": dominant,
         "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},

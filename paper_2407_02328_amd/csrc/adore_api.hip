@@ -111,7 +111,7 @@ Layout make_layout(const adore_config &c) {
   l.fwd_q = take(fwd_rows * c.heads * c.head_dim * es);
   l.fwd_o = take(fwd_rows * c.heads * c.head_dim * es);
   l.fwd_x = take(fwd_rows * c.hidden * es);
-  l.rope = take(c.rope_base > 0.f ? size_t(c.max_positions) * (c.head_dim / 2) * 16 : 0);
+  l.rope = take(c.rope_base > 0.f ? size_t(c.max_positions) * (c.head_dim / 2) * 24 : 0);   // fp64 table, fp32 copy
   l.total = off;
   return l;
 }
@@ -248,6 +248,7 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->fwd_o = base + l.fwd_o;
   ctx->fwd_x = base + l.fwd_x;
   ctx->rope = base + l.rope;
+  ctx->rope_f = reinterpret_cast<float2 *>(base + l.rope + size_t(cfg->max_positions) * (cfg->head_dim / 2) * 16);
   ctx->forward = false;
   ctx->r_pending = 0;
   ctx->ins_stride = 1;
@@ -341,7 +342,6 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   const size_t hs_layer = size_t(c.batch) * c.max_positions * c.hidden * es;
   for (int l = 0; l < c.layers && !forward; ++l) {
     ADORE_TRY(launch_rebuild_gemm(ctx, l, static_cast<const char *>(hidden_store) + l * hs_layer, ctx->cur + 1, r0));
-    ADORE_TRY(launch_rope_rebuilt(ctx, l, ctx->cur + 1, r0));
   }
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, st));   // the first selections wait for everything above
   ctx->steps_done = 0;
@@ -417,7 +417,6 @@ int do_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer) {
     ADORE_TRY(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
   }
   ADORE_TRY(launch_rebuild_gemm(ctx, layer, hidden_store_layer, (ctx->cur + 1) % kRing, ctx->r_step));
-  ADORE_TRY(launch_rope_rebuilt(ctx, layer, (ctx->cur + 1) % kRing, ctx->r_step));
   ctx->rebuilt[layer] = 1;
   if (++ctx->n_rebuilt == ctx->cfg.layers) {
     ctx->n++;
@@ -453,7 +452,6 @@ int do_ridden_step(adore_ctx *ctx, const void *q, const void *k_new, const void 
   sel.map_out = slot_map; sel.rel_out = nullptr; sel.rb_out = nullptr;
   ADORE_TRY(launch_attend(ctx, 0, q, k_new, v_new, out, &sel));
   ADORE_TRY(launch_rebuild_gemm(ctx, 0, hidden_store, dst, r, ctx->slot_pos[dst], slot_map));
-  ADORE_TRY(launch_rope_rebuilt(ctx, 0, dst, r));
   ctx->occ = kept + r;
   ctx->n++;
   ctx->steps_done++;
@@ -558,7 +556,6 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     const bool by_pos = l == 0;
     const bool last = l == c.layers - 1;
     ADORE_TRY(launch_fwd_qkv(ctx, l, wq + size_t(l) * Hd * c.hidden * es, x_rows, by_pos, r));
-    ADORE_TRY(launch_rope_forward(ctx, l, r));
     ADORE_TRY(launch_fwd_attend(ctx, l, r));
     if (last && runs_ahead(ctx) && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,

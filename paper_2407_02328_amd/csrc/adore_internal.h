@@ -69,6 +69,7 @@ struct adore_ctx {
   void *fwd_q, *fwd_o;       // rebuild forward: [B*(R+1)][H*d] query rows / attention outputs of the layer in flight
   void *fwd_x;               // rebuild forward: [B*(R+1)][D]   rows handed from layer to layer
   void *rope;                // rope_base > 0: [N_max][d/2] (cos, sin) of pos * base^(-2j/d), fp64
+  float2 *rope_f;            // ... and the same rounded to fp32
 
   // --- host-side step state ---
   bool inited;
@@ -173,11 +174,10 @@ int fwd_attend_max_slots();
 hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, const void *x_rows, bool by_position,
                           int r);
 hipError_t launch_fwd_attend(adore_ctx *ctx, int layer, int r);
-// rotary embedding (no-ops unless rope_base > 0): the table, once per init; the keys a rebuild projection wrote;
-// the keys and queries the forward's projection wrote
+// rotary embedding (no-ops unless rope_base > 0): the angle table, once per init; the rotation of rows a projection
+// wrote and did not rotate itself (the projections call it)
 hipError_t launch_rope_table(adore_ctx *ctx);
-hipError_t launch_rope_rebuilt(adore_ctx *ctx, int layer, int lists, int r);
-hipError_t launch_rope_forward(adore_ctx *ctx, int layer, int r);
+hipError_t launch_rope_rows(adore_ctx *ctx, int layer, int lists, int r, int j0, int j1, bool queries, int cur_pos);
 hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x_rows, bool by_position, void *out,
                             int out_rps, int out_cur, int r);
 

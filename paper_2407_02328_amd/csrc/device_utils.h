@@ -67,6 +67,13 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
   return uint16_t(u >> 16);
 }
 
+// Rotary embedding of one plane: (lo, hi) = elements j and j + d/2 of a head, cs = (cos, sin) of the angle.
+// fp64 for fp32 storage.  For bf16 storage fp32 is enough (its error is a thousandth of the spacing of the storage
+// values); written with explicit fused operations so that every kernel that turns a row gets the same bits.
+__device__ inline double rope_lo(double lo, double hi, double2 cs) { return lo * cs.x - hi * cs.y; }
+__device__ inline double rope_hi(double lo, double hi, double2 cs) { return lo * cs.y + hi * cs.x; }
+__device__ inline float rope_lo(float lo, float hi, float2 cs) { return fmaf(lo, cs.x, -(hi * cs.y)); }
+__device__ inline float rope_hi(float lo, float hi, float2 cs) { return fmaf(lo, cs.y, hi * cs.x); }
 __device__ inline void store_elem(float *p, float v) { *p = v; }
 __device__ inline void store_elem(bf16_t *p, float v) { p->bits = f32_to_bf16_rne(v); }
 

@@ -63,6 +63,8 @@ struct GemmArgs {
   int out_rps, out_cur;        // OPROJ: rank j is written to row b * out_rps + j, the current token to b * out_rps + out_cur
   int n_cur;                   // QKV / OPROJ: the first n_cur workgroups of the tile launch take the current tokens' rows
   int cur_ks;                  // ... with the contraction cut over cur_ks (1, 2, 4, 8) of a workgroup's waves
+  const float2 *rope;          // tile kernel: [N_max][d/2] (cos, sin), the key (and query) tiles turn their rows by
+                               // position as they leave; null: no rotary embedding, or a pass of its own does it
 };
 
 __device__ inline size_t row_by_position(const GemmArgs &a, int b, int j) {
@@ -230,6 +232,7 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   __shared__ u32x4 smem[SMEM_BYTES / 16];
   __shared__ long long s_dst[BM * NH_MAX];   // element offset of each output row slice in its destination, -1 = none
   __shared__ long long s_res[MODE == MODE_OPROJ ? BM : 1];   // element offset of each row's residual, -1 = none
+  __shared__ int s_rpos[MODE == MODE_REBUILD || MODE == MODE_QKV ? BM : 1];   // position of each row's token
   // rows are 128 B (BK = 64) or 64 B (BK = 32): 16 consecutive rows at one chunk index hit 16 different bank groups
   auto swz = [](int row, int chunk) { return row * CH + (chunk ^ (CH == 8 ? (row >> 1) & 7 : (row >> 2) & 3)); };
 
@@ -348,6 +351,12 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
       }
     }
     s_dst[t] = off;
+  }
+  if ((MODE == MODE_REBUILD || MODE == MODE_QKV) && a.rope) {
+    for (int row = tid; row < BM; row += 512) {
+      const int mi = min(m0 + row, a.M - 1);
+      s_rpos[row] = a.rebuilt_pos[size_t(mi / a.r) * a.Rdim + (mi % a.r)];
+    }
   }
   if (MODE == MODE_OPROJ) {
     for (int row = tid; row < BM; row += 512) {
@@ -491,6 +500,56 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   bf16_t *dst_half = static_cast<bf16_t *>(MODE == MODE_OPROJ ? a.Out
                                            : MODE == MODE_QKV ? (section == 0 ? a.Out : section == 1 ? a.Kc : a.Vc)
                                                               : (section == 0 ? a.Kc : a.Vc));
+  // Rotary embedding (query and key tiles, when the tile holds whole heads): the rounded row is turned by its
+  // token's position on the way out, in fp32, and rounded again.  A thread takes 8 planes at a time: the 8-element
+  // vectors of elements j and j + d/2 of a head, which share their angles; the angles of two such pairs are fetched
+  // before either is used (a fetch costs a trip to the L2).
+  const bool turn = (MODE == MODE_REBUILD ? section == 0 : MODE == MODE_QKV ? section <= 1 : false) && a.rope != nullptr;
+  if (turn) {
+    constexpr int PV = BM * BN / 16;           // pairs of vectors in the tile
+    const int half = a.d / 2, hv = half / 8;   // vectors per half head
+    const int per_row = BN / 16;
+    for (int i0 = 0; i0 < (PV + 511) / 512; i0 += 2) {
+      float2 cs[2][8];
+      u32x4 lo[2], hi[2];
+      long long offv[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int idx = tid + (i0 + u) * 512;
+        offv[u] = -1;
+        if (idx < PV) {
+          const int row = idx / per_row, rem = idx - row * per_row;
+          const int hh = rem / hv, v = rem - hh * hv;
+          const long long off = s_dst[row * nh + hh];
+          if (off >= 0) {
+            offv[u] = off + v * 8;
+            const float2 *src = a.rope + size_t(s_rpos[row]) * half + v * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) cs[u][e] = src[e];
+            lo[u] = *reinterpret_cast<const u32x4 *>(sOut + row * BN + hh * a.d + v * 8);
+            hi[u] = *reinterpret_cast<const u32x4 *>(sOut + row * BN + hh * a.d + half + v * 8);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (offv[u] < 0) continue;
+        uint32_t rl[8], rh[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float x = __uint_as_float(((lo[u][e / 2] >> (16 * (e & 1))) & 0xffffu) << 16);
+          const float y = __uint_as_float(((hi[u][e / 2] >> (16 * (e & 1))) & 0xffffu) << 16);
+          rl[e] = f32_to_bf16_rne(rope_lo(x, y, cs[u][e]));
+          rh[e] = f32_to_bf16_rne(rope_hi(x, y, cs[u][e]));
+        }
+        *reinterpret_cast<u32x4 *>(dst_half + offv[u]) =
+            u32x4{rl[0] | (rl[1] << 16), rl[2] | (rl[3] << 16), rl[4] | (rl[5] << 16), rl[6] | (rl[7] << 16)};
+        *reinterpret_cast<u32x4 *>(dst_half + offv[u] + half) =
+            u32x4{rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16)};
+      }
+    }
+    return;
+  }
   constexpr int VPR = BN / 8;   // 16-byte vectors per tile row
   for (int idx = tid; idx < BM * VPR; idx += 512) {
     const int row = idx / VPR, vec = idx - row * VPR;
@@ -689,6 +748,7 @@ void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
   a.tiles_m = a.tiles_n = 0;
   a.n_cur = 0;
   a.cur_ks = 1;
+  a.rope = nullptr;
 }
 
 }  // namespace
@@ -709,6 +769,10 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
   a.map_dst = map_dst; a.map_out = map_out;
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_GEMM, ctx->stream);
   const int pick = c.dtype == ADORE_BF16 ? pick_tile(a.M, a.N, c.hidden, c.heads * c.head_dim, c.head_dim, false) : -1;
+  // the key tiles turn their rows themselves when a tile holds whole heads; otherwise a pass of its own follows
+  const bool rope = c.rope_base > 0.f;
+  const bool turned = rope && pick >= 0 && kTiles[pick].bn >= c.head_dim;
+  if (turned) a.rope = ctx->rope_f;
   if (pick >= 0) {
     launch_tile<MODE_REBUILD>(t, ctx->stream, pick, a);
   } else {
@@ -720,7 +784,9 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
       ADORE_LAUNCH(t, (rebuild_dot_kernel<float>), dim3(blocks), dim3(256), 0, ctx->stream, a);
     }
   }
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && rope && !turned) e = launch_rope_rows(ctx, layer, lists, r, 0, r, false, 0);
+  return e;
 }
 
 // ---- rebuild forward: the two projections around the attention of a layer ----------------------------
@@ -792,17 +858,23 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
   a.Out = ctx->fwd_q;
   a.xrps = r + 1; a.cur_pos = ctx->n; a.a_gather = by_position ? 1 : 0;
   a.M = c.batch * r; a.N = 3 * Hd;
+  bool turned = false;   // the tiles turned the rebuilt tokens' query and key rows themselves
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
     const int pick = pick_with_riders(a, c.hidden, Hd, c.head_dim, false);
     if (pick < 0) return hipErrorInvalidValue;
+    turned = c.rope_base > 0.f && kTiles[pick].bn >= c.head_dim;
+    if (turned) a.rope = ctx->rope_f;
     launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
   }
   if (a.n_cur == 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV_CUR, ctx->stream);
     launch_cur_rows<MODE_QKV>(t, ctx->stream, a);
   }
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  // rotary embedding: the current tokens' rows always, the rebuilt tokens' rows unless the tiles did it
+  if (e == hipSuccess) e = launch_rope_rows(ctx, layer, ctx->cur, r, turned ? r : 0, r + 1, true, ctx->n);
+  return e;
 }
 
 // x' = round(x + W_o . o): residual rows like launch_fwd_qkv's x_rows; output rows at out[b * out_rps + j] for

@@ -106,7 +106,7 @@ def test_create_rejects_bad_arguments(lib):
                                 ctypes.byref(h)) == -1
     rp = cfg_for(w, rope_base=10000.0)
     big = lib.adore_workspace_bytes(ctypes.byref(rp))
-    assert n + w.N_max * (w.d // 2) * 16 <= big < n + w.N_max * (w.d // 2) * 16 + 512
+    assert n + w.N_max * (w.d // 2) * 24 <= big < n + w.N_max * (w.d // 2) * 24 + 512
     assert lib.adore_create(ctypes.byref(rp), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -4
     assert lib.adore_create(ctypes.byref(rp), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
     assert lib.adore_destroy(h) == 0

@@ -780,6 +780,19 @@ def test_rotary_embedding_on_rebuilt_keys(name, kw, calls):
     job.adore.close()
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("d", [64, 128])
+def test_rotary_embedding_with_every_tile_shape(tile, d, monkeypatch):
+    """The key tiles turn their rows themselves when a tile holds whole heads (256- to 64-wide tiles at d = 64,
+    256- and 128-wide ones at d = 128); narrower tiles leave it to the pass that follows.  Both give the same rows."""
+    h = _harness()
+    monkeypatch.setenv("ADORE_GEMM_TILE", str(tile))
+    w = Workload("rope_tiles", L=1, B=3, H=512 // d, d=d, D=448, K=128, R=45, S=200, T=4, dtype="bf16", dprime=32,
+                 rope_base=10000.0)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=1)
+    job.adore.close()
+
+
 def test_rotary_embedding_changes_the_keys_and_nothing_else():
     """The same job with and without the embedding on the GPU: selections and value rows agree, rebuilt key
     rows differ (so the tests above do not pass by the rotation being skipped on both sides)."""
