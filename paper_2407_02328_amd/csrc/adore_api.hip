@@ -158,7 +158,16 @@ int ensure_side_stream(adore_ctx *ctx) {
   ok = ok && hipEventCreateWithFlags(&ctx->ev_att, kSyncEventFlags) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_join, kSyncEventFlags) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->ev_in, kSyncEventFlags) == hipSuccess;
-  if (!ok) return ADORE_E_HIP;
+  if (!ok) {   // leave the context as it was: whatever was made so far goes again
+    if (ctx->side != ctx->stream && ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->side2 != ctx->stream && ctx->side2) (void)hipStreamDestroy(ctx->side2);
+    for (hipEvent_t *e : {&ctx->ev_ctrl, &ctx->ev_att, &ctx->ev_join, &ctx->ev_in}) {
+      if (*e) (void)hipEventDestroy(*e);
+      *e = nullptr;
+    }
+    ctx->side = ctx->side2 = ctx->stream;
+    return ADORE_E_HIP;
+  }
   ctx->side_ready = true;
   return ADORE_OK;
 }
@@ -637,6 +646,7 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
     ADORE_TRY(hipMemcpyAsync(ctx->z, z, size_t(c.batch) * c.ctrl_hidden * 4, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_k) ADORE_TRY(hipMemcpyAsync(ctx->cache_k, cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_v) ADORE_TRY(hipMemcpyAsync(ctx->cache_v, cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+  ADORE_TRY(launch_rope_table(ctx));              // a context restored without an init has none yet
   ADORE_TRY(hipStreamSynchronize(ctx->stream));   // `ins` lives on this stack frame
   if (ctx->overlap) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));   // the next selections may start at once
   ctx->steps_done = 0;

@@ -834,3 +834,30 @@ def test_rotary_embedding_at_the_benchmark_shape():
     worst, job, _ = h.lockstep(w, steps=4, check_cache_every=2, whole=lambda t: True, full_size_rows=True)
     print(f"rope llama7b_layer: worst output error {worst:.3e}", flush=True)
     job.adore.close()
+
+
+def test_rotary_embedding_in_a_context_restored_without_an_init():
+    """A snapshot taken from one context and restored into a fresh one (adore_set_state with no adore_init_cache
+    before it): the next steps give the same bits, so the angle table is there although no init made it."""
+    h = _harness()
+    w = Workload("rope_snap", L=1, B=2, H=2, d=64, D=128, K=40, R=4, S=60, T=12, dtype="bf16", dprime=32,
+                 rope_base=10000.0)
+    inp = SyntheticInputs(w)
+    job = h.GpuJob(w, inp)
+    job.init()
+    for n in range(w.S, w.S + 4):
+        job.step(n)
+    saved = {k: v.clone() for k, v in job.state.items()}
+    step = job.adore.get_state(**saved)
+    torch.cuda.synchronize()
+    ref = [job.step(n) for n in range(w.S + 4, w.S + 8)]
+    ref_k = job.snapshot()["cache_k"]
+    fresh = h.GpuJob(w, inp)
+    fresh.adore.set_state(saved["slot_pos"], saved["scores"], saved["z"], saved["cache_k"], saved["cache_v"], step)
+    again = [fresh.step(n) for n in range(w.S + 4, w.S + 8)]
+    for a, b in zip(ref, again):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    occ = job.snapshot()["slot_pos"] >= 0
+    assert np.array_equal(ref_k[0][occ], fresh.snapshot()["cache_k"][0][occ])
+    job.adore.close(); fresh.adore.close()
