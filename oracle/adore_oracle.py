@@ -56,6 +56,12 @@ Readings of points the paper leaves open (each used exactly as stated here):
     rotation works on that: a rotated row is rounded twice, once as a projection and once
     after the rotation.  Keys and queries the caller supplies are taken as they are.  In the rebuild forward the
     queries of the R+1 rows are rotated as well.
+  * Top-K attention over a whole sequence (Sec. 2.1: computing the full weights and keeping
+    the highest is the ideal sparsity; Sec. 2.2, first strategy, and App. "Implementation
+    Details": the backbone is fine-tuned with attention whose weights outside the top K are
+    masked out): causal, per head; the K largest products q_i . k_j over j <= i are kept (all
+    of them while i + 1 <= K), equal products go to the lower position, the softmax runs over
+    the kept ones only (masking before the softmax, as an attention mask does).
   * Rows never move: a released row frees its slot; incoming rows take the
     lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
     token -> lowest free slot at its insert).
@@ -506,3 +512,26 @@ def full_attention(q: np.ndarray, Kall: np.ndarray, Vall: np.ndarray) -> np.ndar
     """Eq. 1 over all past rows, per head.  q: [H,d]; Kall, Vall: [H,n,d]."""
     return np.stack([attention_row(q[h].astype(F64), Kall[h].astype(F64), Vall[h].astype(F64))[0]
                      for h in range(q.shape[0])])
+
+
+# --------------------------------------------------------------------------
+# top-K attention over a whole sequence (Sec. 2.1 / 2.2; see the readings in the header)
+# --------------------------------------------------------------------------
+def topk_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, top_k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """q, k, v: [rows, S, d] (rows = sequences x heads).  Returns (out [rows, S, d] fp64,
+    kept [rows, S, S] bool: kept[r, i, j] = query i of row r keeps key j)."""
+    q, k, v = (np.asarray(a, dtype=F64) for a in (q, k, v))
+    rows, S, d = q.shape
+    out = np.zeros((rows, S, d), dtype=F64)
+    kept = np.zeros((rows, S, S), dtype=bool)
+    for r in range(rows):
+        for i in range(S):
+            w = k[r, :i + 1] @ q[r, i]                          # the weights of query i, before scaling
+            if i + 1 > top_k:
+                order = np.argsort(-w, kind="stable")           # descending; equal weights: lower position first
+                sel = np.sort(order[:top_k])
+            else:
+                sel = np.arange(i + 1)
+            kept[r, i, sel] = True
+            out[r, i] = softmax_row(w[sel] / np.sqrt(F64(d))) @ v[r, sel]
+    return out, kept

@@ -703,3 +703,65 @@ def test_decode_oracle_rotates_only_the_rebuilt_keys():
                     # rebuilt in an earlier step and still resident
                     assert pos < n
     assert seen > 0
+
+
+# --------------------------------------------------------------------------
+# top-K attention over a whole sequence
+# --------------------------------------------------------------------------
+def test_topk_attention_with_k_covering_the_sequence_is_causal_attention():
+    rng = np.random.default_rng(11)
+    q, k, v = (rng.standard_normal((3, 19, 8)) for _ in range(3))
+    want = torch.nn.functional.scaled_dot_product_attention(torch.tensor(q), torch.tensor(k), torch.tensor(v),
+                                                            is_causal=True).numpy()
+    for top_k in (19, 64):
+        got, kept = O.topk_attention(q, k, v, top_k)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+        assert np.array_equal(kept, np.broadcast_to(np.tril(np.ones((19, 19), dtype=bool)), kept.shape))
+
+
+def test_topk_attention_with_k_one_returns_the_value_of_the_largest_weight():
+    rng = np.random.default_rng(12)
+    q, k, v = (rng.standard_normal((2, 15, 4)) for _ in range(3))
+    got, kept = O.topk_attention(q, k, v, 1)
+    for r in range(2):
+        for i in range(15):
+            j = int(np.argmax(k[r, :i + 1] @ q[r, i]))
+            assert np.array_equal(got[r, i], v[r, j]) and kept[r, i].sum() == 1 and kept[r, i, j]
+
+
+def test_topk_attention_by_brute_force_over_subsets():
+    """Tiny case: of all subsets of top_k past keys, the kept one has the largest sum of weights (that is the
+    top-K set when no two weights are equal), and the output is the softmax over exactly that subset."""
+    rng = np.random.default_rng(13)
+    S, d, top_k = 7, 3, 3
+    q, k, v = (rng.standard_normal((1, S, d)) for _ in range(3))
+    got, kept = O.topk_attention(q, k, v, top_k)
+    for i in range(S):
+        w = k[0, :i + 1] @ q[0, i]
+        size = min(top_k, i + 1)
+        best = max(itertools.combinations(range(i + 1), size), key=lambda c: sum(w[list(c)]))
+        assert sorted(best) == list(np.nonzero(kept[0, i])[0])
+        p = scipy.special.softmax(w[list(best)] / np.sqrt(d))
+        np.testing.assert_allclose(got[0, i], p @ v[0, list(best)], rtol=1e-12, atol=1e-13)
+
+
+def test_topk_attention_rows_sum_to_one_and_ties_go_to_the_lower_position():
+    rng = np.random.default_rng(14)
+    S, d, top_k = 12, 4, 5
+    k, v = rng.standard_normal((1, S, d)), rng.standard_normal((1, S, d))
+    ones = np.ones((1, S, d))
+    q = rng.standard_normal((1, S, d))
+    got, _ = O.topk_attention(q, k, ones, top_k)            # softmax weights sum to 1
+    np.testing.assert_allclose(got, ones, rtol=1e-13)
+    got, kept = O.topk_attention(np.zeros((1, S, d)), k, v, top_k)      # all weights equal: the first top_k positions
+    for i in range(S):
+        n = min(top_k, i + 1)
+        assert list(np.nonzero(kept[0, i])[0]) == list(range(n))
+        np.testing.assert_allclose(got[0, i], v[0, :n].mean(axis=0), rtol=1e-13, atol=1e-14)
+    # two equal weights at the cut: keys 2 and 6 are identical, K = 2 and the best key is 9 -> 9 and 2 stay
+    k2 = rng.standard_normal((1, S, d)) * 0.01
+    qv = np.array([1.0, 0.0, 0.0, 0.0])
+    k2[0, 2] = k2[0, 6] = 2 * qv
+    k2[0, 9] = 3 * qv
+    _, kept = O.topk_attention(np.broadcast_to(qv, (1, S, d)), k2, v, 2)
+    assert list(np.nonzero(kept[0, 11])[0]) == [2, 9]
