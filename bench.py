@@ -344,6 +344,64 @@ def prefill_line(w, args):
     }
 
 
+def topk_line(w, args):
+    """JSON line of the top-K attention over the workload's prompts (adore_topk_attention: B * H rows of S tokens,
+    K = args.topk): one call per step; the duration comes from HIP events on the stream the call enqueues on."""
+    import torch
+    from gen import DeviceNormals
+    from paper_2407_02328_amd import topk_attention, load_library
+    dev = "cuda:0"
+    rows, S, d, K = w.B * w.H, w.S, w.d, args.topk
+    drawer = DeviceNormals(w.seed, dev)
+    q, k, v = (drawer.normal((rows, S, d), 1.0, torch.bfloat16) for _ in range(3))
+    out = torch.empty_like(q)
+    ws = torch.empty(load_library().adore_topk_attention_workspace_bytes(rows, S, d), dtype=torch.uint8, device=dev)
+    reps, warm = max(3, min(args.steps, 50)), 3
+    for _ in range(warm):
+        topk_attention(q, k, v, K, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]      # the call enqueues on torch's current stream
+    t1 = time.perf_counter()
+    ev[0].record()
+    for _ in range(reps):
+        topk_attention(q, k, v, K, out=out, workspace=ws)
+    ev[1].record()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t1) / reps
+    us = 1e3 * ev[0].elapsed_time(ev[1]) / reps
+    assert bool(torch.isfinite(out.float()).all())
+    # what the method has to compute: every weight of the causal triangle, and the kept probabilities times V
+    kept = sum(min(i + 1, K) for i in range(S))
+    flops = 2.0 * rows * d * (S * (S + 1) / 2 + kept)
+    roof = dict(kernel="topk_attention (transpose of V + attention)", bound="mfma",
+                achieved=round(flops / (us * 1e-6) / 1e12, 1), peak=MFMA_PEAK_TFLOPS["bf16"], unit="TFLOP/s",
+                frac=round(flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4), traffic=None,
+                us_per_launch=round(us, 1), algorithmic_flops=flops,
+                note="the selection (a four-pass radix select per query: LDS histograms, wave scans) runs beside the matrix work")
+    line = {
+        "metric": "prompt tokens/sec through top-K attention (one layer)", "value": round(w.B * S / elapsed, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": warm, "ms_per_step": round(1e3 * elapsed, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name + "_topk_attention", "batch": w.B, "heads": w.H, "head_dim": d, "prompt": S,
+                   "top_k": K, "path": "adore_topk_attention: causal attention, every query keeps its K largest weights"},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import adore_oracle as O
+        from threadpoolctl import threadpool_info
+        sample = min(rows, 256)
+        qs, ks, vs = (t[:sample].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
+        t0 = time.perf_counter()
+        O.topk_attention(qs, ks, vs, K)
+        dt = time.perf_counter() - t0
+        cores = max([int(i.get("num_threads", 1)) for i in threadpool_info()] + [1])
+        line["cpu_baseline"] = {"value": round(sample * S / w.H / dt, 2), "unit": "tokens/s", "cores": cores,
+                                "kind": "oracle", "seconds": round(dt, 2),
+                                "sample": f"{sample} of the {rows} rows (one head of one sequence each), all {S} queries "
+                                          f"(numpy fp64, a Python loop over the queries); scaled to whole sequences of {w.H} heads"}
+    return line
+
+
 def run_cpu_baseline(w, seqs=16, steps=40):
     """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
     from threadpoolctl import threadpool_info
@@ -381,6 +439,9 @@ def main():
                     help="controller scores every token again at every step (relative position)")
     ap.add_argument("--rope-base", type=float, default=0.0,
                     help="rotary position embedding with this base on the keys (and forward queries) the library makes")
+    ap.add_argument("--topk-attention", action="store_true",
+                    help="time adore_topk_attention over the workload's prompts (B * H rows of S tokens)")
+    ap.add_argument("--topk", type=int, default=96, help="K of --topk-attention (the paper fine-tunes with 96)")
     ap.add_argument("--forward", type=int, default=0, metavar="LAYERS",
                     help="time the rebuild forward (adore_forward_step) through this many layers of the workload's shape")
     ap.add_argument("--input-order", choices=["ready", "stream"], default="ready",
@@ -408,6 +469,9 @@ def main():
         return
     if args.prefill:
         print(json.dumps(prefill_line(w, args)), flush=True)
+        return
+    if args.topk_attention:
+        print(json.dumps(topk_line(w, args)), flush=True)
         return
     work = algorithmic_work(w)
     stack = None

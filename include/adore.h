@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 5
+#define ADORE_ABI_VERSION 6
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -269,6 +269,23 @@ enum {
 int adore_set_timing(adore_ctx *ctx, int32_t enable);
 int adore_read_timing(adore_ctx *ctx, float *ms, int32_t *launches);
 const char *adore_kernel_name(int32_t kernel);
+
+/* Top-K attention over a whole sequence (Sec. 2.1: keeping the highest of a query's full weights is the ideal
+ * sparsity; Sec. 2.2, first strategy, and App. "Implementation Details": the attention the backbone is fine-tuned
+ * with, the weights outside the top K masked out).  Stateless: no context.  Causal, per row (= sequence x head):
+ *   w[i][j] = q_i . k_j for j <= i;  query i keeps its top_k largest weights (all while i + 1 <= top_k; equal
+ *   weights go to the lower j);  out_i = sum over the kept j of softmax_j(w[i][j] / sqrt(head_dim)) v_j.
+ * q, k, v, out: DEVICE [rows][seq][head_dim] bf16, dense; out may not alias the inputs.  workspace: DEVICE,
+ * 256-byte aligned, at least adore_topk_attention_workspace_bytes(rows, seq, head_dim) bytes (a transposed copy of
+ * v), caller-owned, free to reuse after the work enqueued here has run.  The call only enqueues work on
+ * hip_stream (a hipStream_t, NULL = the default stream).  The selection is exact on the weights as the kernel
+ * computes them (bf16 products accumulated in fp32); inputs must be finite.
+ * Errors: E_INVALID (null, sizes <= 0, top_k < 1), E_UNSUPPORTED (head_dim not in {64,128}, seq > 2048,
+ * rows > 65535), E_WORKSPACE, E_HIP. */
+size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t head_dim);
+int adore_topk_attention(const void *q, const void *k, const void *v, void *out, void *workspace,
+                         size_t workspace_bytes, int32_t rows, int32_t seq, int32_t head_dim, int32_t top_k,
+                         void *hip_stream);
 
 const char *adore_strerror(int code);
 int adore_abi_version(void);

@@ -23,6 +23,7 @@ EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
     "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_forward_step", "adore_get_state", "adore_set_state",
     "adore_set_input_order", "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
+    "adore_topk_attention_workspace_bytes", "adore_topk_attention",
 ]
 
 
@@ -101,6 +102,10 @@ def load_library() -> ctypes.CDLL:
     lib.adore_strerror.argtypes = [ctypes.c_int]
     lib.adore_abi_version.restype = ctypes.c_int
     lib.adore_abi_version.argtypes = []
+    lib.adore_topk_attention_workspace_bytes.restype = sz
+    lib.adore_topk_attention_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.adore_topk_attention.restype = ctypes.c_int
+    lib.adore_topk_attention.argtypes = [vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -115,6 +120,30 @@ def make_config(*, layers, batch, heads, head_dim, hidden, cache_slots, rebuild_
     code = {"f32": ADORE_F32, "bf16": ADORE_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
     return AdoreConfig(layers, batch, heads, head_dim, hidden, cache_slots, rebuild_budget, max_positions,
                        ctrl_hidden, code, pos_scale, int(score_mode), float(rope_base))
+
+
+def topk_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, top_k: int, out: torch.Tensor = None,
+                   workspace: torch.Tensor = None) -> torch.Tensor:
+    """adore_topk_attention on torch's current stream.  q, k, v: [rows, seq, head_dim] bf16, contiguous, on the GPU;
+    out and workspace (uint8) are allocated here unless given."""
+    lib = load_library()
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.shape != q.shape or t.dim() != 3:
+            raise ValueError(f"{name}: expected a contiguous bf16 GPU tensor [rows, seq, head_dim]")
+    rows, seq, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.dtype != torch.bfloat16 or not out.is_contiguous() or out.shape != q.shape or out.device != q.device:
+        raise ValueError("out: expected a contiguous bf16 tensor like q")
+    need = lib.adore_topk_attention_workspace_bytes(rows, seq, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != q.device:
+        raise ValueError("workspace: expected a contiguous uint8 tensor on q's device")
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(lib, lib.adore_topk_attention(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), workspace.data_ptr(),
+                                         workspace.numel(), rows, seq, d, int(top_k), stream))
+    return out
 
 
 class Adore:

@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 5
+    assert lib.adore_abi_version() == 6
 
 
 def test_workspace_bytes(lib):
@@ -165,3 +165,19 @@ def test_strerror_and_kernel_names(lib):
     assert len(seen) == 7
     from paper_2407_02328_amd import KERNELS
     assert [lib.adore_kernel_name(i).decode() for i in range(len(KERNELS))] == KERNELS
+
+
+def test_topk_attention_host_checks(lib):
+    ws = lib.adore_topk_attention_workspace_bytes
+    assert ws(0, 8, 64) == 0 and ws(1, 0, 64) == 0
+    assert ws(3, 100, 128) == 3 * 128 * 128 * 2          # keys padded to a multiple of 32
+    assert ws(1, 33, 64) % 256 == 0 and ws(1, 33, 64) >= 64 * 64 * 2
+    call = lib.adore_topk_attention
+    n = ws(2, 64, 64)
+    assert call(None, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 64, 4, None) == -1
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 64, 0, None) == -1
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 0, 64, 64, 4, None) == -1
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 96, 4, None) == -3
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, 2, 4096, 64, 4, None) == -3
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n - 1, 2, 64, 64, 4, None) == -4
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE + 16, n, 2, 64, 64, 4, None) == -4

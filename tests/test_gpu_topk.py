@@ -1,0 +1,124 @@
+"""GPU parity of adore_topk_attention (top-K attention over a whole sequence) against the oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _mods():
+    import torch
+    from oracle import adore_oracle as O
+    from paper_2407_02328_amd import topk_attention
+    return torch, O, topk_attention
+
+
+def _to_gpu(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:0").to(torch.bfloat16).contiguous()
+
+
+def _bf16_values(torch, a):
+    """The values a bf16 tensor holds, as fp64 (so that the oracle sees what the GPU sees)."""
+    return _to_gpu(torch, a).float().cpu().numpy().astype(np.float64)
+
+
+def _row_err(got, want):
+    return np.abs(got - want).max(axis=-1) / np.maximum(np.abs(want).max(axis=-1), 1e-30)
+
+
+GRID_CASES = [
+    # rows, S, d, top_k
+    (2, 1, 64, 1),            # a single token
+    (3, 17, 64, 5),           # one ragged query block
+    (2, 100, 128, 1),         # K = 1: the value row of the largest weight
+    (2, 100, 128, 32),
+    (1, 257, 128, 96),        # ragged tail of one query and one key
+    (2, 600, 64, 96),         # several query blocks, every wave has several key blocks
+    (1, 300, 128, 1000),      # K beyond the sequence: plain causal attention
+    (1, 1024, 128, 96),       # the largest sequence the 32-query blocks take
+    (1, 1100, 64, 200),       # 16-query blocks
+]
+
+
+@pytest.mark.parametrize("rows,S,d,top_k", GRID_CASES)
+def test_topk_attention_on_exactly_representable_weights(rows, S, d, top_k):
+    """q and k on a grid of quarters in [-2, 2]: every product sum is exact in fp32 and in fp64, so both sides
+    select from identical weights, equal weights abound (the tie rule decides many rows) and the kept sets are
+    the same; the outputs then differ by the arithmetic of the softmax and the second product only."""
+    torch, O, topk_attention = _mods()
+    rng = np.random.default_rng(1000 * S + top_k)
+    q = rng.integers(-8, 9, size=(rows, S, d)) / 4.0
+    k = rng.integers(-8, 9, size=(rows, S, d)) / 4.0
+    v = _bf16_values(torch, rng.standard_normal((rows, S, d)))
+    want, kept = O.topk_attention(q, k, v, top_k)
+    got = topk_attention(_to_gpu(torch, q), _to_gpu(torch, k), _to_gpu(torch, v), top_k)
+    torch.cuda.synchronize()
+    e = _row_err(got.float().cpu().numpy().astype(np.float64), want)
+    print(f"grid rows={rows} S={S} d={d} K={top_k}: worst row error {e.max():.2e}", flush=True)
+    assert e.max() < 2e-3 + 2.0 ** -8          # attention tolerance + the rounding of the bf16 output
+
+
+@pytest.mark.parametrize("rows,S,d,top_k", [(2, 500, 128, 96), (2, 333, 64, 48), (1, 1500, 128, 512)])
+def test_topk_attention_on_gaussian_inputs(rows, S, d, top_k):
+    """Gaussian q, k, v.  The GPU takes its decision on fp32 weights, the oracle on fp64 ones: where the K-th and
+    the (K+1)-th largest weight of a query are further apart than the fp32 accumulation error can bridge, the kept
+    sets are the same and the output must agree to the attention tolerance; the few other queries may swap one
+    key at the cut, which moves the output by at most that key's probability (<= 1/K) times the value range."""
+    torch, O, topk_attention = _mods()
+    rng = np.random.default_rng(7 * S + top_k)
+    q, k, v = (_bf16_values(torch, rng.standard_normal((rows, S, d))) for _ in range(3))
+    want, kept = O.topk_attention(q, k, v, top_k)
+    got = topk_attention(_to_gpu(torch, q), _to_gpu(torch, k), _to_gpu(torch, v), top_k).float().cpu().numpy().astype(np.float64)
+    torch.cuda.synchronize()
+    e = _row_err(got, want)
+    clear = np.ones((rows, S), dtype=bool)
+    for r in range(rows):
+        for i in range(top_k, S):
+            w = np.sort(k[r, :i + 1] @ q[r, i])[::-1]
+            clear[r, i] = w[top_k - 1] - w[top_k] > 1e-3
+    print(f"gauss rows={rows} S={S} K={top_k}: worst clear row {e[clear].max():.2e}, unclear rows {(~clear).sum()}, "
+          f"worst of them {e[~clear].max() if (~clear).any() else 0:.2e}", flush=True)
+    assert clear.mean() > 0.9
+    assert e[clear].max() < 2e-3 + 2.0 ** -8
+    assert e.max() < 2e-3 + 2.0 ** -8 + 2.0 * 8.0 / top_k     # |v| <= 4 sigma: a swapped key moves a row by <= 2 * 4 / K of it
+
+
+def test_topk_attention_at_the_benchmark_shape_sampled_rows():
+    """B16 x H32 rows of 1024 tokens, head_dim 128, K = 96 (the paper's fine-tuning setting), as bench.py
+    --topk-attention times it: eight rows checked in full against the oracle, Gaussian inputs drawn on the device."""
+    torch, O, topk_attention = _mods()
+    from gen import DeviceNormals
+    rows, S, d, top_k = 512, 1024, 128, 96
+    drawer = DeviceNormals(20240702, "cuda:0")
+    q, k, v = (drawer.normal((rows, S, d), 1.0, torch.bfloat16) for _ in range(3))
+    got = topk_attention(q, k, v, top_k)
+    torch.cuda.synchronize()
+    pick = [0, 1, 63, 200, 255, 256, 400, 511]
+    sel = torch.tensor(pick, device="cuda:0")
+    q64, k64, v64 = (t[sel].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
+    want, _ = O.topk_attention(q64, k64, v64, top_k)
+    e = _row_err(got[sel].float().cpu().numpy().astype(np.float64), want)
+    clear = np.ones(e.shape, dtype=bool)
+    for r in range(len(pick)):
+        for i in range(top_k, S):
+            w = np.sort(k64[r, :i + 1] @ q64[r, i])[::-1]
+            clear[r, i] = w[top_k - 1] - w[top_k] > 1e-3
+    print(f"benchmark shape: worst clear row {e[clear].max():.2e}, unclear {(~clear).sum()} of {clear.size}", flush=True)
+    assert clear.mean() > 0.9
+    assert e[clear].max() < 2e-3 + 2.0 ** -8
+    assert e.max() < 2e-3 + 2.0 ** -8 + 2.0 * 8.0 / top_k
+
+
+def test_topk_attention_rejects_what_it_does_not_take():
+    torch, O, topk_attention = _mods()
+    from paper_2407_02328_amd import AdoreError
+    q = torch.zeros((1, 8, 96), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(AdoreError):
+        topk_attention(q, q, q, 4)                      # head_dim 96
+    q = torch.zeros((1, 2049, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(AdoreError):
+        topk_attention(q, q, q, 4)                      # sequence too long for the LDS rows
+    q = torch.zeros((1, 8, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(AdoreError):
+        topk_attention(q, q, q, 0)
+    with pytest.raises(AdoreError):
+        topk_attention(q, q, q, 4, workspace=torch.empty(16, dtype=torch.uint8, device="cuda:0"))
