@@ -5,18 +5,19 @@
 //   w[i][j] = q_i . k_j  (j <= i);   kept(i) = the top_k largest w[i][.], equal weights to the lower j
 //   out_i   = sum_{j in kept(i)} softmax_j(w[i][j] / sqrt(d)) v_j
 //
-// One workgroup of 8 waves takes 16 or 32 consecutive queries of one (sequence, head) and the keys they can see:
+// One workgroup of 8 waves takes 16 consecutive queries of one (sequence, head) and the keys they can see:
 //
 //   A  logits^T = K . Q^T on the matrix cores (16x16x32 bf16; the key rows come from global memory straight into
 //      the operand layout, Q from an LDS tile), written to LDS as fp32, one row per query, -inf beyond the
-//      diagonal.  All the weights of a query have to exist before its K-th largest is known, and 32 x 1024 fp32
-//      is what LDS holds: hence the block of 32 queries (16 for sequences up to 2048).
+//      diagonal.  All the weights of a query have to exist before its K-th largest is known; 16 x 2048 fp32 is
+//      what LDS holds, and at 1024 keys two workgroups fit a compute unit.
 //   S  one wave per query row: the row's maximum and its K-th largest weight by a radix select on the
 //      order-preserving integer image of the floats: four passes of 8 bits over the row held in registers, each
 //      a 256-bin histogram in LDS (wave-private, LDS atomics) scanned from the top; the rank left over in the last
 //      bin says how many of the weights equal to the K-th largest stay, and ballots in position order say up to
-//      which position.  (A bit-by-bit search with ballots, 32 counting passes, took 5.6 ms of 8.0 ms at 512 rows of
-//      1024 tokens, K = 96; the radix select takes 1.5 ms of 3.4 ms.)
+//      which position.  As soon as at most 64 weights share the bits decided so far (as a rule after two passes)
+//      they are gathered one per lane and ranked directly, which gives the last key that stays at once.  (A bit-by-bit search with ballots, 32 counting passes, took 5.6 ms of 8.0 ms at 512 rows of
+//      1024 tokens, K = 96, in blocks of 32 queries; the radix select 1.5 ms of 3.4 ms.)
 //   B  P = exp2((w - max) / sqrt(d) . log2 e) for the kept weights straight from the LDS rows (the maximum is
 //      known, so there is no running rescale), as two bf16 terms (16 significant bits), and O^T += V^T . P^T on
 //      the matrix cores.  V^T comes from a transposed copy of V made by a pass of its own ([d][S], zero-padded),
@@ -81,8 +82,9 @@ __device__ inline uint32_t weight_key(float x) {
   return b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
-template <int DH, int NQB>
-__global__ __launch_bounds__(64 * kWaves, 1) void topk_attend_kernel(const TopkArgs a) {
+// NQB: blocks of 16 queries per workgroup; NKMAX: keys of a row a lane can hold (64 * NKMAX >= the keys of a row)
+template <int DH, int NQB, int NKMAX>
+__global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void topk_attend_kernel(const TopkArgs a) {
   constexpr int KT = DH / 32;          // matrix instructions along d per 16x16 logit block
   constexpr int MB = DH / 16;          // 16-wide blocks of the head dimension
   constexpr int FIN = MB < kWaves ? MB : kWaves;   // waves that finish and store
@@ -90,7 +92,6 @@ __global__ __launch_bounds__(64 * kWaves, 1) void topk_attend_kernel(const TopkA
   constexpr int NQ16 = NQB * 16;
   constexpr int QSTR = DH * 2 + 16;    // bytes per Q row in LDS
   constexpr int LPR = DH / 8;          // 16-byte vectors per row
-  constexpr int NKMAX = kMaxSeq / NQB / 64;   // keys of a row per lane: 16 (32 queries, S <= 1024) or 32
   constexpr int RPW = NQ16 / kWaves;   // query rows a wave selects for
   extern __shared__ __align__(16) unsigned char smem[];
   float *s_log = reinterpret_cast<float *>(smem);                        // [NQ16][lstr]; later the merge buffer
@@ -236,25 +237,68 @@ __global__ __launch_bounds__(64 * kWaves, 1) void topk_attend_kernel(const TopkA
               bin = 253 - 4 * lane; rest = need - excl - c0 - c1;
             }
             const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(mine));
+            int inbin = c3;
+            if (need <= excl + c0) inbin = c0;
+            else if (need <= excl + c0 + c1) inbin = c1;
+            else if (need <= excl + c0 + c1 + c2) inbin = c2;
             bin = __shfl(bin, src, 64);
             need = __shfl(rest, src, 64);
+            inbin = __shfl(inbin, src, 64);
             prefix |= uint32_t(bin) << shift;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the reads above come before the next zeroing
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the reads above come before the next writes
             __builtin_amdgcn_wave_barrier();
+            if (shift > 0 && inbin <= 64) {
+              // Few images share the bits decided so far: rank them directly instead of two or three more passes.
+              // They are gathered in position order (ballots), one per lane; the one with need-1 others before it
+              // in the order (image descending, position ascending) is the last key that stays.
+              const uint32_t decided = 0xffffffffu << shift;
+              uint32_t *cand = hist;          // [64] images, [64] positions: the histogram is not needed any more
+              int base = 0;
+#pragma unroll
+              for (int t = 0; t < NKMAX; ++t) {
+                if (t < tmax) {
+                  const bool member = u[t] != 0u && (u[t] & decided) == prefix;
+                  const unsigned long long m = __builtin_amdgcn_ballot_w64(member);
+                  if (m != 0ull) {
+                    if (member) {
+                      const int slot = base + int(__builtin_amdgcn_mbcnt_hi(uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u)));
+                      cand[slot] = u[t];
+                      cand[64 + slot] = uint32_t(lane + 64 * t);
+                    }
+                    base += __builtin_popcountll(m);
+                  }
+                }
+              }
+              __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+              __builtin_amdgcn_wave_barrier();
+              const bool have = lane < base;
+              const uint32_t ui = have ? cand[lane] : 0u;
+              const int pi = have ? int(cand[64 + lane]) : 0;
+              int before = 0;
+              for (int j = 0; j < base; ++j) {
+                const uint32_t uj = cand[j];
+                const int pj = int(cand[64 + j]);
+                before += (uj > ui || (uj == ui && pj < pi)) ? 1 : 0;
+              }
+              const int last = __builtin_ctzll(__builtin_amdgcn_ballot_w64(have && before == need - 1));
+              prefix = __shfl(ui, last, 64);
+              tie = __shfl(pi, last, 64);
+              __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+              __builtin_amdgcn_wave_barrier();
+              break;
+            }
           }
           T = prefix;   // all 32 bits decided: `need` of the weights equal to it stay, the lowest positions first
 #pragma unroll
           for (int t = 0; t < NKMAX; ++t) {
-            if (t < tmax) {
+            if (t < tmax && tie < 0) {
               unsigned long long m = __builtin_amdgcn_ballot_w64(u[t] == T);
               const int cnt = __builtin_popcountll(m);
-              if (tie < 0) {
-                if (need > cnt) {
-                  need -= cnt;
-                } else {
-                  for (int i = 1; i < need; ++i) m &= m - 1;   // drop the need-1 lowest positions
-                  tie = __builtin_ctzll(m) + 64 * t;
-                }
+              if (need > cnt) {
+                need -= cnt;
+              } else {
+                for (int i = 1; i < need; ++i) m &= m - 1;   // drop the need-1 lowest positions
+                tie = __builtin_ctzll(m) + 64 * t;
               }
             }
           }
@@ -368,7 +412,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void topk_attend_kernel(const TopkA
 
 size_t padded_keys(int S) { return size_t(S + 31) / 32 * 32; }
 
-template <int DH, int NQB>
+template <int DH, int NQB, int NKMAX>
 hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
   TopkArgs a = base;
   constexpr int NQ16 = NQB * 16;
@@ -377,11 +421,11 @@ hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
   const int merge_bytes = kWaves * (DH / 16) * NQB * 64 * 16;
   a.region0 = (logit_bytes > merge_bytes ? logit_bytes : merge_bytes);
   const int lds = a.region0 + NQ16 * (DH * 2 + 16) + NQ16 * 12 + kWaves * NQ16 * 4 + kWaves * 256 * 4;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_attend_kernel<DH, NQB>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_attend_kernel<DH, NQB, NKMAX>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return e;
   const dim3 grid((a.S + NQ16 - 1) / NQ16, rows), block(64 * kWaves);
-  hipLaunchKernelGGL((topk_attend_kernel<DH, NQB>), grid, block, lds, st, a);
+  hipLaunchKernelGGL((topk_attend_kernel<DH, NQB, NKMAX>), grid, block, lds, st, a);
   return hipGetLastError();
 }
 
@@ -418,10 +462,13 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
   a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(head_dim));
   hipError_t e;
+  // 16 queries per workgroup: their fp32 weights take 64 KB of LDS at 1024 keys, so two workgroups (16 waves) share
+  // a compute unit and hide each other's latencies (32 queries per workgroup, one workgroup per unit, read K and V
+  // half as often and took 3.33 ms where this takes 2.27 ms)
   if (seq <= kMaxSeq / 2)
-    e = head_dim == 128 ? launch<128, 2>(a, rows, st) : launch<64, 2>(a, rows, st);
+    e = head_dim == 128 ? launch<128, 1, 16>(a, rows, st) : launch<64, 1, 16>(a, rows, st);
   else
-    e = head_dim == 128 ? launch<128, 1>(a, rows, st) : launch<64, 1>(a, rows, st);
+    e = head_dim == 128 ? launch<128, 1, 32>(a, rows, st) : launch<64, 1, 32>(a, rows, st);
   return e == hipSuccess ? ADORE_OK : ADORE_E_HIP;
 }
 

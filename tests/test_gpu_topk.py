@@ -34,8 +34,10 @@ GRID_CASES = [
     (1, 257, 128, 96),        # ragged tail of one query and one key
     (2, 600, 64, 96),         # several query blocks, every wave has several key blocks
     (1, 300, 128, 1000),      # K beyond the sequence: plain causal attention
-    (1, 1024, 128, 96),       # the largest sequence the 32-query blocks take
-    (1, 1100, 64, 200),       # 16-query blocks
+    (1, 1024, 128, 96),       # the longest rows a lane holds as 16 keys
+    (1, 1100, 64, 200),       # 32 keys per lane
+    (1, 2048, 128, 300),      # the longest sequence taken
+    (2, 200, 64, 64),         # K a multiple of the wave: the cut falls on a lane boundary
 ]
 
 
