@@ -454,7 +454,7 @@ def main():
     INPUTS_ORDERED = args.input_order == "stream"
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (the decode step shards by "
-                 "sequence or by head with no exchange; see DESIGN.md). Run with --gpus 1.")
+                 "sequence or by head with no exchange step). Run with --gpus 1.")
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU (the HIP path has no CPU fallback)")
