@@ -375,7 +375,8 @@ def topk_line(w, args):
     flops = 2.0 * rows * d * (S * (S + 1) / 2 + kept)
     roof = dict(kernel="topk_attention (transpose of V + attention)", bound="mfma",
                 achieved=round(flops / (us * 1e-6) / 1e12, 1), peak=MFMA_PEAK_TFLOPS["bf16"], unit="TFLOP/s",
-                frac=round(flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4), traffic=None,
+                frac=round(flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4),
+                traffic=(recorded_traffic(w, "topk_attention").get("topk_attention") if K == 96 else None),
                 us_per_launch=round(us, 1), algorithmic_flops=flops,
                 note="the selection (a four-pass radix select per query: LDS histograms, wave scans) runs beside the matrix work")
     line = {

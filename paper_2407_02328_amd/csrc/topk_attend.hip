@@ -70,6 +70,7 @@ struct TopkArgs {
   const bf16_t *Vt;      // [rows][d][Sp]
   bf16_t *O;             // [rows][S][d]
   int S, Sp, topk, lstr; // lstr: floats per logit row in LDS
+  int rows;
   int region0;           // bytes of the first LDS region (logit rows, later the merge buffer)
   float scale_log2;      // log2(e) / sqrt(d)
 };
@@ -102,8 +103,24 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
   float *s_l = s_max + NQ16;                                             // [kWaves][NQ16]
   uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_l + kWaves * NQ16);  // [kWaves][256] radix histograms
 
-  const int qblk = int(gridDim.x) - 1 - int(blockIdx.x);   // the blocks with the most keys start first
-  const size_t bh = blockIdx.y;
+  // Workgroup -> (row, query block).  Consecutive workgroups go to the 8 XCDs in turn, each with an L2 of its own:
+  // all query blocks of a row are given to one XCD (workgroups L, L + 8, L + 16 ...), so that the row's K and V^T
+  // come from memory once instead of once per XCD; within a row the blocks with the most keys start first.
+  const int nq = (a.S + NQ16 - 1) / NQ16;
+  const int full = a.rows / 8 * 8;             // rows that form whole groups of 8
+  const int L = blockIdx.x;
+  int row_, qi;
+  if (L < full * nq) {
+    const int slot = L >> 3;
+    row_ = slot / nq * 8 + (L & 7);
+    qi = slot - slot / nq * nq;
+  } else {
+    const int rest = L - full * nq;
+    row_ = full + rest / nq;
+    qi = rest - rest / nq * nq;
+  }
+  const int qblk = nq - 1 - qi;
+  const size_t bh = size_t(row_);
   const int q0 = qblk * NQ16;
   const int nkeys = min(a.S, q0 + NQ16);    // keys a query of this block can see
   const int nb32 = (nkeys + 31) / 32;
@@ -424,7 +441,8 @@ hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_attend_kernel<DH, NQB, NKMAX>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return e;
-  const dim3 grid((a.S + NQ16 - 1) / NQ16, rows), block(64 * kWaves);
+  a.rows = rows;
+  const dim3 grid(unsigned((a.S + NQ16 - 1) / NQ16) * unsigned(rows)), block(64 * kWaves);
   hipLaunchKernelGGL((topk_attend_kernel<DH, NQB, NKMAX>), grid, block, lds, st, a);
   return hipGetLastError();
 }
@@ -459,7 +477,7 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
   a.K = static_cast<const bf16_t *>(k);
   a.Vt = static_cast<const bf16_t *>(workspace);
   a.O = static_cast<bf16_t *>(out);
-  a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0;
+  a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0; a.rows = rows;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(head_dim));
   hipError_t e;
   // 16 queries per workgroup: their fp32 weights take 64 KB of LDS at 1024 keys, so two workgroups (16 waves) share

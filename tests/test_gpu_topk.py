@@ -38,6 +38,7 @@ GRID_CASES = [
     (1, 1100, 64, 200),       # 32 keys per lane
     (1, 2048, 128, 300),      # the longest sequence taken
     (2, 200, 64, 64),         # K a multiple of the wave: the cut falls on a lane boundary
+    (11, 70, 64, 20),         # one whole group of 8 rows (one per XCD) and a tail of 3
 ]
 
 
