@@ -63,6 +63,8 @@ struct GemmArgs {
   int out_rps, out_cur;        // OPROJ: rank j is written to row b * out_rps + j, the current token to b * out_rps + out_cur
   int n_cur;                   // QKV / OPROJ: the first n_cur workgroups of the tile launch take the current tokens' rows
   int cur_ks;                  // ... with the contraction cut over cur_ks (1, 2, 4, 8) of a workgroup's waves
+  const float2 *rope_cur;      // QKV: the workgroups of the current tokens' rows turn their query and key rows (same
+                               // table; null: they do not)
   const float2 *rope;          // tile kernel: [N_max][d/2] (cos, sin), the key (and query) tiles turn their rows by
                                // position as they leave; null: no rotary embedding, or a pass of its own does it
 };
@@ -155,6 +157,7 @@ __device__ inline void cur_rows_role(const GemmArgs &a, int e, u32x4 *smem) {
     }
   }
 #undef CUR_LOAD
+  const bool turning = MODE == MODE_QKV && a.rope_cur != nullptr;   // uniform over the launch
   if (ks > 1) {   // the parts of the contraction meet in the wave that holds part 0, in order
     float *red = reinterpret_cast<float *>(smem + 8 * (32 * 8));   // [8 waves][2][4][64], behind the waves' tiles
 #pragma unroll
@@ -162,12 +165,71 @@ __device__ inline void cur_rows_role(const GemmArgs &a, int e, u32x4 *smem) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[((wave * 2 + nc) * 4 + v) * 64 + lane] = acc[nc][v];
     __syncthreads();
-    if (kpart != 0) return;
-    for (int p = 1; p < ks; ++p)
+    if (kpart != 0 && !turning) return;   // (when the rows are turned below, every wave stays for the barrier)
+    for (int p = 1; p < (kpart == 0 ? ks : 1); ++p)
 #pragma unroll
       for (int nc = 0; nc < 2; ++nc)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[nc][v] += red[(((wave + p) * 2 + nc) * 4 + v) * 64 + lane];
+  }
+  if (turning) {
+    // Rotary embedding: the workgroup's columns are whole heads of one section (launcher).  The rounded results meet
+    // in an LDS tile [16 sequences][wg_cols]; then a thread takes 8 planes at a time (the 8-element vectors of
+    // elements j.. and j + d/2.. of a head), turns query and key rows to the current position, and stores 16 bytes.
+    uint16_t *sT = reinterpret_cast<uint16_t *>(smem + 8 * (32 * 8) + 8 * 2 * 4 * 64 / 4);   // behind tiles and sums
+    if (kpart == 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int nc = 0; nc < 2; ++nc)
+          sT[(4 * g + v) * wg_cols + (wave / ks) * 32 + nc * 16 + c] = f32_to_bf16_rne(acc[nc][v]);
+    }
+    __syncthreads();
+    const int section = (jn * wg_cols) / Hd;             // 0: queries, 1: keys, 2: values
+    const int half = a.d / 2;
+    const bool turn = section <= 1;
+    const int upr = turn ? wg_cols / 16 : wg_cols / 8;   // units per sequence: vector pairs, or single vectors
+    for (int idx = tid; idx < 16 * upr; idx += 512) {
+      const int seq = idx / upr, uu = idx - seq * upr;
+      const int b = t0 + seq;
+      if (b >= a.B) continue;
+      int col, jp = 0;
+      if (turn) {
+        const int hv = half / 8, hh = uu / hv;
+        jp = (uu - hh * hv) * 8;
+        col = hh * a.d + jp;
+      } else {
+        col = uu * 8;
+      }
+      const int rem = jn * wg_cols + col - section * Hd;
+      const int h = rem / a.d;
+      bf16_t *dst;
+      if (section == 0) {
+        dst = static_cast<bf16_t *>(a.Out) + (size_t(b) * a.xrps + a.r) * Hd + rem;
+      } else {
+        const int slot = a.insert_slot[size_t(b) * a.H + h];
+        dst = static_cast<bf16_t *>(section == 1 ? a.Kc : a.Vc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+      }
+      const u32x4 lo = *reinterpret_cast<const u32x4 *>(sT + seq * wg_cols + col);
+      if (!turn) {
+        *reinterpret_cast<u32x4 *>(dst) = lo;
+        continue;
+      }
+      const u32x4 hi = *reinterpret_cast<const u32x4 *>(sT + seq * wg_cols + col + half);
+      const float2 *cs = a.rope_cur + size_t(a.cur_pos) * half + jp;
+      uint32_t rl[8], rh[8];
+#pragma unroll
+      for (int e2 = 0; e2 < 8; ++e2) {
+        const float x = __uint_as_float(((lo[e2 / 2] >> (16 * (e2 & 1))) & 0xffffu) << 16);
+        const float y = __uint_as_float(((hi[e2 / 2] >> (16 * (e2 & 1))) & 0xffffu) << 16);
+        rl[e2] = f32_to_bf16_rne(rope_lo(x, y, cs[e2]));
+        rh[e2] = f32_to_bf16_rne(rope_hi(x, y, cs[e2]));
+      }
+      *reinterpret_cast<u32x4 *>(dst) = u32x4{rl[0] | (rl[1] << 16), rl[2] | (rl[3] << 16), rl[4] | (rl[5] << 16), rl[6] | (rl[7] << 16)};
+      *reinterpret_cast<u32x4 *>(dst + half) =
+          u32x4{rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16)};
+    }
+    return;
   }
   // accumulator element v of lane (c, g): sequence 4*g + v of the block, column c of the tile
 #pragma unroll
@@ -749,6 +811,7 @@ void fill_common(adore_ctx *ctx, GemmArgs &a, int lists, int r) {
   a.n_cur = 0;
   a.cur_ks = 1;
   a.rope = nullptr;
+  a.rope_cur = nullptr;
 }
 
 }  // namespace
@@ -859,12 +922,16 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
   a.xrps = r + 1; a.cur_pos = ctx->n; a.a_gather = by_position ? 1 : 0;
   a.M = c.batch * r; a.N = 3 * Hd;
   bool turned = false;   // the tiles turned the rebuilt tokens' query and key rows themselves
+  bool cur_turned = false;   // ... and the workgroups of the current tokens' rows theirs
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
     const int pick = pick_with_riders(a, c.hidden, Hd, c.head_dim, false);
     if (pick < 0) return hipErrorInvalidValue;
     turned = c.rope_base > 0.f && kTiles[pick].bn >= c.head_dim;
     if (turned) a.rope = ctx->rope_f;
+    // the current tokens' rows riding in this launch turn themselves when a workgroup's columns are whole heads
+    cur_turned = c.rope_base > 0.f && a.n_cur > 0 && (kCurCols / a.cur_ks) % c.head_dim == 0;
+    if (cur_turned) a.rope_cur = ctx->rope_f;
     launch_tile<MODE_QKV>(t, ctx->stream, pick, a);
   }
   if (a.n_cur == 0) {
@@ -872,8 +939,8 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
     launch_cur_rows<MODE_QKV>(t, ctx->stream, a);
   }
   hipError_t e = hipGetLastError();
-  // rotary embedding: the current tokens' rows always, the rebuilt tokens' rows unless the tiles did it
-  if (e == hipSuccess) e = launch_rope_rows(ctx, layer, ctx->cur, r, turned ? r : 0, r + 1, true, ctx->n);
+  // rotary embedding: whatever rows the launch above did not turn itself
+  if (e == hipSuccess) e = launch_rope_rows(ctx, layer, ctx->cur, r, turned ? r : 0, cur_turned ? r : r + 1, true, ctx->n);
   return e;
 }
 
