@@ -861,3 +861,40 @@ def test_rotary_embedding_in_a_context_restored_without_an_init():
     occ = job.snapshot()["slot_pos"] >= 0
     assert np.array_equal(ref_k[0][occ], fresh.snapshot()["cache_k"][0][occ])
     job.adore.close(); fresh.adore.close()
+
+
+# ---- the sweeps of random shapes again with the rotary embedding on --------------------------------
+@pytest.mark.parametrize("name,kw,calls,ordered", _random_workloads(24, 515))
+def test_random_small_configurations_with_rotary_embedding(name, kw, calls, ordered):
+    h = _harness()
+    w = Workload(name, rope_base=float(10 ** (2 + len(name) % 3)), **kw)        # bases 100, 1000, 10000
+    whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=3, whole=whole, ordered=ordered)
+    job.adore.close()
+
+
+@pytest.mark.parametrize("name,kw", _random_rescore_workloads(6, 99))
+def test_random_small_configurations_rescore_with_rotary_embedding(name, kw):
+    h = _harness()
+    w = Workload(name, rope_base=10000.0, **kw)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=(lambda t: t % 2 == 0) if w.L == 1 else None)
+    job.adore.close()
+
+
+@pytest.mark.parametrize("name,kw", _random_forward_workloads(12, 23))
+def test_random_small_configurations_forward_with_rotary_embedding(name, kw):
+    """Widths H*d that are multiples of 256 turn the current tokens' rows inside the projection launch (whole heads
+    per workgroup, or not: then the pass of its own), the others go through the pass; tiles wide and narrow."""
+    h = _harness()
+    w = Workload(name, dtype="bf16", dprime=32, w_std=0.96 / np.sqrt(kw["D"]), rope_base=10000.0, **kw)
+    worst, mean = h.forward_lockstep(w, w.T)
+    assert mean < 2.0 ** -10
+
+
+@pytest.mark.parametrize("name,kw,calls,ordered", _random_medium_workloads(4, 41))
+def test_random_medium_configurations_with_rotary_embedding(name, kw, calls, ordered):
+    h = _harness()
+    w = Workload(name, rope_base=10000.0, **kw)
+    whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=2, whole=whole, ordered=ordered, full_size_rows=True)
+    job.adore.close()
