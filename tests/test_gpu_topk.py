@@ -125,3 +125,31 @@ def test_topk_attention_rejects_what_it_does_not_take():
         topk_attention(q, q, q, 0)
     with pytest.raises(AdoreError):
         topk_attention(q, q, q, 4, workspace=torch.empty(16, dtype=torch.uint8, device="cuda:0"))
+
+
+def _random_topk_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        S = int(rng.integers(1, 700))
+        out.append((int(rng.integers(1, 12)), S, int(rng.choice([64, 128])), int(rng.integers(1, S + 40)),
+                    int(rng.choice([1, 2, 4, 8]))))
+    return out
+
+
+@pytest.mark.parametrize("rows,S,d,top_k,levels", _random_topk_cases(24, 2407))
+def test_topk_attention_random_shapes_on_exactly_representable_weights(rows, S, d, top_k, levels):
+    """Random shapes; q and k on grids of `levels` steps per unit (coarse grids: most weights of a query tie, so
+    the cut among equal weights decides nearly every row; fine grids: few ties)."""
+    torch, O, topk_attention = _mods()
+    rng = np.random.default_rng(rows * 100003 + S * 17 + top_k)
+    q = rng.integers(-2 * levels, 2 * levels + 1, size=(rows, S, d)) / float(levels)
+    k = rng.integers(-2 * levels, 2 * levels + 1, size=(rows, S, d)) / float(levels)
+    if levels == 1:                        # very coarse: make whole runs of keys identical
+        k[:, ::3] = k[:, :1]
+    v = _bf16_values(torch, rng.standard_normal((rows, S, d)))
+    want, kept = O.topk_attention(q, k, v, top_k)
+    got = topk_attention(_to_gpu(torch, q), _to_gpu(torch, k), _to_gpu(torch, v), top_k)
+    torch.cuda.synchronize()
+    e = _row_err(got.float().cpu().numpy().astype(np.float64), want)
+    assert e.max() < 2e-3 + 2.0 ** -8, f"rows={rows} S={S} d={d} K={top_k} levels={levels}: {e.max()}"
