@@ -352,8 +352,8 @@ def topk_line(w, args):
     from paper_2407_02328_amd import topk_attention, load_library
     dev = "cuda:0"
     rows, S, d, K = w.B * w.H, w.S, w.d, args.topk
-    if S > 2048 or d not in (64, 128):
-        sys.exit(f"adore_topk_attention takes sequences up to 2048 tokens and head_dim 64 or 128 (asked: {S}, {d})")
+    if S > 32768 or d not in (64, 128):
+        sys.exit(f"adore_topk_attention takes sequences up to 32768 tokens and head_dim 64 or 128 (asked: {S}, {d})")
     drawer = DeviceNormals(w.seed, dev)
     q, k, v = (drawer.normal((rows, S, d), 1.0, torch.bfloat16) for _ in range(3))
     out = torch.empty_like(q)

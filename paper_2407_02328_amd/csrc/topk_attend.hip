@@ -44,7 +44,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 8;
-constexpr int kMaxSeq = 2048;
+constexpr int kMaxSeq = 2048;        // longest sequence whose logit rows (16 queries) fit LDS
+constexpr int kMaxLongSeq = 32768;   // longest sequence taken at all (rows in the workspace)
 
 // V [rows][S][d] -> V^T [rows][d][Sp], keys S .. Sp-1 as zeros.  One workgroup per 32 keys of one row.
 __global__ __launch_bounds__(256) void topk_vt_kernel(const bf16_t *V, bf16_t *Vt, int S, int Sp, int d) {
@@ -69,8 +70,9 @@ struct TopkArgs {
   const bf16_t *Q, *K;   // [rows][S][d]
   const bf16_t *Vt;      // [rows][d][Sp]
   bf16_t *O;             // [rows][S][d]
-  int S, Sp, topk, lstr; // lstr: floats per logit row in LDS
+  int S, Sp, topk, lstr; // lstr: floats per logit row
   int rows;
+  float *rowbuf;         // long sequences: [workgroups][16][lstr] logit rows in the workspace
   int region0;           // bytes of the first LDS region (logit rows, later the merge buffer)
   float scale_log2;      // log2(e) / sqrt(d)
 };
@@ -81,6 +83,34 @@ __device__ inline uint32_t weight_key(float x) {
   if (x == -INFINITY) return 0u;
   const uint32_t b = __float_as_uint(x + 0.0f);
   return b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+}
+
+// Scan of a 256-bin histogram from the top bin down: the bin in which the rank `need` (1 = the largest) falls, the
+// rank left inside it, and how many entries it holds.  Lane l owns bins 255 - 4l .. 252 - 4l.  Wave-uniform results.
+__device__ inline void pick_bin(const uint32_t *hist, int lane, int need, int &bin, int &rest, int &inbin) {
+  const u32x4 hv = *reinterpret_cast<const u32x4 *>(hist + 252 - 4 * lane);
+  const int c0 = int(hv[3]), c1 = int(hv[2]), c2 = int(hv[1]), c3 = int(hv[0]);
+  const int own = c0 + c1 + c2 + c3;
+  int incl = own;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int other = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += other;
+  }
+  const int excl = incl - own;
+  const bool mine = excl < need && need <= incl;   // exactly one lane: need <= the number of candidates
+  int b = 252 - 4 * lane, r = need - excl - c0 - c1 - c2, n = c3;
+  if (need <= excl + c0) {
+    b = 255 - 4 * lane; r = need - excl; n = c0;
+  } else if (need <= excl + c0 + c1) {
+    b = 254 - 4 * lane; r = need - excl - c0; n = c1;
+  } else if (need <= excl + c0 + c1 + c2) {
+    b = 253 - 4 * lane; r = need - excl - c0 - c1; n = c2;
+  }
+  const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(mine));
+  bin = __shfl(b, src, 64);
+  rest = __shfl(r, src, 64);
+  inbin = __shfl(n, src, 64);
 }
 
 // NQB: blocks of 16 queries per workgroup; NKMAX: keys of a row a lane can hold (64 * NKMAX >= the keys of a row)
@@ -95,7 +125,10 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
   constexpr int LPR = DH / 8;          // 16-byte vectors per row
   constexpr int RPW = NQ16 / kWaves;   // query rows a wave selects for
   extern __shared__ __align__(16) unsigned char smem[];
-  float *s_log = reinterpret_cast<float *>(smem);                        // [NQ16][lstr]; later the merge buffer
+  // the weights of the block's queries: [NQ16][lstr] fp32 in LDS (later the merge buffer), or, for sequences whose
+  // rows LDS cannot hold, in the workgroup's own piece of the workspace (written and read by this workgroup only)
+  constexpr bool LONG = NKMAX == 0;
+  float *s_log = LONG ? a.rowbuf + size_t(blockIdx.x) * NQ16 * a.lstr : reinterpret_cast<float *>(smem);
   unsigned char *s_q = smem + a.region0;                                 // [NQ16][QSTR]
   uint32_t *s_T = reinterpret_cast<uint32_t *>(s_q + NQ16 * QSTR);       // [NQ16] image of the K-th largest weight
   int32_t *s_tie = reinterpret_cast<int32_t *>(s_T + NQ16);              // [NQ16] equal weights kept up to here
@@ -196,7 +229,57 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
       uint32_t T = 0xffffffffu;               // rows beyond the sequence keep nothing
       int tie = -1;
       float mx = 0.f;
-      if (p < a.S) {
+      if (LONG && p < a.S) {
+        // The row stays in memory (it was written by this workgroup and comes from the L2): every pass reads it
+        // again, 64 keys at a time.  Four passes always; then the cut among the equal weights in position order.
+        const float *lrow = s_log + row * lstr;
+        const int nkp = nb32 * 32;
+        mx = -INFINITY;
+        for (int j = lane; j < nkp; j += 64) mx = fmaxf(mx, lrow[j]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        if (p + 1 <= a.topk) {
+          T = 1u;
+          tie = 0x7fffffff;
+        } else {
+          uint32_t *hist = s_hist + wave * 256;
+          uint32_t prefix = 0u;
+          int need = a.topk;
+#pragma unroll 1
+          for (int shift = 24; shift >= 0; shift -= 8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hist[lane + 64 * i] = 0u;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t himask = shift == 24 ? 0u : 0xffffffffu << (shift + 8);
+            for (int j = lane; j < nkp; j += 64) {
+              const uint32_t uj = weight_key(lrow[j]);
+              if (uj != 0u && (uj & himask) == prefix) atomicAdd(&hist[(uj >> shift) & 255u], 1u);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            int bin, rest, inbin;
+            pick_bin(hist, lane, need, bin, rest, inbin);
+            need = rest;
+            prefix |= uint32_t(bin) << shift;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+          }
+          T = prefix;
+          for (int j0 = 0; j0 < nkp && tie < 0; j0 += 64) {     // nkp is a multiple of 32: guard the last half group
+            const uint32_t uj = j0 + lane < nkp ? weight_key(lrow[j0 + lane]) : 0u;
+            unsigned long long m = __builtin_amdgcn_ballot_w64(uj == T);
+            const int cnt = __builtin_popcountll(m);
+            if (need > cnt) {
+              need -= cnt;
+            } else {
+              for (int i = 1; i < need; ++i) m &= m - 1;
+              tie = __builtin_ctzll(m) + j0;
+            }
+          }
+        }
+      }
+      if constexpr (!LONG) if (p < a.S) {
         const float *lrow = s_log + row * lstr;
         uint32_t u[NKMAX];
         mx = -INFINITY;
@@ -233,34 +316,9 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
               if (t < tmax && u[t] != 0u && (u[t] & himask) == prefix) atomicAdd(&hist[(u[t] >> shift) & 255u], 1u);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            // lane l owns bins 255 - 4l .. 252 - 4l; counts from the top bin down
-            const u32x4 hv = *reinterpret_cast<const u32x4 *>(hist + 252 - 4 * lane);
-            const int c0 = int(hv[3]), c1 = int(hv[2]), c2 = int(hv[1]), c3 = int(hv[0]);
-            const int own = c0 + c1 + c2 + c3;
-            int incl = own;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-              const int other = __shfl_up(incl, off, 64);
-              if (lane >= off) incl += other;
-            }
-            const int excl = incl - own;
-            const bool mine = excl < need && need <= incl;   // exactly one lane: need <= the number of candidates
-            int bin = 252 - 4 * lane, rest = need - excl - c0 - c1 - c2;
-            if (need <= excl + c0) {
-              bin = 255 - 4 * lane; rest = need - excl;
-            } else if (need <= excl + c0 + c1) {
-              bin = 254 - 4 * lane; rest = need - excl - c0;
-            } else if (need <= excl + c0 + c1 + c2) {
-              bin = 253 - 4 * lane; rest = need - excl - c0 - c1;
-            }
-            const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(mine));
-            int inbin = c3;
-            if (need <= excl + c0) inbin = c0;
-            else if (need <= excl + c0 + c1) inbin = c1;
-            else if (need <= excl + c0 + c1 + c2) inbin = c2;
-            bin = __shfl(bin, src, 64);
-            need = __shfl(rest, src, 64);
-            inbin = __shfl(inbin, src, 64);
+            int bin, rest, inbin;
+            pick_bin(hist, lane, need, bin, rest, inbin);
+            need = rest;
             prefix |= uint32_t(bin) << shift;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the reads above come before the next writes
             __builtin_amdgcn_wave_barrier();
@@ -428,13 +486,14 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
 }
 
 size_t padded_keys(int S) { return size_t(S + 31) / 32 * 32; }
+size_t vt_bytes(int rows, int S, int d) { return (size_t(rows) * d * padded_keys(S) * 2 + 255) / 256 * 256; }
 
 template <int DH, int NQB, int NKMAX>
 hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
   TopkArgs a = base;
   constexpr int NQ16 = NQB * 16;
   a.lstr = a.Sp + 4;
-  const int logit_bytes = NQ16 * a.lstr * 4;
+  const int logit_bytes = NKMAX == 0 ? 0 : NQ16 * a.lstr * 4;
   const int merge_bytes = kWaves * (DH / 16) * NQB * 64 * 16;
   a.region0 = (logit_bytes > merge_bytes ? logit_bytes : merge_bytes);
   const int lds = a.region0 + NQ16 * (DH * 2 + 16) + NQ16 * 12 + kWaves * NQ16 * 4 + kWaves * 256 * 4;
@@ -455,7 +514,10 @@ extern "C" {
 
 size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t head_dim) {
   if (rows <= 0 || seq <= 0 || head_dim <= 0) return 0;
-  return (size_t(rows) * head_dim * adore::padded_keys(seq) * 2 + 255) / 256 * 256;
+  const size_t vt = adore::vt_bytes(rows, seq, head_dim);
+  // sequences whose logit rows LDS cannot hold: 16 rows of fp32 weights per workgroup of 16 queries
+  const size_t rowbuf = seq > adore::kMaxSeq ? size_t(rows) * ((seq + 15) / 16) * 16 * (adore::padded_keys(seq) + 4) * 4 : 0;
+  return vt + (rowbuf + 255) / 256 * 256;
 }
 
 int adore_topk_attention(const void *q, const void *k, const void *v, void *out, void *workspace,
@@ -463,7 +525,7 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
                          void *hip_stream) {
   using namespace adore;
   if (!q || !k || !v || !out || !workspace || rows <= 0 || seq <= 0 || head_dim <= 0 || top_k < 1) return ADORE_E_INVALID;
-  if ((head_dim != 64 && head_dim != 128) || seq > kMaxSeq || rows > 65535) return ADORE_E_UNSUPPORTED;
+  if ((head_dim != 64 && head_dim != 128) || seq > kMaxLongSeq || rows > 65535) return ADORE_E_UNSUPPORTED;
   if (workspace_bytes < adore_topk_attention_workspace_bytes(rows, seq, head_dim) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
     return ADORE_E_WORKSPACE;
@@ -478,6 +540,7 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
   a.Vt = static_cast<const bf16_t *>(workspace);
   a.O = static_cast<bf16_t *>(out);
   a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0; a.rows = rows;
+  a.rowbuf = reinterpret_cast<float *>(static_cast<char *>(workspace) + vt_bytes(rows, seq, head_dim));
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(head_dim));
   hipError_t e;
   // 16 queries per workgroup: their fp32 weights take 64 KB of LDS at 1024 keys, so two workgroups (16 waves) share
@@ -485,8 +548,10 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
   // half as often and took 3.33 ms where this takes 2.27 ms)
   if (seq <= kMaxSeq / 2)
     e = head_dim == 128 ? launch<128, 1, 16>(a, rows, st) : launch<64, 1, 16>(a, rows, st);
-  else
+  else if (seq <= kMaxSeq)
     e = head_dim == 128 ? launch<128, 1, 32>(a, rows, st) : launch<64, 1, 32>(a, rows, st);
+  else   // logit rows in the workspace
+    e = head_dim == 128 ? launch<128, 1, 0>(a, rows, st) : launch<64, 1, 0>(a, rows, st);
   return e == hipSuccess ? ADORE_OK : ADORE_E_HIP;
 }
 

@@ -178,6 +178,9 @@ def test_topk_attention_host_checks(lib):
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 64, 0, None) == -1
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 0, 64, 64, 4, None) == -1
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 96, 4, None) == -3
-    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, 2, 4096, 64, 4, None) == -3
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, 2, 40000, 64, 4, None) == -3
+    long = ws(2, 4096, 64)            # beyond 2048 tokens the weights of every query live in the workspace
+    assert long >= 2 * 64 * 4096 * 2 + 2 * 4096 * 4096 * 4
+    assert call(FAKE, FAKE, FAKE, FAKE, FAKE, long - 1, 2, 4096, 64, 4, None) == -4
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n - 1, 2, 64, 64, 4, None) == -4
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE + 16, n, 2, 64, 64, 4, None) == -4
