@@ -93,11 +93,13 @@ def test_injected_ties_are_broken_by_position():
     job.adore.close()
 
 
-def test_hand_worked_trajectory_on_gpu():
+@pytest.mark.parametrize("name,K,R", [("slot_trajectory_K4_R1.txt", 4, 1), ("slot_trajectory_K7_R3.txt", 7, 3)])
+def test_hand_worked_trajectory_on_gpu(name, K, R):
+    """The slot maps worked out by hand; the second file pins which free slot each rebuilt rank takes."""
     h = _harness()
-    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, "slot_trajectory_K4_R1.txt"))
+    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, name))
     S = len(init_scores)
-    w = Workload("golden", L=1, B=1, H=2, d=64, D=64, K=4, R=1, S=S, T=len(steps), dtype="f32", dprime=16)
+    w = Workload("golden", L=1, B=1, H=2, d=64, D=64, K=K, R=R, S=S, T=len(steps), dtype="f32", dprime=16)
     job = h.GpuJob(w)
     job.init(init_scores[None, :])
     snap = job.snapshot()

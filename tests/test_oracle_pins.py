@@ -244,10 +244,14 @@ def _run(orc, inp, w, steps, override=None, collect=None):
     return outs, hs, pk, pv
 
 
-def test_hand_worked_trajectory():
-    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, "slot_trajectory_K4_R1.txt"))
+@pytest.mark.parametrize("name,K,R", [("slot_trajectory_K4_R1.txt", 4, 1), ("slot_trajectory_K7_R3.txt", 7, 3)])
+def test_hand_worked_trajectory(name, K, R):
+    """Slot maps worked out by hand from the rules.  The second file rebuilds three tokens per step into free
+    slots that are not neighbours, so the order in which the ranks take the free slots (rank rho -> rho-th
+    lowest free slot) decides every line of it."""
+    init_scores, after_init, steps = parse_trajectory(os.path.join(GOLDEN, name))
     S = len(init_scores)
-    w = Workload("golden", L=1, B=1, H=2, d=4, D=8, K=4, R=1, S=S, T=len(steps), dtype="f32", dprime=4)
+    w = Workload("golden", L=1, B=1, H=2, d=4, D=8, K=K, R=R, S=S, T=len(steps), dtype="f32", dprime=4)
     orc, inp, _ = make_oracle(w)
     hs = inp.hidden_store()
     pk, pv = inp.prompt_kv()
