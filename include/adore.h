@@ -35,8 +35,12 @@
  *     until then.  Inputs may be produced by work enqueued on that stream before
  *     the call (see adore_set_input_order for the one exception a caller can
  *     ask for).
- *   - The return value is the only error channel.  Arguments are validated on
- *     the host before anything is enqueued: a call that fails has no effect.
+ *   - The return value is the only error channel.  Arguments and the order of
+ *     calls are validated on the host before anything is enqueued: a call that
+ *     returns E_INVALID, E_STATE, E_UNSUPPORTED or E_WORKSPACE has had no effect.
+ *     E_HIP means the HIP runtime refused something in the middle of a call;
+ *     part of the step may have been enqueued, and the context has to be
+ *     restarted with adore_init_cache (or adore_set_state) before its next step.
  *   - A context is bound to one stream and is not thread-safe.  Contexts are
  *     independent of each other.
  *   - Ties between equal sigma are broken in favour of the lower position, so
@@ -52,7 +56,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 6
+#define ADORE_ABI_VERSION 7
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -207,6 +211,8 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
  *   score_override, slot_map, released_pos, rebuilt_pos: as adore_schedule
  *   rows_out  [B][R+1][D] storage type: the last layer's rows; rank j at [b][j], the current token
  *             at [b][R]; rows of unused ranks are left untouched
+ *   layer_rows [L][B][R+1][D] storage type or NULL: the rows leaving every layer (the hidden states of the
+ *             rebuilt tokens and of the current one, layer by layer), laid out like rows_out; [L-1] equals rows_out
  * Requires a context initialised with hidden_store == NULL, bf16 storage, R + 1 <= 64, K <= 8192,
  * H*d and D multiples of 128.  Enqueues work; does not synchronise.
  * Errors: E_INVALID, E_STATE (not initialised for the forward, step past N_max). */
@@ -215,7 +221,7 @@ typedef struct {
   const void *w_o;
 } adore_forward_weights;
 int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const void *embed,
-                       const float *score_override, void *rows_out, int32_t *slot_map,
+                       const float *score_override, void *rows_out, void *layer_rows, int32_t *slot_map,
                        int32_t *released_pos, int32_t *rebuilt_pos);
 
 /* Snapshot / restore between steps.  Any pointer may be NULL (skipped).
@@ -240,7 +246,13 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
  * are complete in memory when the step's call is made (say, the token's embedding
  * was gathered before the stream was last synchronised); that event is dropped and
  * the side work of later steps may start early.  All other inputs are read on the
- * context's stream in either mode.  HOST call between steps.
+ * context's stream in either mode.  Outputs with ordered == 0: slot_map, released_pos
+ * and rebuilt_pos of a step may then be written as soon as its call is made, ahead of
+ * work queued on the context's stream; a caller whose earlier work on that stream
+ * still reads the previous step's values gives each step buffers of its own (or
+ * synchronises first).  `out` and rows_out are written on the context's stream.
+ * The first step after adore_init_cache starts behind the init in either mode.
+ * HOST call between steps.
  * Errors: E_INVALID, E_STATE (in the middle of a step). */
 int adore_set_input_order(adore_ctx *ctx, int32_t ordered);
 

@@ -419,6 +419,7 @@ class AdoreForwardOracle(AdoreOracle):
         self._wo64: Dict[int, np.ndarray] = {}
         self.pending: List[List[int]] = [[] for _ in range(cfg.B)]   # chosen last step, rebuilt in the next
         self.last_rows = None            # [L+1][B] list of (positions, X) of the last step (diagnostics)
+        self.own = None                  # the last step's own per-layer values when it ran with `adopt`
 
     def _place_rebuilt(self, b, rebuilt, hidden_store):
         """Slots are assigned now (rank rho -> rho-th lowest free slot); their K/V follow at the next step."""
@@ -437,15 +438,27 @@ class AdoreForwardOracle(AdoreOracle):
             cache[layer] = np.asarray(self.wts[name][layer], dtype=F64)
         return cache[layer]
 
-    def forward_step(self, embed: np.ndarray, score_override: Optional[np.ndarray] = None):
+    def forward_step(self, embed: np.ndarray, score_override: Optional[np.ndarray] = None,
+                     adopt: Optional[Dict[str, np.ndarray]] = None):
         """embed: [B, N_max, D] token embeddings (rows <= n valid).  Returns (x_out [B,D] fp64: last layer's
         row of the current token, rows_out [B,R+1,D]: last layer's rows in rank order with the current token
-        last (unused rows zero), slot_map, released_pos, rebuilt_pos, own_score)."""
+        last (unused rows zero), slot_map, released_pos, rebuilt_pos, own_score).
+
+        adopt (lockstep runs against another implementation of this step): what that implementation stored
+        for the rows of this step, "x" [L,B,R+1,D] (the rows leaving every layer) and "k", "v" [L,B,H,R+1,d]
+        (the rows' K/V states), rank j at index j and the current token at index R.  Every layer then computes
+        its own K/V and rows from the inputs it is given, keeps them in self.own (same keys and shapes, for the
+        caller to compare), and hands the adopted ones on: to its attention (K/V) and to the next layer (rows).
+        The arithmetic of a layer is the same with and without it."""
         c = self.cfg
         n = self.n
         if n >= c.N_max:
             raise RuntimeError("step past N_max")
         Hd = c.H * c.d
+        if adopt is not None:
+            self.own = dict(x=np.zeros((c.L, c.B, c.R + 1, c.D), dtype=F64),
+                            k=np.zeros((c.L, c.B, c.H, c.R + 1, c.d), dtype=F64),
+                            v=np.zeros((c.L, c.B, c.H, c.R + 1, c.d), dtype=F64))
         released_pos = np.full((c.B, c.H, c.R + 1), -1, dtype=np.int32)
         rebuilt_pos = np.full((c.B, c.R), -1, dtype=np.int32)
         own_score = np.zeros(c.B, dtype=F64)
@@ -467,6 +480,12 @@ class AdoreForwardOracle(AdoreOracle):
                     Q = round_to_storage(rotary(Q.reshape(-1, c.H, c.d), positions, c.rope_base).reshape(-1, Hd),
                                          c.dtype)
                 KV = self._project(l, X, positions)                      # [r+1, 2*H*d], rounded
+                if adopt is not None:
+                    at = list(range(len(positions) - 1)) + [c.R]         # where the rows sit in the adopted arrays
+                    self.own["k"][l, b][:, at] = KV[:, :Hd].reshape(-1, c.H, c.d).transpose(1, 0, 2)
+                    self.own["v"][l, b][:, at] = KV[:, Hd:].reshape(-1, c.H, c.d).transpose(1, 0, 2)
+                    KV = np.concatenate([adopt["k"][l, b][:, at].transpose(1, 0, 2).reshape(-1, Hd),
+                                         adopt["v"][l, b][:, at].transpose(1, 0, 2).reshape(-1, Hd)], axis=1).astype(F64)
                 O = np.zeros((len(positions), Hd), dtype=F64)
                 for h in range(c.H):
                     slot_of = {int(p): k for k, p in enumerate(self.slot_pos[b, h]) if p >= 0}
@@ -481,6 +500,10 @@ class AdoreForwardOracle(AdoreOracle):
                                                                        self.Vc[l, b, h, valid])
                 O = round_to_storage(O, c.dtype)
                 X = round_to_storage(X + O @ Wo.T, c.dtype)
+                if adopt is not None:
+                    self.own["x"][l, b, at] = X
+                    if l < c.L - 1:
+                        X = np.asarray(adopt["x"][l, b, at], dtype=F64)
             rows_out[b, :len(positions) - 1] = X[:-1]
             rows_out[b, c.R] = X[-1]
             # controller, release, choice of the next rebuild set: as in the base class

@@ -85,7 +85,7 @@ def load_library() -> ctypes.CDLL:
     lib.adore_decode_step.restype = ctypes.c_int
     lib.adore_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.adore_forward_step.restype = ctypes.c_int
-    lib.adore_forward_step.argtypes = [vp, ctypes.POINTER(AdoreForwardWeights), vp, vp, vp, vp, vp, vp]
+    lib.adore_forward_step.argtypes = [vp, ctypes.POINTER(AdoreForwardWeights), vp, vp, vp, vp, vp, vp, vp]
     lib.adore_get_state.restype = ctypes.c_int
     lib.adore_get_state.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(i32)]
     lib.adore_set_state.restype = ctypes.c_int
@@ -250,7 +250,7 @@ class Adore:
             self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True)))
 
     def forward_step(self, w_q, w_o, embed, score_override, rows_out, slot_map=None, released_pos=None,
-                     rebuilt_pos=None):
+                     rebuilt_pos=None, layer_rows=None):
         c, st = self.cfg, self.storage
         Hd = c.heads * c.head_dim
         fw = AdoreForwardWeights(self._ptr(w_q, (c.layers, Hd, c.hidden), st, "w_q"),
@@ -260,6 +260,7 @@ class Adore:
             self._ptr(embed, (c.batch, c.max_positions, c.hidden), st, "embed"),
             self._ptr(score_override, (c.batch,), torch.float32, "score_override", optional=True),
             self._ptr(rows_out, (c.batch, c.rebuild_budget + 1, c.hidden), st, "rows_out"),
+            self._ptr(layer_rows, (c.layers, c.batch, c.rebuild_budget + 1, c.hidden), st, "layer_rows", optional=True),
             self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True),
             self._ptr(released_pos, (c.batch, c.heads, c.rebuild_budget + 1), torch.int32, "released_pos",
                       optional=True),

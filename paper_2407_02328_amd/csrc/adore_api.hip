@@ -24,6 +24,7 @@
 // stream then never runs ahead and the periodic wait above is not needed.  A caller whose inputs are
 // complete in memory when the call is made switches this off and saves that event.
 // ADORE_NO_OVERLAP=1 puts everything on the caller's stream.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -272,6 +273,13 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->overlap = !(no && atoi(no) != 0);
   const char *nr = getenv("ADORE_NO_RIDE");
   ctx->ride = ctx->overlap && !(nr && atoi(nr) != 0);
+  // Whether the selections may ride in the attention launch: static scores, a cache that releases, and the role's
+  // LDS at the last step of the longest sequence (its need grows with n) within what a workgroup gets without
+  // asking for more, 64 KB, next to the attention kernel's own static LDS.  Decided once, here, so that no step
+  // in the middle of a sequence finds its launch refused.
+  ctx->ride_fits = cfg->score_mode == ADORE_SCORE_STATIC && cfg->cache_slots <= kMaxSlots &&
+                   riding_lds_bytes(cfg->max_positions - 1, cfg->cache_slots, cfg->rebuild_budget) + kAttendStaticLds <=
+                       64 * 1024;
   ctx->side = ctx->side2 = ctx->stream;
   ctx->ev_ctrl = nullptr;
   ctx->ev_att = ctx->ev_join = ctx->ev_in = nullptr;
@@ -357,6 +365,11 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   if (ctx->overlap) {   // what the first step waits for is all above
     ADORE_TRY(hipEventRecord(ctx->ev_join, st));
     ADORE_TRY(hipEventRecord(ctx->ev_ctrl, st));
+    // The side streams start behind the init whatever the input order: the first step's controller reads the GRU
+    // state the prompt scan leaves and reuses its scratch, the first selections read the slot map.  (With ordered
+    // inputs every step waits for the caller's stream anyway; without, nothing else would hold them back.)
+    ADORE_TRY(hipStreamWaitEvent(ctx->side2, ctx->ev_ctrl, 0));
+    ADORE_TRY(hipStreamWaitEvent(ctx->side, ctx->ev_ctrl, 0));
   }
   ctx->n = S;
   ctx->occ = keep + r0;
@@ -507,9 +520,7 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
   if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
-  // the riding selections keep a sequence's scores and ranking keys in LDS (12 bytes per position)
-  const bool fits_lds = size_t(ctx->cfg.max_positions) * 12 + size_t(ctx->cfg.cache_slots) * 4 <= 56 * 1024;
-  if (ctx->ride && ctx->cfg.score_mode == ADORE_SCORE_STATIC && ctx->cfg.cache_slots <= kMaxSlots && fits_lds) {
+  if (ctx->ride && ctx->ride_fits) {
     if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
     return do_ridden_step(ctx, q, k_new, v_new, hidden_store, x_n, score_override, out, slot_map);
   }
@@ -523,8 +534,8 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
 }
 
 int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const void *embed,
-                       const float *score_override, void *rows_out, int32_t *slot_map, int32_t *released_pos,
-                       int32_t *rebuilt_pos) {
+                       const float *score_override, void *rows_out, void *layer_rows, int32_t *slot_map,
+                       int32_t *released_pos, int32_t *rebuilt_pos) {
   if (!ctx || !fw || !fw->w_q || !fw->w_o || !embed || !rows_out) return ADORE_E_INVALID;
   if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
   if (!ctx->inited || !ctx->forward || ctx->n >= ctx->cfg.max_positions) return ADORE_E_STATE;
@@ -569,6 +580,19 @@ int adore_forward_step(adore_ctx *ctx, const adore_forward_weights *fw, const vo
     if (last && runs_ahead(ctx) && (ctx->steps_done + 2) % kSyncEvery == 0) ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(launch_fwd_oproj(ctx, wo + size_t(l) * c.hidden * Hd * es, x_rows, by_pos, last ? rows_out : ctx->fwd_x,
                                last ? c.rebuild_budget + 1 : r + 1, last ? c.rebuild_budget : r, r));
+    if (layer_rows) {   // the caller's copy of the rows leaving this layer, in the layout of rows_out
+      const size_t row = size_t(c.hidden) * es, seq = row * (c.rebuild_budget + 1);
+      char *dst = static_cast<char *>(layer_rows) + size_t(l) * c.batch * seq;
+      if (last) {
+        ADORE_TRY(hipMemcpyAsync(dst, rows_out, size_t(c.batch) * seq, hipMemcpyDeviceToDevice, ctx->stream));
+      } else {
+        const char *src = static_cast<const char *>(ctx->fwd_x);
+        if (r > 0)
+          ADORE_TRY(hipMemcpy2DAsync(dst, seq, src, row * (r + 1), row * r, c.batch, hipMemcpyDeviceToDevice, ctx->stream));
+        ADORE_TRY(hipMemcpy2DAsync(dst + row * c.rebuild_budget, seq, src + row * r, row * (r + 1), row, c.batch,
+                                   hipMemcpyDeviceToDevice, ctx->stream));
+      }
+    }
   }
   ctx->r_pending = ctx->r_step;
   ctx->n++;
@@ -636,6 +660,23 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
     if (cnt != occ) return ADORE_E_INVALID;   // uniform policy: same occupancy everywhere
     ins[row] = first_free;
   }
+  // uniform policy: every head of a sequence holds the same positions (the per-sequence choice of the tokens to
+  // rebuild reads which ones from head 0 alone), each of them once
+  {
+    std::vector<int32_t> ref, mine;
+    for (int b = 0; b < c.batch; ++b) {
+      for (int h = 0; h < c.heads; ++h) {
+        const int32_t *rowp = host.data() + (size_t(b) * c.heads + h) * c.cache_slots;
+        std::vector<int32_t> &v = h == 0 ? ref : mine;
+        v.clear();
+        for (int k = 0; k < c.cache_slots; ++k)
+          if (rowp[k] >= 0) v.push_back(rowp[k]);
+        std::sort(v.begin(), v.end());
+        if (std::adjacent_find(v.begin(), v.end()) != v.end()) return ADORE_E_INVALID;
+        if (h > 0 && mine != ref) return ADORE_E_INVALID;
+      }
+    }
+  }
   ADORE_TRY(hipMemcpyAsync(ctx->slot_pos[ctx->cur], slot_pos, BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
                            ctx->stream));
   ADORE_TRY(hipMemcpyAsync(ctx->insert_slot[ctx->cur], ins.data(), BH * 4, hipMemcpyHostToDevice, ctx->stream));
@@ -670,6 +711,7 @@ int adore_set_input_order(adore_ctx *ctx, int32_t ordered) {
     // from here on the side stream runs ahead again: start its periodic wait like after an init
     ADORE_TRY(hipEventRecord(ctx->ev_att, ctx->stream));
     ADORE_TRY(hipStreamWaitEvent(ctx->side, ctx->ev_att, 0));
+    ADORE_TRY(hipStreamWaitEvent(ctx->side2, ctx->ev_att, 0));
     ctx->steps_done = 0;
     ctx->rode = false;
   }

@@ -27,6 +27,10 @@ constexpr int kRing = 8;              // copies of the per-step lists (slot map,
 constexpr int kSyncEvery = 4;         // the side stream waits for the caller's stream once in this many steps
 static_assert(kSyncEvery + 3 <= kRing, "a list is rewritten kRing - 1 steps after its last reader; see adore_api.hip");
 
+// Static LDS of the attention kernel with 4 waves (merge of the lane groups: at most 32 groups x 64 or 16 x 128
+// floats, and two floats per group), rounded up: what its extra workgroups have to leave room for.
+constexpr size_t kAttendStaticLds = 8704;
+
 struct TimedLaunch {
   int kernel;
   hipEvent_t start, stop;
@@ -82,6 +86,7 @@ struct adore_ctx {
   int32_t ins_stride, ins_off;
   bool ins_from_list;
   bool ride;                 // decode_step lets the selections ride in the attention launch when it can
+  bool ride_fits;            // ... and this configuration allows it (score mode, slots, LDS at the last step)
   bool rode;                 // the last step did
   int32_t cur;               // ring index valid for the next attention
   int32_t steps_done;        // steps since the last init / set_state
@@ -143,6 +148,8 @@ struct RidingSelections {
   int x, r;                // rows to release per (b,h), tokens to rebuild per sequence
   int32_t *map_out, *rel_out, *rb_out;   // the caller's copies, or null
 };
+// dynamic LDS of a workgroup that carries a sequence's selections in the attention launch at step n
+size_t riding_lds_bytes(int n, int K, int r);
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new,
                          const void *v_new, float *out, const RidingSelections *sel = nullptr);
 hipError_t launch_ctrl_input(adore_ctx *ctx, hipStream_t st, const void *x, int ntok, int per_seq,

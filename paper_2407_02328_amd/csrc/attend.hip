@@ -276,6 +276,10 @@ hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows, int waves
 
 }  // namespace
 
+size_t riding_lds_bytes(int n, int K, int r) {
+  return size_t((n + 2) / 2) * 8 + size_t((K + 1) / 2) * 8 + ridden_choice_lds_bytes(r, n);
+}
+
 // sel: null, or the selections of this step to carry in the same launch (see SchedArgs).
 hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new,
                          float *out, const RidingSelections *sel) {
@@ -318,7 +322,7 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
     r.words = (c.max_positions + 31) / 32;
     extra = c.batch * (s.rel_wgs + 1);
     a.n_sel = extra;
-    dyn = size_t((ctx->n + 2) / 2) * 8 + size_t((c.cache_slots + 1) / 2) * 8 + ridden_choice_lds_bytes(sel->r, ctx->n);
+    dyn = riding_lds_bytes(ctx->n, c.cache_slots, sel->r);
   }
   if (c.dtype == ADORE_BF16) {
     return c.head_dim == 128 ? launch_typed<bf16_t, 128>(ctx, a, rows, waves, extra, dyn)

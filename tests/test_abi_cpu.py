@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 6
+    assert lib.adore_abi_version() == 7
 
 
 def test_workspace_bytes(lib):
@@ -95,7 +95,7 @@ def test_create_rejects_bad_arguments(lib):
     big = lib.adore_workspace_bytes(ctypes.byref(re))
     assert big > n                                   # one d'-vector per token on top of the static layout
     assert lib.adore_create(ctypes.byref(re), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
-    assert lib.adore_schedule(h, FAKE, FAKE, None, None, None) == -1
+    assert lib.adore_schedule(h, FAKE, FAKE, None, None, None, None) == -1
     assert lib.adore_decode_step(h, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
     assert lib.adore_set_state(h, FAKE, None, None, None, None, 5) == -3
     assert lib.adore_destroy(h) == 0
@@ -145,11 +145,11 @@ def test_calls_out_of_order_are_state_errors(lib):
         # a forward path (fp32 storage) -- all caught on the host
         from paper_2407_02328_amd.binding import AdoreForwardWeights
         fw = AdoreForwardWeights(FAKE, FAKE)
-        assert lib.adore_forward_step(h, None, FAKE, None, FAKE, None, None, None) == -1
-        assert lib.adore_forward_step(h, ctypes.byref(fw), None, None, FAKE, None, None, None) == -1
-        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, None, None, None, None) == -1
-        assert lib.adore_forward_step(h, ctypes.byref(AdoreForwardWeights(None, FAKE)), FAKE, None, FAKE, None, None, None) == -1
-        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, FAKE, None, None, None) == -2
+        assert lib.adore_forward_step(h, None, FAKE, None, FAKE, None, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), None, None, FAKE, None, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, None, None, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(AdoreForwardWeights(None, FAKE)), FAKE, None, FAKE, None, None, None, None) == -1
+        assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, FAKE, None, None, None, None) == -2
         assert lib.adore_init_cache(h, FAKE, FAKE, None, FAKE, None, 4) == -3     # tiny is fp32: no forward path
     finally:
         assert lib.adore_destroy(h) == 0

@@ -473,7 +473,7 @@ def test_forward_step_matches_the_forward_oracle(name, kw):
     h = _harness()
     w = Workload("fwd_" + name, dtype="bf16", dprime=32, w_std=0.06, **kw)
     worst, mean = h.forward_lockstep(w, w.T)
-    print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
     assert mean < 2.0 ** -10
 
 
@@ -494,7 +494,7 @@ def test_forward_step_llama7b_layer_full_size():
     h = _harness()
     w = workload("llama7b_layer").scaled(L=2, T=4)
     worst, mean = h.forward_lockstep(w, 3)
-    print(f"forward llama7b_layer x2: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    print(f"forward llama7b_layer x2: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
     assert mean < 2.0 ** -10
 
 
@@ -655,6 +655,49 @@ def test_inputs_produced_on_the_stream_are_waited_for():
             assert np.array_equal(g, r), f"{what} at n={n}"
     ref.adore.close()
     lazy.adore.close()
+
+
+@pytest.mark.parametrize("calls", ["whole", "fine"])
+def test_first_steps_without_a_synchronise_after_the_init_when_inputs_are_not_ordered(calls):
+    """Input order off (the side streams wait for nothing of a step's own): adore_init_cache and the first steps
+    enqueued back to back with no synchronisation in between, every input prepared beforehand and every step with
+    output buffers of its own.  The controller of the first step must still start behind the prompt scan (it reads
+    the GRU state the scan leaves and reuses its scratch).  Same bits as the run that synchronises after every call."""
+    h = _harness()
+    w = Workload("order_init", **dict(ORDER_W, S=900, T=8))      # two prompt chunks: the scan alone takes ~0.7 ms
+    inp = SyntheticInputs(w)
+    ref = h.GpuJob(w, inp)
+    ref.init()
+    want = [ref.step(w.S + t, whole=calls == "whole") for t in range(w.T)]
+    want_state = ref.snapshot()
+    ref.adore.close()
+
+    job = h.GpuJob(w, inp, ordered=False)
+    st = job.st
+    pk, pv = (h.to_dev(a, st) for a in job.prompt_np)
+    ctrl = job.hidden[0][:, :w.S].contiguous()
+    qkv = [[h.to_dev(a[0], st) for a in inp.step_qkv(w.S + t)] for t in range(w.T)]
+    xs = [job.hidden[0][:, w.S + t].contiguous() for t in range(w.T)]
+    outs = [torch.empty((w.B, w.H, w.d), dtype=torch.float32, device=h.DEV) for _ in range(w.T)]
+    maps = [torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=h.DEV) for _ in range(w.T)]
+    torch.cuda.synchronize()
+    job.adore.init_cache(pk, pv, job.hidden, ctrl, None, w.S)
+    for t in range(w.T):
+        q, k, v = qkv[t]
+        if calls == "whole":
+            job.adore.decode_step(q, k, v, job.hidden[0], xs[t], None, outs[t], maps[t])
+        else:
+            job.adore.attend(0, q, k, v, outs[t])
+            job.adore.schedule(xs[t], None, maps[t], None, None)
+            job.adore.rebuild(0, job.hidden[0])
+    torch.cuda.synchronize()
+    for t in range(w.T):
+        assert np.array_equal(maps[t].cpu().numpy(), want[t][1]), f"slot map at step {t}"
+        assert np.array_equal(outs[t].cpu().numpy().astype(np.float64), want[t][0][0]), f"output at step {t}"
+    got_state = job.snapshot()
+    assert np.array_equal(got_state["scores"][:, :w.S + w.T], want_state["scores"][:, :w.S + w.T])
+    assert np.array_equal(got_state["z"], want_state["z"])
+    job.adore.close()
 
 
 # ---- a sweep of random small shapes ----------------------------------------------------------------------
@@ -823,17 +866,16 @@ def test_forward_step_with_rotary_embedding(name, kw):
     h = _harness()
     w = Workload("fwd_rope_" + name, dtype="bf16", dprime=32, w_std=0.06, rope_base=10000.0, **kw)
     worst, mean = h.forward_lockstep(w, w.T)
-    print(f"forward rope {name}: worst row error {worst:.2e}, mean {mean:.2e} (bound {h.forward_tol(w):.2e})", flush=True)
+    print(f"forward rope {name}: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
     assert mean < 2.0 ** -10
 
 
 def test_rotary_embedding_at_the_benchmark_shape():
     """llama7b_layer with the embedding on, in the launch configuration bench.py times: init and four steps
-    through adore_decode_step, everything against the oracle (16384 rebuilt key rows per step: the row check of
-    the full-size runs)."""
+    through adore_decode_step, everything against the oracle (16384 rebuilt key rows per step)."""
     h = _harness()
     w = workload("llama7b_layer").scaled(T=6, rope_base=10000.0)
-    worst, job, _ = h.lockstep(w, steps=4, check_cache_every=2, whole=lambda t: True, full_size_rows=True)
+    worst, job, _ = h.lockstep(w, steps=4, check_cache_every=2, whole=lambda t: True)
     print(f"rope llama7b_layer: worst output error {worst:.3e}", flush=True)
     job.adore.close()
 
@@ -898,5 +940,5 @@ def test_random_medium_configurations_with_rotary_embedding(name, kw, calls, ord
     h = _harness()
     w = Workload(name, rope_base=10000.0, **kw)
     whole = {"fine": None, "whole": lambda t: True, "mixed": lambda t: t % 3 != 1}[calls]
-    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=2, whole=whole, ordered=ordered, full_size_rows=True)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=2, whole=whole, ordered=ordered)
     job.adore.close()

@@ -550,6 +550,32 @@ def test_forward_without_rebuild_budget_is_the_single_query_step():
         assert np.allclose(x_out, want, rtol=0, atol=1e-12)
 
 
+def test_forward_adoption_hook_leaves_the_arithmetic_alone():
+    """forward_step(adopt=...) hands given per-layer rows and K/V on instead of its own.  Fed its own values
+    (found pass by pass: with a guess adopted, the first pass gives the right K/V of the first layer, the second
+    its rows, the third the K/V of the second layer, ...) it must return exactly what the plain step returns,
+    and report those values as its own."""
+    import copy
+    w = Workload("fwd_adopt", L=3, B=2, H=2, d=8, D=16, K=10, R=3, S=14, T=4, dtype="bf16", dprime=8, w_std=0.25,
+                 rope_base=100.0)
+    orc, inp, wts = _forward_oracle(w)
+    E = inp.hidden_store_layer(0)
+    pk, pv = inp.prompt_kv()
+    orc.init_cache(pk, pv, None, E[:, :w.S], w.S)
+    for t in range(w.T):
+        guess = dict(x=np.zeros((w.L, w.B, w.R + 1, w.D)), k=np.zeros((w.L, w.B, w.H, w.R + 1, w.d)),
+                     v=np.zeros((w.L, w.B, w.H, w.R + 1, w.d)))
+        for _ in range(2 * w.L + 1):
+            twin = copy.deepcopy(orc)
+            got = twin.forward_step(E, adopt=guess)
+            guess = twin.own
+        want = orc.forward_step(E)
+        for g, r in zip(got, want):
+            assert np.array_equal(g, r)
+        assert np.array_equal(twin.Kc, orc.Kc) and np.array_equal(twin.Vc, orc.Vc)
+        assert np.array_equal(twin.own["x"][w.L - 1], want[1])
+
+
 def test_forward_invariants_with_a_small_budget():
     """R smaller than the pool: counts and residency as in the base step; the tokens rebuilt in a step are
     the ones chosen in the step before; every output is finite."""
