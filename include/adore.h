@@ -300,6 +300,20 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
                          size_t workspace_bytes, int32_t rows, int32_t seq, int32_t head_dim, int32_t top_k,
                          void *hip_stream);
 
+/* adore_topk_attention for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): the same kernels and the same result, bit for bit, with the transposed copy of v
+ * in a fixed array inside the library (ADORE_TOPK_STATIC_SCRATCH_BYTES of device memory on every GPU the library is
+ * loaded on, held until the process ends) instead of a caller's workspace.  The call allocates and frees nothing.
+ * Limits: seq <= 2048 and rows * head_dim * ceil(seq / 32) * 64 <= ADORE_TOPK_STATIC_SCRATCH_BYTES, else E_WORKSPACE
+ * (e.g. 256 rows of 1024 tokens at head_dim 128).  All calls on one GPU share that array: calls whose work may
+ * overlap on a GPU (different streams, different threads) race; calls on one stream are safe.  Nothing in the array
+ * has to be cleared between calls (every call writes all of what it then reads).  The first call on a device looks
+ * the array's address up (hipGetSymbolAddress), so make that call outside a graph capture.
+ * Errors: as adore_topk_attention; E_WORKSPACE when the shape exceeds the array. */
+#define ADORE_TOPK_STATIC_SCRATCH_BYTES (64u << 20)
+int adore_topk_attention_static(const void *q, const void *k, const void *v, void *out, int32_t rows, int32_t seq,
+                                int32_t head_dim, int32_t top_k, void *hip_stream);
+
 const char *adore_strerror(int code);
 int adore_abi_version(void);
 

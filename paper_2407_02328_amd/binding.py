@@ -23,7 +23,7 @@ EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
     "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_forward_step", "adore_get_state", "adore_set_state",
     "adore_set_input_order", "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
-    "adore_topk_attention_workspace_bytes", "adore_topk_attention",
+    "adore_topk_attention_workspace_bytes", "adore_topk_attention", "adore_topk_attention_static",
 ]
 
 
@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.adore_topk_attention_workspace_bytes.argtypes = [i32, i32, i32]
     lib.adore_topk_attention.restype = ctypes.c_int
     lib.adore_topk_attention.argtypes = [vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, vp]
+    lib.adore_topk_attention_static.restype = ctypes.c_int
+    lib.adore_topk_attention_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -143,6 +145,19 @@ def topk_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, top_k: int
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(lib, lib.adore_topk_attention(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), workspace.data_ptr(),
                                          workspace.numel(), rows, seq, d, int(top_k), stream))
+    return out
+
+
+def topk_attention_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, top_k: int, out: torch.Tensor) -> torch.Tensor:
+    """adore_topk_attention_static on torch's current stream: no workspace, nothing allocated (out is the caller's)."""
+    lib = load_library()
+    for name, t in (("q", q), ("k", k), ("v", v), ("out", out)):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.shape != q.shape or t.dim() != 3:
+            raise ValueError(f"{name}: expected a contiguous bf16 GPU tensor [rows, seq, head_dim]")
+    rows, seq, d = q.shape
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(lib, lib.adore_topk_attention_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), rows, seq, d,
+                                                int(top_k), stream))
     return out
 
 

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "adore.h"
 #include "device_utils.h"
@@ -510,6 +511,65 @@ hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
 
 }  // namespace adore
 
+// ---- the entry point that allocates nothing ---------------------------------------------------------------
+// The transposed copy of V of adore_topk_attention_static lives in this array instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy of it, at its own address, until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress: what kernels and copies get is the address looked up
+// below, once per device.
+static __device__ __align__(256) unsigned char scratch[ADORE_TOPK_STATIC_SCRATCH_BYTES];
+
+namespace adore {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};   // by device ordinal; null = not looked up yet
+
+// The address of `scratch` on the current device (looked up on the first call on that device), or null.
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// The launches of both entry points: the transposed copy of V into vt, then the attention.  seq <= kMaxSeq unless
+// rowbuf is given.
+int enqueue_topk(const void *q, const void *k, const void *v, void *out, void *vt, float *rowbuf, int rows, int seq,
+                 int head_dim, int top_k, hipStream_t st) {
+  const int Sp = int(padded_keys(seq));
+  hipLaunchKernelGGL(topk_vt_kernel, dim3(Sp / 32, rows), dim3(256), 0, st, static_cast<const bf16_t *>(v),
+                     static_cast<bf16_t *>(vt), seq, Sp, head_dim);
+  if (hipGetLastError() != hipSuccess) return ADORE_E_HIP;
+  TopkArgs a;
+  a.Q = static_cast<const bf16_t *>(q);
+  a.K = static_cast<const bf16_t *>(k);
+  a.Vt = static_cast<const bf16_t *>(vt);
+  a.O = static_cast<bf16_t *>(out);
+  a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0; a.rows = rows;
+  a.rowbuf = rowbuf;
+  a.scale_log2 = 1.4426950408889634f / sqrtf(float(head_dim));
+  hipError_t e;
+  // 16 queries per workgroup: their fp32 weights take 64 KB of LDS at 1024 keys, so two workgroups (16 waves) share
+  // a compute unit and hide each other's latencies (32 queries per workgroup, one workgroup per unit, read K and V
+  // half as often and took 3.33 ms where this takes 2.27 ms)
+  if (seq <= kMaxSeq / 2)
+    e = head_dim == 128 ? launch<128, 1, 16>(a, rows, st) : launch<64, 1, 16>(a, rows, st);
+  else if (seq <= kMaxSeq)
+    e = head_dim == 128 ? launch<128, 1, 32>(a, rows, st) : launch<64, 1, 32>(a, rows, st);
+  else   // logit rows in the workspace
+    e = head_dim == 128 ? launch<128, 1, 0>(a, rows, st) : launch<64, 1, 0>(a, rows, st);
+  return e == hipSuccess ? ADORE_OK : ADORE_E_HIP;
+}
+
+}  // namespace
+}  // namespace adore
+
 extern "C" {
 
 size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t head_dim) {
@@ -529,30 +589,20 @@ int adore_topk_attention(const void *q, const void *k, const void *v, void *out,
   if (workspace_bytes < adore_topk_attention_workspace_bytes(rows, seq, head_dim) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
     return ADORE_E_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int Sp = int(padded_keys(seq));
-  hipLaunchKernelGGL(topk_vt_kernel, dim3(Sp / 32, rows), dim3(256), 0, st, static_cast<const bf16_t *>(v),
-                     static_cast<bf16_t *>(workspace), seq, Sp, head_dim);
-  if (hipGetLastError() != hipSuccess) return ADORE_E_HIP;
-  TopkArgs a;
-  a.Q = static_cast<const bf16_t *>(q);
-  a.K = static_cast<const bf16_t *>(k);
-  a.Vt = static_cast<const bf16_t *>(workspace);
-  a.O = static_cast<bf16_t *>(out);
-  a.S = seq; a.Sp = Sp; a.topk = top_k; a.lstr = 0; a.region0 = 0; a.rows = rows;
-  a.rowbuf = reinterpret_cast<float *>(static_cast<char *>(workspace) + vt_bytes(rows, seq, head_dim));
-  a.scale_log2 = 1.4426950408889634f / sqrtf(float(head_dim));
-  hipError_t e;
-  // 16 queries per workgroup: their fp32 weights take 64 KB of LDS at 1024 keys, so two workgroups (16 waves) share
-  // a compute unit and hide each other's latencies (32 queries per workgroup, one workgroup per unit, read K and V
-  // half as often and took 3.33 ms where this takes 2.27 ms)
-  if (seq <= kMaxSeq / 2)
-    e = head_dim == 128 ? launch<128, 1, 16>(a, rows, st) : launch<64, 1, 16>(a, rows, st);
-  else if (seq <= kMaxSeq)
-    e = head_dim == 128 ? launch<128, 1, 32>(a, rows, st) : launch<64, 1, 32>(a, rows, st);
-  else   // logit rows in the workspace
-    e = head_dim == 128 ? launch<128, 1, 0>(a, rows, st) : launch<64, 1, 0>(a, rows, st);
-  return e == hipSuccess ? ADORE_OK : ADORE_E_HIP;
+  float *rowbuf = reinterpret_cast<float *>(static_cast<char *>(workspace) + vt_bytes(rows, seq, head_dim));
+  return enqueue_topk(q, k, v, out, workspace, rowbuf, rows, seq, head_dim, top_k, static_cast<hipStream_t>(hip_stream));
+}
+
+int adore_topk_attention_static(const void *q, const void *k, const void *v, void *out, int32_t rows, int32_t seq,
+                                int32_t head_dim, int32_t top_k, void *hip_stream) {
+  using namespace adore;
+  if (!q || !k || !v || !out || rows <= 0 || seq <= 0 || head_dim <= 0 || top_k < 1) return ADORE_E_INVALID;
+  if ((head_dim != 64 && head_dim != 128) || rows > 65535) return ADORE_E_UNSUPPORTED;
+  // beyond kMaxSeq tokens the weights of a query block need a buffer that grows with seq * seq: not in this variant
+  if (seq > kMaxSeq || vt_bytes(rows, seq, head_dim) > size_t(ADORE_TOPK_STATIC_SCRATCH_BYTES)) return ADORE_E_WORKSPACE;
+  void *vt = static_scratch();
+  if (!vt) return ADORE_E_HIP;
+  return enqueue_topk(q, k, v, out, vt, nullptr, rows, seq, head_dim, top_k, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"
