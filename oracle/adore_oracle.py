@@ -62,6 +62,8 @@ Readings of points the paper leaves open (each used exactly as stated here):
     masked out): causal, per head; the K largest products q_i . k_j over j <= i are kept (all
     of them while i + 1 <= K), equal products go to the lower position, the softmax runs over
     the kept ones only (masking before the softmax, as an attention mask does).
+  * H2O(Rebuilt) (Sec. 3.1, baselines): see AdoreH2OOracle for the reading of the two sentences the paper
+    spends on it (per-head cumulative attention as the score, per-sequence rebuild on the sum over heads).
   * Rows never move: a released row frees its slot; incoming rows take the
     lowest free slots (rebuilt rank rho -> rho-th lowest free slot; the next
     token -> lowest free slot at its insert).
@@ -529,6 +531,120 @@ class AdoreForwardOracle(AdoreOracle):
             self._place_rebuilt(b, rebuilt, None)
         self.n = n + 1
         return rows_out[:, c.R].copy(), rows_out, self.slot_pos.copy(), released_pos, rebuilt_pos, own_score
+
+
+class AdoreH2OOracle(AdoreOracle):
+    """H2O(Rebuilt) (Sec. 3.1, baselines 6 and 7): the score of a token is the attention it has received so far,
+    counted per head, and the tokens a head has evicted are candidates for this paper's rebuild.
+
+    The paper gives the two baselines one sentence each (H2O evicts the tokens that contribute least to the
+    cumulative attention; the rebuilt variant rebuilds K/V states of evicted tokens on top of it), so the rest is
+    a reading, stated here and used exactly so:
+      * score[b, h, i] = sum over the steps at which head h held a row of token i (its own step included) of the
+        probability the step's query gave that row (Eq. 1's softmax); kept in fp32, added to in the order of the
+        steps.  A token a head has evicted keeps the score it had; when it is rebuilt it collects again.
+        Prompt tokens start from score_init (the attention they collected during the prompt, which is computed
+        by whoever ran the prompt) or from zero.
+      * Release: per head, as in the base class, on that head's scores: the current token is exempt, ties go to
+        the lower position.  Heads evict different tokens, so every head has its own slot map.
+      * Rebuild: one row of the re-projection makes the K/V of a token for all heads, so the choice is per
+        sequence.  Candidates: the tokens at least one head is missing.  Order: the sum of a token's scores over
+        the heads (fp32, heads added in order from head 0), equal sums to the lower position; the best
+        min(R, candidates) are rebuilt.  A head that still holds a chosen token keeps its row; the others put the
+        token into their free slots, lowest slot first in the order of the ranks.
+      * One layer per job (the cumulative attention of H2O belongs to a layer)."""
+
+    def __init__(self, cfg: OracleConfig, weights: Dict[str, np.ndarray]):
+        if cfg.L != 1:
+            raise ValueError("H2O scores are kept per layer: one layer per job")
+        super().__init__(cfg, weights)
+        self.hscore = np.zeros((cfg.B, cfg.H, cfg.N_max), dtype=np.float32)
+        self.own_scores = None           # [B,H,n+1] fp64: the scores of the last step before any override
+
+    def _aggregate(self, b: int, n: int) -> np.ndarray:
+        agg = np.zeros(n + 1, dtype=np.float32)
+        for h in range(self.cfg.H):
+            agg = (agg + self.hscore[b, h, :n + 1]).astype(np.float32)
+        return agg
+
+    def _choose_and_place(self, b: int, n: int, hidden_store: np.ndarray) -> List[int]:
+        c = self.cfg
+        held = [set(int(p) for p in self.slot_pos[b, h] if p >= 0) for h in range(c.H)]
+        pool = [i for i in range(n + 1) if any(i not in held[h] for h in range(c.H))]
+        rebuilt = ranked(pool, self._aggregate(b, n))[:min(c.R, len(pool))]
+        if rebuilt:
+            kv = self._project(0, hidden_store[0, b, rebuilt, :], rebuilt)     # [r, 2*H*d]
+            for h in range(c.H):
+                free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]   # ascending
+                taken = 0
+                for rho, pos in enumerate(rebuilt):
+                    if pos in held[h]:
+                        continue
+                    s = free[taken]
+                    taken += 1
+                    self.Kc[0, b, h, s] = kv[rho, h * c.d:(h + 1) * c.d]
+                    self.Vc[0, b, h, s] = kv[rho, c.H * c.d + h * c.d: c.H * c.d + (h + 1) * c.d]
+                    self.slot_pos[b, h, s] = pos
+        return rebuilt
+
+    def init_cache(self, prompt_k, prompt_v, hidden_store, S: int, score_init: Optional[np.ndarray] = None):
+        """prompt_k/v: [1,B,H,S,d]; hidden_store: [1,B,N_max,D]; score_init: [B,H,S] or None (zeros).
+        Per head: token S-1 and the best min(S,m)-1 older tokens by that head's scores, in ascending position
+        from slot 0; then the rebuild choice above.  Returns the rebuilt positions per sequence."""
+        c = self.cfg
+        self.slot_pos[:] = -1
+        self.hscore[:] = 0.0
+        if score_init is not None:
+            self.hscore[:, :, :S] = np.asarray(score_init, dtype=np.float32)
+        rebuilt_all = []
+        keep = min(S, c.m)
+        for b in range(c.B):
+            for h in range(c.H):
+                older = ranked(range(S - 1), self.hscore[b, h])[:keep - 1]
+                for s_idx, pos in enumerate(sorted(older + [S - 1])):
+                    self.Kc[:, b, h, s_idx] = prompt_k[:, b, h, pos]
+                    self.Vc[:, b, h, s_idx] = prompt_v[:, b, h, pos]
+                    self.slot_pos[b, h, s_idx] = pos
+            rebuilt_all.append(self._choose_and_place(b, S - 1, hidden_store))
+        self.n = S
+        return rebuilt_all
+
+    def decode_step(self, q, k_new, v_new, hidden_store, score_override: Optional[np.ndarray] = None):
+        """q, k_new, v_new: [1,B,H,d]; hidden_store: [1,B,N_max,D]; score_override: [B,H,n+1] or None: the scores
+        after this step's attention as another implementation holds them (adopted once the caller has checked
+        them against own_scores).  Returns (out [1,B,H,d], slot_map [B,H,K], released_pos [B,H,R+1] in ascending
+        slot order, rebuilt_pos [B,R])."""
+        c = self.cfg
+        n = self.n
+        if n >= c.N_max:
+            raise RuntimeError("step past N_max")
+        out = np.zeros((1, c.B, c.H, c.d), dtype=F64)
+        released_pos = np.full((c.B, c.H, c.R + 1), -1, dtype=np.int32)
+        rebuilt_pos = np.full((c.B, c.R), -1, dtype=np.int32)
+        self.own_scores = self.hscore[:, :, :n + 1].astype(F64)
+        for b in range(c.B):
+            for h in range(c.H):
+                free = [k for k in range(c.K) if self.slot_pos[b, h, k] < 0]
+                s = free[0]
+                self.Kc[0, b, h, s] = k_new[0, b, h]
+                self.Vc[0, b, h, s] = v_new[0, b, h]
+                self.slot_pos[b, h, s] = n
+                valid = np.nonzero(self.slot_pos[b, h] >= 0)[0]
+                out[0, b, h], p = attention_row(q[0, b, h].astype(F64), self.Kc[0, b, h, valid], self.Vc[0, b, h, valid])
+                for k, pk in zip(valid, p):                      # every row collects what the query gave it
+                    self.own_scores[b, h, self.slot_pos[b, h, k]] += pk
+            self.hscore[b, :, :n + 1] = (self.own_scores[b].astype(np.float32) if score_override is None
+                                         else np.asarray(score_override[b], dtype=np.float32))
+            for h in range(c.H):
+                freed = release_lowest(self.slot_pos[b, h], self.hscore[b, h], n, c.m)
+                for j, s in enumerate(freed):
+                    released_pos[b, h, j] = self.slot_pos[b, h, s]
+                for s in freed:
+                    self.slot_pos[b, h, s] = -1
+            rebuilt = self._choose_and_place(b, n, hidden_store)
+            rebuilt_pos[b, :len(rebuilt)] = rebuilt
+        self.n = n + 1
+        return out, self.slot_pos.copy(), released_pos, rebuilt_pos
 
 
 def full_attention(q: np.ndarray, Kall: np.ndarray, Vall: np.ndarray) -> np.ndarray:
