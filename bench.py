@@ -63,7 +63,7 @@ def recorded_traffic(w, path_name="decode_step"):
 def run_gpu(w, steps, warmup, prof_steps, ordered_steps=0):
     import torch
     from gen import SyntheticInputs
-    from tests.gpu_harness import GpuJob, to_dev
+    from gen.gpu_job import GpuJob, to_dev
     t0 = time.time()
     inp = SyntheticInputs(w)
     job = GpuJob(w, inp, ordered=INPUTS_ORDERED)
@@ -139,7 +139,7 @@ def run_stack(w, steps, warmup, prof_steps):
     import torch
     from gen import SyntheticInputs
     from paper_2407_02328_amd import Adore, make_config
-    from tests.gpu_harness import DEV, storage_dtype, to_dev
+    from gen.gpu_job import DEV, storage_dtype, to_dev
     st = storage_dtype(w)
     total = warmup + steps + prof_steps
     assert w.S + total <= w.N_max, "not enough positions for this many steps"
@@ -216,7 +216,7 @@ def run_forward(w, steps, warmup, prof_steps):
     import torch
     from gen import SyntheticInputs
     from paper_2407_02328_amd import Adore, make_config
-    from tests.gpu_harness import DEV, storage_dtype, to_dev
+    from gen.gpu_job import DEV, storage_dtype, to_dev
     st = storage_dtype(w)
     total = warmup + steps + prof_steps
     assert w.S + total <= w.N_max, "not enough positions for this many steps"
@@ -296,7 +296,7 @@ def prefill_line(w, args):
     prompt token: input projection, recurrence, scoring; choice and fill of the residents; first rebuild)."""
     import torch
     from gen import SyntheticInputs
-    from tests.gpu_harness import GpuJob, to_dev
+    from gen.gpu_job import GpuJob, to_dev
     inp = SyntheticInputs(w)
     job = GpuJob(w, inp)
     pk, pv = (to_dev(a, job.st) for a in job.prompt_np)

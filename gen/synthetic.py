@@ -56,6 +56,7 @@ class Workload:
     salience: bool = False   # heavy-tailed per-token offset (long-context workload)
     rescore: bool = False    # controller scores every token again at every step (relative position)
     rope_base: float = 0.0   # > 0: rotary position embedding with this base on keys/queries made from hidden states
+    h2o: bool = False        # scores are the attention each head has given a token so far (the H2O(Rebuilt) baseline)
     seed: int = BASE_SEED
 
     @property

@@ -56,7 +56,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 7
+#define ADORE_ABI_VERSION 8
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -69,7 +69,20 @@ enum { ADORE_F32 = 0, ADORE_BF16 = 1 };
  *          token", Sec. 2.2 and the caption of Fig. 2); both selections of the step use the new values,
  *          so a rebuilt token can be kept.  score_override must be NULL in every call, set_state is
  *          not available, and d' must be a multiple of 4. */
-enum { ADORE_SCORE_STATIC = 0, ADORE_SCORE_RESCORE = 1 };
+/* H2O:     the H2O(Rebuilt) baseline of Sec. 3.1 (baselines 6 and 7): no controller; the score of a token is the
+ *          attention it has received so far, kept per head: score[b][h][i] = sum over the steps at which head h
+ *          held a row of token i of the probability the step's query gave that row (fp32, added in step order; an
+ *          evicted token keeps its score and collects again once rebuilt).  Every head releases on its own scores
+ *          and has its own slot map.  The rebuild is per sequence (one row of the re-projection serves all heads):
+ *          candidates are the tokens at least one head is missing, ranked by the fp32 sum of their scores over the
+ *          heads (head 0 first), equal sums to the lower position; a head that still holds a chosen token keeps its
+ *          row, the others put it into their lowest free slots in rank order.  (The paper gives the baseline two
+ *          sentences; the rest is this reading.)  One layer per context, no rotary embedding, heads <= 255,
+ *          max_positions <= about 7000 (the keys of a sequence live in 64 KB of LDS; fewer with a large R); x_n and the controller weights are not read (x_n may be NULL, the weight
+ *          pointers must still be non-null); score_override of adore_init_cache is [B][H][S], the attention the
+ *          prompt tokens collected during the prompt (NULL: zeros), and must be NULL in the step calls; the scores
+ *          of get_state are [B][H][N_max]; no set_state, no adore_forward_step. */
+enum { ADORE_SCORE_STATIC = 0, ADORE_SCORE_RESCORE = 1, ADORE_SCORE_H2O = 2 };
 
 enum {
   ADORE_OK = 0,
@@ -86,7 +99,7 @@ typedef struct {
   int32_t ctrl_hidden;                                /* d' */
   int32_t dtype;                                      /* ADORE_F32 | ADORE_BF16 */
   float pos_scale;                                    /* position feature of token i = (float)i * pos_scale */
-  int32_t score_mode;                                 /* ADORE_SCORE_STATIC | ADORE_SCORE_RESCORE */
+  int32_t score_mode;                                 /* ADORE_SCORE_STATIC | ADORE_SCORE_RESCORE | ADORE_SCORE_H2O */
   float rope_base;                                    /* 0: off.  > 0: rotary position embedding (the one the paper's
                                                          backbones apply to q and k; the paper names it in its related
                                                          work on length extrapolation) on every key the library makes
@@ -276,6 +289,8 @@ enum {
   ADORE_KERNEL_FWD_OPROJ,       /* rebuild forward: output projection + residual, rebuilt tokens' rows */
   ADORE_KERNEL_FWD_OPROJ_CUR,   /* rebuild forward: the same for the current tokens' rows */
   ADORE_KERNEL_ROPE,            /* rotary embedding of the rows a projection just wrote (rope_base > 0) */
+  ADORE_KERNEL_H2O_RELEASE,     /* H2O mode: the step's attention added to the scores, then the per-head release */
+  ADORE_KERNEL_H2O_CHOICE,      /* H2O mode: per-sequence choice on the sum over heads + per-head slot assignment */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

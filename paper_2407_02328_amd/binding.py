@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libadore.so")
 
 ADORE_F32, ADORE_BF16 = 0, 1
 KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "rebuild_select", "rebuild_gemm",
-           "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur", "rope"]
+           "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur", "rope", "h2o_release",
+           "h2o_choice"]
+SCORE_STATIC, SCORE_RESCORE, SCORE_H2O = 0, 1, 2
 
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
@@ -226,7 +228,8 @@ class Adore:
             self._ptr(hidden_store, (c.layers, c.batch, c.max_positions, c.hidden), st, "hidden_store",
                       optional=True),                    # None: prepare for forward_step
             self._ptr(ctrl_input, (c.batch, S, c.hidden), st, "ctrl_input"),
-            self._ptr(score_override, (c.batch, S), torch.float32, "score_override", optional=True), S))
+            self._ptr(score_override, (c.batch, c.heads, S) if c.score_mode == SCORE_H2O else (c.batch, S),
+                      torch.float32, "score_override", optional=True), S))
 
     def attend(self, layer: int, q, k_new, v_new, out):
         c, st = self.cfg, self.storage
@@ -238,7 +241,7 @@ class Adore:
     def schedule(self, x_n, score_override=None, slot_map=None, released_pos=None, rebuilt_pos=None):
         c = self.cfg
         _check(self.lib, self.lib.adore_schedule(
-            self.handle, self._ptr(x_n, (c.batch, c.hidden), self.storage, "x_n"),
+            self.handle, self._ptr(x_n, (c.batch, c.hidden), self.storage, "x_n", optional=c.score_mode == SCORE_H2O),
             self._ptr(score_override, (c.batch,), torch.float32, "score_override", optional=True),
             self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True),
             self._ptr(released_pos, (c.batch, c.heads, c.rebuild_budget + 1), torch.int32, "released_pos",
@@ -259,7 +262,7 @@ class Adore:
             self.handle, self._ptr(q, shp, st, "q"), self._ptr(k_new, shp, st, "k_new"),
             self._ptr(v_new, shp, st, "v_new"),
             self._ptr(hidden_store, (c.batch, c.max_positions, c.hidden), st, "hidden_store"),
-            self._ptr(x_n, (c.batch, c.hidden), st, "x_n"),
+            self._ptr(x_n, (c.batch, c.hidden), st, "x_n", optional=c.score_mode == SCORE_H2O),
             self._ptr(score_override, (c.batch,), torch.float32, "score_override", optional=True),
             self._ptr(out, shp, torch.float32, "out"),
             self._ptr(slot_map, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_map", optional=True)))
@@ -286,10 +289,14 @@ class Adore:
         c, st = self.cfg, self.storage
         cs = (c.layers, c.batch, c.heads, c.cache_slots, c.head_dim)
         return (self._ptr(slot_pos, (c.batch, c.heads, c.cache_slots), torch.int32, "slot_pos", optional=True),
-                self._ptr(scores, (c.batch, c.max_positions), torch.float32, "scores", optional=True),
+                self._ptr(scores, self._score_shape(), torch.float32, "scores", optional=True),
                 self._ptr(z, (c.batch, c.ctrl_hidden), torch.float32, "z", optional=True),
                 self._ptr(cache_k, cs, st, "cache_k", optional=True),
                 self._ptr(cache_v, cs, st, "cache_v", optional=True))
+
+    def _score_shape(self):
+        c = self.cfg
+        return (c.batch, c.heads, c.max_positions) if c.score_mode == SCORE_H2O else (c.batch, c.max_positions)
 
     def get_state(self, slot_pos=None, scores=None, z=None, cache_k=None, cache_v=None) -> int:
         step = ctypes.c_int32(-1)
@@ -318,6 +325,6 @@ class Adore:
         c, st, dev = self.cfg, self.storage, self.device
         cs = (c.layers, c.batch, c.heads, c.cache_slots, c.head_dim)
         return dict(slot_pos=torch.empty((c.batch, c.heads, c.cache_slots), dtype=torch.int32, device=dev),
-                    scores=torch.empty((c.batch, c.max_positions), dtype=torch.float32, device=dev),
+                    scores=torch.empty(self._score_shape(), dtype=torch.float32, device=dev),
                     z=torch.empty((c.batch, c.ctrl_hidden), dtype=torch.float32, device=dev),
                     cache_k=torch.empty(cs, dtype=st, device=dev), cache_v=torch.empty(cs, dtype=st, device=dev))

@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libadore.so")
-SOURCES = ["adore_api.hip", "attend.hip", "controller.hip", "select.hip", "rebuild.hip", "forward_attend.hip", "rope.hip", "topk_attend.hip"]
+SOURCES = ["adore_api.hip", "attend.hip", "controller.hip", "select.hip", "rebuild.hip", "forward_attend.hip", "rope.hip", "topk_attend.hip", "h2o.hip"]
 HEADERS = ["adore_internal.h", "device_utils.h", "select_device.h"]
 
 HIPCC_FLAGS = [

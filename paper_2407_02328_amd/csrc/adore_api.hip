@@ -59,14 +59,15 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
-      att_part, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, rope, total;
+      att_part, att_logit, att_ml, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, rope, total;
 };
 
 bool config_ok(const adore_config *c) {
   return c && c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
          c->cache_slots >= 2 && c->rebuild_budget >= 0 && c->rebuild_budget <= c->cache_slots - 2 &&
          c->max_positions >= 2 && c->ctrl_hidden > 0 && (c->dtype == ADORE_F32 || c->dtype == ADORE_BF16) &&
-         (c->score_mode == ADORE_SCORE_STATIC || c->score_mode == ADORE_SCORE_RESCORE) &&
+         (c->score_mode == ADORE_SCORE_STATIC || c->score_mode == ADORE_SCORE_RESCORE ||
+          c->score_mode == ADORE_SCORE_H2O) &&
          std::isfinite(c->pos_scale) && std::isfinite(c->rope_base) && c->rope_base >= 0.f;
 }
 
@@ -74,9 +75,16 @@ bool config_supported(const adore_config *c) {
   // the selecting release kernel keeps a row's keys in the registers of one wave; a cache that never has to
   // release (K - R - 1 >= N_max: full attention) may have any number of slots
   const bool never_releases = c->cache_slots - c->rebuild_budget - 1 >= c->max_positions;
+  if (c->score_mode == ADORE_SCORE_H2O) {
+    // scores belong to a layer; the per-sequence choice counts in 8 bits how many heads hold a token and keeps the
+    // ranking keys of a sequence in LDS
+    if (c->layers != 1 || c->heads > 255 || c->rope_base > 0.f || c->cache_slots > kMaxSlots ||
+        h2o_choice_lds_bytes(*c, c->max_positions - 1) > 64 * 1024)
+      return false;
+  }
   return (c->head_dim == 64 || c->head_dim == 128) && (c->cache_slots <= kMaxSlots || never_releases) &&
          c->hidden % 8 == 0 && c->max_positions <= kMaxPositions && c->ctrl_hidden <= 1024 &&
-         (c->score_mode == ADORE_SCORE_STATIC || c->ctrl_hidden % 4 == 0);
+         (c->score_mode != ADORE_SCORE_RESCORE || c->ctrl_hidden % 4 == 0);
 }
 
 Layout make_layout(const adore_config &c) {
@@ -93,14 +101,17 @@ Layout make_layout(const adore_config &c) {
   l.cache_k = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
   l.cache_v = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
   l.slot_pos = take(kRing * BH * c.cache_slots * 4);
-  l.score = take(size_t(c.batch) * c.max_positions * 4);
+  const bool h2o = c.score_mode == ADORE_SCORE_H2O;
+  l.score = take(size_t(c.batch) * (h2o ? c.heads : 1) * c.max_positions * 4);   // H2O: per head
   l.z = take(size_t(c.batch) * c.ctrl_hidden * 4);
   l.insert_slot = take(kRing * align_up(BH * 4));
   l.free_list = take(kRing * align_up(BH * R1 * 4));
   l.released_pos = take(BH * R1 * 4);
   l.rebuilt_pos = take(kRing * align_up(size_t(c.batch) * (c.rebuild_budget > 0 ? c.rebuild_budget : 1) * 4));
-  l.init_res = take(size_t(c.batch) * c.cache_slots * 4);
+  l.init_res = take(size_t(c.batch) * (h2o ? c.heads : 1) * c.cache_slots * 4);
   l.att_part = take(BH * kMaxSplits * (size_t(c.head_dim) + 2) * 4);
+  l.att_logit = take(h2o ? BH * c.cache_slots * 4 : 0);
+  l.att_ml = take(h2o ? BH * 2 * 4 : 0);
   size_t gi_rows = size_t(c.batch) * kPromptChunk;
   if (gi_rows < size_t(kMaxCtrlSplit) * kCtrlSplitTokens) gi_rows = size_t(kMaxCtrlSplit) * kCtrlSplitTokens;
   l.gi = take(gi_rows * 3 * c.ctrl_hidden * 4);
@@ -250,6 +261,8 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->released_pos = reinterpret_cast<int32_t *>(base + l.released_pos);
   ctx->init_res = reinterpret_cast<int32_t *>(base + l.init_res);
   ctx->att_part = reinterpret_cast<float *>(base + l.att_part);
+  ctx->att_logit = reinterpret_cast<float *>(base + l.att_logit);
+  ctx->att_ml = reinterpret_cast<float *>(base + l.att_ml);
   ctx->gi = reinterpret_cast<float *>(base + l.gi);
   ctx->zseq = reinterpret_cast<float *>(base + l.zseq);
   ctx->cvec = reinterpret_cast<float *>(base + l.cvec);
@@ -270,7 +283,9 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->occ = 0;
   ctx->cur = 0;
   const char *no = getenv("ADORE_NO_OVERLAP");
-  ctx->overlap = !(no && atoi(no) != 0);
+  // H2O scores come out of the step's own attention: its selections follow it on the caller's stream, and there
+  // is no controller to run beside them
+  ctx->overlap = !(no && atoi(no) != 0) && cfg->score_mode != ADORE_SCORE_H2O;
   const char *nr = getenv("ADORE_NO_RIDE");
   ctx->ride = ctx->overlap && !(nr && atoi(nr) != 0);
   // Whether the selections may ride in the attention launch: static scores, a cache that releases, and the role's
@@ -324,6 +339,7 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
     return ADORE_E_UNSUPPORTED;
   const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
   if (rescore && score_override) return ADORE_E_INVALID;   // scores are recomputed at every step
+  if (h2o_mode(ctx) && forward) return ADORE_E_UNSUPPORTED;
   const size_t es = elem_size(c);
   const int m = c.cache_slots - c.rebuild_budget - 1;
   const int keep = S < m ? S : m;
@@ -338,6 +354,26 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   }
   hipStream_t st = ctx->stream;
   ctx->cur = 0;
+  if (h2o_mode(ctx)) {
+    // the prompt's scores are given (or zero); every head picks its own residents, then the per-sequence choice
+    ADORE_TRY(launch_h2o_init_scores(ctx, score_override, S));
+    ADORE_TRY(launch_h2o_init_select(ctx, ctx->cur, ctx->cur + 1, S, keep));
+    ADORE_TRY(launch_h2o_choice(ctx, ctx->cur, ctx->cur + 1, S - 1, nullptr, nullptr));
+    ADORE_TRY(launch_init_copy(ctx, prompt_k, prompt_v, S, keep));
+    if (pool > 0) ADORE_TRY(launch_rebuild_gemm(ctx, 0, hidden_store, ctx->cur + 1, c.rebuild_budget));
+    ctx->steps_done = 0;
+    ctx->n = S;
+    ctx->occ = 0;
+    ctx->inited = true;
+    ctx->forward = false;
+    ctx->r_pending = 0;
+    ctx->ins_stride = 1;
+    ctx->ins_off = 0;
+    ctx->ins_from_list = false;
+    ctx->rode = false;
+    reset_step(ctx);
+    return ADORE_OK;
+  }
   ADORE_TRY(launch_rope_table(ctx));
   // controller over the prompt: z_{-1} = 0, tokens in order, in chunks
   ADORE_TRY(launch_fill_i32(ctx, reinterpret_cast<int32_t *>(ctx->z), 0, size_t(c.batch) * c.ctrl_hidden));
@@ -400,6 +436,18 @@ int do_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new, c
 int do_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
                 int32_t *released_pos, int32_t *rebuilt_pos) {
   const adore_config &c = ctx->cfg;
+  if (h2o_mode(ctx)) {
+    // The step's attention is added to the scores, every head releases on its own (how many rows, it counts
+    // itself), then the per-sequence choice.  Tokens exist to be rebuilt once some head has had to give one up,
+    // which cannot happen before there are more tokens than persistent rows; how many are chosen is decided on
+    // the device, and the GEMM skips the ranks that stay empty.
+    const int dst = (ctx->cur + 1) % kRing;
+    ADORE_TRY(launch_h2o_release(ctx, ctx->cur, dst, slot_map, released_pos));
+    ADORE_TRY(launch_h2o_choice(ctx, dst, dst, ctx->n, slot_map, rebuilt_pos));
+    ctx->scheduled = true;
+    ctx->r_step = ctx->n + 1 > c.cache_slots - c.rebuild_budget - 1 ? c.rebuild_budget : 0;
+    return ADORE_OK;
+  }
   const int m = c.cache_slots - c.rebuild_budget - 1;
   const int o = ctx->occ + 1;
   const int x = o > m ? o - m : 0;
@@ -499,8 +547,8 @@ int adore_attend(adore_ctx *ctx, int32_t layer, const void *q, const void *k_new
 
 int adore_schedule(adore_ctx *ctx, const void *x_n, const float *score_override, int32_t *slot_map,
                    int32_t *released_pos, int32_t *rebuilt_pos) {
-  if (!ctx || !x_n) return ADORE_E_INVALID;
-  if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
+  if (!ctx || (!x_n && !h2o_mode(ctx))) return ADORE_E_INVALID;
+  if (score_override && ctx->cfg.score_mode != ADORE_SCORE_STATIC) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != ctx->cfg.layers) return ADORE_E_STATE;
   return do_schedule(ctx, x_n, score_override, slot_map, released_pos, rebuilt_pos);
 }
@@ -515,14 +563,21 @@ int adore_rebuild(adore_ctx *ctx, int32_t layer, const void *hidden_store_layer)
 int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const void *v_new,
                       const void *hidden_store, const void *x_n, const float *score_override, float *out,
                       int32_t *slot_map) {
-  if (!ctx || !q || !k_new || !v_new || !hidden_store || !x_n || !out) return ADORE_E_INVALID;
+  if (!ctx || !q || !k_new || !v_new || !hidden_store || (!x_n && !h2o_mode(ctx)) || !out) return ADORE_E_INVALID;
   if (ctx->cfg.layers != 1) return ADORE_E_INVALID;
-  if (score_override && ctx->cfg.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_INVALID;
+  if (score_override && ctx->cfg.score_mode != ADORE_SCORE_STATIC) return ADORE_E_INVALID;
   if (!ctx->inited || ctx->forward || ctx->scheduled || ctx->n_attended != 0 || ctx->n >= ctx->cfg.max_positions)
     return ADORE_E_STATE;
   if (ctx->ride && ctx->ride_fits) {
     if (ensure_side_stream(ctx) != ADORE_OK) return ADORE_E_HIP;
     return do_ridden_step(ctx, q, k_new, v_new, hidden_store, x_n, score_override, out, slot_map);
+  }
+  if (h2o_mode(ctx)) {   // the selections need this step's attention
+    int rc = do_attend(ctx, 0, q, k_new, v_new, out);
+    if (rc != ADORE_OK) return rc;
+    rc = do_schedule(ctx, x_n, score_override, slot_map, nullptr, nullptr);
+    if (rc != ADORE_OK) return rc;
+    return do_rebuild(ctx, 0, hidden_store);
   }
   // The selections do not depend on this step's attention: enqueue them first so that they start
   // while the previous step's GEMM is still running.
@@ -618,9 +673,9 @@ int adore_get_state(adore_ctx *ctx, int32_t *slot_pos, float *scores, float *z, 
     ADORE_TRY(hipMemcpyAsync(slot_pos, ctx->slot_pos[ctx->cur], BH * c.cache_slots * 4, hipMemcpyDeviceToDevice,
                              ctx->stream));
   if (scores)
-    ADORE_TRY(hipMemcpyAsync(scores, ctx->score, size_t(c.batch) * c.max_positions * 4, hipMemcpyDeviceToDevice,
-                             ctx->stream));
-  if (z)
+    ADORE_TRY(hipMemcpyAsync(scores, ctx->score, size_t(c.batch) * (h2o_mode(ctx) ? c.heads : 1) * c.max_positions * 4,
+                             hipMemcpyDeviceToDevice, ctx->stream));
+  if (z && !h2o_mode(ctx))   // no controller, no GRU state
     ADORE_TRY(hipMemcpyAsync(z, ctx->z, size_t(c.batch) * c.ctrl_hidden * 4, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_k) ADORE_TRY(hipMemcpyAsync(cache_k, ctx->cache_k, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
   if (cache_v) ADORE_TRY(hipMemcpyAsync(cache_v, ctx->cache_v, cache_bytes, hipMemcpyDeviceToDevice, ctx->stream));
@@ -631,7 +686,8 @@ int adore_set_state(adore_ctx *ctx, const int32_t *slot_pos, const float *scores
                     const void *cache_k, const void *cache_v, int32_t step) {
   if (!ctx || !slot_pos) return ADORE_E_INVALID;
   const adore_config &c = ctx->cfg;
-  if (c.score_mode == ADORE_SCORE_RESCORE) return ADORE_E_UNSUPPORTED;   // the per-token vectors are not part of a snapshot
+  if (c.score_mode != ADORE_SCORE_STATIC) return ADORE_E_UNSUPPORTED;   // rescore: the per-token vectors are not part of a
+                                                                         // snapshot; H2O: heads differ in what they hold
   if (step < 1 || step >= c.max_positions) return ADORE_E_INVALID;
   if (ctx->scheduled || ctx->n_attended != 0 || ctx->forward) return ADORE_E_STATE;
   const size_t BH = size_t(c.batch) * c.heads;
@@ -765,6 +821,8 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_FWD_OPROJ: return "fwd_oproj";
     case ADORE_KERNEL_FWD_OPROJ_CUR: return "fwd_oproj_cur";
     case ADORE_KERNEL_ROPE: return "rope";
+    case ADORE_KERNEL_H2O_RELEASE: return "h2o_release";
+    case ADORE_KERNEL_H2O_CHOICE: return "h2o_choice";
     default: return "?";
   }
 }
@@ -777,7 +835,8 @@ const char *adore_strerror(int code) {
     case ADORE_E_UNSUPPORTED:
       return "unsupported configuration (need head_dim in {64,128}, cache_slots <= 1024 or "
              "cache_slots - rebuild_budget - 1 >= max_positions, hidden % 8 == 0, max_positions <= 262144, "
-             "ctrl_hidden <= 1024, ctrl_hidden % 4 == 0 in rescore mode; no set_state in rescore mode)";
+             "ctrl_hidden <= 1024, ctrl_hidden % 4 == 0 in rescore mode; H2O mode: one layer, heads <= 255, "
+             "max_positions <= about 7000, no rotary embedding, no forward; set_state in static mode only)";
     case ADORE_E_WORKSPACE: return "workspace too small or not 256-byte aligned";
     case ADORE_E_HIP: return "HIP runtime call failed";
     default: return "unknown error";

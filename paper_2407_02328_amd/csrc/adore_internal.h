@@ -66,6 +66,8 @@ struct adore_ctx {
   int32_t *rebuilt_pos[adore::kRing];  // xR [B][max(R,1)]
   int32_t *init_res;         // [B][K]      residents chosen at init, ascending position
   float *att_part;           // [B*H][kMaxSplits][d+2]
+  float *att_logit;          // H2O mode: [B*H][K] the step's logits in base 2, as the attention kernel scaled them
+  float *att_ml;             // H2O mode: [B*H][2] their maximum and the sum of exp2(logit - maximum) over the row
   float *gi;                 // [ksplit][tokens][3d'] GRU input pre-activations, per D-slice
   float *zseq;               // [B][kPromptChunk][d'] GRU states of a prompt chunk, between its scan and its scoring
   float *cvec;               // rescore mode: [B][N_max][d']  W_1 (z_i + pos_b) + b_1 of every token
@@ -172,6 +174,14 @@ hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int kee
 hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *prompt_v, int S,
                             int keep);
 hipError_t launch_fill_i32(adore_ctx *ctx, int32_t *dst, int32_t value, size_t count);
+// H2O mode (scores = attention collected per head; see csrc/h2o.hip).  All on the context's stream.
+inline bool h2o_mode(const adore_ctx *ctx) { return ctx->cfg.score_mode == ADORE_SCORE_H2O; }
+hipError_t launch_h2o_init_scores(adore_ctx *ctx, const float *score_init, int S);
+hipError_t launch_h2o_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep);
+hipError_t launch_h2o_release(adore_ctx *ctx, int src, int dst, int32_t *map_out, int32_t *rel_out);
+// n: the last position that exists (the current token of a step, S - 1 at init)
+hipError_t launch_h2o_choice(adore_ctx *ctx, int maps, int lists, int n, int32_t *map_out, int32_t *rb_out);
+size_t h2o_choice_lds_bytes(const adore_config &c, int n);
 // rescore mode: the distance vector W_1 pos_w (once per init), and sigma of tokens 0..upto seen from token n
 hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st);
 hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n, int upto);

@@ -45,6 +45,9 @@ struct AttendArgs {
   SchedArgs s;
   float *part;                     // [B*H][nsplit][d+2]
   float *out;                      // [B*H][d]
+  float *logit_out;                // null, or [B*H][K]: every slot's logit as scaled here (base 2; -inf for a free slot)
+  float *ml_out;                   // ... and [B*H][2]: the row's maximum logit and the sum of exp2(logit - maximum),
+                                   // from which a row's probabilities follow (the scores of the H2O mode)
   int K, chunk, nsplit;
   float scale_log2;                // log2(e) / sqrt(d)
 };
@@ -179,6 +182,7 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
       for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
       logit[u] = valid[u] ? dot : -INFINITY;
       mb = fmaxf(mb, logit[u]);
+      if (a.logit_out && lig == 0 && base + u * G + grp < end) a.logit_out[size_t(bh) * a.K + base + u * G + grp] = logit[u];
     }
     if (mb == -INFINITY) continue;  // nothing occupied so far in this lane group
     const float corr = exp2f(m - mb);
@@ -223,6 +227,10 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
     }
     if (a.nsplit == 1) {
       a.out[size_t(bh) * DH + tid] = sum / L;   // the current token is always present: L > 0
+      if (a.ml_out && tid == 0) {
+        a.ml_out[size_t(bh) * 2] = M;
+        a.ml_out[size_t(bh) * 2 + 1] = L;
+      }
     } else {
       float *p = a.part + (size_t(bh) * a.nsplit + sp) * (DH + 2);
       p[tid] = sum;
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
 }
 
 template <int DH>
-__global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, float *out, int nsplit) {
+__global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, float *out, int nsplit, float *ml_out) {
   const int bh = blockIdx.x;
   const int tid = threadIdx.x;
   const float *p = part + size_t(bh) * nsplit * (DH + 2);
@@ -249,6 +257,10 @@ __global__ __launch_bounds__(DH) void attend_combine_kernel(const float *part, f
     L = fmaf(p[s * (DH + 2) + DH + 1], f, L);
   }
   out[size_t(bh) * DH + tid] = sum / L;
+  if (ml_out && tid == 0) {
+    ml_out[size_t(bh) * 2] = M;
+    ml_out[size_t(bh) * 2 + 1] = L;
+  }
 }
 
 template <typename T, int DH>
@@ -268,7 +280,7 @@ hipError_t launch_typed(adore_ctx *ctx, const AttendArgs &a, int rows, int waves
   if (a.nsplit > 1) {
     ScopedTimer t(ctx, ADORE_KERNEL_ATTEND_COMBINE, ctx->stream);
     ADORE_LAUNCH(t, (attend_combine_kernel<DH>), dim3(rows), dim3(DH), 0, ctx->stream, a.part, a.out,
-                       a.nsplit);
+                       a.nsplit, a.ml_out);
     e = hipGetLastError();
   }
   return e;
@@ -294,6 +306,8 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
   a.ins_stride = ctx->ins_stride; a.ins_off = ctx->ins_off;
   a.part = ctx->att_part;
   a.out = out;
+  a.logit_out = h2o_mode(ctx) ? ctx->att_logit : nullptr;
+  a.ml_out = h2o_mode(ctx) ? ctx->att_ml : nullptr;
   a.K = c.cache_slots; a.chunk = ctx->chunk; a.nsplit = ctx->nsplit;
   a.scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
   const int rows = c.batch * c.heads;

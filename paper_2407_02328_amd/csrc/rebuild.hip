@@ -69,8 +69,10 @@ struct GemmArgs {
                                // position as they leave; null: no rotary embedding, or a pass of its own does it
 };
 
+// A rank that stays empty (position -1: fewer tokens were chosen than the launch has rows for) reads row 0 of its
+// sequence; nothing of it is written.
 __device__ inline size_t row_by_position(const GemmArgs &a, int b, int j) {
-  return size_t(b) * a.N_max + a.rebuilt_pos[size_t(b) * a.Rdim + j];
+  return size_t(b) * a.N_max + max(a.rebuilt_pos[size_t(b) * a.Rdim + j], 0);
 }
 
 // The current token's row of every sequence (rebuild forward) as workgroups of the tile kernel's launch.  B rows
@@ -404,6 +406,8 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
         } else {
           const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + j];
           off = ((long long)(size_t(b) * a.H + h) * a.K + slot) * a.d + (rem - h * a.d);
+          // no slot: the head still holds this token's row (heads with maps of their own), or the rank is empty
+          if (MODE == MODE_REBUILD && (slot < 0 || a.rebuilt_pos[size_t(b) * a.Rdim + j] < 0)) off = -1;
           if (MODE == MODE_REBUILD && a.map_dst && section == 0) {   // the K half's tiles visit every (token, head)
             const int pos = a.rebuilt_pos[size_t(b) * a.Rdim + j];
             a.map_dst[(size_t(b) * a.H + h) * a.K + slot] = pos;
@@ -417,7 +421,7 @@ __global__ __launch_bounds__(512) void rebuild_mfma_kernel(const GemmArgs a) {
   if ((MODE == MODE_REBUILD || MODE == MODE_QKV) && a.rope) {
     for (int row = tid; row < BM; row += 512) {
       const int mi = min(m0 + row, a.M - 1);
-      s_rpos[row] = a.rebuilt_pos[size_t(mi / a.r) * a.Rdim + (mi % a.r)];
+      s_rpos[row] = max(a.rebuilt_pos[size_t(mi / a.r) * a.Rdim + (mi % a.r)], 0);
     }
   }
   if (MODE == MODE_OPROJ) {
@@ -633,6 +637,7 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
   const int mi = int(wid / a.N), nf = int(wid - size_t(mi) * a.N);
   const int b = mi / a.r, rho = mi - b * a.r;
   const int pos = a.rebuilt_pos[size_t(b) * a.Rdim + rho];
+  if (pos < 0) return;   // an empty rank (uniform over the wave)
   const T *x = static_cast<const T *>(a.X) + (size_t(b) * a.N_max + pos) * a.D;
   const T *wrow = static_cast<const T *>(a.W) + size_t(nf) * a.D;
   float s = 0.f;
@@ -649,6 +654,7 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
     const int half = nf / Hd, rem = nf - half * Hd;
     const int h = rem / a.d, cc = rem - h * a.d;
     const int slot = a.free_list[(size_t(b) * a.H + h) * a.R1 + rho];
+    if (slot < 0) return;   // the head still holds this token's row
     T *dst = static_cast<T *>(half ? a.Vc : a.Kc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + cc;
     store_elem(dst, s);
     if (a.map_dst && half == 0 && cc == 0) {

@@ -89,8 +89,10 @@ struct InitSelectArgs {
   int32_t *free_list;      // [B][H][R1]
   int32_t *rebuilt_pos;    // [B][Rdim]
   int32_t *insert_slot;    // [B][H]
-  int32_t *init_res;       // [B][K]
+  int32_t *init_res;       // [B][K]; per_head: [B][H][K]
   int K, H, N_max, S, keep, r0, R1, Rdim, words;
+  int per_head;            // 1: one workgroup per (sequence, head) with a score row of its own (H2O mode); it picks
+                           // the head's residents only: the first rebuild set is chosen by another kernel
 };
 
 __global__ __launch_bounds__(1024) void init_select_kernel(const InitSelectArgs a) {
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(1024) void init_select_kernel(const InitSelectArgs 
   __shared__ int s_count;
   __shared__ int s_cnt[16];
   __shared__ int s_carry;
-  const int b = blockIdx.x;
+  const int b = blockIdx.x;     // per_head: the row index b * H + h
   const int tid = threadIdx.x;
   const float *sc = a.score + size_t(b) * a.N_max;
 
@@ -155,6 +157,12 @@ __global__ __launch_bounds__(1024) void init_select_kernel(const InitSelectArgs 
     }
     __syncthreads();
   }
+  if (a.per_head) {   // this head's slot map and its free slots in ascending order; the rest follows in h2o_choice_kernel
+    const int32_t *res = a.init_res + size_t(b) * a.K;   // written above by this block
+    for (int s = tid; s < a.K; s += blockDim.x) a.slot_pos[size_t(b) * a.K + s] = s < a.keep ? res[s] : -1;
+    for (int idx = tid; idx < a.R1; idx += blockDim.x) a.free_list[size_t(b) * a.R1 + idx] = a.keep + idx;
+    return;
+  }
   // first rebuild set: best r0 of the non-residents
   if (a.r0 > 0) {
     auto key_pool = [&](int i) -> uint64_t {
@@ -187,16 +195,16 @@ __global__ __launch_bounds__(1024) void init_select_kernel(const InitSelectArgs 
 __global__ __launch_bounds__(256) void init_copy_kernel(const uint4 *__restrict__ prompt_k,
                                                         const uint4 *__restrict__ prompt_v,
                                                         uint4 *__restrict__ cache_k, uint4 *__restrict__ cache_v,
-                                                        const int32_t *__restrict__ init_res, int B, int H,
-                                                        int K, int S, int keep, int vec_per_row, size_t total) {
+                                                        const int32_t *__restrict__ init_res, int res_heads, int B,
+                                                        int H, int K, int S, int keep, int vec_per_row, size_t total) {
   const size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (i >= total) return;
   const int v = int(i % vec_per_row);
   size_t rest = i / vec_per_row;
   const int s = int(rest % keep);
   rest /= keep;                       // (l*B + b)*H + h
-  const int b = int((rest / H) % B);
-  const int pos = init_res[size_t(b) * K + s];
+  const int b = int((rest / H) % B), h = int(rest % H);
+  const int pos = init_res[(size_t(b) * res_heads + (res_heads > 1 ? h : 0)) * K + s];   // res_heads: 1, or H when heads differ
   const size_t src = (rest * S + pos) * vec_per_row + v;
   const size_t dst = (rest * K + s) * vec_per_row + v;
   cache_k[dst] = prompt_k[src];
@@ -262,8 +270,25 @@ hipError_t launch_init_select(adore_ctx *ctx, int dst, int lists, int S, int kee
   a.K = c.cache_slots; a.H = c.heads; a.N_max = c.max_positions; a.S = S; a.keep = keep; a.r0 = r0;
   a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.words = (c.max_positions + 31) / 32;
+  a.per_head = 0;
   const size_t smem = size_t(max(r0, 1)) * 8 + 4 * 8 + 256 * 4 + size_t(a.words) * 4 + size_t(max(r0, 1)) * 4;
   hipLaunchKernelGGL(init_select_kernel, dim3(c.batch), dim3(1024), smem, ctx->stream, a);
+  return hipGetLastError();
+}
+
+// H2O mode: every head picks its residents on its own scores (slot map -> ring copy dst, ascending free slots ->
+// ring copy lists, where h2o_choice_kernel takes them from).
+hipError_t launch_h2o_init_select(adore_ctx *ctx, int dst, int lists, int S, int keep) {
+  const adore_config &c = ctx->cfg;
+  InitSelectArgs a;
+  a.slot_pos = ctx->slot_pos[dst]; a.score = ctx->score; a.free_list = ctx->free_list[lists];
+  a.rebuilt_pos = nullptr; a.insert_slot = nullptr; a.init_res = ctx->init_res;
+  a.K = c.cache_slots; a.H = c.heads; a.N_max = c.max_positions; a.S = S; a.keep = keep; a.r0 = 0;
+  a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
+  a.words = (c.max_positions + 31) / 32;
+  a.per_head = 1;
+  const size_t smem = 8 + 4 * 8 + 256 * 4 + size_t(a.words) * 4 + 4;
+  hipLaunchKernelGGL(init_select_kernel, dim3(c.batch * c.heads), dim3(1024), smem, ctx->stream, a);
   return hipGetLastError();
 }
 
@@ -275,7 +300,7 @@ hipError_t launch_init_copy(adore_ctx *ctx, const void *prompt_k, const void *pr
   hipLaunchKernelGGL(init_copy_kernel, dim3(blocks), dim3(256), 0, ctx->stream,
                      static_cast<const uint4 *>(prompt_k), static_cast<const uint4 *>(prompt_v),
                      reinterpret_cast<uint4 *>(ctx->cache_k), reinterpret_cast<uint4 *>(ctx->cache_v),
-                     ctx->init_res, c.batch, c.heads, c.cache_slots, S, keep, vec_per_row, total);
+                     ctx->init_res, h2o_mode(ctx) ? c.heads : 1, c.batch, c.heads, c.cache_slots, S, keep, vec_per_row, total);
   return hipGetLastError();
 }
 

@@ -101,7 +101,7 @@ __device__ inline void collect_sorted(KeyFn key_of, int ncand, int c, uint64_t t
 // raw, if not null, holds what release_fetch read of the row earlier (so that the read is under way
 // while something else is waited for).
 // Lane L holds the keys of slots L, L+64, ...
-// (KPL per lane).  The x lowest keys are found by a binary radix select from the top bit
+// (KPL per lane).  The x lowest keys (x < 0: as many as leave m_keep rows) are found by a binary radix select from the top bit
 // down: a ballot counts the candidates whose bit is 0; if there are at least `need` of them
 // the ones drop out, otherwise all zeros are taken and the search goes on among the ones.
 // Bits on which all candidates agree are skipped.  Keys are distinct, so exactly x are taken.
@@ -122,7 +122,8 @@ __device__ inline void release_row(int row, int s_ins, const int32_t *__restrict
                                    int32_t *__restrict__ slot_dst, const float *sc,
                                    int32_t *__restrict__ free_list, int32_t *__restrict__ released_pos,
                                    int32_t *__restrict__ map_out, int32_t *__restrict__ rel_out, int K,
-                                   int n, int x, int R1, int32_t *row_copy, const int *raw = nullptr) {
+                                   int n, int x, int R1, int32_t *row_copy, const int *raw = nullptr,
+                                   int m_keep = 0) {
   const int lane = threadIdx.x & 63;
   const int32_t *sp = slot_src + size_t(row) * K;
 
@@ -159,6 +160,9 @@ __device__ inline void release_row(int row, int s_ins, const int32_t *__restrict
   int nactive = 0;                              // candidates still in play, whole row
 #pragma unroll
   for (int j = 0; j < KPL; ++j) nactive += __popcll(__ballot((cand >> j) & 1u));
+  // x < 0: the row counts for itself how many rows it has to give up to be left with m_keep (the current token
+  // included): heads that hold different numbers of rows (H2O mode) cannot be told from the host
+  if (x < 0) need = max(0, nactive + 1 - m_keep);
   if (need > 0) {
 #pragma unroll 1
     for (int word = 1; word >= 0 && need > 0 && nactive > need; --word) {

@@ -3,94 +3,9 @@ import numpy as np
 import torch
 
 from gen import SyntheticInputs, Workload
+from gen.gpu_job import DEV, GpuJob, adore_config, device_weights, storage_dtype, to_dev
 from paper_2407_02328_amd import Adore, make_config
 from tests.helpers import make_oracle
-
-DEV = "cuda:0"
-
-
-def storage_dtype(w: Workload):
-    return torch.bfloat16 if w.dtype == "bf16" else torch.float32
-
-
-def to_dev(a: np.ndarray, dtype) -> torch.Tensor:
-    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
-
-
-def adore_config(w: Workload):
-    return make_config(layers=w.L, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K,
-                       rebuild_budget=w.R, max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype,
-                       pos_scale=w.pos_scale, score_mode=1 if w.rescore else 0, rope_base=w.rope_base)
-
-
-def device_weights(w: Workload, wts):
-    st = storage_dtype(w)
-    return {k: to_dev(v, st if k in ("w_kv", "gru_w_ih", "gru_w_hh") else torch.float32) for k, v in wts.items()}
-
-
-class GpuJob:
-    """Device-side twin of an oracle run: same workload, same inputs, uploaded byte for byte."""
-
-    def __init__(self, w: Workload, inp: SyntheticInputs = None, wts=None, hidden=None, prompt=None, ordered=True):
-        self.w = w
-        self.ordered = ordered     # False: inputs are complete in memory at every call (synchronised first)
-        self.inp = inp or SyntheticInputs(w)
-        self.wts = wts if wts is not None else self.inp.weights()
-        st = storage_dtype(w)
-        self.st = st
-        self.adore = Adore(adore_config(w), device_weights(w, self.wts), DEV)
-        if not ordered:
-            self.adore.set_input_order(False)
-        self.hidden_np = self.inp.hidden_store() if hidden is None else hidden
-        self.hidden = to_dev(self.hidden_np, st)
-        self.prompt_np = self.inp.prompt_kv() if prompt is None else prompt
-        self.out = torch.empty((w.L, w.B, w.H, w.d), dtype=torch.float32, device=DEV)
-        self.slot_map = torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=DEV)
-        self.released = torch.empty((w.B, w.H, w.R + 1), dtype=torch.int32, device=DEV)
-        self.rebuilt = torch.empty((w.B, max(w.R, 1)), dtype=torch.int32, device=DEV)
-        self.state = self.adore.empty_state()
-
-    def init(self, score_override=None):
-        w = self.w
-        pk, pv = self.prompt_np
-        ov = None if score_override is None else to_dev(score_override, torch.float32)
-        self.adore.init_cache(to_dev(pk, self.st), to_dev(pv, self.st), self.hidden,
-                              self.hidden[0][:, :w.S].contiguous(), ov, w.S)
-        torch.cuda.synchronize()
-
-    def step(self, n, qkv=None, override=None, whole=False, x_n=None):
-        """One step through the fine-grained calls, or (whole, L = 1) through adore_decode_step, which reports
-        the slot map only.  x_n: a device buffer to pass as the controller input instead of a fresh copy of the
-        token's row.  Returns numpy (out, slot_map, released, rebuilt, score_n)."""
-        w = self.w
-        q, k, v = self.inp.step_qkv(n) if qkv is None else qkv
-        qd, kd, vd = (to_dev(a, self.st) for a in (q, k, v))
-        ov = None if override is None else to_dev(np.asarray(override, dtype=np.float32), torch.float32)
-        if x_n is None:
-            x_n = self.hidden[0][:, n].contiguous()  # a copy kernel on the stream the context is bound to
-        if not self.ordered:
-            torch.cuda.synchronize()
-        if whole:
-            self.adore.decode_step(qd[0], kd[0], vd[0], self.hidden[0], x_n, ov, self.out[0], self.slot_map)
-        else:
-            for l in range(w.L):
-                self.adore.attend(l, qd[l], kd[l], vd[l], self.out[l])
-            self.adore.schedule(x_n, ov, self.slot_map, self.released, self.rebuilt)
-            for l in range(w.L):
-                self.adore.rebuild(l, self.hidden[l])
-        # the scores, and the caches as the step leaves them (device copies: adopt_rebuilt_rows reads rows of them)
-        self.adore.get_state(scores=self.state["scores"], cache_k=self.state["cache_k"], cache_v=self.state["cache_v"])
-        torch.cuda.synchronize()
-        sc = self.state["scores"]
-        score_n = sc[:, :n + 1].cpu().numpy() if w.rescore else sc[:, n].cpu().numpy()
-        return (self.out.cpu().numpy().astype(np.float64), self.slot_map.cpu().numpy(),
-                self.released.cpu().numpy(), self.rebuilt.cpu().numpy()[:, :w.R], score_n)
-
-    def snapshot(self):
-        self.adore.get_state(**self.state)
-        torch.cuda.synchronize()
-        return {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
-                for k, v in self.state.items()}
 
 
 def row_rel_err(got: np.ndarray, want: np.ndarray) -> float:
@@ -335,15 +250,17 @@ def adopt_rebuilt_rows(w: Workload, orc, cache_k: torch.Tensor, cache_v: torch.T
     cache_k, cache_v: device copies [L][B][H][K][d] of the GPU's caches after the step; rebuilt: per oracle
     sequence the positions just rebuilt; seqs: the GPU's sequences the oracle follows (default: all)."""
     c = orc.cfg
-    r = len(rebuilt[0])
-    assert all(len(x) == r for x in rebuilt)
+    r = max(len(x) for x in rebuilt)
     if r == 0:
         return
+    # (sequences may have chosen different numbers of tokens where the heads decide for themselves: the lists are
+    # padded with their own first entry, which is then checked and adopted twice)
     slots = np.empty((c.B, c.H, r), dtype=np.int64)
     for b in range(c.B):
+        lst = list(rebuilt[b]) + [rebuilt[b][0]] * (r - len(rebuilt[b])) if rebuilt[b] else None
         for h in range(c.H):
             slot_of = {int(p): k for k, p in enumerate(orc.slot_pos[b, h]) if p >= 0}
-            slots[b, h] = [slot_of[p] for p in rebuilt[b]]
+            slots[b, h] = [slot_of[p] for p in lst] if lst else int(np.nonzero(orc.slot_pos[b, h] >= 0)[0][0])
     idx = torch.from_numpy(slots).to(cache_k.device)[None, :, :, :, None].expand(c.L, -1, -1, -1, c.d)
     at = slots[None, :, :, :, None]
     for name, dev, ref in (("cache_k", cache_k, orc.Kc), ("cache_v", cache_v, orc.Vc)):
@@ -353,6 +270,63 @@ def adopt_rebuilt_rows(w: Workload, orc, cache_k: torch.Tensor, cache_v: torch.T
         for l in range(c.L):
             check_cache_rows(w, name, rows[l].reshape(-1, c.d), want[l].reshape(-1, c.d))
         np.put_along_axis(ref, at, rows, axis=3)
+
+
+# ---------------------------------------------------------------------------------------------
+# H2O(Rebuilt): scores = the attention each head has given a token so far
+# ---------------------------------------------------------------------------------------------
+def h2o_score_check(own: np.ndarray, got: np.ndarray, what: str):
+    """The GPU's accumulated scores against the oracle's: the oracle adds this step's fp64 probability to the fp32
+    score both sides started the step from; the GPU adds its fp32 probability in fp32.  So: the softmax's own error
+    (1e-5, as for sigma) plus one fp32 rounding of the sum (2^-23 of it; scores grow with the steps)."""
+    err = np.abs(own - got.astype(np.float64))
+    assert np.all(err <= 1e-5 + 2.0 ** -22 * np.abs(own)), f"{what}: {err.max()}"
+
+
+def h2o_lockstep(w: Workload, steps: int, score_init=None, whole=None, check_cache_every=0, zero_queries=False):
+    """The H2O score mode next to its oracle: after every step the GPU's scores [B,H,n+1] are checked against the
+    oracle's own and adopted, then slot maps (one per head), released and rebuilt positions must be identical, outputs
+    within the attention tolerance; rebuilt rows are checked and adopted as in lockstep.
+    Returns (worst output error, job, oracle, number of steps at which two heads of a sequence held different tokens)."""
+    from oracle.adore_oracle import AdoreH2OOracle
+    from tests.helpers import oracle_config
+    assert w.h2o and w.L == 1
+    inp = SyntheticInputs(w)
+    wts = inp.weights()
+    orc = AdoreH2OOracle(oracle_config(w), wts)
+    job = GpuJob(w, inp, wts)
+    hs = job.hidden_np
+    pk, pv = job.prompt_np
+    job.init(score_init)
+    snap = job.snapshot()
+    rb0 = orc.init_cache(pk, pv, hs, w.S, score_init=score_init)
+    assert np.array_equal(snap["scores"][:, :, :w.S], orc.hscore[:, :, :w.S])
+    assert np.array_equal(snap["slot_pos"], orc.slot_pos), "slot map after init"
+    compare_cache(w, snap, orc)
+    adopt_rebuilt_rows(w, orc, job.state["cache_k"], job.state["cache_v"], rb0)
+    worst, differ = 0.0, 0
+    for t in range(steps):
+        n = w.S + t
+        q, k, v = inp.step_qkv(n)
+        if zero_queries:
+            q = np.zeros_like(q)
+        one_call = whole is not None and bool(whole(t))
+        out_g, map_g, rel_g, rb_g, score_g = job.step(n, (q, k, v), whole=one_call)
+        out_o, map_o, rel_o, rb_o = orc.decode_step(q, k, v, hs, score_override=score_g)
+        h2o_score_check(orc.own_scores, score_g, f"scores at n={n}")
+        assert np.array_equal(map_g, map_o), f"slot map at n={n}"
+        if not one_call:
+            assert np.array_equal(rel_g, rel_o), f"released at n={n}"
+            assert np.array_equal(rb_g, rb_o), f"rebuilt at n={n}"
+        err = row_rel_err(out_g, out_o)
+        worst = max(worst, err)
+        assert err < out_tol(w), f"attention output at n={n}: {err}"
+        adopt_rebuilt_rows(w, orc, job.state["cache_k"], job.state["cache_v"], rebuilt_lists(rb_o))
+        differ += any(set(map_o[b, h][map_o[b, h] >= 0]) != set(map_o[b, 0][map_o[b, 0] >= 0])
+                      for b in range(w.B) for h in range(1, w.H))
+        if check_cache_every and (t + 1) % check_cache_every == 0:
+            compare_cache(w, job.snapshot(), orc)
+    return worst, job, orc, differ
 
 
 # ---------------------------------------------------------------------------------------------

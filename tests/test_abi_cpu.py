@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 7
+    assert lib.adore_abi_version() == 8
 
 
 def test_workspace_bytes(lib):
@@ -87,7 +87,22 @@ def test_create_rejects_bad_arguments(lib):
     big = lib.adore_workspace_bytes(ctypes.byref(over))
     assert lib.adore_create(ctypes.byref(over), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3
     # rescore mode: unknown mode value, d' not a multiple of 4, no overrides, no set_state
-    assert lib.adore_create(ctypes.byref(cfg_for(w, score_mode=2)), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1
+    assert lib.adore_create(ctypes.byref(cfg_for(w, score_mode=3)), ctypes.byref(wt), FAKE, n, None, ctypes.byref(h)) == -1
+    # H2O mode: scores per head (a larger workspace), one layer, no rotary embedding, a bounded number of positions,
+    # no override in a step, no set_state, x_n not needed
+    h2o = cfg_for(w, score_mode=2)
+    big = lib.adore_workspace_bytes(ctypes.byref(h2o))
+    assert big >= n + (w.H - 1) * w.B * w.N_max * 4
+    for kw in (dict(layers=2), dict(rope_base=100.0), dict(max_positions=8000), dict(heads=256)):
+        uns = cfg_for(w, score_mode=2, **kw)
+        assert lib.adore_create(ctypes.byref(uns), ctypes.byref(wt), FAKE, lib.adore_workspace_bytes(ctypes.byref(uns)),
+                                None, ctypes.byref(h)) == -3, kw
+    assert lib.adore_create(ctypes.byref(h2o), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == 0
+    assert lib.adore_schedule(h, None, FAKE, None, None, None, None) == -1        # an override
+    assert lib.adore_schedule(h, None, None, None, None, None) == -2              # (valid arguments; no init yet)
+    assert lib.adore_set_state(h, FAKE, None, None, None, None, 5) == -3
+    assert lib.adore_init_cache(h, FAKE, FAKE, None, FAKE, None, 4) == -3         # no rebuild forward in this mode
+    assert lib.adore_destroy(h) == 0
     odd = cfg_for(w, score_mode=1, ctrl_hidden=6)
     big = lib.adore_workspace_bytes(ctypes.byref(odd))
     assert lib.adore_create(ctypes.byref(odd), ctypes.byref(wt), FAKE, big, None, ctypes.byref(h)) == -3
