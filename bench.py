@@ -127,6 +127,80 @@ def run_gpu(w, steps, warmup, prof_steps, ordered_steps=0):
     return elapsed, per_kernel_us, other
 
 
+def run_gpu_device_inputs(w, steps, warmup, prof_steps):
+    """A single-layer workload through adore_decode_step with its large tensors drawn on the device (seeded torch
+    generator; the host generator of the parity tests takes minutes at these sizes).  Inputs complete in memory
+    before every call.  Returns (seconds for `steps` steps, microseconds per launch and kernel)."""
+    import torch
+    from gen import DeviceNormals, SyntheticInputs
+    from gen.gpu_job import DEV, storage_dtype, to_dev
+    from paper_2407_02328_amd import Adore, make_config
+    st = storage_dtype(w)
+    total = warmup + steps + prof_steps
+    w = w.scaled(T=max(w.T, total))
+    drawer = DeviceNormals(w.seed, DEV)
+    small = SyntheticInputs(w.scaled(L=1, H=1, d=64, B=1)).weights()    # controller tensors do not depend on L, H, d, B
+    wts = {k: to_dev(v, st if k in ("gru_w_ih", "gru_w_hh") else torch.float32) for k, v in small.items() if k != "w_kv"}
+    wts["w_kv"] = drawer.normal((1, 2 * w.H * w.d, w.D), w.w_std, st)
+    hidden = drawer.normal((1, w.B, w.N_max, w.D), w.act_std, st)
+    prompt_k = drawer.normal((1, w.B, w.H, w.S, w.d), w.act_std, st)
+    prompt_v = drawer.normal((1, w.B, w.H, w.S, w.d), w.act_std, st)
+    q, k, v = (drawer.normal((w.B, w.H, w.d), w.act_std, st) for _ in range(3))
+    out = torch.empty((w.B, w.H, w.d), dtype=torch.float32, device=DEV)
+    slot_map = torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=DEV)
+    cfg = make_config(layers=1, batch=w.B, heads=w.H, head_dim=w.d, hidden=w.D, cache_slots=w.K, rebuild_budget=w.R,
+                      max_positions=w.N_max, ctrl_hidden=w.dprime, dtype=w.dtype, pos_scale=w.pos_scale,
+                      score_mode=2 if w.h2o else 1 if w.rescore else 0, rope_base=w.rope_base)
+    a = Adore(cfg, wts, DEV)
+    a.set_input_order(INPUTS_ORDERED)
+    a.init_cache(prompt_k, prompt_v, hidden, hidden[0][:, :w.S].contiguous(), None, w.S)
+    xs = [hidden[0][:, w.S + t].contiguous() for t in range(total)]
+    torch.cuda.synchronize()
+
+    def step(t):
+        a.decode_step(q, k, v, hidden[0], xs[t], None, out, slot_map)
+
+    for t in range(warmup):
+        step(t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    a.set_timing(True)
+    for t in range(warmup + steps, total):
+        step(t)
+    timing = a.read_timing()
+    a.set_timing(False)
+    assert bool(torch.isfinite(out).all())
+    a.close()
+    return elapsed, {kk: (1e3 * ms / cnt if cnt else 0.0) for kk, (ms, cnt) in timing.items()}
+
+
+def other_workload_entry(name, steps=150, warmup=30, prof_steps=30):
+    """Compact record of another single-layer workload for the default line: step time, the attention launch against
+    the HBM peak and the GEMM against the MFMA peak (or, where M is too small for that, against what streaming W costs)."""
+    from gen import workload
+    w = workload(name)
+    elapsed, us = run_gpu_device_inputs(w, steps, warmup, prof_steps)
+    work = algorithmic_work(w)
+    att = us["attend"] + us["attend_combine"]
+    gemm = us["rebuild_gemm"]
+    entry = {"workload": name, "batch": w.B, "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S,
+             "ms_per_step": round(1e3 * elapsed / steps, 4), "tokens_per_s_per_layer": round(w.B * steps / elapsed, 1),
+             "attend_us": round(att, 2), "attend_algorithmic_bytes": work["attend_bytes"],
+             "attend_GBs": round(work["attend_bytes"] / (att * 1e-6) / 1e9, 1),
+             "attend_frac_of_hbm_peak": round(work["attend_bytes"] / (att * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+             "rebuild_gemm_us": round(gemm, 2), "rebuild_gemm_TFLOPs": round(work["gemm_flops"] / (gemm * 1e-6) / 1e12, 1),
+             "rebuild_gemm_frac_of_mfma_peak": round(work["gemm_flops"] / (gemm * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4),
+             "inputs": "drawn on the device (seeded)"}
+    if w.B * w.R < 400:     # below the ridge the GEMM streams W: priced against HBM as well
+        wbytes = 2.0 * w.H * w.d * w.D * 2
+        entry["rebuild_gemm_weight_stream_frac_of_hbm_peak"] = round(wbytes / (gemm * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+    return entry
+
+
 def run_stack(w, steps, warmup, prof_steps):
     """Layer-stack workload: every step runs attend x L, one schedule, rebuild x L through the fine-grained
     calls, layers launched one after the other.  Next to it the full-attention comparator of Eq. 1: the
@@ -405,29 +479,61 @@ def topk_line(w, args):
     return line
 
 
-def run_cpu_baseline(w, seqs=16, steps=40):
-    """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps."""
-    from threadpoolctl import threadpool_info
-    from gen import SyntheticInputs
+def run_cpu_baseline(w, seqs=16, steps=40, single_thread_steps=8):
+    """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps: once with the
+    threads numpy's BLAS takes by itself, once (fewer steps) limited to one thread; per-stage seconds from timers
+    wrapped around the oracle's functions (attention rows, controller, the two selections, re-projection + placement)."""
+    from collections import defaultdict
+    from threadpoolctl import threadpool_info, threadpool_limits
+    import oracle.adore_oracle as O
     from tests.helpers import make_oracle
     seqs = min(seqs, w.B)
-    ws = w.scaled(B=seqs, T=steps + 1)
+    ws = w.scaled(B=seqs, T=steps + single_thread_steps + 1)
     orc, inp, _ = make_oracle(ws)
     hs = inp.hidden_store()
     pk, pv = inp.prompt_kv()
     rng = np.random.default_rng(ws.seed)
     prompt_scores = rng.random((ws.B, ws.S), dtype=np.float32)     # skip nothing: init still runs the GRU
     orc.init_cache(pk, pv, hs, hs[0][:, :ws.S], ws.S, score_override=prompt_scores)
-    qkvs = [inp.step_qkv(ws.S + t) for t in range(steps)]
-    t0 = time.perf_counter()
-    for t in range(steps):
-        orc.decode_step(*qkvs[t], hs, hs[0][:, ws.S + t])
-    dt = time.perf_counter() - t0
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    qkvs = [inp.step_qkv(ws.S + t) for t in range(steps + single_thread_steps)]
+    stage = defaultdict(float)
+
+    def timed(name, fn):
+        def wrapper(*a, **k):
+            t = time.perf_counter()
+            r = fn(*a, **k)
+            stage[name] += time.perf_counter() - t
+            return r
+        return wrapper
+
+    saved = (O.attention_row, O.release_lowest, O.rebuild_choice)
+    O.attention_row = timed("attention", O.attention_row)
+    O.release_lowest = timed("release_select", O.release_lowest)
+    O.rebuild_choice = timed("rebuild_select", O.rebuild_choice)
+    orc._controller = timed("controller", orc._controller)
+    orc._place_rebuilt = timed("rebuild_projection_and_placement", orc._place_rebuilt)
+    try:
+        t0 = time.perf_counter()
+        for t in range(steps):
+            orc.decode_step(*qkvs[t], hs, hs[0][:, ws.S + t])
+        dt = time.perf_counter() - t0
+        per_stage = {k: round(v, 3) for k, v in stage.items()}
+        per_stage["insert_and_bookkeeping"] = round(dt - sum(stage.values()), 3)
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for t in range(steps, steps + single_thread_steps):
+                orc.decode_step(*qkvs[t], hs, hs[0][:, ws.S + t])
+            dt1 = time.perf_counter() - t0
+    finally:
+        O.attention_row, O.release_lowest, O.rebuild_choice = saved
     return dict(value=seqs * steps / dt, unit="tokens/s/layer", cores=int(threads), kind="oracle",
                 sample=f"{seqs} of {w.B} sequences, {steps} steady-state steps after a {ws.S}-token prompt "
                        f"(numpy fp64; BLAS threads for the re-projection, Python loops elsewhere)",
-                seconds=round(dt, 2))
+                seconds=round(dt, 2), stage_seconds=per_stage,
+                single_thread=dict(value=round(seqs * single_thread_steps / dt1, 2), unit="tokens/s/layer", cores=1,
+                                   sample=f"the next {single_thread_steps} steps with every thread pool limited to one thread",
+                                   seconds=round(dt1, 2)))
 
 
 def main():
@@ -440,6 +546,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rescore", action="store_true",
                     help="controller scores every token again at every step (relative position)")
+    ap.add_argument("--h2o", action="store_true",
+                    help="H2O(Rebuilt) score mode: per-head cumulative attention instead of the controller")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="leave the compact high_batch / long_context records out of the default line")
     ap.add_argument("--rope-base", type=float, default=0.0,
                     help="rotary position embedding with this base on the keys (and forward queries) the library makes")
     ap.add_argument("--topk-attention", action="store_true",
@@ -467,6 +577,8 @@ def main():
         w = w.scaled(rescore=True)
     if args.rope_base:
         w = w.scaled(rope_base=args.rope_base)
+    if args.h2o:
+        w = w.scaled(h2o=True)
     if args.forward:
         print(json.dumps(forward_line(w.scaled(L=args.forward), args)), flush=True)
         return
@@ -522,8 +634,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.H, "head_dim": w.d, "hidden": w.D,
                    "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S, "layers": w.L,
-                   "score_mode": "rescore" if w.rescore else "static", "input_order": args.input_order,
-                   "rope_base": w.rope_base},
+                   "score_mode": "h2o" if w.h2o else "rescore" if w.rescore else "static",
+                   "input_order": args.input_order, "library_default_input_order": "stream", "rope_base": w.rope_base},
         "roofline": dominant,
         "roofline_attend": roof_att, "roofline_rebuild_gemm": roof_gemm,
         "kernel_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
@@ -534,7 +646,20 @@ def main():
             "ms_per_step": round(1e3 * other, 4), "value": round(w.B / other, 1)}
     if stack:
         line["stack"] = stack
-    if not args.no_cpu_baseline:
+    default_line = (args.workload == "llama7b_layer" and w.L == 1 and not (args.rescore or args.h2o or args.rope_base))
+    if default_line and not args.no_other_workloads:
+        # the other single-layer workloads, compactly: high_batch is the one whose cache (546 MB per step) does not
+        # fit the 256 MB last-level cache, so its attention figure is the HBM-bound one
+        t0 = time.time()
+        line["other_workloads"] = [other_workload_entry("high_batch"), other_workload_entry("long_context")]
+        hb = line["other_workloads"][0]
+        traffic_hb = recorded_traffic(workload("high_batch"))
+        line["roofline_attend_high_batch"] = dict(
+            kernel="attend", bound="hbm", achieved=hb["attend_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
+            frac=hb["attend_frac_of_hbm_peak"], traffic=traffic_hb.get("attend"), us_per_launch=hb["attend_us"],
+            algorithmic_bytes=hb["attend_algorithmic_bytes"])
+        log(f"other workloads took {time.time() - t0:.1f}s")
+    if not args.no_cpu_baseline and not w.h2o:
         t0 = time.time()
         line["cpu_baseline"] = run_cpu_baseline(w)
         log(f"cpu baseline took {time.time() - t0:.1f}s in total")

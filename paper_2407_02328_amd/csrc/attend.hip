@@ -12,6 +12,8 @@
 // whole L2 and costs far more than the extra launch).  When there are enough
 // rows, one workgroup of up to 16 waves takes a whole row and no merge kernel
 // runs.  Softmax runs online in fp32, base 2.
+#include <cstdlib>
+
 #include "select_device.h"
 
 namespace adore {
@@ -55,8 +57,10 @@ struct AttendArgs {
 // Dynamic LDS of a workgroup in this role: [scores of the sequence, n + 1 floats][head 0's row, K ints][choice].
 // The scores are copied once and the rows are read at the same time, so that afterwards the ranking keys come
 // from LDS: under the attention's traffic every dependent trip to memory costs five to seven microseconds.
+// hist: 256 words of LDS per wave for the release's radix select (the attention's own merge buffer, which these
+// workgroups do not use otherwise).
 template <int WAVES, int KPL>
-__device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn) {
+__device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn, uint32_t *hist) {
   const SchedArgs &s = a.s;
   const int per_seq = s.rel_wgs + 1;
   const int b = e / per_seq, part = e - b * per_seq;
@@ -75,14 +79,14 @@ __device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn
   if (part < s.rel_wgs) {
     if (releases)
       release_row<KPL>(row, s_ins, s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
-                       s.rel_out, s.K, s.n, s.x, s.R1, nullptr, raw);
+                       s.rel_out, s.K, s.n, s.x, s.R1, nullptr, hist + wave * 256, raw);
     return;
   }
   int32_t *row_copy = reinterpret_cast<int32_t *>(dyn + (s.n + 2) / 2);   // head 0's positions after the release
   uint64_t *choice = dyn + (s.n + 2) / 2 + (s.K + 1) / 2;
   if (wave == 0) {
     release_row<KPL>(row, s_ins, s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
-                     s.rel_out, s.K, s.n, s.x, s.R1, row_copy, raw);
+                     s.rel_out, s.K, s.n, s.x, s.R1, row_copy, hist, raw);
   } else {
     choice_fill_keys(s_score, s.n, choice, tid - 64, 64 * (WAVES - 1));   // the other waves meanwhile
   }
@@ -97,15 +101,21 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
   constexpr int RPW = 64 / LPR;         // rows per wave and load
   constexpr int G = WAVES * RPW;        // lane groups (rows in flight) per workgroup
   static_assert(LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must be a power-of-two lane group");
+  // merge of the lane groups at the end of a row; a workgroup that carries selections instead keeps its waves'
+  // radix histograms there
+  __shared__ float s_m[G], s_l[G];
+  __shared__ float s_acc[G][DH];
+  static_assert(G * DH >= WAVES * 256, "room for one 256-bin histogram per wave");
 
   if (int(blockIdx.x) < a.n_sel) {   // uniform over the workgroup
     extern __shared__ uint64_t dyn_smem[];
     const int e = blockIdx.x;
+    uint32_t *hist = reinterpret_cast<uint32_t *>(&s_acc[0][0]);
     switch (a.s.kpl) {
-      case 2: selections_role<WAVES, 2>(a, e, dyn_smem); break;
-      case 4: selections_role<WAVES, 4>(a, e, dyn_smem); break;
-      case 8: selections_role<WAVES, 8>(a, e, dyn_smem); break;
-      default: selections_role<WAVES, 16>(a, e, dyn_smem); break;
+      case 2: selections_role<WAVES, 2>(a, e, dyn_smem, hist); break;
+      case 4: selections_role<WAVES, 4>(a, e, dyn_smem, hist); break;
+      case 8: selections_role<WAVES, 8>(a, e, dyn_smem, hist); break;
+      default: selections_role<WAVES, 16>(a, e, dyn_smem, hist); break;
     }
     return;
   }
@@ -206,8 +216,6 @@ __global__ __launch_bounds__(64 * WAVES, 4) void attend_kernel(const AttendArgs 
 #undef ATTEND_FETCH
 
   // ---- merge the G lane groups of this workgroup ----
-  __shared__ float s_m[G], s_l[G];
-  __shared__ float s_acc[G][DH];
   if (lig == 0) s_m[grp] = m;
   __syncthreads();
   float M = -INFINITY;
@@ -319,6 +327,10 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
     // 4 waves per workgroup: half of a compute unit's wave slots and registers then stay free, so the extra
     // workgroups start at once next to the attention's instead of waiting for a round of them to end
     waves = 4;
+    if (const char *e = getenv("ADORE_RIDE_WAVES")) {   // tuning runs
+      const int v = atoi(e);
+      if (v == 4 || v == 8) waves = v;
+    }
     SchedArgs &s = a.s;
     s.kpl = c.cache_slots <= 128 ? 2 : c.cache_slots <= 256 ? 4 : c.cache_slots <= 512 ? 8 : 16;
     s.rel_wgs = (c.heads - 1 + waves - 1) / waves;

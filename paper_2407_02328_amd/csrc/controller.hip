@@ -242,6 +242,13 @@ __device__ inline float gi_sum(const CellArgs &a, size_t tok, int j) {
   const float *p = a.gi + tok * 3 * a.dp + j;
   float s = 0.f;
   int k = 0;
+  for (; k + 16 <= a.ksplit; k += 16) {   // (sixteen at a time where there are that many: one trip to memory, same order)
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = p[size_t(k + u) * stride];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s += v[u];
+  }
   for (; k + 8 <= a.ksplit; k += 8) {
     float v[8];
 #pragma unroll
@@ -317,64 +324,85 @@ __device__ inline void rows_times_vec(const T *W, int row0, float x0, float x1, 
   }
 }
 
+// The same product in two halves: the N row loads go out where the caller wants them (next to everything else a
+// step reads), the arithmetic follows once x is known.
+template <typename T, int N>
+__device__ inline void rows_request(const T *W, int row0, int lane, decltype(load_raw2(W)) (&raw)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) raw[i] = load_raw2(W + size_t(row0 + i) * 128 + 2 * lane);
+}
+template <typename R, int N>
+__device__ inline void rows_finish(const R (&raw)[N], int row0, float x0, float x1, const float *bias, float *out, int lane) {
+  float v[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dot2(raw[i], x0, x1);
+  const float s = reduce_rows<N>(v, lane);
+  constexpr int LPRW = 64 / N;   // lanes holding the same row
+  if ((lane & (LPRW - 1)) == 0) {
+    const int r = row0 + lane / LPRW;
+    out[r] = s + bias[r];
+  }
+}
+
+// One token per sequence (a decode step).  One workgroup of 12 waves per sequence.  A step's cost is not its
+// arithmetic (100 k multiply-adds) but its trips to memory, each of which takes microseconds next to the
+// attention's traffic: so everything the step reads is requested at the top, before anything is waited for: the
+// state, the D-slices of the input pre-activations, W_hh (32 rows per wave), W_1 (32 rows each for 4 of the
+// waves), the small vectors.  After that the kernel only computes, with three barriers.
 template <typename T>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void ctrl_cell128_kernel(const CellArgs a) {
-  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
+__global__ __launch_bounds__(768) void ctrl_cell128_kernel(const CellArgs a) {
+  __builtin_amdgcn_s_setprio(3);   // short, latency-bound work next to the attention: its waves go first
   constexpr int DP = 128;
-  __shared__ float h[DP];        // z_{i-1}, then z_i
-  __shared__ float t_in[DP];     // p_i + z_i
-  __shared__ float gh[3 * DP];   // W_hh h + b_hh
-  __shared__ float u1[DP];       // W_1 (p + z) + b_1
+  __shared__ float gi_s[3 * DP];   // W_ih x + b_ih
+  __shared__ float gh[3 * DP];     // W_hh h + b_hh
+  __shared__ float t_in[DP];       // p_i + z_i
+  __shared__ float u1[DP];         // W_1 (p + z) + b_1
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T *W_hh = static_cast<const T *>(a.W_hh);
-  if (tid < DP) h[tid] = a.z[size_t(b) * DP + tid];
-  __syncthreads();
-
-  for (int i = 0; i < a.nsteps; ++i) {
-    // weights are streamed from L2 for every token rather than parked in registers: the kernel must
-    // stay small enough to run beside the GEMM
-    asm volatile("" ::: "memory");
-    const size_t tok = size_t(b) * a.nsteps + i;
-    float g_r = 0.f, g_u = 0.f, g_n = 0.f;
-    if (tid < DP) {   // the loads of the input pre-activations go out before the row products
-      g_r = gi_sum(a, tok, tid) + a.b_ih[tid];
-      g_u = gi_sum(a, tok, DP + tid) + a.b_ih[DP + tid];
-      g_n = gi_sum(a, tok, 2 * DP + tid) + a.b_ih[2 * DP + tid];
-    }
-    {   // recurrent pre-activations: 96 rows per wave
-      const float x0 = h[2 * lane], x1 = h[2 * lane + 1];
-#pragma unroll 1   // one batch of 32 row loads in flight at a time: keeps the register count low
-      for (int part = 0; part < 3; ++part)
-        rows_times_vec<T, 32>(W_hh, wave * 96 + part * 32, x0, x1, a.b_hh, gh, lane);
-    }
-    __syncthreads();
-    if (tid < DP) {
-      const float r = sigmoidf_(g_r + gh[tid]);
-      const float u = sigmoidf_(g_u + gh[DP + tid]);
-      const float cand = tanhf(g_n + r * gh[2 * DP + tid]);
-      const float hnew = (1.0f - u) * cand + u * h[tid];
-      const float delta = a.cvec ? 0.f : float(a.pos0 + i) * a.pos_scale;   // rescore mode: distance to itself
-      h[tid] = hnew;
-      t_in[tid] = fmaf(a.pos_w[tid], delta, a.pos_b[tid]) + hnew;
-    }
-    __syncthreads();
-    {   // interaction layer: 32 rows per wave
-      const float x0 = t_in[2 * lane], x1 = t_in[2 * lane + 1];
-      rows_times_vec<float, 32>(a.W1, wave * 32, x0, x1, a.b1, u1, lane);
-    }
-    __syncthreads();
-    if (a.cvec && tid < DP) a.cvec[(size_t(b) * a.N_max + a.pos0 + i) * DP + tid] = u1[tid];
-    if (wave == 0) {   // output layer and sigmoid
-      float s = fmaf(a.out_w[lane], tanhf(u1[lane]), a.out_w[lane + 64] * tanhf(u1[lane + 64]));
-      s = wave_sum(s);
-      if (lane == 0) {
-        float sig = sigmoidf_(s + a.out_b[0]);
-        if (a.override_) sig = a.override_[size_t(b) * a.override_stride + i];
-        a.score[size_t(b) * a.N_max + a.pos0 + i] = sig;
-      }
-    }
+  const size_t tok = size_t(b);    // nsteps == 1
+  // ---- requests ----
+  const float2 hx = *reinterpret_cast<const float2 *>(a.z + size_t(b) * DP + 2 * lane);   // z_{i-1}, in every wave
+  decltype(load_raw2(W_hh)) rhh[32];
+  rows_request<T, 32>(W_hh, wave * 32, lane, rhh);
+  float2 rw1[32];                  // (batches of 32 rows, as where a prompt chunk is scored: the same sums in the same order)
+  if (wave < 4) rows_request<float, 32>(a.W1, wave * 32, lane, rw1);
+  float g = 0.f, hold = 0.f, pw = 0.f, pb = 0.f, ow0 = 0.f, ow1 = 0.f, ob = 0.f, ov = 0.f;
+  if (tid < 3 * DP) g = gi_sum(a, tok, tid) + a.b_ih[tid];
+  if (tid < DP) {
+    hold = a.z[size_t(b) * DP + tid];
+    pw = a.pos_w[tid];
+    pb = a.pos_b[tid];
   }
-  if (tid < DP) a.z[size_t(b) * DP + tid] = h[tid];
+  if (wave == 0) {
+    ow0 = a.out_w[lane];
+    ow1 = a.out_w[lane + 64];
+    ob = a.out_b[0];
+    if (a.override_) ov = a.override_[size_t(b) * a.override_stride];
+  }
+  __builtin_amdgcn_sched_barrier(0);   // all of the above is under way before the first use
+  // ---- recurrent pre-activations, the gates, the new state ----
+  rows_finish<decltype(load_raw2(W_hh)), 32>(rhh, wave * 32, hx.x, hx.y, a.b_hh, gh, lane);
+  if (tid < 3 * DP) gi_s[tid] = g;
+  __syncthreads();
+  if (tid < DP) {
+    const float r = sigmoidf_(gi_s[tid] + gh[tid]);
+    const float u = sigmoidf_(gi_s[DP + tid] + gh[DP + tid]);
+    const float cand = tanhf(gi_s[2 * DP + tid] + r * gh[2 * DP + tid]);
+    const float hnew = (1.0f - u) * cand + u * hold;
+    const float delta = a.cvec ? 0.f : float(a.pos0) * a.pos_scale;   // rescore mode: distance to itself
+    a.z[size_t(b) * DP + tid] = hnew;
+    t_in[tid] = fmaf(pw, delta, pb) + hnew;
+  }
+  __syncthreads();
+  // ---- interaction layer, output layer, sigmoid ----
+  if (wave < 4) rows_finish<float2, 32>(rw1, wave * 32, t_in[2 * lane], t_in[2 * lane + 1], a.b1, u1, lane);
+  __syncthreads();
+  if (a.cvec && tid < DP) a.cvec[(size_t(b) * a.N_max + a.pos0) * DP + tid] = u1[tid];
+  if (wave == 0) {
+    float s = fmaf(ow0, tanhf(u1[lane]), ow1 * tanhf(u1[lane + 64]));
+    s = wave_sum(s);
+    if (lane == 0) a.score[size_t(b) * a.N_max + a.pos0] = a.override_ ? ov : sigmoidf_(s + ob);
+  }
 }
 
 // ---- a prompt chunk, d' = 128: the recurrence alone, then the layers above it for all tokens at once ----
@@ -722,9 +750,9 @@ hipError_t launch_ctrl_cell(adore_ctx *ctx, hipStream_t st, int nsteps, int pos0
   ScopedTimer t(ctx, ADORE_KERNEL_CTRL_CELL, st);
   if (c.ctrl_hidden == 128) {
     if (c.dtype == ADORE_BF16) {
-      ADORE_LAUNCH(t, (ctrl_cell128_kernel<bf16_t>), dim3(c.batch), dim3(256), 0, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell128_kernel<bf16_t>), dim3(c.batch), dim3(768), 0, st, a);
     } else {
-      ADORE_LAUNCH(t, (ctrl_cell128_kernel<float>), dim3(c.batch), dim3(256), 0, st, a);
+      ADORE_LAUNCH(t, (ctrl_cell128_kernel<float>), dim3(c.batch), dim3(768), 0, st, a);
     }
   } else {
     const size_t smem = size_t(6 * c.ctrl_hidden + 8) * sizeof(float);

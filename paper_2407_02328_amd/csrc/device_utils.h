@@ -97,4 +97,38 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
+// Scan of a 256-bin histogram from the top bin down: the bin in which the rank `need` (1 = the largest) falls, the
+// rank left inside it, and how many entries it holds.  Lane l owns bins 255 - 4l .. 252 - 4l.  Wave-uniform results.
+__device__ inline void pick_bin(const uint32_t *hist, int lane, int need, int &bin, int &rest, int &inbin) {
+  const uint4 hq = *reinterpret_cast<const uint4 *>(hist + 252 - 4 * lane);
+  const int c0 = int(hq.w), c1 = int(hq.z), c2 = int(hq.y), c3 = int(hq.x);
+  const int own = c0 + c1 + c2 + c3;
+  int incl = own;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int other = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += other;
+  }
+  const int excl = incl - own;
+  const bool mine = excl < need && need <= incl;   // exactly one lane: need <= the number of candidates
+  int b = 252 - 4 * lane, r = need - excl - c0 - c1 - c2, n = c3;
+  if (need <= excl + c0) {
+    b = 255 - 4 * lane; r = need - excl; n = c0;
+  } else if (need <= excl + c0 + c1) {
+    b = 254 - 4 * lane; r = need - excl - c0; n = c1;
+  } else if (need <= excl + c0 + c1 + c2) {
+    b = 253 - 4 * lane; r = need - excl - c0 - c1; n = c2;
+  }
+  const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(mine));
+  bin = __shfl(b, src, 64);
+  rest = __shfl(r, src, 64);
+  inbin = __shfl(n, src, 64);
+}
+
+// One wave's LDS operations run in order; this keeps the compiler from moving them across the point.
+__device__ inline void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 }  // namespace adore

@@ -34,6 +34,7 @@ __global__ __launch_bounds__(256) void h2o_release_kernel(const int32_t *__restr
                                                           int32_t *__restrict__ free_list, int32_t *__restrict__ released_pos,
                                                           int32_t *__restrict__ map_out, int32_t *__restrict__ rel_out,
                                                           int rows, int K, int N_max, int n, int m, int R1) {
+  __shared__ uint32_t s_hist[4][256];           // one radix histogram per wave
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;                      // whole wave leaves together
   const int lane = threadIdx.x & 63;
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void h2o_release_kernel(const int32_t *__restr
   }
   // the lane that wrote a score is the lane that reads it back below (same slot, same lane)
   release_row<KPL>(row, s_ins, slot_src, slot_dst, sc, free_list, released_pos, map_out, rel_out, K, n, -1, R1, nullptr,
-                   nullptr, m);
+                   s_hist[threadIdx.x >> 6], nullptr, m);
 }
 
 struct H2OChoiceArgs {

@@ -30,10 +30,12 @@ __global__ __launch_bounds__(256) void release_kernel(const int32_t *__restrict_
                                                       int32_t *__restrict__ rel_out, int rows, int K,
                                                       int H, int N_max, int n, int x, int R1) {
   __builtin_amdgcn_s_setprio(3);   // short, latency-bound work that shares compute units with the GEMM: its waves go first
+  __shared__ uint32_t s_hist[4][256];           // one radix histogram per wave
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;                      // whole wave leaves together
   release_row<KPL>(row, insert_slot[size_t(row) * ins_stride + ins_off], slot_src, slot_dst,
-                   score + size_t(row / H) * N_max, free_list, released_pos, map_out, rel_out, K, n, x, R1, nullptr);
+                   score + size_t(row / H) * N_max, free_list, released_pos, map_out, rel_out, K, n, x, R1, nullptr,
+                   s_hist[threadIdx.x >> 6]);
 }
 
 // Release step of a row that gives nothing up (x = 0: the cache still has room for every token, which
