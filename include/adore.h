@@ -304,8 +304,8 @@ const char *adore_kernel_name(int32_t kernel);
  *   weights go to the lower j);  out_i = sum over the kept j of softmax_j(w[i][j] / sqrt(head_dim)) v_j.
  * q, k, v, out: DEVICE [rows][seq][head_dim] bf16, dense; out may not alias the inputs.  workspace: DEVICE,
  * 256-byte aligned, at least adore_topk_attention_workspace_bytes(rows, seq, head_dim) bytes (a transposed copy of
- * v; for seq > 2048 also the weights of every query, rows * seq * (seq + 36) * 4 bytes or so, which shorter
- * sequences keep on chip), caller-owned, free to reuse after the work enqueued here has run.  The call only enqueues work on
+ * v; for seq > 2048 also the weights of the query blocks in flight, 512 * 16 * (seq + 36) * 4 bytes or so, which
+ * shorter sequences keep on chip), caller-owned, free to reuse after the work enqueued here has run.  The call only enqueues work on
  * hip_stream (a hipStream_t, NULL = the default stream).  The selection is exact on the weights as the kernel
  * computes them (bf16 products accumulated in fp32); inputs must be finite.
  * Errors: E_INVALID (null, sizes <= 0, top_k < 1), E_UNSUPPORTED (head_dim not in {64,128}, seq > 32768,

@@ -27,6 +27,7 @@ namespace {
 // The chosen positions are entered into the slot maps by the kernel that writes their rows.
 struct SchedArgs {
   int kpl, rel_wgs;                 // keys per lane of a row (K / 64 rounded up to 2, 4, 8, 16); 0 workgroups = off
+  int hpw;                          // heads a wave releases one after the other (1, or 4 for short rows of many sequences)
   const int32_t *slot_src;          // [B*H][K]
   int32_t *slot_dst;                // [B*H][K]
   const float *score;               // [B][N_max]
@@ -61,27 +62,46 @@ struct AttendArgs {
 // workgroups do not use otherwise).
 template <int WAVES, int KPL>
 __device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn, uint32_t *hist) {
+  // Rows short enough to fit four of them into a wave's registers can be released four to a wave: with hundreds of
+  // sequences the role's workgroups would otherwise take half of the chip's wave slots from the attention for the
+  // time their trips to memory take.
+  constexpr int HPW = KPL <= 4 ? 4 : 1;
   const SchedArgs &s = a.s;
   const int per_seq = s.rel_wgs + 1;
   const int b = e / per_seq, part = e - b * per_seq;
   const int tid = threadIdx.x, wave = tid >> 6;
   __builtin_amdgcn_s_setprio(3);   // few waves with a long chain of dependent steps: they go first on their SIMD
   float *s_score = reinterpret_cast<float *>(dyn);
-  const int h = part < s.rel_wgs ? 1 + part * WAVES + wave : 0;
-  const bool releases = part < s.rel_wgs ? h < s.H : wave == 0;   // whole waves
-  const int row = b * s.H + (h < s.H ? h : 0);
-  const int s_ins = a.insert_slot[size_t(row) * a.ins_stride + a.ins_off];
-  int raw[KPL];
-  if (releases) release_fetch<KPL>(row, s.slot_src, s.K, raw);
   const float *sc = s.score + size_t(b) * s.N_max;
-  for (int i = tid; i <= s.n; i += 64 * WAVES) s_score[i] = sc[i];
-  __syncthreads();
-  if (part < s.rel_wgs) {
-    if (releases)
-      release_row<KPL>(row, s_ins, s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
-                       s.rel_out, s.K, s.n, s.x, s.R1, nullptr, hist + wave * 256, raw);
+  if (part < s.rel_wgs) {          // heads 1 .. H-1
+    const int hpw = HPW > 1 ? s.hpw : 1;
+    const int h0 = 1 + (part * WAVES + wave) * hpw;
+    int raw[HPW][KPL], s_ins[HPW];
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      if (i < hpw && h0 + i < s.H) {   // whole waves
+        const int row = b * s.H + h0 + i;
+        s_ins[i] = a.insert_slot[size_t(row) * a.ins_stride + a.ins_off];
+        release_fetch<KPL>(row, s.slot_src, s.K, raw[i]);
+      }
+    }
+    for (int i = tid; i <= s.n; i += 64 * WAVES) s_score[i] = sc[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) {
+      if (i < hpw && h0 + i < s.H)
+        release_row<KPL>(b * s.H + h0 + i, s_ins[i], s.slot_src, s.slot_dst, s_score, s.free_list, s.released_pos, s.map_out,
+                         s.rel_out, s.K, s.n, s.x, s.R1, nullptr, hist + wave * 256, raw[i]);
+    }
     return;
   }
+  // head 0, then the choice of the tokens to rebuild from the positions it keeps
+  const int row = b * s.H;
+  const int s_ins = a.insert_slot[size_t(row) * a.ins_stride + a.ins_off];
+  int raw[KPL];
+  if (wave == 0) release_fetch<KPL>(row, s.slot_src, s.K, raw);
+  for (int i = tid; i <= s.n; i += 64 * WAVES) s_score[i] = sc[i];
+  __syncthreads();
   int32_t *row_copy = reinterpret_cast<int32_t *>(dyn + (s.n + 2) / 2);   // head 0's positions after the release
   uint64_t *choice = dyn + (s.n + 2) / 2 + (s.K + 1) / 2;
   if (wave == 0) {
@@ -333,7 +353,13 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
     }
     SchedArgs &s = a.s;
     s.kpl = c.cache_slots <= 128 ? 2 : c.cache_slots <= 256 ? 4 : c.cache_slots <= 512 ? 8 : 16;
-    s.rel_wgs = (c.heads - 1 + waves - 1) / waves;
+    // four heads to a wave where a row is short (four of them fit a wave's registers) and the role would otherwise
+    // take more than a quarter of the chip's wave slots
+    s.hpw = s.kpl <= 4 && c.batch * c.heads > 2048 ? 4 : 1;
+    if (const char *e = getenv("ADORE_RIDE_HPW")) {   // tests: the four-heads path on a small shape
+      if (atoi(e) == 4 && s.kpl <= 4) s.hpw = 4;
+    }
+    s.rel_wgs = (c.heads - 1 + waves * s.hpw - 1) / (waves * s.hpw);
     s.slot_src = ctx->slot_pos[ctx->cur]; s.slot_dst = ctx->slot_pos[sel->dst];
     s.score = ctx->score; s.free_list = ctx->free_list[sel->dst];
     s.released_pos = ctx->released_pos; s.map_out = sel->map_out; s.rel_out = sel->rel_out;

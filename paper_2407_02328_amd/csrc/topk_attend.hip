@@ -47,6 +47,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWaves = 8;
 constexpr int kMaxSeq = 2048;        // longest sequence whose logit rows (16 queries) fit LDS
 constexpr int kMaxLongSeq = 32768;   // longest sequence taken at all (rows in the workspace)
+constexpr int kLongGrid = 512;       // workgroups of a launch over such sequences (two per compute unit; a multiple of 8)
 
 // V [rows][S][d] -> V^T [rows][d][Sp], keys S .. Sp-1 as zeros.  One workgroup per 32 keys of one row.
 __global__ __launch_bounds__(256) void topk_vt_kernel(const bf16_t *V, bf16_t *Vt, int S, int Sp, int d) {
@@ -73,7 +74,8 @@ struct TopkArgs {
   bf16_t *O;             // [rows][S][d]
   int S, Sp, topk, lstr; // lstr: floats per logit row
   int rows;
-  float *rowbuf;         // long sequences: [workgroups][16][lstr] logit rows in the workspace
+  int tiles;             // query blocks of the whole launch
+  float *rowbuf;         // long sequences: [workgroups in flight][16][lstr] logit rows in the workspace
   int region0;           // bytes of the first LDS region (logit rows, later the merge buffer)
   float scale_log2;      // log2(e) / sqrt(d)
 };
@@ -87,8 +89,10 @@ __device__ inline uint32_t weight_key(float x) {
 }
 
 // NQB: blocks of 16 queries per workgroup; NKMAX: keys of a row a lane can hold (64 * NKMAX >= the keys of a row)
+// One tile of the launch: the 16 * NQB queries of block L (see the mapping below).  slot: which piece of the row
+// buffer in the workspace this workgroup owns (long sequences only).
 template <int DH, int NQB, int NKMAX>
-__global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void topk_attend_kernel(const TopkArgs a) {
+__device__ inline void topk_tile(const TopkArgs &a, const int L, const int slot) {
   constexpr int KT = DH / 32;          // matrix instructions along d per 16x16 logit block
   constexpr int MB = DH / 16;          // 16-wide blocks of the head dimension
   constexpr int FIN = MB < kWaves ? MB : kWaves;   // waves that finish and store
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
   // the weights of the block's queries: [NQ16][lstr] fp32 in LDS (later the merge buffer), or, for sequences whose
   // rows LDS cannot hold, in the workgroup's own piece of the workspace (written and read by this workgroup only)
   constexpr bool LONG = NKMAX == 0;
-  float *s_log = LONG ? a.rowbuf + size_t(blockIdx.x) * NQ16 * a.lstr : reinterpret_cast<float *>(smem);
+  float *s_log = LONG ? a.rowbuf + size_t(slot) * NQ16 * a.lstr : reinterpret_cast<float *>(smem);
   unsigned char *s_q = smem + a.region0;                                 // [NQ16][QSTR]
   uint32_t *s_T = reinterpret_cast<uint32_t *>(s_q + NQ16 * QSTR);       // [NQ16] image of the K-th largest weight
   int32_t *s_tie = reinterpret_cast<int32_t *>(s_T + NQ16);              // [NQ16] equal weights kept up to here
@@ -114,7 +118,6 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
   // come from memory once instead of once per XCD; within a row the blocks with the most keys start first.
   const int nq = (a.S + NQ16 - 1) / NQ16;
   const int full = a.rows / 8 * 8;             // rows that form whole groups of 8
-  const int L = blockIdx.x;
   int row_, qi;
   if (L < full * nq) {
     const int slot = L >> 3;
@@ -458,6 +461,22 @@ __global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void 
   }
 }
 
+// Sequences whose logit rows live in LDS: one workgroup per tile.  Longer ones (NKMAX == 0): a grid of as many
+// workgroups as the chip holds at once, each walking over tiles L, L + gridDim, ... with one piece of the row buffer
+// of its own, so that the buffer is sized by the workgroups in flight, not by the tiles (rows * seq * seq floats).
+// gridDim is a multiple of 8 there, so a workgroup's tiles stay on its XCD's rows.
+template <int DH, int NQB, int NKMAX>
+__global__ __launch_bounds__(64 * kWaves, NQB == 1 && NKMAX <= 16 ? 2 : 1) void topk_attend_kernel(const TopkArgs a) {
+  if constexpr (NKMAX != 0) {
+    topk_tile<DH, NQB, NKMAX>(a, blockIdx.x, 0);
+  } else {
+    for (int L = blockIdx.x; L < a.tiles; L += gridDim.x) {
+      topk_tile<DH, NQB, NKMAX>(a, L, blockIdx.x);
+      __syncthreads();   // the next tile reuses LDS and the workgroup's rows in the workspace
+    }
+  }
+}
+
 size_t padded_keys(int S) { return size_t(S + 31) / 32 * 32; }
 size_t vt_bytes(int rows, int S, int d) { return (size_t(rows) * d * padded_keys(S) * 2 + 255) / 256 * 256; }
 
@@ -474,7 +493,8 @@ hipError_t launch(const TopkArgs &base, int rows, hipStream_t st) {
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return e;
   a.rows = rows;
-  const dim3 grid(unsigned((a.S + NQ16 - 1) / NQ16) * unsigned(rows)), block(64 * kWaves);
+  a.tiles = ((a.S + NQ16 - 1) / NQ16) * rows;
+  const dim3 grid(unsigned(NKMAX == 0 ? min(a.tiles, kLongGrid) : a.tiles)), block(64 * kWaves);
   hipLaunchKernelGGL((topk_attend_kernel<DH, NQB, NKMAX>), grid, block, lds, st, a);
   return hipGetLastError();
 }
@@ -548,7 +568,10 @@ size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t h
   if (rows <= 0 || seq <= 0 || head_dim <= 0) return 0;
   const size_t vt = adore::vt_bytes(rows, seq, head_dim);
   // sequences whose logit rows LDS cannot hold: 16 rows of fp32 weights per workgroup of 16 queries
-  const size_t rowbuf = seq > adore::kMaxSeq ? size_t(rows) * ((seq + 15) / 16) * 16 * (adore::padded_keys(seq) + 4) * 4 : 0;
+  const size_t tiles = size_t(rows) * ((seq + 15) / 16);
+  const size_t rowbuf = seq > adore::kMaxSeq ? (tiles < size_t(adore::kLongGrid) ? tiles : size_t(adore::kLongGrid)) * 16 *
+                                                   (adore::padded_keys(seq) + 4) * 4
+                                             : 0;
   return vt + (rowbuf + 255) / 256 * 256;
 }
 

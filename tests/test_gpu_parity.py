@@ -534,6 +534,18 @@ def test_decode_step_call_matches_the_oracle(name, kw, steps):
     job.adore.close()
 
 
+@pytest.mark.parametrize("H,K", [(9, 130), (6, 256), (17, 40)])
+def test_decode_step_call_with_four_heads_to_a_wave(H, K, monkeypatch):
+    """Large batches of short rows let a wave of the riding selections release four heads one after the other (as the
+    full-size high-batch run does); here that path is forced on small shapes whose head counts leave waves with
+    four, some and no heads."""
+    monkeypatch.setenv("ADORE_RIDE_HPW", "4")
+    h = _harness()
+    w = Workload("ds_hpw", L=1, B=2, H=H, d=64, D=128, K=K, R=7, S=K + 30, T=20, dtype="bf16", dprime=32)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=5, whole=lambda t: True)
+    job.adore.close()
+
+
 def test_decode_step_call_on_long_sequences():
     """Beyond about 4500 positions a sequence's scores and ranking keys no longer fit the LDS of the riding selections,
     and adore_decode_step goes through the selection kernels on the side stream.  5000-token prompts, rows of 300

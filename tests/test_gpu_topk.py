@@ -182,18 +182,22 @@ def test_topk_attention_random_shapes_on_exactly_representable_weights(rows, S, 
     assert e.max() < TOL, f"rows={rows} S={S} d={d} K={top_k} levels={levels}: {e.max()}"
 
 
-@pytest.mark.timeout(600)
-def test_topk_attention_at_the_long_context_shape_one_row():
+@pytest.mark.timeout(900)
+def test_topk_attention_at_the_long_context_shape_sampled_rows():
     """B4 x H32 rows of 8192 tokens (the long-context workload's prompts), K = 96: the weights of a query block go
-    through the workspace (34 GB of it).  One row checked in full against the oracle."""
+    through the workspace, one piece per workgroup in flight (0.3 GB in all).  Two rows that sit on different XCDs
+    checked in full against the oracle."""
     torch, O, topk_attention = _mods()
     from gen import DeviceNormals
+    from paper_2407_02328_amd import load_library
     rows, S, d, top_k = 128, 8192, 128, 96
+    assert load_library().adore_topk_attention_workspace_bytes(rows, S, d) < (1 << 30)
     drawer = DeviceNormals(20240703, "cuda:0")
     q, k, v = (drawer.normal((rows, S, d), 1.0, torch.bfloat16) for _ in range(3))
     got = topk_attention(q, k, v, top_k)
     torch.cuda.synchronize()
-    r = 77
-    q64, k64, v64 = (t[r:r + 1].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
-    _check_rows_allowing_swaps_at_the_cut(O, q64, k64, v64, got[r:r + 1].float().cpu().numpy().astype(np.float64), top_k,
+    pick = [77, 122]
+    sel = torch.tensor(pick, device="cuda:0")
+    q64, k64, v64 = (t[sel].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
+    _check_rows_allowing_swaps_at_the_cut(O, q64, k64, v64, got[sel].float().cpu().numpy().astype(np.float64), top_k,
                                           "long-context shape")
