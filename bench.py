@@ -201,6 +201,30 @@ def other_workload_entry(name, steps=150, warmup=30, prof_steps=30):
     return entry
 
 
+def stack_workload_entry(steps=24, warmup=6, prof_steps=6):
+    """Compact record of the 32-layer stack for the default line: per-layer step time through the fine-grained calls
+    and the throughput ratio against the full-attention comparator of Eq. 1 on the same shapes (see run_stack)."""
+    from gen import workload
+    w = workload("stack32")
+    w = w.scaled(T=warmup + steps + prof_steps)
+    el_s, us_s, el_f, us_f = run_stack(w, steps, warmup, prof_steps)
+    work = algorithmic_work(w)
+    att = us_s["attend"] + us_s["attend_combine"]
+    n_mid = w.S + warmup + steps // 2
+    return {"workload": "stack32", "layers": w.L, "batch": w.B, "cache_slots_K": w.K, "rebuild_budget_R": w.R, "prompt": w.S,
+            "ms_per_step_all_layers": round(1e3 * el_s / steps, 4), "ms_per_step": round(1e3 * el_s / steps / w.L, 4),
+            "tokens_per_s_per_layer": round(w.B * w.L * steps / el_s, 1),
+            "attend_us": round(att, 2), "attend_GBs": round(work["attend_bytes"] / (att * 1e-6) / 1e9, 1),
+            "attend_frac_of_hbm_peak": round(work["attend_bytes"] / (att * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+            "rebuild_gemm_us": round(us_s["rebuild_gemm"], 2),
+            "rebuild_gemm_TFLOPs": round(work["gemm_flops"] / (us_s["rebuild_gemm"] * 1e-6) / 1e12, 1),
+            "rebuild_gemm_frac_of_mfma_peak": round(work["gemm_flops"] / (us_s["rebuild_gemm"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4),
+            "full_attention_ms_per_step_all_layers": round(1e3 * el_f / steps, 4),
+            "full_attention_rows_per_head": n_mid + 1,
+            "sparse_vs_full_throughput": round(el_f / el_s, 3),
+            "inputs": "drawn on the device (seeded)"}
+
+
 def run_stack(w, steps, warmup, prof_steps):
     """Layer-stack workload: every step runs attend x L, one schedule, rebuild x L through the fine-grained
     calls, layers launched one after the other.  Next to it the full-attention comparator of Eq. 1: the
@@ -651,7 +675,8 @@ def main():
         # the other single-layer workloads, compactly: high_batch is the one whose cache (546 MB per step) does not
         # fit the 256 MB last-level cache, so its attention figure is the HBM-bound one
         t0 = time.time()
-        line["other_workloads"] = [other_workload_entry("high_batch"), other_workload_entry("long_context")]
+        line["other_workloads"] = [other_workload_entry("high_batch"), other_workload_entry("long_context"),
+                                   stack_workload_entry()]
         hb = line["other_workloads"][0]
         traffic_hb = recorded_traffic(workload("high_batch"))
         line["roofline_attend_high_batch"] = dict(

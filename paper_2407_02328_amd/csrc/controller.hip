@@ -672,12 +672,14 @@ __global__ __launch_bounds__(256) void rescore_kernel(const float *__restrict__ 
 }
 
 // Number of D-slices of the bf16 input projection: enough workgroups to cover the chip when
-// there are few tokens, one slice when there are many.  A slice is a multiple of 128 (4 waves x 32).
+// there are few tokens, and slices short enough that a wave walks at most four 32-wide steps of its quarter (the
+// operand loads of a step touch 64 cache lines and wait for each other: at 128 tokens, two slices of 2048 took
+// 225 us); one slice when there are many tokens.  A slice is a multiple of 128 (4 waves x 32).
 int ctrl_input_ksplit(const adore_config &c, int ntok) {
   const int tiles = ((3 * c.ctrl_hidden + 15) / 16) * ((ntok + 15) / 16);
   int ks = 1;
   if (ntok > kCtrlSplitTokens) return 1;
-  while (ks < kMaxCtrlSplit && tiles * ks < 256 && c.hidden % (ks * 2 * 128) == 0) ks *= 2;
+  while (ks < kMaxCtrlSplit && (tiles * ks < 256 || c.hidden / ks > 512) && c.hidden % (ks * 2 * 128) == 0) ks *= 2;
   return ks;
 }
 
