@@ -27,6 +27,7 @@ namespace {
 // The chosen positions are entered into the slot maps by the kernel that writes their rows.
 struct SchedArgs {
   int kpl, rel_wgs;                 // keys per lane of a row (K / 64 rounded up to 2, 4, 8, 16); 0 workgroups = off
+  int prio;                         // wave priority of the role (0 .. 3)
   int hpw;                          // heads a wave releases one after the other (1, or 4 for short rows of many sequences)
   const int32_t *slot_src;          // [B*H][K]
   int32_t *slot_dst;                // [B*H][K]
@@ -70,7 +71,12 @@ __device__ inline void selections_role(const AttendArgs &a, int e, uint64_t *dyn
   const int per_seq = s.rel_wgs + 1;
   const int b = e / per_seq, part = e - b * per_seq;
   const int tid = threadIdx.x, wave = tid >> 6;
-  __builtin_amdgcn_s_setprio(3);   // few waves with a long chain of dependent steps: they go first on their SIMD
+  switch (s.prio) {   // few waves with a long chain of dependent steps
+    case 3: __builtin_amdgcn_s_setprio(3); break;
+    case 2: __builtin_amdgcn_s_setprio(2); break;
+    case 1: __builtin_amdgcn_s_setprio(1); break;
+    default: break;
+  }
   float *s_score = reinterpret_cast<float *>(dyn);
   const float *sc = s.score + size_t(b) * s.N_max;
   if (part < s.rel_wgs) {          // heads 1 .. H-1
@@ -355,6 +361,8 @@ hipError_t launch_attend(adore_ctx *ctx, int layer, const void *q, const void *k
     s.kpl = c.cache_slots <= 128 ? 2 : c.cache_slots <= 256 ? 4 : c.cache_slots <= 512 ? 8 : 16;
     // four heads to a wave where a row is short (four of them fit a wave's registers) and the role would otherwise
     // take more than a quarter of the chip's wave slots
+    s.prio = 3;
+    if (const char *e = getenv("ADORE_ROLE_PRIO")) s.prio = atoi(e);   // tuning runs
     s.hpw = s.kpl <= 4 && c.batch * c.heads > 2048 ? 4 : 1;
     if (const char *e = getenv("ADORE_RIDE_HPW")) {   // tests: the four-heads path on a small shape
       if (atoi(e) == 4 && s.kpl <= 4) s.hpw = 4;

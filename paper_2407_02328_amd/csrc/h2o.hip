@@ -95,8 +95,18 @@ __global__ __launch_bounds__(kChoiceThreads) void h2o_choice_kernel(const H2OCho
   const float *sc = a.score + size_t(b) * a.H * a.N_max;
   int mine = 0;
   for (int i = tid; i < n1; i += kChoiceThreads) {
+    // fp32, heads in order (the order is part of the result); the loads go out eight at a time: one after the
+    // other they cost a trip to the L2 per head
     float agg = 0.f;
-    for (int h = 0; h < a.H; ++h) agg = agg + sc[size_t(h) * a.N_max + i];   // fp32, heads in order: the order is part of the result
+    int h = 0;
+    for (; h + 8 <= a.H; h += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = sc[size_t(h + u) * a.N_max + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) agg = agg + v[u];
+    }
+    for (; h < a.H; ++h) agg = agg + sc[size_t(h) * a.N_max + i];
     const int holders = int((s_cnt[i >> 2] >> (8 * (i & 3))) & 255u);
     const uint64_t key = holders == a.H ? uint64_t(0) : rank_key(agg, i);
     s_all[i] = key;
