@@ -157,8 +157,8 @@ int adore_destroy(adore_ctx *ctx);
  * hidden_store == NULL prepares the context for adore_forward_step instead: the best min(R, rest)
  * tokens are chosen and given their slots, but their K/V are computed by the first forward step.
  * Enqueues work; does not synchronise.  May be called again to restart.
- * Errors: E_INVALID (null, S < 1, S >= N_max), E_UNSUPPORTED (hidden_store == NULL and the
- * configuration has no forward path: see adore_forward_step). */
+ * Errors: E_INVALID (null, S < 1, S >= N_max), E_UNSUPPORTED (hidden_store == NULL and K > 8192 or
+ * H2O scores: see adore_forward_step). */
 int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
                      const void *hidden_store, const void *ctrl_input,
                      const float *score_override, int32_t S);
@@ -226,8 +226,11 @@ int adore_decode_step(adore_ctx *ctx, const void *q, const void *k_new, const vo
  *             at [b][R]; rows of unused ranks are left untouched
  *   layer_rows [L][B][R+1][D] storage type or NULL: the rows leaving every layer (the hidden states of the
  *             rebuilt tokens and of the current one, layer by layer), laid out like rows_out; [L-1] equals rows_out
- * Requires a context initialised with hidden_store == NULL, bf16 storage, R + 1 <= 64, K <= 8192,
- * H*d and D multiples of 128.  Enqueues work; does not synchronise.
+ * Requires a context initialised with hidden_store == NULL and K <= 8192.  bf16 storage with H*d and D
+ * multiples of 128 runs the projections on the matrix cores, and with R + 1 <= 64 the attention too; any
+ * other configuration (fp32 storage, other widths, more rows) takes plain kernels for that part, one wave
+ * per output element: the same arithmetic in fp32, a reference path rather than a fast one.
+ * Enqueues work; does not synchronise.
  * Errors: E_INVALID, E_STATE (not initialised for the forward, step past N_max). */
 typedef struct {
   const void *w_q;

@@ -337,8 +337,7 @@ int adore_init_cache(adore_ctx *ctx, const void *prompt_k, const void *prompt_v,
   const adore_config &c = ctx->cfg;
   if (S < 1 || S >= c.max_positions) return ADORE_E_INVALID;
   const bool forward = hidden_store == nullptr;
-  if (forward && !(fwd_gemm_supported(c) && c.rebuild_budget + 1 <= 64 && c.cache_slots <= fwd_attend_max_slots()))
-    return ADORE_E_UNSUPPORTED;
+  if (forward && c.cache_slots > fwd_attend_max_slots()) return ADORE_E_UNSUPPORTED;
   const bool rescore = c.score_mode == ADORE_SCORE_RESCORE;
   if (rescore && score_override) return ADORE_E_INVALID;   // scores are recomputed at every step
   if (h2o_mode(ctx) && forward) return ADORE_E_UNSUPPORTED;

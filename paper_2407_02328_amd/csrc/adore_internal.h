@@ -187,6 +187,7 @@ hipError_t launch_ctrl_avec(adore_ctx *ctx, hipStream_t st);
 hipError_t launch_rescore(adore_ctx *ctx, hipStream_t st, int n, int upto);
 // rebuild forward (one layer = qkv projection, attention of the r+1 rows, output projection with residual)
 bool fwd_gemm_supported(const adore_config &c);
+bool fwd_attend_mfma(const adore_config &c);
 int fwd_attend_max_slots();
 hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, const void *x_rows, bool by_position,
                           int r);

@@ -387,14 +387,91 @@ hipError_t launch_dh(adore_ctx *ctx, const FwdAttendArgs &a, int rows) {
   return hipGetLastError();
 }
 
+// The same attention for storage types and shapes the kernel above does not take (fp32 storage, more than 64 rows per
+// sequence): one wave per (sequence, head, query row), the definition written out.  Logits of the visible slots go to
+// LDS (a lane takes every 64th slot and walks its key row), maximum and sum over the wave, then a lane takes every
+// 64th element of the head dimension and walks the slots.  fp32 throughout, one rounding to the storage type.
+template <typename T>
+__global__ __launch_bounds__(64) void fwd_attend_plain_kernel(const void *Q_, const void *Kc_, const void *Vc_,
+                                                              const int32_t *slot_pos, const int32_t *insert_slot,
+                                                              const int32_t *rebuilt_pos, void *O_, int H, int K, int d,
+                                                              int nq, int r, int Rdim, int n, float scale_log2) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float *s_w = reinterpret_cast<float *>(smem);   // [K] logit, then probability; < 0 marks nothing (see s_vis)
+  int32_t *s_vis = reinterpret_cast<int32_t *>(s_w + K);   // [K] 1 = visible to this query
+  const int bh = blockIdx.x / nq, j = blockIdx.x - bh * nq;
+  const int b = bh / H, h = bh - b * H;
+  const int lane = threadIdx.x;
+  const int Hd = H * d;
+  const int P = j < r ? rebuilt_pos[size_t(b) * Rdim + j] : n;   // this query's position
+  const T *q = static_cast<const T *>(Q_) + (size_t(b) * nq + j) * Hd + h * d;
+  const T *Kb = static_cast<const T *>(Kc_) + size_t(bh) * K * d;
+  const T *Vb = static_cast<const T *>(Vc_) + size_t(bh) * K * d;
+  const int32_t *sp = slot_pos + size_t(bh) * K;
+  const int s_ins = insert_slot[bh];
+  float mx = -INFINITY;
+  for (int k = lane; k < K; k += 64) {
+    const int pos = k == s_ins ? n : sp[k];
+    const bool vis = pos >= 0 && pos <= P;
+    float w = 0.f;
+    if (vis) {
+      for (int c = 0; c < d; ++c) w = fmaf(to_float(q[c]), to_float(Kb[size_t(k) * d + c]), w);
+      mx = fmaxf(mx, w);
+    }
+    s_w[k] = w;
+    s_vis[k] = vis ? 1 : 0;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float l = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float p = s_vis[k] ? exp2f((s_w[k] - mx) * scale_log2) : 0.f;
+    s_w[k] = p;
+    l += p;
+  }
+  l = wave_sum(l);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // one wave: its LDS stores before its LDS loads below
+  __builtin_amdgcn_wave_barrier();
+  T *o = static_cast<T *>(O_) + (size_t(b) * nq + j) * Hd + h * d;
+  for (int c = lane; c < d; c += 64) {
+    float acc = 0.f;
+    for (int k = 0; k < K; ++k)
+      if (s_vis[k]) acc = fmaf(s_w[k], to_float(Vb[size_t(k) * d + c]), acc);
+    store_elem(o + c, acc / l);
+  }
+}
+
 }  // namespace
 
 // Largest cache the forward attention takes: the slot positions of a row sit in LDS next to the tiles.
 int fwd_attend_max_slots() { return 8192; }
 
+// Whether the matrix-core kernel takes this configuration's forward attention (otherwise the plain kernel does).
+bool fwd_attend_mfma(const adore_config &c) {
+  return c.dtype == ADORE_BF16 && c.rebuild_budget + 1 <= 64 && (c.head_dim == 64 || c.head_dim == 128);
+}
+
 hipError_t launch_fwd_attend(adore_ctx *ctx, int layer, int r) {
   const adore_config &c = ctx->cfg;
   const size_t layer_elems = size_t(c.batch) * c.heads * c.cache_slots * c.head_dim;
+  if (!fwd_attend_mfma(c)) {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_ATTEND, ctx->stream);
+    const size_t es = elem_size(c);
+    const dim3 grid(unsigned(c.batch * c.heads * (r + 1))), block(64);
+    const int lds = c.cache_slots * 8;
+    const float scale_log2 = 1.4426950408889634f / sqrtf(float(c.head_dim));
+    const void *Kl = ctx->cache_k + layer * layer_elems * es, *Vl = ctx->cache_v + layer * layer_elems * es;
+    if (c.dtype == ADORE_BF16) {
+      ADORE_LAUNCH(t, (fwd_attend_plain_kernel<bf16_t>), grid, block, lds, ctx->stream, ctx->fwd_q, Kl, Vl,
+                   ctx->slot_pos[ctx->cur], ctx->insert_slot[ctx->cur], ctx->rebuilt_pos[ctx->cur], ctx->fwd_o, c.heads,
+                   c.cache_slots, c.head_dim, r + 1, r, max(c.rebuild_budget, 1), ctx->n, scale_log2);
+    } else {
+      ADORE_LAUNCH(t, (fwd_attend_plain_kernel<float>), grid, block, lds, ctx->stream, ctx->fwd_q, Kl, Vl,
+                   ctx->slot_pos[ctx->cur], ctx->insert_slot[ctx->cur], ctx->rebuilt_pos[ctx->cur], ctx->fwd_o, c.heads,
+                   c.cache_slots, c.head_dim, r + 1, r, max(c.rebuild_budget, 1), ctx->n, scale_log2);
+    }
+    return hipGetLastError();
+  }
   FwdAttendArgs a;
   a.Q = static_cast<const bf16_t *>(ctx->fwd_q);
   a.Kc = reinterpret_cast<const bf16_t *>(ctx->cache_k) + layer * layer_elems;

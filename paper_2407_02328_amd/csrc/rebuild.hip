@@ -664,6 +664,53 @@ __global__ __launch_bounds__(256) void rebuild_dot_kernel(const GemmArgs a) {
   }
 }
 
+// The forward's two projections (QKV, OPROJ) for storage types and widths the tile kernel does not take (fp32
+// storage, widths that are no multiples of 128): one wave per output element, all r + 1 rows of a sequence alike
+// (rank j < r, the current token at j = r).  fp32 products and sums, one rounding to the storage type.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void proj_dot_kernel(const GemmArgs a) {
+  constexpr int EPL = Vec16<T>::EPL;
+  const size_t wid = (size_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+  const int lane = threadIdx.x & 63;
+  const int rps = a.r + 1;
+  if (wid >= size_t(a.B) * rps * a.N) return;
+  const int mi = int(wid / a.N), nf = int(wid - size_t(mi) * a.N);
+  const int b = mi / rps, j = mi - b * rps;
+  const bool cur = j == a.r;
+  const int pos = cur ? a.cur_pos : a.rebuilt_pos[size_t(b) * a.Rdim + j];
+  if (pos < 0) return;   // an empty rank (uniform over the wave)
+  const int Hd = a.H * a.d;
+  const size_t xrow = a.a_gather ? size_t(b) * a.N_max + pos : size_t(b) * a.xrps + j;
+  const T *x = static_cast<const T *>(a.X) + xrow * a.D;
+  const T *wrow = MODE == MODE_QKV && nf < Hd ? static_cast<const T *>(a.Wq) + size_t(nf) * a.D
+                  : MODE == MODE_QKV          ? static_cast<const T *>(a.W) + size_t(nf - Hd) * a.D
+                                              : static_cast<const T *>(a.W) + size_t(nf) * a.D;
+  float s = 0.f;
+  for (int c = lane * EPL; c < a.D; c += 64 * EPL) {
+    float xf[EPL], wf[EPL];
+    Vec16<T>::load(x + c, xf);
+    Vec16<T>::load(wrow + c, wf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s = fmaf(xf[e], wf[e], s);
+  }
+  s = wave_sum(s);
+  if (lane != 0) return;
+  if (MODE == MODE_OPROJ) {
+    const size_t rrow = a.res_gather ? size_t(b) * a.N_max + pos : size_t(b) * a.xrps + j;
+    s += to_float(static_cast<const T *>(a.Res)[rrow * a.N + nf]);
+    store_elem(static_cast<T *>(a.Out) + (size_t(b) * a.out_rps + (cur ? a.out_cur : j)) * a.N + nf, s);
+    return;
+  }
+  const int section = nf / Hd, rem = nf - section * Hd;
+  if (section == 0) {
+    store_elem(static_cast<T *>(a.Out) + (size_t(b) * a.xrps + j) * Hd + rem, s);
+    return;
+  }
+  const int h = rem / a.d, cc = rem - h * a.d;
+  const int slot = cur ? a.insert_slot[size_t(b) * a.H + h] : a.free_list[(size_t(b) * a.H + h) * a.R1 + j];
+  store_elem(static_cast<T *>(section == 1 ? a.Kc : a.Vc) + ((size_t(b) * a.H + h) * a.K + slot) * a.d + cc, s);
+}
+
 // The current token's row of every sequence (rebuild forward): B rows against the same weights, a skinny product
 // that only streams W.  One workgroup owns 16 sequences x NC*16 output columns; its 4 waves cut the contraction
 // into quarters (summed through LDS in a fixed order).  16x16x32 tiles; lane (c, g) holds, for matrix instruction
@@ -859,7 +906,8 @@ hipError_t launch_rebuild_gemm(adore_ctx *ctx, int layer, const void *hidden_lay
 }
 
 // ---- rebuild forward: the two projections around the attention of a layer ----------------------------
-// Whether the kernels take both projections of this configuration (the forward has no other path).
+// Whether the tile kernels take both projections of this configuration; otherwise the forward runs them as one
+// wave per output element (proj_dot_kernel).
 bool fwd_gemm_supported(const adore_config &c) {
   const int Hd = c.heads * c.head_dim;
   return c.dtype == ADORE_BF16 && c.hidden % 128 == 0 && Hd % 128 == 0 &&
@@ -899,6 +947,17 @@ int pick_with_riders(GemmArgs &a, int kdim, int section, int head_dim, bool dens
 }
 
 template <int MODE>
+void launch_proj_dot(ScopedTimer &t, hipStream_t stream, bool bf16, const GemmArgs &a) {
+  const size_t waves = size_t(a.B) * (a.r + 1) * a.N;
+  const dim3 grid(unsigned((waves + 3) / 4)), block(256);
+  if (bf16) {
+    ADORE_LAUNCH(t, (proj_dot_kernel<bf16_t, MODE>), grid, block, 0, stream, a);
+  } else {
+    ADORE_LAUNCH(t, (proj_dot_kernel<float, MODE>), grid, block, 0, stream, a);
+  }
+}
+
+template <int MODE>
 void launch_cur_rows(ScopedTimer &t, hipStream_t stream, const GemmArgs &a) {
   const int seq_blocks = (a.B + 15) / 16;
   if (a.N % 32 == 0 && (a.N / 32) * seq_blocks >= 256) {
@@ -916,11 +975,12 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
                           int r) {
   const adore_config &c = ctx->cfg;
   const int Hd = c.heads * c.head_dim;
-  const size_t layer_bytes = size_t(c.batch) * Hd * c.cache_slots * 2;
+  const size_t es = elem_size(c);
+  const size_t layer_bytes = size_t(c.batch) * Hd * c.cache_slots * es;
   GemmArgs a;
   fill_common(ctx, a, ctx->cur, r);
   a.X = x_rows;
-  a.W = static_cast<const char *>(ctx->w.w_kv) + size_t(layer) * 2 * Hd * c.hidden * 2;
+  a.W = static_cast<const char *>(ctx->w.w_kv) + size_t(layer) * 2 * Hd * c.hidden * es;
   a.Wq = w_q_layer;
   a.Kc = ctx->cache_k + layer * layer_bytes;
   a.Vc = ctx->cache_v + layer * layer_bytes;
@@ -929,6 +989,15 @@ hipError_t launch_fwd_qkv(adore_ctx *ctx, int layer, const void *w_q_layer, cons
   a.M = c.batch * r; a.N = 3 * Hd;
   bool turned = false;   // the tiles turned the rebuilt tokens' query and key rows themselves
   bool cur_turned = false;   // ... and the workgroups of the current tokens' rows theirs
+  if (!fwd_gemm_supported(c)) {   // all r + 1 rows of every sequence, one wave per output element
+    {
+      ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
+      launch_proj_dot<MODE_QKV>(t, ctx->stream, c.dtype == ADORE_BF16, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = launch_rope_rows(ctx, layer, ctx->cur, r, 0, r + 1, true, ctx->n);
+    return e;
+  }
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_QKV, ctx->stream);
     const int pick = pick_with_riders(a, c.hidden, Hd, c.head_dim, false);
@@ -967,6 +1036,11 @@ hipError_t launch_fwd_oproj(adore_ctx *ctx, const void *w_o_layer, const void *x
   a.xrps = r + 1; a.cur_pos = ctx->n; a.a_gather = 0; a.res_gather = by_position ? 1 : 0;
   a.out_rps = out_rps; a.out_cur = out_cur;
   a.M = c.batch * r; a.N = c.hidden;
+  if (!fwd_gemm_supported(c)) {
+    ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
+    launch_proj_dot<MODE_OPROJ>(t, ctx->stream, c.dtype == ADORE_BF16, a);
+    return hipGetLastError();
+  }
   if (r > 0) {
     ScopedTimer t(ctx, ADORE_KERNEL_FWD_OPROJ, ctx->stream);
     const int pick = pick_with_riders(a, Hd, c.hidden, c.head_dim, true);

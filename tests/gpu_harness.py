@@ -341,7 +341,7 @@ def forward_row_check(w: Workload, got: np.ndarray, want: np.ndarray, what: str)
     one unit of its own last place plus 2e-3 of the row's largest entry.  Returns the largest row error
     max|got - want| / max|want| for the report."""
     assert np.isfinite(got).all(), what
-    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - (7 if w.dtype == "bf16" else 23))
     top = np.abs(want).max(axis=-1, keepdims=True)
     bad = np.abs(got - want) > ulp * 1.0001 + out_tol(w) * top
     assert not bad.any(), f"{what}: {int(bad.sum())} entries, worst {float((np.abs(got - want) / top).max()):.3e} of the row maximum"

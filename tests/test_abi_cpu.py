@@ -156,8 +156,7 @@ def test_calls_out_of_order_are_state_errors(lib):
         assert lib.adore_set_input_order(None, 0) == -1
         assert lib.adore_set_input_order(h, 0) == 0
         assert lib.adore_set_input_order(h, 1) == 0
-        # the rebuild forward: null arguments, a context not initialised for it, a configuration without
-        # a forward path (fp32 storage) -- all caught on the host
+        # the rebuild forward: null arguments, a context not initialised for it -- all caught on the host
         from paper_2407_02328_amd.binding import AdoreForwardWeights
         fw = AdoreForwardWeights(FAKE, FAKE)
         assert lib.adore_forward_step(h, None, FAKE, None, FAKE, None, None, None, None) == -1
@@ -165,9 +164,15 @@ def test_calls_out_of_order_are_state_errors(lib):
         assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, None, None, None, None, None) == -1
         assert lib.adore_forward_step(h, ctypes.byref(AdoreForwardWeights(None, FAKE)), FAKE, None, FAKE, None, None, None, None) == -1
         assert lib.adore_forward_step(h, ctypes.byref(fw), FAKE, None, FAKE, None, None, None, None) == -2
-        assert lib.adore_init_cache(h, FAKE, FAKE, None, FAKE, None, 4) == -3     # tiny is fp32: no forward path
     finally:
         assert lib.adore_destroy(h) == 0
+    # a cache of more than 8192 slots (one that never releases) has no forward path: caught on the host
+    wide = cfg_for(w, cache_slots=9000, max_positions=9000 - w.R - 1)
+    h2 = ctypes.c_void_p()
+    assert lib.adore_create(ctypes.byref(wide), ctypes.byref(wt), FAKE, lib.adore_workspace_bytes(ctypes.byref(wide)),
+                            None, ctypes.byref(h2)) == 0
+    assert lib.adore_init_cache(h2, FAKE, FAKE, None, FAKE, None, 4) == -3
+    assert lib.adore_destroy(h2) == 0
     assert lib.adore_destroy(None) == -1
 
 

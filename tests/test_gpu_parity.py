@@ -6,6 +6,7 @@ within 1e-5.  Both sides rank tokens from the same fp32 sigma bits (the oracle c
 value against the GPU's, then adopts the GPU's bits).
 """
 import os
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -475,6 +476,36 @@ def test_forward_step_matches_the_forward_oracle(name, kw):
     worst, mean = h.forward_lockstep(w, w.T)
     print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
     assert mean < 2.0 ** -10
+
+
+@pytest.mark.parametrize("name,dtype,kw", [
+    # fp32 storage (the 1e-5 parity point of the forward): the projections and the attention as plain kernels
+    ("f32_r8_d64", "f32", dict(L=3, B=2, H=4, d=64, D=256, K=64, R=8, S=40, T=40)),
+    ("f32_r20_d128", "f32", dict(L=2, B=3, H=2, d=128, D=128, K=96, R=20, S=130, T=10)),
+    ("f32_r0", "f32", dict(L=2, B=2, H=2, d=64, D=128, K=48, R=0, S=60, T=10)),
+    ("f32_rope", "f32", dict(L=2, B=2, H=2, d=64, D=128, K=72, R=10, S=90, T=12, rope_base=10000.0)),
+    # bf16 with a model width that is no multiple of 128: plain projections around the matrix-core attention
+    ("bf16_D200", "bf16", dict(L=2, B=2, H=3, d=64, D=200, K=80, R=12, S=100, T=12)),
+    # bf16 with more than 64 rows per sequence: plain attention between matrix-core projections
+    ("bf16_r70", "bf16", dict(L=1, B=2, H=2, d=64, D=128, K=160, R=70, S=200, T=6)),
+])
+def test_forward_step_on_the_plain_kernels(name, dtype, kw):
+    """Configurations the matrix-core kernels of the forward do not take run the same arithmetic as one wave per
+    output element; fp32 storage is held to 1e-5."""
+    h = _harness()
+    w = Workload("fwdp_" + name, dtype=dtype, dprime=32, w_std=0.96 / np.sqrt(kw["D"]), **kw)
+    worst, mean = h.forward_lockstep(w, w.T)
+    print(f"forward {name}: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
+    assert mean < (2.0 ** -10 if dtype == "bf16" else 1e-6)
+
+
+def test_forward_step_tiny_config_fp32():
+    """The fp32 configuration of the parity suite through the rebuild forward (it had no forward path before)."""
+    h = _harness()
+    w = replace(workload("tiny"), L=2, T=24)
+    worst, mean = h.forward_lockstep(w, w.T)
+    print(f"forward tiny fp32 x2: worst row error {worst:.2e}, mean {mean:.2e}", flush=True)
+    assert worst < 1e-5
 
 
 def test_forward_step_with_the_current_rows_in_a_launch_of_their_own(monkeypatch):
