@@ -56,7 +56,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 8
+#define ADORE_ABI_VERSION 9
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -333,6 +333,15 @@ int adore_topk_attention_static(const void *q, const void *k, const void *v, voi
                                 int32_t head_dim, int32_t top_k, void *hip_stream);
 
 const char *adore_strerror(int code);
+/* Debug aid for callers and tests, not a step of the method (no passage of the paper): with ADORE_GUARD_WORDS=1
+ * in the environment of the process, adore_workspace_bytes and adore_create lay the workspace out with 256 bytes of
+ * a fixed pattern behind each of its regions (cache, slot maps, scores, lists, scratch).  No kernel has a reason to
+ * touch them; a kernel that writes past the end of a region does.  adore_check_guards waits for the context's
+ * streams and writes to *damaged (host) the number of 4-byte guard words that no longer hold the pattern: 0 after
+ * any sequence of calls, -1 if the context has no guard words (the variable was not set at create, or no call has
+ * touched the GPU yet).  Errors: E_INVALID (null), E_HIP. */
+int adore_check_guards(adore_ctx *ctx, int32_t *damaged);
+
 int adore_abi_version(void);
 
 #ifdef __cplusplus

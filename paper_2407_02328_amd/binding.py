@@ -24,7 +24,7 @@ SCORE_STATIC, SCORE_RESCORE, SCORE_H2O = 0, 1, 2
 EXPORTS = [
     "adore_workspace_bytes", "adore_create", "adore_destroy", "adore_init_cache", "adore_attend",
     "adore_schedule", "adore_rebuild", "adore_decode_step", "adore_forward_step", "adore_get_state", "adore_set_state",
-    "adore_set_input_order", "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
+    "adore_set_input_order", "adore_check_guards", "adore_set_timing", "adore_read_timing", "adore_kernel_name", "adore_strerror", "adore_abi_version",
     "adore_topk_attention_workspace_bytes", "adore_topk_attention", "adore_topk_attention_static",
 ]
 
@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.adore_kernel_name.argtypes = [i32]
     lib.adore_strerror.restype = ctypes.c_char_p
     lib.adore_strerror.argtypes = [ctypes.c_int]
+    lib.adore_check_guards.restype = ctypes.c_int
+    lib.adore_check_guards.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     lib.adore_abi_version.restype = ctypes.c_int
     lib.adore_abi_version.argtypes = []
     lib.adore_topk_attention_workspace_bytes.restype = sz
@@ -310,6 +312,12 @@ class Adore:
 
     def set_input_order(self, ordered: bool):
         _check(self.lib, self.lib.adore_set_input_order(self.handle, int(ordered)))
+
+    def check_guards(self) -> int:
+        """Damaged guard words of the debug layout (ADORE_GUARD_WORDS=1 at create), or -1 if there are none."""
+        bad = ctypes.c_int32(0)
+        _check(self.lib, self.lib.adore_check_guards(self.handle, ctypes.byref(bad)))
+        return int(bad.value)
 
     def set_timing(self, enable: bool):
         _check(self.lib, self.lib.adore_set_timing(self.handle, int(enable)))

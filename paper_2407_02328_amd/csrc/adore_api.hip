@@ -60,7 +60,18 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t cache_k, cache_v, slot_pos, score, z, insert_slot, free_list, released_pos, rebuilt_pos, init_res,
       att_part, att_logit, att_ml, gi, zseq, cvec, avec, fwd_q, fwd_o, fwd_x, rope, total;
+  std::vector<size_t> guards;   // offsets of the guard words (debug layout), one run behind every region
 };
+
+// Debug layout (ADORE_GUARD_WORDS=1 in the environment of the process): every region of the workspace is followed
+// by kGuardBytes of a fixed pattern that no kernel ever has a reason to touch; adore_check_guards counts the words
+// that changed.  adore_workspace_bytes and adore_create read the variable alike.
+constexpr size_t kGuardBytes = 256;
+constexpr uint32_t kGuardWord = 0xA5A5A5A5u;
+bool guard_words_on() {
+  const char *e = getenv("ADORE_GUARD_WORDS");
+  return e && atoi(e) != 0;
+}
 
 bool config_ok(const adore_config *c) {
   return c && c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
@@ -93,9 +104,14 @@ Layout make_layout(const adore_config &c) {
   const size_t R1 = size_t(c.rebuild_budget) + 1;
   Layout l;
   size_t off = 0;
+  const bool guarded = guard_words_on();
   auto take = [&](size_t bytes) {
     const size_t at = off;
     off = align_up(off + bytes);
+    if (guarded) {
+      l.guards.push_back(off);
+      off += kGuardBytes;
+    }
     return at;
   };
   l.cache_k = take(size_t(c.layers) * BH * c.cache_slots * c.head_dim * es);
@@ -164,7 +180,17 @@ void choose_split(adore_ctx *ctx) {
 // fence (cache write-back and invalidation for the host's and other devices' sake) when they complete.
 constexpr unsigned kSyncEventFlags = hipEventDisableTiming | hipEventDisableSystemFence;
 
+// The guard words get their pattern on the first call that touches the GPU (a context can be created without one).
+int ensure_guards(adore_ctx *ctx) {
+  if (ctx->guards_ready) return ADORE_OK;
+  for (size_t off : ctx->guard_off)
+    if (hipMemsetAsync(ctx->ws_base + off, int(kGuardWord & 0xff), kGuardBytes, ctx->stream) != hipSuccess) return ADORE_E_HIP;
+  ctx->guards_ready = true;
+  return ADORE_OK;
+}
+
 int ensure_side_stream(adore_ctx *ctx) {
+  if (ensure_guards(ctx) != ADORE_OK) return ADORE_E_HIP;
   if (!ctx->overlap || ctx->side_ready) return ADORE_OK;
   bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking) == hipSuccess;
@@ -274,6 +300,9 @@ int adore_create(const adore_config *cfg, const adore_weights *weights, void *wo
   ctx->fwd_x = base + l.fwd_x;
   ctx->rope = base + l.rope;
   ctx->rope_f = reinterpret_cast<float2 *>(base + l.rope + size_t(cfg->max_positions) * (cfg->head_dim / 2) * 16);
+  ctx->ws_base = base;
+  ctx->guard_off = l.guards;
+  ctx->guards_ready = false;
   ctx->forward = false;
   ctx->r_pending = 0;
   ctx->ins_stride = 1;
@@ -773,6 +802,27 @@ int adore_set_input_order(adore_ctx *ctx, int32_t ordered) {
     ctx->rode = false;
   }
   ctx->ordered = on;
+  return ADORE_OK;
+}
+
+int adore_check_guards(adore_ctx *ctx, int32_t *damaged) {
+  if (!ctx || !damaged) return ADORE_E_INVALID;
+  if (ctx->guard_off.empty() || !ctx->guards_ready) {
+    *damaged = -1;
+    return ADORE_OK;
+  }
+  ADORE_TRY(hipStreamSynchronize(ctx->stream));
+  if (ctx->overlap && ctx->side_ready) {
+    ADORE_TRY(hipStreamSynchronize(ctx->side));
+    ADORE_TRY(hipStreamSynchronize(ctx->side2));
+  }
+  std::vector<uint32_t> host(kGuardBytes / 4);
+  int32_t bad = 0;
+  for (size_t off : ctx->guard_off) {
+    ADORE_TRY(hipMemcpy(host.data(), ctx->ws_base + off, kGuardBytes, hipMemcpyDeviceToHost));
+    for (uint32_t w : host) bad += w != kGuardWord;
+  }
+  *damaged = bad;
   return ADORE_OK;
 }
 

@@ -56,6 +56,9 @@ struct adore_ctx {
   // Arrays marked xR are rings of kRing copies indexed by `cur`: a step's attention reads [cur] while its
   // selections write [cur + 1], so the selections of step n+1 may run while the GEMM of step n still
   // reads the lists of step n, and the side stream may run a few steps ahead of the caller's stream.
+  char *ws_base;                    // the caller's workspace
+  std::vector<size_t> guard_off;    // debug layout: where the guard words sit in it (empty: none)
+  bool guards_ready;                // ... and whether they have their pattern yet
   char *cache_k, *cache_v;   // [L][B][H][K][d] storage type
   int32_t *slot_pos[adore::kRing];     // xR [B][H][K]   position per slot, -1 = free
   float *score;              // [B][N_max]  sigma_i

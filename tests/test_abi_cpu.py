@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 8
+    assert lib.adore_abi_version() == 9
 
 
 def test_workspace_bytes(lib):
@@ -174,6 +174,25 @@ def test_calls_out_of_order_are_state_errors(lib):
     assert lib.adore_init_cache(h2, FAKE, FAKE, None, FAKE, None, 4) == -3
     assert lib.adore_destroy(h2) == 0
     assert lib.adore_destroy(None) == -1
+
+
+def test_guard_word_layout_on_the_host(lib, monkeypatch):
+    """ADORE_GUARD_WORDS=1: the workspace grows by 256 bytes per region, create takes it, and a context that has
+    not touched the GPU reports that it has no guard words to count yet."""
+    w = workload("tiny")
+    c, wt = cfg_for(w), fake_weights()
+    plain = lib.adore_workspace_bytes(ctypes.byref(c))
+    monkeypatch.setenv("ADORE_GUARD_WORDS", "1")
+    guarded = lib.adore_workspace_bytes(ctypes.byref(c))
+    assert guarded > plain and (guarded - plain) % 256 == 0 and guarded - plain >= 20 * 256
+    h = ctypes.c_void_p()
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), FAKE, plain, None, ctypes.byref(h)) == -4
+    assert lib.adore_create(ctypes.byref(c), ctypes.byref(wt), FAKE, guarded, None, ctypes.byref(h)) == 0
+    bad = ctypes.c_int32(7)
+    assert lib.adore_check_guards(None, ctypes.byref(bad)) == -1
+    assert lib.adore_check_guards(h, None) == -1
+    assert lib.adore_check_guards(h, ctypes.byref(bad)) == 0 and bad.value == -1
+    assert lib.adore_destroy(h) == 0
 
 
 def test_strerror_and_kernel_names(lib):
