@@ -135,7 +135,8 @@ size_t adore_workspace_bytes(const adore_config *cfg);
  * adore_destroy).  `hip_stream` is a hipStream_t (NULL = the default stream).
  * cfg and weights are HOST structs and are copied.  The cache starts empty;
  * call adore_init_cache before the first step.
- * Errors: E_INVALID (null, R > K-2, sizes <= 0), E_UNSUPPORTED (head_dim not in
+ * Errors: E_INVALID (null, R > K-2, sizes <= 0, or sizes beyond what 32-bit counts hold with a wide
+ * margin: L > 4096, B*H > 2^20, H*d or D > 2^20, K > 2^20, N_max > 2^24), E_UNSUPPORTED (head_dim not in
  * {64,128}, K > 1024 unless K - R - 1 >= N_max, i.e. a cache that holds every
  * token and is the full attention of Eq. 1 ... see adore_strerror), E_WORKSPACE. */
 int adore_create(const adore_config *cfg, const adore_weights *weights, void *workspace,
@@ -312,7 +313,8 @@ const char *adore_kernel_name(int32_t kernel);
  * hip_stream (a hipStream_t, NULL = the default stream).  The selection is exact on the weights as the kernel
  * computes them (bf16 products accumulated in fp32); inputs must be finite.
  * Errors: E_INVALID (null, sizes <= 0, top_k < 1), E_UNSUPPORTED (head_dim not in {64,128}, seq > 32768,
- * rows > 65535), E_WORKSPACE, E_HIP. */
+ * rows > 65535), E_WORKSPACE, E_HIP.  adore_topk_attention_workspace_bytes is a HOST call and returns 0 for
+ * sizes the entry point would not take. */
 size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t head_dim);
 int adore_topk_attention(const void *q, const void *k, const void *v, void *out, void *workspace,
                          size_t workspace_bytes, int32_t rows, int32_t seq, int32_t head_dim, int32_t top_k,

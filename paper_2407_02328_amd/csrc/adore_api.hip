@@ -73,8 +73,20 @@ bool guard_words_on() {
   return e && atoi(e) != 0;
 }
 
+// Upper limits that keep every row, slot and token count of a configuration (and their products, which kernels and
+// launch shapes hold in 32-bit integers) far inside the range of int; byte counts are 64-bit throughout.
+constexpr int kMaxLayers = 4096, kMaxRows = 1 << 20 /* batch x heads */, kMaxWidth = 1 << 20 /* hidden, H x d */,
+              kMaxAnySlots = 1 << 20;
+
 bool config_ok(const adore_config *c) {
-  return c && c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
+  if (!c) return false;
+  if (c->layers > kMaxLayers || c->batch > kMaxRows || c->heads > kMaxRows || c->head_dim > kMaxWidth ||
+      c->hidden > kMaxWidth || c->cache_slots > kMaxAnySlots || c->max_positions > (1 << 24) || c->ctrl_hidden > kMaxWidth)
+    return false;
+  if (c->batch > 0 && c->heads > 0 && c->head_dim > 0 &&
+      ((long long)c->batch * c->heads > kMaxRows || (long long)c->heads * c->head_dim > kMaxWidth))
+    return false;
+  return c->layers > 0 && c->batch > 0 && c->heads > 0 && c->head_dim > 0 && c->hidden > 0 &&
          c->cache_slots >= 2 && c->rebuild_budget >= 0 && c->rebuild_budget <= c->cache_slots - 2 &&
          c->max_positions >= 2 && c->ctrl_hidden > 0 && (c->dtype == ADORE_F32 || c->dtype == ADORE_BF16) &&
          (c->score_mode == ADORE_SCORE_STATIC || c->score_mode == ADORE_SCORE_RESCORE ||

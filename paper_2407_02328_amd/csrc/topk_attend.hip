@@ -566,6 +566,7 @@ extern "C" {
 
 size_t adore_topk_attention_workspace_bytes(int32_t rows, int32_t seq, int32_t head_dim) {
   if (rows <= 0 || seq <= 0 || head_dim <= 0) return 0;
+  if (seq > adore::kMaxLongSeq || rows > 65535 || head_dim > 1024) return 0;   // nothing the entry point would take
   const size_t vt = adore::vt_bytes(rows, seq, head_dim);
   // sequences whose logit rows LDS cannot hold: 16 rows of fp32 weights per workgroup of 16 queries
   const size_t tiles = size_t(rows) * ((seq + 15) / 16);
@@ -593,7 +594,7 @@ int adore_topk_attention_static(const void *q, const void *k, const void *v, voi
   using namespace adore;
   if (!q || !k || !v || !out || rows <= 0 || seq <= 0 || head_dim <= 0 || top_k < 1) return ADORE_E_INVALID;
   if ((head_dim != 64 && head_dim != 128) || rows > 65535) return ADORE_E_UNSUPPORTED;
-  // beyond kMaxSeq tokens the weights of a query block need a buffer that grows with seq * seq: not in this variant
+  // beyond kMaxSeq tokens the weights of the query blocks need a buffer of 512 x 16 rows of seq floats: not in this variant
   if (seq > kMaxSeq || vt_bytes(rows, seq, head_dim) > size_t(ADORE_TOPK_STATIC_SCRATCH_BYTES)) return ADORE_E_WORKSPACE;
   void *vt = static_scratch();
   if (!vt) return ADORE_E_HIP;

@@ -218,8 +218,12 @@ def test_topk_attention_host_checks(lib):
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 0, 64, 64, 4, None) == -1
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n, 2, 64, 96, 4, None) == -3
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, 2, 40000, 64, 4, None) == -3
-    long = ws(2, 4096, 64)            # beyond 2048 tokens the weights of every query live in the workspace
-    assert long >= 2 * 64 * 4096 * 2 + 2 * 4096 * 4096 * 4
+    # beyond 2048 tokens the weights of a query block live in the workspace: one piece of 16 rows per workgroup of
+    # the launch, which has at most 512 of them (fewer when there are fewer query blocks)
+    long = ws(2, 4096, 64)
+    assert long >= 2 * 64 * 4096 * 2 + 2 * 256 * 16 * 4096 * 4
+    big = ws(128, 8192, 128)
+    assert 128 * 128 * 8192 * 2 + 512 * 16 * 8192 * 4 <= big < 128 * 128 * 8192 * 2 + 512 * 16 * 8192 * 4 + (4 << 20)
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, long - 1, 2, 4096, 64, 4, None) == -4
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE, n - 1, 2, 64, 64, 4, None) == -4
     assert call(FAKE, FAKE, FAKE, FAKE, FAKE + 16, n, 2, 64, 64, 4, None) == -4
