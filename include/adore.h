@@ -56,7 +56,7 @@
 extern "C" {
 #endif
 
-#define ADORE_ABI_VERSION 9
+#define ADORE_ABI_VERSION 10
 
 typedef struct adore_ctx adore_ctx; /* opaque */
 
@@ -294,7 +294,8 @@ enum {
   ADORE_KERNEL_FWD_OPROJ_CUR,   /* rebuild forward: the same for the current tokens' rows */
   ADORE_KERNEL_ROPE,            /* rotary embedding of the rows a projection just wrote (rope_base > 0) */
   ADORE_KERNEL_H2O_RELEASE,     /* H2O mode: the step's attention added to the scores, then the per-head release */
-  ADORE_KERNEL_H2O_CHOICE,      /* H2O mode: per-sequence choice on the sum over heads + per-head slot assignment */
+  ADORE_KERNEL_H2O_CHOICE,      /* H2O mode: per-sequence choice of the tokens to rebuild on the sum over heads */
+  ADORE_KERNEL_H2O_PLACE,       /* H2O mode: per head, the slots of the chosen tokens it is missing */
   ADORE_N_KERNELS
 };
 int adore_set_timing(adore_ctx *ctx, int32_t enable);

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libadore.so")
 ADORE_F32, ADORE_BF16 = 0, 1
 KERNELS = ["attend", "attend_combine", "ctrl_input", "ctrl_cell", "release", "rebuild_select", "rebuild_gemm",
            "rescore", "fwd_qkv", "fwd_qkv_cur", "fwd_attend", "fwd_oproj", "fwd_oproj_cur", "rope", "h2o_release",
-           "h2o_choice"]
+           "h2o_choice", "h2o_place"]
 SCORE_STATIC, SCORE_RESCORE, SCORE_H2O = 0, 1, 2
 
 EXPORTS = [

@@ -886,6 +886,7 @@ const char *adore_kernel_name(int32_t kernel) {
     case ADORE_KERNEL_ROPE: return "rope";
     case ADORE_KERNEL_H2O_RELEASE: return "h2o_release";
     case ADORE_KERNEL_H2O_CHOICE: return "h2o_choice";
+    case ADORE_KERNEL_H2O_PLACE: return "h2o_place";
     default: return "?";
   }
 }

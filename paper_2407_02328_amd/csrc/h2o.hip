@@ -68,7 +68,7 @@ struct H2OChoiceArgs {
 };
 
 // One workgroup per sequence.  LDS: keys of tokens 0 .. n, how many heads hold each token (8 bits each), the select's
-// scratch, and per wave a copy of a head's free slots.
+// scratch.  Writes the chosen positions (best first, then -1); h2o_place_kernel gives them their slots.
 template <int KPL>
 __global__ __launch_bounds__(kChoiceThreads) void h2o_choice_kernel(const H2OChoiceArgs a) {
   extern __shared__ uint64_t smem64[];
@@ -80,25 +80,38 @@ __global__ __launch_bounds__(kChoiceThreads) void h2o_choice_kernel(const H2OCho
   uint32_t *s_cnt = s_hist + 256;                               // [(n + 4) / 4] four counters per word
   int *s_sel = reinterpret_cast<int *>(s_cnt + (a.n + 4) / 4);  // [Rr] chosen positions, best first
   int *s_misc = s_sel + Rr;                                     // [0] collect's counter, [1] candidates
-  int *s_free = s_misc + 4;                                     // [waves][R1]
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   for (int wd = tid; wd < (a.n + 4) / 4; wd += kChoiceThreads) s_cnt[wd] = 0;
   if (tid == 0) s_misc[1] = 0;
   __syncthreads();
   const int32_t *maps = a.slot_pos + size_t(b) * a.H * a.K;
-  for (int idx = tid; idx < a.H * a.K; idx += kChoiceThreads) {
-    const int p = maps[idx];
-    if (p >= 0) atomicAdd(&s_cnt[p >> 2], 1u << (8 * (p & 3)));
+  for (int idx0 = tid; idx0 < a.H * a.K; idx0 += 8 * kChoiceThreads) {   // eight loads on their way at a time
+    int p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = idx0 + u * kChoiceThreads;
+      p[u] = idx < a.H * a.K ? maps[idx] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p[u] >= 0) atomicAdd(&s_cnt[p[u] >> 2], 1u << (8 * (p[u] & 3)));
   }
   __syncthreads();
   const float *sc = a.score + size_t(b) * a.H * a.N_max;
   int mine = 0;
   for (int i = tid; i < n1; i += kChoiceThreads) {
-    // fp32, heads in order (the order is part of the result); the loads go out eight at a time: one after the
-    // other they cost a trip to the L2 per head
+    // fp32, heads in order (the order is part of the result); the loads go out 32 (or eight) at a time: one after
+    // the other they cost a trip to the L2 per head
     float agg = 0.f;
     int h = 0;
+    for (; h + 32 <= a.H; h += 32) {
+      float v[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) v[u] = sc[size_t(h + u) * a.N_max + i];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) agg = agg + v[u];
+    }
     for (; h + 8 <= a.H; h += 8) {
       float v[8];
 #pragma unroll
@@ -127,50 +140,56 @@ __global__ __launch_bounds__(kChoiceThreads) void h2o_choice_kernel(const H2OCho
     a.rebuilt_pos[size_t(b) * a.Rdim + t] = p;
     if (a.rb_out) a.rb_out[size_t(b) * a.Rdim + t] = p;
   }
-  // every head: a wave holds the head's row; the chosen tokens it is missing take its free slots, lowest first
-  for (int h0 = 0; h0 < a.H; h0 += kChoiceWaves) {          // uniform trip count: the barrier below sees every wave
-    const int h = h0 + wave;
-    const size_t row = size_t(b) * a.H + min(h, a.H - 1);
-    int *fr = s_free + wave * a.R1;
-    for (int t = lane; t < a.R1; t += 64) fr[t] = a.free_list[row * a.R1 + t];
-    int pos[KPL];
+}
+
+// Placement, one wave per (sequence, head): the wave holds the head's row; the chosen tokens the head is missing take
+// its free slots, lowest first, in rank order.  (Inside the choice kernel the heads of a sequence queued behind its
+// eight waves, four rounds of loads and a serial walk over the ranks each.)
+template <int KPL>
+__global__ __launch_bounds__(256) void h2o_place_kernel(const H2OChoiceArgs a, int rows) {
+  extern __shared__ int s_place[];               // [4 waves][R1 free slots + Rdim chosen positions]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;                       // whole wave leaves together; no barrier below
+  const int b = row / a.H;
+  int *fr = s_place + wave * (a.R1 + a.Rdim), *sel = fr + a.R1;
+  for (int t = lane; t < a.R1; t += 64) fr[t] = a.free_list[size_t(row) * a.R1 + t];
+  for (int t = lane; t < a.Rdim; t += 64) sel[t] = a.rebuilt_pos[size_t(b) * a.Rdim + t];
+  int pos[KPL];
 #pragma unroll
-    for (int j = 0; j < KPL; ++j) {
-      const int k = j * 64 + lane;
-      pos[j] = k < a.K ? a.slot_pos[row * a.K + k] : -1;
-    }
-    __syncthreads();
-    if (h < a.H) {
-      int taken = 0;
-      for (int rho = 0; rho < r; ++rho) {
-        const int t = s_sel[rho];
-        bool found = false;
-#pragma unroll
-        for (int j = 0; j < KPL; ++j) found |= pos[j] == t;
-        const bool held = __ballot(found) != 0;
-        int slot = -1;
-        if (!held) slot = fr[taken++];
-        if (lane == 0) {
-          a.free_list[row * a.R1 + rho] = slot;
-          if (slot >= 0) {
-            a.slot_pos[row * a.K + slot] = t;
-            if (a.map_out) a.map_out[row * a.K + slot] = t;
-          }
-        }
-      }
-      for (int rho = r + lane; rho < a.R; rho += 64) a.free_list[row * a.R1 + rho] = -1;
-      if (lane == 0) a.insert_slot[row] = fr[taken];      // taken <= R: the list holds R + 1 free slots
-    }
-    __syncthreads();
+  for (int j = 0; j < KPL; ++j) {
+    const int k = j * 64 + lane;
+    pos[j] = k < a.K ? a.slot_pos[size_t(row) * a.K + k] : -1;
   }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // the wave's LDS stores before its LDS loads
+  __builtin_amdgcn_wave_barrier();
+  int taken = 0, rho = 0;
+  for (; rho < a.R; ++rho) {
+    const int t = sel[rho];
+    if (t < 0) break;                            // the chosen positions come first, then -1 (uniform over the wave)
+    bool found = false;
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) found |= pos[j] == t;
+    const bool held = __ballot(found) != 0;
+    int slot = -1;
+    if (!held) slot = fr[taken++];
+    if (lane == 0) {
+      a.free_list[size_t(row) * a.R1 + rho] = slot;
+      if (slot >= 0) {
+        a.slot_pos[size_t(row) * a.K + slot] = t;
+        if (a.map_out) a.map_out[size_t(row) * a.K + slot] = t;
+      }
+    }
+  }
+  for (int q = rho + lane; q < a.R; q += 64) a.free_list[size_t(row) * a.R1 + q] = -1;
+  if (lane == 0) a.insert_slot[row] = fr[taken];   // taken <= R: the list holds R + 1 free slots
 }
 
 }  // namespace
 
 size_t h2o_choice_lds_bytes(const adore_config &c, int n) {
   const size_t Rr = size_t(c.rebuild_budget > 0 ? c.rebuild_budget : 1);
-  return size_t(n + 1) * 8 + Rr * 8 + 4 * 8 + 256 * 4 + size_t((n + 4) / 4) * 4 + Rr * 4 + 16 +
-         size_t(kChoiceWaves) * (c.rebuild_budget + 1) * 4;
+  return size_t(n + 1) * 8 + Rr * 8 + 4 * 8 + 256 * 4 + size_t((n + 4) / 4) * 4 + Rr * 4 + 16;
 }
 
 hipError_t launch_h2o_init_scores(adore_ctx *ctx, const float *score_init, int S) {
@@ -214,6 +233,15 @@ hipError_t launch_h2o_choice(adore_ctx *ctx, int maps, int lists, int n, int32_t
   else if (c.cache_slots <= 256) ADORE_LAUNCH(t, (h2o_choice_kernel<4>), grid, block, smem, ctx->stream, a);
   else if (c.cache_slots <= 512) ADORE_LAUNCH(t, (h2o_choice_kernel<8>), grid, block, smem, ctx->stream, a);
   else ADORE_LAUNCH(t, (h2o_choice_kernel<16>), grid, block, smem, ctx->stream, a);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  ScopedTimer tp(ctx, ADORE_KERNEL_H2O_PLACE, ctx->stream);
+  const int rows = c.batch * c.heads;
+  const dim3 pgrid((rows + 3) / 4), pblock(256);
+  const size_t psmem = size_t(4) * (a.R1 + a.Rdim) * 4;
+  if (c.cache_slots <= 128) ADORE_LAUNCH(tp, (h2o_place_kernel<2>), pgrid, pblock, psmem, ctx->stream, a, rows);
+  else if (c.cache_slots <= 256) ADORE_LAUNCH(tp, (h2o_place_kernel<4>), pgrid, pblock, psmem, ctx->stream, a, rows);
+  else if (c.cache_slots <= 512) ADORE_LAUNCH(tp, (h2o_place_kernel<8>), pgrid, pblock, psmem, ctx->stream, a, rows);
+  else ADORE_LAUNCH(tp, (h2o_place_kernel<16>), pgrid, pblock, psmem, ctx->stream, a, rows);
   return hipGetLastError();
 }
 

@@ -45,7 +45,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.adore_abi_version() == 9
+    assert lib.adore_abi_version() == 10
 
 
 def test_workspace_bytes(lib):
