@@ -743,6 +743,112 @@ def test_first_steps_without_a_synchronise_after_the_init_when_inputs_are_not_or
     job.adore.close()
 
 
+@pytest.mark.parametrize("name,ordered,steps", [
+    ("llama7b_layer", False, 48), ("llama7b_layer", True, 48), ("high_batch", False, 24), ("long_context", False, 24)])
+def test_free_running_steps_as_the_benchmark_times_them(name, ordered, steps):
+    """What bench.py times is a run of steps enqueued back to back with no synchronisation, at full size, most of
+    them in the order-off mode: the side streams then run ahead through the rings of per-step lists and catch up at
+    their periodic waits.  Here the same is done with every step keeping its outputs: the init and `steps` steps
+    (several times round the rings) without a synchronisation in between must leave, step for step, the bits of a
+    run that synchronises after every call (which is the run the oracle follows in the tests above)."""
+    h = _harness()
+    w = workload(name)
+    inp = SyntheticInputs(w)
+    st = h.storage_dtype(w)
+    qkv = [[h.to_dev(a, st) for a in inp.step_qkv(w.S + t)] for t in range(steps)]
+
+    def run(sync_every_call):
+        job = h.GpuJob(w, inp, ordered=ordered)
+        pk, pv = (h.to_dev(a, st) for a in job.prompt_np)
+        ctrl = job.hidden[0][:, :w.S].contiguous()
+        xs = [job.hidden[0][:, w.S + t].contiguous() for t in range(steps)]
+        outs = [torch.empty((w.L, w.B, w.H, w.d), dtype=torch.float32, device=h.DEV) for _ in range(steps)]
+        maps = [torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=h.DEV) for _ in range(steps)]
+        torch.cuda.synchronize()
+        job.adore.init_cache(pk, pv, job.hidden, ctrl, None, w.S)
+        for t in range(steps):
+            if sync_every_call:
+                torch.cuda.synchronize()
+            q, k, v = qkv[t]
+            if w.L == 1:
+                job.adore.decode_step(q[0], k[0], v[0], job.hidden[0], xs[t], None, outs[t][0], maps[t])
+            else:
+                for l in range(w.L):
+                    job.adore.attend(l, q[l], k[l], v[l], outs[t][l])
+                job.adore.schedule(xs[t], None, maps[t], None, None)
+                for l in range(w.L):
+                    job.adore.rebuild(l, job.hidden[l])
+        torch.cuda.synchronize()
+        state = job.snapshot()
+        result = ([o.cpu().numpy() for o in outs], [m.cpu().numpy() for m in maps], state)
+        job.adore.close()
+        return result
+
+    want = run(True)
+    got = run(False)
+    for t in range(steps):
+        assert np.array_equal(got[1][t], want[1][t]), f"slot map at step {t}"
+        assert np.array_equal(got[0][t], want[0][t]), f"output at step {t}"
+    assert np.array_equal(got[2]["slot_pos"], want[2]["slot_pos"])
+    assert np.array_equal(got[2]["scores"][:, :w.S + steps], want[2]["scores"][:, :w.S + steps])
+    occ = want[2]["slot_pos"] >= 0
+    for key in ("cache_k", "cache_v"):
+        for l in range(w.L):
+            assert np.array_equal(got[2][key][l][occ], want[2][key][l][occ]), key
+
+
+@pytest.mark.parametrize("ordered", [False, True])
+def test_free_running_forward_steps_as_the_benchmark_times_them(ordered):
+    """The same for adore_forward_step (bench.py --forward): two layers of the benchmark shape, 20 steps back to
+    back against 20 steps with a synchronisation before each."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(L=2)
+    steps = 20
+    inp = SyntheticInputs(w)
+    st = h.storage_dtype(w)
+    wts = dict(inp.weights(), **inp.forward_weights())
+    wq, wo = h.to_dev(wts["w_q"], st), h.to_dev(wts["w_o"], st)
+    Ed = h.to_dev(inp.hidden_store_layer(0), st)
+    pk, pv = (h.to_dev(a, st) for a in inp.prompt_kv())
+    dev_w = h.device_weights(w, {k: v for k, v in wts.items() if k not in ("w_q", "w_o")})
+
+    def run(sync_every_call):
+        from paper_2407_02328_amd.binding import Adore
+        adore = Adore(h.adore_config(w), dev_w, h.DEV)
+        if not ordered:
+            adore.set_input_order(False)
+        rows = [torch.zeros((w.B, w.R + 1, w.D), dtype=st, device=h.DEV) for _ in range(steps)]
+        maps = [torch.empty((w.B, w.H, w.K), dtype=torch.int32, device=h.DEV) for _ in range(steps)]
+        rebuilt = [torch.empty((w.B, w.R), dtype=torch.int32, device=h.DEV) for _ in range(steps)]
+        torch.cuda.synchronize()
+        adore.init_cache(pk, pv, None, Ed[:, :w.S].contiguous(), None, w.S)
+        for t in range(steps):
+            if sync_every_call:
+                torch.cuda.synchronize()
+            adore.forward_step(wq, wo, Ed, None, rows[t], maps[t], None, rebuilt[t])
+        torch.cuda.synchronize()
+        state = adore.empty_state()
+        adore.get_state(**state)
+        torch.cuda.synchronize()
+        result = ([r.float().cpu().numpy() for r in rows], [m.cpu().numpy() for m in maps],
+                  [r.cpu().numpy() for r in rebuilt], {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+                                                       for k, v in state.items()})
+        adore.close()
+        return result
+
+    want = run(True)
+    got = run(False)
+    for t in range(steps):
+        assert np.array_equal(got[1][t], want[1][t]), f"slot map at step {t}"
+        assert np.array_equal(got[2][t], want[2][t]), f"rebuilt positions at step {t}"
+        assert np.array_equal(got[0][t], want[0][t]), f"rows at step {t}"
+    assert np.array_equal(got[3]["slot_pos"], want[3]["slot_pos"])
+    occ = want[3]["slot_pos"] >= 0
+    for key in ("cache_k", "cache_v"):
+        for l in range(w.L):
+            assert np.array_equal(got[3][key][l][occ], want[3][key][l][occ]), key
+
+
 # ---- a sweep of random small shapes ----------------------------------------------------------------------
 def _random_workloads(count, seed):
     """Small shapes drawn at random within what the library documents as supported: every axis ragged against the
