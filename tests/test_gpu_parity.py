@@ -323,6 +323,17 @@ def test_llama7b_layer_full_size_steps():
     job.adore.close()
 
 
+@pytest.mark.timeout(600)
+def test_llama7b_layer_full_size_many_steps_sampled_sequences():
+    """The benchmark workload at full size over 72 steps of adore_decode_step (several times round the rings of
+    per-step lists, across a 64-token boundary of the controller's scratch); the oracle follows sequences 3 and 12."""
+    h = _harness()
+    w = workload("llama7b_layer").scaled(T=80)
+    worst, job, _ = h.sampled_lockstep(w, steps=72, seqs=[3, 12])
+    print(f"llama7b_layer (full size, 72 steps, 2 of 16 sequences): worst output error {worst:.3e}")
+    job.adore.close()
+
+
 def test_long_context_reduced_with_salience():
     """The long-context recipe (Zipf salience in key dimension 0 and in the controller input, K = 1024,
     rows split over several workgroups) at a prompt the oracle finishes in seconds."""
