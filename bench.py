@@ -503,6 +503,37 @@ def topk_line(w, args):
     return line
 
 
+def other_path_entries(w):
+    """The library's other paths at the same workload, compactly, for the default line: the rebuild forward through
+    four layers, the cache initialisation over the prompts, the top-K attention over the prompts, the decode step in
+    the H2O score mode.  Each is the measurement of its own flag (--forward, --prefill, --topk-attention, --h2o) with
+    fewer steps and no oracle sample."""
+    import argparse
+    quick = argparse.Namespace(steps=60, warmup=10, profile_steps=20, topk=96, no_cpu_baseline=True)
+    fw = forward_line(w.scaled(L=4), quick)
+    pf = prefill_line(w, quick)
+    tk = topk_line(w, quick)
+    wh = w.scaled(h2o=True)
+    el, us, _ = run_gpu(wh, 100, 20, 30)
+    pick = lambda d, keys: {k: d[k] for k in keys if k in d}
+    return [
+        {"path": "rebuild forward (adore_forward_step), 4 layers", "ms_per_step_per_layer": fw["ms_per_step"],
+         "tokens_per_s_per_layer": fw["value"],
+         "kernel_us": pick(fw["kernel_us"], ("fwd_qkv", "fwd_attend", "fwd_oproj")),
+         "fwd_attend_frac_of_hbm_peak": fw["roofline_fwd_attend"]["frac"],
+         "fwd_qkv_frac_of_mfma_peak": fw["roofline_fwd_qkv"]["frac"],
+         "fwd_oproj_frac_of_mfma_peak": fw["roofline_fwd_oproj"]["frac"]},
+        {"path": "cache initialisation over the prompts (adore_init_cache)", "ms_per_init": pf["ms_per_step"],
+         "prompt_tokens_per_s": pf["value"], "kernel_us": pf["kernel_us"]},
+        {"path": "top-K attention over the prompts (adore_topk_attention, K = 96)", "ms_per_call": tk["ms_per_step"],
+         "prompt_tokens_per_s": tk["value"], "frac_of_mfma_peak": tk["roofline"]["frac"]},
+        {"path": "decode step with H2O scores (score_mode = h2o)", "ms_per_step": round(1e3 * el / 100, 4),
+         "tokens_per_s_per_layer": round(wh.B * 100 / el, 1),
+         "kernel_us": {k: round(v, 2) for k, v in us.items() if v and k in
+                       ("attend", "h2o_release", "h2o_choice", "h2o_place", "rebuild_gemm")}},
+    ]
+
+
 def run_cpu_baseline(w, seqs=16, steps=40, single_thread_steps=8):
     """The oracle as it stands, on `seqs` sequences of the same workload, steady-state steps: once with the
     threads numpy's BLAS takes by itself, once (fewer steps) limited to one thread; per-stage seconds from timers
@@ -684,6 +715,9 @@ def main():
             frac=hb["attend_frac_of_hbm_peak"], traffic=traffic_hb.get("attend"), us_per_launch=hb["attend_us"],
             algorithmic_bytes=hb["attend_algorithmic_bytes"])
         log(f"other workloads took {time.time() - t0:.1f}s")
+        t0 = time.time()
+        line["other_paths"] = other_path_entries(workload("llama7b_layer"))
+        log(f"other paths took {time.time() - t0:.1f}s")
     if not args.no_cpu_baseline and not w.h2o:
         t0 = time.time()
         line["cpu_baseline"] = run_cpu_baseline(w)
