@@ -635,6 +635,21 @@ def test_inputs_complete_at_call_time(calls):
     job.adore.close()
 
 
+@pytest.mark.parametrize("ordered", [True, False])
+def test_context_bound_to_a_stream_of_the_callers(ordered):
+    """Everything above runs on the default stream.  A context created while another stream is current is bound to
+    that stream (default priority): its inputs are produced there, its side streams order themselves against it,
+    and the trajectory is the oracle's all the same, through the whole-step call and the fine-grained ones."""
+    h = _harness()
+    w = Workload("own_stream", **ORDER_W)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=4, whole=lambda t: (t // 3) % 2 == 0, ordered=ordered)
+        assert job.adore.stream.cuda_stream == stream.cuda_stream != 0
+        job.adore.close()
+    torch.cuda.synchronize()
+
+
 def test_input_order_switched_between_steps():
     h = _harness()
     w = Workload("order_switch", **ORDER_W)
