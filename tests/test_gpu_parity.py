@@ -276,6 +276,46 @@ def test_state_machine_on_device():
     job.adore.close()
 
 
+@pytest.mark.parametrize("ordered", [True, False])
+def test_init_again_restarts_the_context(ordered):
+    """adore_init_cache may be called again: after some steps a second init over the same prompt (enqueued right
+    behind the last step, no synchronisation) starts the same trajectory again, bit for bit, and a third over a
+    shorter prompt gives what a context that has seen nothing else gives."""
+    h = _harness()
+    w = Workload("restart", **dict(ORDER_W, T=12))
+    inp = SyntheticInputs(w)
+    job = h.GpuJob(w, inp, ordered=ordered)
+    job.init()
+    first = [job.step(w.S + t, whole=t % 2 == 0) for t in range(w.T)]
+    st = job.st
+    pk, pv = (h.to_dev(a, st) for a in job.prompt_np)
+    job.adore.init_cache(pk, pv, job.hidden, job.hidden[0][:, :w.S].contiguous(), None, w.S)
+    second = [job.step(w.S + t, whole=t % 2 == 0) for t in range(w.T)]
+    def same(a_run, b_run, whole_steps, when):
+        for t, (a, b) in enumerate(zip(a_run, b_run)):
+            for x, y, what in zip(a, b, ("output", "slot map", "released", "rebuilt", "score")):
+                if what in ("released", "rebuilt") and t % 2 == whole_steps:
+                    continue        # the whole-step call reports the slot map only
+                assert np.array_equal(x, y), f"{what} at step {t} {when}"
+
+    same(first, second, 0, "after the second init")
+    # a third init over a shorter prompt, in the same context: nothing of the longer runs is left behind (the same
+    # steps in a context that has seen nothing else give the same bits)
+    S2 = 50
+    pk2, pv2 = (t[:, :, :, :S2].contiguous() for t in (pk, pv))
+
+    def short_run(j):
+        j.adore.init_cache(pk2, pv2, j.hidden, j.hidden[0][:, :S2].contiguous(), None, S2)
+        return [j.step(S2 + t, whole=t % 2 == 1) for t in range(w.T)]
+
+    third = short_run(job)
+    job.adore.close()
+    fresh = h.GpuJob(w, inp, ordered=ordered)
+    want = short_run(fresh)
+    fresh.adore.close()
+    same(third, want, 1, "after the init over the shorter prompt")
+
+
 @pytest.mark.parametrize("split,waves", [(1, 4), (1, 16), (2, 8), (4, 4), (3, 16)])
 def test_attention_launch_shapes(split, waves, monkeypatch):
     """Every split count / workgroup width of the attention kernel gives the oracle's result."""
