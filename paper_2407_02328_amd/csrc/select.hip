@@ -259,6 +259,11 @@ hipError_t launch_rebuild_select(adore_ctx *ctx, hipStream_t st, int dst, int r,
   a.R1 = c.rebuild_budget + 1; a.Rdim = max(c.rebuild_budget, 1);
   a.words = (c.max_positions + 31) / 32;
   const size_t smem = rebuild_choice_lds_bytes(r, a.words, ctx->n);
+  if (smem > 48 * 1024) {   // more than a workgroup gets without asking (host-side setting, once per process would do)
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&rebuild_select_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kChoiceLdsLimit));
+    if (e != hipSuccess) return e;
+  }
   ScopedTimer t(ctx, ADORE_KERNEL_REBUILD_SELECT, st);
   ADORE_LAUNCH(t, rebuild_select_kernel, dim3(c.batch), dim3(1024), smem, st, a);
   return hipGetLastError();

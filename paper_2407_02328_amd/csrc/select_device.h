@@ -251,6 +251,13 @@ struct RebuildSelectArgs {
 __host__ __device__ inline bool choice_keys_cached(int n, int words) {
   return size_t(n + 1) * 8 + size_t(words) * 4 <= 56 * 1024;
 }
+// Beyond that a copy of the scores themselves (4 bytes a token, the key is made from it on the fly) still fits the
+// LDS a workgroup may ask for (the stand-alone choice does; the limit leaves room for its other arrays): one read
+// of the scores instead of one per pass up to about 33000 tokens.
+constexpr size_t kChoiceLdsLimit = 152 * 1024;
+__host__ __device__ inline bool choice_scores_cached(int n, int words) {
+  return !choice_keys_cached(n, words) && size_t(n + 1) * 4 + size_t(words) * 4 + 16384 <= kChoiceLdsLimit;
+}
 
 // The choice for sequence b by one workgroup of any size.  res_row: the positions held by head 0 of the sequence
 // after the release (uniform policy: every head of a sequence holds the same positions).  assign_heads: also
@@ -259,8 +266,10 @@ __host__ __device__ inline bool choice_keys_cached(int n, int words) {
 __device__ inline void rebuild_choice_block(const RebuildSelectArgs &a, int b, const int32_t *res_row,
                                             bool assign_heads, uint64_t *smem64) {
   const bool cached = choice_keys_cached(a.n, a.words);
+  const bool sc_cached = choice_scores_cached(a.n, a.words);
   uint64_t *s_cache = smem64;                                   // [n + 1] keys, 0 = resident (if cached)
-  uint64_t *s_keys = smem64 + (cached ? a.n + 1 : 0);           // [max(r,1)]
+  float *s_score = reinterpret_cast<float *>(smem64);           // or [n + 1] scores (if sc_cached), padded to 8 bytes
+  uint64_t *s_keys = smem64 + (cached ? a.n + 1 : sc_cached ? (a.n + 2) / 2 : 0);   // [max(r,1)]
   uint64_t *s_ctl = s_keys + max(a.r, 1);                       // [4]
   uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_ctl + 4);   // [256]
   uint32_t *s_bits = s_hist + 256;                              // [words] residency bitmap
@@ -289,6 +298,14 @@ __device__ inline void rebuild_choice_block(const RebuildSelectArgs &a, int b, c
       auto key_c = [&](int i) -> uint64_t { return s_cache[i]; };
       radix_select(key_c, a.n + 1, r, s_hist, s_ctl, &thr, &shift);
       collect_sorted(key_c, a.n + 1, r, thr, shift, s_keys, s_count, s_sel);
+    } else if (sc_cached) {   // the scores once, the keys from the copy in every pass
+      for (int i = tid; i <= a.n; i += blockDim.x) s_score[i] = sc[i];
+      __syncthreads();
+      auto key_s = [&](int i) -> uint64_t {
+        return (s_bits[i >> 5] >> (i & 31)) & 1u ? uint64_t(0) : rank_key(s_score[i], i);
+      };
+      radix_select(key_s, a.n + 1, r, s_hist, s_ctl, &thr, &shift);
+      collect_sorted(key_s, a.n + 1, r, thr, shift, s_keys, s_count, s_sel);
     } else {
       radix_select(key_of, a.n + 1, r, s_hist, s_ctl, &thr, &shift);
       collect_sorted(key_of, a.n + 1, r, thr, shift, s_keys, s_count, s_sel);
@@ -366,7 +383,8 @@ inline size_t ridden_choice_lds_bytes(int r, int n) {
 // n: position of the current token (keys of tokens 0 .. n)
 inline size_t rebuild_choice_lds_bytes(int r, int words, int n) {
   const size_t rr = size_t(r > 0 ? r : 1);
-  const size_t cache = choice_keys_cached(n, words) ? size_t(n + 1) * 8 : 0;
+  const size_t cache = choice_keys_cached(n, words) ? size_t(n + 1) * 8
+                       : choice_scores_cached(n, words) ? size_t((n + 2) / 2) * 8 : 0;
   return cache + rr * 8 + 4 * 8 + 256 * 4 + size_t(words) * 4 + rr * 4 + 8;
 }
 

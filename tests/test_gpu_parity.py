@@ -638,6 +638,17 @@ def test_decode_step_call_on_long_sequences():
     job.adore.close()
 
 
+@pytest.mark.parametrize("S", [9000, 40000])
+def test_rebuild_choice_over_sequences_beyond_the_key_cache(S):
+    """The per-sequence choice keeps the ranking keys of a sequence in LDS up to about 7000 tokens, a copy of the
+    scores up to about 33000, and reads the scores from memory in every pass beyond: one short-headed job on either
+    side of the second limit (the first tier is what every other test runs)."""
+    h = _harness()
+    w = Workload(f"choice_{S}", L=1, B=2, H=2, d=64, D=64, K=40, R=6, S=S, T=6, dtype="f32", dprime=16)
+    worst, job, _ = h.lockstep(w, steps=w.T, check_cache_every=3, whole=lambda t: t % 2 == 0)
+    job.adore.close()
+
+
 def test_decode_step_call_mixed_with_fine_grained_calls():
     """Steps alternate in blocks between adore_decode_step and attend / schedule / rebuild: the reserved slot is
     handed over correctly in both directions and the side stream catches up when the selections move back to it."""
